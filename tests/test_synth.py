@@ -1,0 +1,46 @@
+"""The seeded input generator: determinism, distributions, layouts (CPU only)."""
+import numpy as np
+
+from paper_2603_29010_amd import synth
+
+
+def test_counter_based_slices_are_reproducible():
+    a = synth.uniform01(7, 3, 1000)
+    b = synth.uniform01(7, 3, 100, start=500)
+    assert np.array_equal(a[500:600], b)
+    assert not np.array_equal(a, synth.uniform01(8, 3, 1000))
+    assert not np.array_equal(a, synth.uniform01(7, 4, 1000))
+
+
+def test_distributions_within_5_sigma():
+    n = 1 << 18
+    u = synth.uniform_pm1(1, 1, n)
+    assert abs(u.mean()) < 5 * (1 / np.sqrt(3)) / np.sqrt(n)
+    assert abs(u.var() - 1 / 3) < 5 * np.sqrt(4 / 45 / n)
+    assert u.min() >= -1 and u.max() < 1
+    z = synth.normal(1, 2, n)
+    assert abs(z.mean()) < 5 / np.sqrt(n)
+    assert abs(z.var() - 1) < 5 * np.sqrt(2 / n)
+    assert abs((z ** 4).mean() - 3) < 0.1
+    k = synth.randint(1, 3, n, -2, 2)
+    assert set(np.unique(k)) == {-2.0, -1.0, 0.0, 1.0, 2.0}
+
+
+def test_storage_round_trip():
+    x = np.array([1.0, -0.5, 3.140625, 2.0 ** -20])
+    for dt in ("bf16", "f16", "f32"):
+        assert np.array_equal(synth.bits_to_f64(synth.to_bits(x, dt), dt), x)
+    assert synth.to_bits(np.array([1 + 2 ** -8]), "bf16")[0] == 0x3F80      # tie -> even
+
+
+def test_config_shapes():
+    c1 = synth.config(1)
+    assert c1["A"].shape == (256, 256) and c1["b_strides"] == (256, 1)
+    assert [s[0] for s in c1["epilogue"]] == ["bias", "relu"]
+    c3 = synth.config(3, shrink=16)
+    assert c3["A"].shape == (4, 512, 128) and c3["dt_out"] == "f32"
+    M_g = synth.grouped_sizes(16, synth.BASE_SEED + 4)
+    assert len(M_g) == 16 and all(128 <= m <= 2048 and m % 64 == 0 for m in M_g)
+    c5 = synth.config(5, shrink=16)
+    assert c5["x"].shape == (2, 56, 56, 64) and c5["w"].shape == (128, 3, 3, 64)
+    assert c5["M"] == 2 * 56 * 56 and c5["K"] == 576
