@@ -1,0 +1,163 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path on one MI355X.
+
+Default workload (config 2 of the baseline): single GEMM M=N=K=4096, A row-major / B column-major
+bf16, fp32 accumulate, fused bias + tanh-GELU epilogue, bf16 output.  A "step" is one pass of the
+whole path: one ucl_gemm call (tile schedule, staged copies, MFMA mainloop, fused epilogue, store)
+on inputs already resident in HBM.  Prints ONE JSON line on stdout.
+
+  python bench.py [--steps K] [--warmup W] [--config {1..5}] [--all] [--no-cpu-baseline]
+
+--all adds a "configs" object with the other four workloads (each timed the same way, HBM-cold by
+rotating over distinct buffer sets for the memory-bound ones).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_MFMA_TFLOPS = 2516.6      # dense bf16 / fp16, 256 CUs x 2.4 GHz x 4096 FLOP/clk
+PEAK_HBM_GBPS = 8000.0
+WORKLOAD_NAMES = {
+    1: "gemm_256x256x256_bf16_bias_relu",
+    2: "gemm_4096x4096x4096_bf16_rowcol_bias_gelu_tanh",
+    3: "batched_gemm_64x512x512x128_f16_scale_f32out",
+    4: "grouped_gemm_16groups_N4096_K1024_bf16_silu",
+    5: "conv2d_fprop_nhwc_32x56x56x64_to_128_3x3_bf16_bias_residual_relu",
+}
+
+
+def time_workload(cfg, steps, warmup, copies=None):
+    """Time `steps` back-to-back launches with HIP events on the launch stream."""
+    import torch
+    from paper_2603_29010_amd import synth
+    from paper_2603_29010_amd.workload import DeviceWorkload
+    spec = synth.config(cfg)
+    probe = DeviceWorkload(spec, poison=False)
+    sol = probe.sol()
+    if copies is None:
+        # memory-bound workloads: rotate over enough distinct operand sets that a launch cannot be
+        # served from the 256 MB last-level cache left warm by the previous one
+        copies = 1 if sol["compute_bound"] else max(2, int(768e6 // sol["bytes"]) + 1)
+    sets = [probe] + [DeviceWorkload(spec, poison=False) for _ in range(copies - 1)]
+    stream = torch.cuda.current_stream()
+    for i in range(warmup):
+        sets[i % copies].run()
+    torch.cuda.synchronize()
+    start = torch.cuda.Event(enable_timing=True)
+    stop = torch.cuda.Event(enable_timing=True)
+    start.record(stream)
+    for i in range(steps):
+        sets[i % copies].run()
+    stop.record(stream)
+    torch.cuda.synchronize()
+    ms = start.elapsed_time(stop) / steps
+    t = ms * 1e-3
+    res = {
+        "workload": WORKLOAD_NAMES[cfg], "ms_per_step": ms, "tflops": sol["flops"] / t / 1e12,
+        "gbps": sol["bytes"] / t / 1e9, "flops": sol["flops"], "bytes": sol["bytes"],
+        "t_sol_us": sol["t_sol"] * 1e6, "frac_of_sol": sol["t_sol"] / t,
+        "bound": "mfma" if sol["compute_bound"] else "hbm", "buffer_sets": copies,
+    }
+    if spec["op"] == "grouped_gemm":
+        res["sum_M"] = int(sum(spec["M_g"]))
+    # integrity self-check (the paper's SOL-ceiling detector): nothing can beat the bound by > 10 %
+    res["below_sol_flag"] = bool(t < 0.9 * sol["t_sol"])
+    return res, spec, probe
+
+
+def cpu_baseline(spec, cfg):
+    """The fp64 oracle, as it stands, on a bounded sample of the same workload."""
+    from oracle import run_spec
+    import numpy as np
+    if spec["op"] in ("gemm", "conv2d_fprop"):
+        M = spec["M"]
+        n = {1: M, 2: 1024, 5: 12544}.get(cfg, min(M, 1024))
+        rows = list(range(0, M, max(1, M // n)))[:n]
+        t0 = time.perf_counter()
+        run_spec.run(spec, rows=rows)
+        dt = time.perf_counter() - t0
+        flops = 2.0 * len(rows) * spec["N"] * spec["K"]
+        sample = f"{len(rows)} of {M} output rows (every {max(1, M // n)}th), all {spec['N']} columns"
+    else:
+        import copy
+        sub = copy.copy(spec)
+        if spec["op"] == "batched_gemm":
+            sub["batch"] = 16
+            sub["A"], sub["B"] = spec["A"][:16], spec["B"][:16]
+            flops = 2.0 * 16 * spec["M"] * spec["N"] * spec["K"]
+            sample = f"16 of {spec['batch']} batches"
+        else:
+            sub["M_g"] = [128] * len(spec["M_g"])
+            offs = np.concatenate([[0], np.cumsum(spec["M_g"])])[:-1]
+            sub["A"] = np.concatenate([spec["A"][o:o + 128] for o in offs])
+            flops = 2.0 * 128 * len(spec["M_g"]) * spec["N"] * spec["K"]
+            sample = "first 128 rows of each of the 16 groups"
+        t0 = time.perf_counter()
+        run_spec.run(sub)
+        dt = time.perf_counter() - t0
+    cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+            "sample": sample, "seconds": dt}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--all", action="store_true", help="also time the other four workloads")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU (the hot path is one kernel on one GPU's share of the "
+              "work); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    import paper_2603_29010_amd as ucl
+    if not os.path.exists(ucl.library_path()):
+        print("bench.py: libucl.so is not built (python -m paper_2603_29010_amd.build)", file=sys.stderr)
+        sys.exit(1)
+
+    res, spec, _ = time_workload(args.config, args.steps, args.warmup)
+    mfma = res["bound"] == "mfma"
+    roofline = {
+        "bound": res["bound"],
+        "achieved": res["tflops"] if mfma else res["gbps"],
+        "peak": PEAK_MFMA_TFLOPS if mfma else PEAK_HBM_GBPS,
+        "unit": "TFLOP/s" if mfma else "GB/s",
+        "frac": (res["tflops"] / PEAK_MFMA_TFLOPS) if mfma else (res["gbps"] / PEAK_HBM_GBPS),
+        "traffic": None,
+    }
+    out = {
+        "metric": "TFLOP/s and % of SOL (MFMA/HBM roofline) per GEMM/conv config, 1 MI355X",
+        "value": res["tflops"], "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16" if spec["dt_in"] == "f16" else "bf16", "data": "synthetic",
+        "config": {"workload": res["workload"], "frac_of_sol": res["frac_of_sol"], "t_sol_us": res["t_sol_us"],
+                   "buffer_sets": res["buffer_sets"]},
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(spec, args.config)
+    if args.all:
+        out["configs"] = {}
+        for c in (1, 2, 3, 4, 5):
+            if c == args.config:
+                out["configs"][str(c)] = res
+                continue
+            r, _, _ = time_workload(c, args.steps, args.warmup)
+            out["configs"][str(c)] = r
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,234 @@
+/*
+ * ucl.h -- C ABI of the MI355X (gfx950) fused-epilogue GEMM / conv library.
+ *
+ * The operations are the ones the paper's kernel DSL names (Sec. 3 and the
+ * appendix grammar, rule `operation`): gemm(), batched_gemm(),
+ * grouped_gemm(expert_count=E), conv2d_fprop(kernel_h, kernel_w); their
+ * configuration knobs (rule `configuration`: dtype triple, layouts, tile,
+ * stages, alignment, swizzle, alpha/beta scaling) become plain arguments; the
+ * `>>` epilogue chain (rule `epilogue_op`, Table (c)) becomes an ordered array
+ * of steps that the kernel applies to the fp32 accumulator in registers before
+ * the one rounding to the output type.  ucl_sol_bound is the paper's
+ * Speed-of-Light analysis (Sec. 4.1) as a function.
+ *
+ * General conventions
+ *   - Every tensor pointer is caller-owned DEVICE memory unless marked HOST.
+ *     The library allocates nothing, frees nothing, keeps no pointer after a
+ *     call returns, and never synchronises: each call validates its arguments
+ *     on the host, then enqueues exactly one kernel on `stream`
+ *     (a hipStream_t passed as void*; NULL = the null stream) and returns.
+ *   - Strides are in ELEMENTS.  Inputs are UCL_BF16 or UCL_F16 (both operands
+ *     the same type), accumulation is fp32, outputs are UCL_BF16, UCL_F16 or
+ *     UCL_F32.
+ *   - Alignment (the paper's rule (alignment * element_size) % 16 == 0,
+ *     grammar notes, constraint 3): A and B base pointers are 16-byte aligned,
+ *     one of their two strides is 1 and the other a multiple of 8, and K (for
+ *     K-contiguous operands) or M / N (for operands contiguous along M / N) is
+ *     a multiple of 8.  D may have any N; it is written with 128-bit stores
+ *     when its leading stride is a multiple of 4 and its base 16-byte aligned,
+ *     with scalar stores otherwise.
+ *   - Errors: a nonzero ucl_status is returned BEFORE anything is launched;
+ *     ucl_last_error() gives a thread-local sentence saying what was wrong and
+ *     why (the paper's compiler explains failed validation the same way,
+ *     Sec. 3 "Compilation").  Nothing aborts or throws.
+ *   - Explicit tuning is honoured exactly or rejected, never silently replaced
+ *     (Sec. 3: all choices explicit, no hidden defaults).  tune == NULL or an
+ *     all-zero struct selects from the built-in per-problem table.
+ */
+#ifndef UCL_H_
+#define UCL_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum ucl_status {
+    UCL_OK = 0,
+    UCL_ERR_INVALID_ARG = 1,   /* null pointer, non-positive extent, bad enum            */
+    UCL_ERR_UNSUPPORTED = 2,   /* legal request outside what the kernels implement       */
+    UCL_ERR_WORKSPACE = 3,     /* tile x stages exceeds the 160 KiB of LDS per CU        */
+    UCL_ERR_LAUNCH = 4         /* the HIP runtime refused the launch                     */
+} ucl_status;
+
+typedef enum ucl_dtype { UCL_F32 = 0, UCL_F16 = 1, UCL_BF16 = 2 } ucl_dtype;
+
+/* Epilogue vocabulary: grammar rule `epilogue_op`.  v is the running fp32
+ * value of output element (m, n); m = output row (GEMM row / flattened n,p,q
+ * of a conv), n = output column (GEMM column / conv output channel). */
+typedef enum ucl_epi_op {
+    UCL_EPI_SCALE = 1,        /* scale(alpha)          v * p0                              */
+    UCL_EPI_BIAS = 2,         /* bias()                v + vec[n]                          */
+    UCL_EPI_AUX_LOAD = 3,     /* aux_load(id)          v + p0 * T[m*ld + n]  (residual; p0 = beta) */
+    UCL_EPI_RELU = 4,
+    UCL_EPI_GELU_TANH = 5,    /* gelu(), tanh form                                          */
+    UCL_EPI_GELU_ERF = 6,     /* gelu(), erf form                                           */
+    UCL_EPI_SILU = 7,
+    UCL_EPI_SIGMOID = 8,
+    UCL_EPI_TANH = 9,
+    UCL_EPI_MISH = 10,
+    UCL_EPI_HARDSWISH = 11,
+    UCL_EPI_LEAKY_RELU = 12,  /* leaky_relu(alpha)     v > 0 ? v : p0 * v                  */
+    UCL_EPI_ELU = 13,         /* elu(alpha)            v > 0 ? v : p0 * (exp(v) - 1)       */
+    UCL_EPI_CLAMP = 14,       /* clip / clamp(min,max) min(max(v, p0), p1)                 */
+    UCL_EPI_PER_ROW_SCALE = 15, /* per_row_scale()     v * vec[m]                          */
+    UCL_EPI_PER_COL_SCALE = 16, /* per_col_scale(), per_channel_scale()   v * vec[n]       */
+    UCL_EPI_ROW_BROADCAST = 17, /* row_broadcast(id)   v + vec[n]                          */
+    UCL_EPI_COL_BROADCAST = 18, /* column_broadcast(id) v + vec[m]                         */
+    UCL_EPI_AUX_STORE = 19    /* aux_store(id)         T[m*ld + n] = round(v); v unchanged */
+} ucl_epi_op;
+
+#define UCL_MAX_EPI_STEPS 8
+#define UCL_MAX_GROUPS 256
+
+/* One step of the chain.  ptr (device) is the step's tensor operand, of type
+ * `dtype` (ucl_dtype): a vector of length N (ops indexed by n) or M (ops
+ * indexed by m), or a matrix addressed as ptr[b*bs + m*ld + n] for AUX_LOAD /
+ * AUX_STORE (b = batch index, bs = 0 shares it across batches).  In
+ * ucl_grouped_gemm, ptr is instead a device array of `groups` pointers, one
+ * operand per group, each indexed with the group's own m.  Steps without a
+ * tensor ignore ptr. */
+typedef struct ucl_epi_step {
+    int32_t op;        /* ucl_epi_op */
+    int32_t dtype;     /* ucl_dtype of ptr */
+    float p0, p1;
+    const void *ptr;
+    int64_t ld;
+    int64_t bs;
+} ucl_epi_step;
+
+typedef struct ucl_epilogue {
+    int32_t n_steps;   /* 0..UCL_MAX_EPI_STEPS; NULL epilogue == 0 steps */
+    int32_t reserved;
+    ucl_epi_step steps[UCL_MAX_EPI_STEPS];
+} ucl_epilogue;
+
+/* Explicit kernel choice (`.with_tile`, `.with_stages`, `.with_swizzle`).
+ * tile_k is 64 in every built kernel.  raster = width, in tile rows, of the
+ * bands the tile order walks column by column (1, 2, 4, 8, 16; the swizzle
+ * knob's Identity1..8), 0 = table default.  The order is also XCD-aware:
+ * workgroup ids that land on the same XCD (id mod 8) get neighbouring tiles. */
+typedef struct ucl_tuning {
+    int32_t tile_m, tile_n, tile_k, stages, raster;
+    int32_t reserved[3];
+} ucl_tuning;
+
+/* D[m,n] = E( sum_k A[m*a_rs + k*a_cs] * B[k*b_rs + n*b_cs] ), written to
+ * D[m*d_rs + n*d_cs] (grammar `gemm_op`; layouts RowMajor / ColumnMajor are
+ * the two stride patterns).  d_cs must be 1 (row-major D); for a column-major
+ * D call with the operands' roles swapped, (A.B)^T = B^T.A^T. */
+ucl_status ucl_gemm(int64_t M, int64_t N, int64_t K,
+                    const void *A, int32_t dtA, int64_t a_rs, int64_t a_cs,
+                    const void *B, int32_t dtB, int64_t b_rs, int64_t b_cs,
+                    void *D, int32_t dtD, int64_t d_rs, int64_t d_cs,
+                    const ucl_epilogue *epi, const ucl_tuning *tune, void *stream);
+
+/* Strided batched GEMM (grammar `batched_gemm_op`): the above for b in
+ * [0, batch) with operands advanced by b * {a,b,d}_bs elements.  A batch
+ * stride of 0 shares that operand. */
+ucl_status ucl_batched_gemm(int64_t batch, int64_t M, int64_t N, int64_t K,
+                            const void *A, int32_t dtA, int64_t a_rs, int64_t a_cs, int64_t a_bs,
+                            const void *B, int32_t dtB, int64_t b_rs, int64_t b_cs, int64_t b_bs,
+                            void *D, int32_t dtD, int64_t d_rs, int64_t d_cs, int64_t d_bs,
+                            const ucl_epilogue *epi, const ucl_tuning *tune, void *stream);
+
+/* Grouped GEMM (grammar `grouped_gemm_op`, expert_count = groups): `groups`
+ * independent problems (M_g[g], N, K) in one launch.  M_g is a HOST array
+ * (so the grid can be sized without a device round trip); M_g[g] == 0 is legal
+ * and skips the group.  A_g, B_g, D_g are DEVICE arrays of `groups` device
+ * pointers (the per-group pointer table); strides are shared by all groups.
+ * groups <= UCL_MAX_GROUPS, M_g[g] < 2^31. */
+ucl_status ucl_grouped_gemm(int32_t groups, const int64_t *M_g, int64_t N, int64_t K,
+                            const void *const *A_g, int32_t dtA, int64_t a_rs, int64_t a_cs,
+                            const void *const *B_g, int32_t dtB, int64_t b_rs, int64_t b_cs,
+                            void *const *D_g, int32_t dtD, int64_t d_rs, int64_t d_cs,
+                            const ucl_epilogue *epi, const ucl_tuning *tune, void *stream);
+
+/* Forward convolution as an implicit GEMM (grammar `conv2d_fprop`, layouts
+ * TensorNHWC): x [N,H,W,C], w [Kout,R,S,C], y [N,P,Q,Kout], all packed,
+ *   y[n,p,q,k] = E( sum_{r,s,c} x[n, p*stride_h - pad_h + r*dil_h,
+ *                                    q*stride_w - pad_w + s*dil_w, c] * w[k,r,s,c] )
+ * with out-of-image taps contributing zero (cross-correlation, no filter flip),
+ * P = (H + 2 pad_h - dil_h (R-1) - 1) / stride_h + 1, Q likewise.  The chain
+ * sees m = (n*P + p)*Q + q and n = k, so bias() is per output channel and an
+ * AUX_LOAD tensor is shaped like y (ld = Kout).  C must be a multiple of 8. */
+ucl_status ucl_conv2d_fprop(int64_t N, int64_t H, int64_t W, int64_t C, int64_t Kout,
+                            int64_t R, int64_t S, int64_t pad_h, int64_t pad_w,
+                            int64_t stride_h, int64_t stride_w, int64_t dil_h, int64_t dil_w,
+                            const void *x, int32_t dtX, const void *w, int32_t dtW,
+                            void *y, int32_t dtY,
+                            const ucl_epilogue *epi, const ucl_tuning *tune, void *stream);
+
+/* ---- Speed-of-Light analysis (paper Sec. 4.1, four steps) ------------------ */
+
+typedef enum ucl_op_kind { UCL_OP_GEMM = 0, UCL_OP_BATCHED_GEMM = 1, UCL_OP_GROUPED_GEMM = 2,
+                           UCL_OP_CONV2D_FPROP = 3 } ucl_op_kind;
+
+/* Problem characterisation input.  GEMM family: batch (1 for gemm), M, N, K;
+ * grouped: groups and M_g (HOST), N, K.  Conv: N,H,W,C,Kout,R,S and pads,
+ * strides, dilations.  dt_in / dt_out are ucl_dtype.  The epilogue matters
+ * only through the bytes of its tensor operands (each read or written once). */
+typedef struct ucl_problem {
+    int32_t op;                 /* ucl_op_kind */
+    int32_t dt_in, dt_out;
+    int32_t groups;
+    int64_t batch, M, N, K;
+    const int64_t *M_g;         /* HOST, grouped only */
+    int64_t cN, cH, cW, cC, cKout, cR, cS;
+    int64_t pad_h, pad_w, stride_h, stride_w, dil_h, dil_w;
+    const ucl_epilogue *epi;    /* may be NULL; pointers inside are not dereferenced */
+} ucl_problem;
+
+/* Hardware limits: published peaks at maximum clocks, scaled linearly by the
+ * ratio current / maximum clock, as the paper's report does.  NULL selects
+ * MI355X: 2516.6 TFLOP/s dense bf16 / fp16 MFMA (256 CUs x 2.4 GHz x 4096
+ * FLOP/clk), 8.0 TB/s HBM3E, ratios 1. */
+typedef struct ucl_hw {
+    double peak_flops_16bit;    /* FLOP/s, dense, bf16 / fp16 inputs */
+    double peak_flops_f32;      /* FLOP/s, fp32 inputs (unused by the built kernels) */
+    double peak_bw;             /* B/s */
+    double compute_clock_ratio; /* (0,1] */
+    double memory_clock_ratio;  /* (0,1] */
+} ucl_hw;
+
+typedef struct ucl_sol_report {
+    double flops;               /* 2 per multiply-accumulate; epilogue not counted        */
+    double bytes;               /* every unique input element read once, every output written once */
+    double peak_flops, peak_bw; /* clock-scaled                                           */
+    double ai, ridge;           /* FLOP/byte                                              */
+    double t_compute, t_mem, t_sol; /* seconds; t_sol = max(t_compute, t_mem)             */
+    int32_t compute_bound;      /* 1 if ai >= ridge, else memory-bound                    */
+    int32_t reserved;
+} ucl_sol_report;
+
+/* HOST only; touches no device.  Returns UCL_ERR_INVALID_ARG on a malformed problem. */
+ucl_status ucl_sol_bound(const ucl_problem *p, const ucl_hw *hw, ucl_sol_report *out);
+
+/* ---- Introspection (HOST only; used by tests and the benchmark) ------------ */
+
+/* The tuning the selection table would pick for a problem (same rules the
+ * launch path applies when tune == NULL). */
+ucl_status ucl_select_tuning(const ucl_problem *p, ucl_tuning *out);
+
+/* The tile schedule, evaluated on the host with the same code the kernels run:
+ * for workgroup id `wg` of a launch covering `groups` sub-problems with
+ * tiles_m[g] x tiles_n tiles each (batched: every entry equal), return the
+ * sub-problem index and tile coordinates it processes.  total = sum of
+ * tiles_m[g] * tiles_n must be > wg >= 0. */
+ucl_status ucl_tile_map(int32_t groups, const int32_t *tiles_m, int32_t tiles_n, int32_t raster,
+                        int32_t wg, int32_t *group, int32_t *tile_m, int32_t *tile_n);
+
+/* Number of kernel variants built in, and the (tile_m, tile_n, tile_k, stages)
+ * of variant i; explicit ucl_tuning must name one of these. */
+int32_t ucl_num_variants(void);
+ucl_status ucl_variant(int32_t i, ucl_tuning *out);
+
+const char *ucl_status_string(ucl_status s);
+const char *ucl_last_error(void);   /* thread-local; valid until the next call on this thread */
+const char *ucl_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* UCL_H_ */

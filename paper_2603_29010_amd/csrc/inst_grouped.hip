@@ -1,0 +1,13 @@
+// grouped_gemm (per-group pointer tables, ragged M), operands contiguous along K.
+#include "ucl_launch.h"
+namespace ucl {
+static const VariantDesc kTable[] = {
+    describe<KernelCfg<256, 256, 2, false, 1, kKContig, kKContig>>(),
+    describe<KernelCfg<128, 128, 3, false, 1, kKContig, kKContig>>(),
+    describe<KernelCfg<64, 64, 2, false, 1, kKContig, kKContig>>(),
+    describe<KernelCfg<256, 256, 2, true, 1, kKContig, kKContig>>(),
+    describe<KernelCfg<128, 128, 3, true, 1, kKContig, kKContig>>(),
+    describe<KernelCfg<64, 64, 2, true, 1, kKContig, kKContig>>(),
+};
+VariantList variants_grouped() { return {kTable, (int)(sizeof(kTable) / sizeof(kTable[0]))}; }
+}  // namespace ucl

@@ -1,0 +1,527 @@
+// Host side of the C ABI declared in include/ucl.h: argument validation with explanatory
+// errors, the per-problem tile / stage selection table, the launch, and the SOL analysis.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <vector>
+
+#include "ucl_variants.h"
+
+namespace ucl {
+namespace {
+
+thread_local char g_err[512] = "";
+
+ucl_status fail(ucl_status st, const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+const std::vector<VariantDesc> &all_variants() {
+    static const std::vector<VariantDesc> v = [] {
+        std::vector<VariantDesc> out;
+        for (VariantList l : {variants_gemm_kk_bf16(), variants_gemm_kk_f16(), variants_gemm_mn_bf16(),
+                              variants_gemm_mn_f16(), variants_grouped(), variants_conv()})
+            for (int i = 0; i < l.n; ++i) out.push_back(l.v[i]);
+        return out;
+    }();
+    return v;
+}
+
+int elem_size(int dt) { return dt == UCL_F32 ? 4 : 2; }
+bool is16(int dt) { return dt == UCL_F16 || dt == UCL_BF16; }
+bool valid_dtype(int dt) { return dt == UCL_F32 || dt == UCL_F16 || dt == UCL_BF16; }
+const char *dtype_name(int dt) { return dt == UCL_F32 ? "fp32" : dt == UCL_F16 ? "fp16" : dt == UCL_BF16 ? "bf16" : "?"; }
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+bool op_has_tensor(int op) {
+    switch (op) {
+    case UCL_EPI_BIAS: case UCL_EPI_AUX_LOAD: case UCL_EPI_PER_ROW_SCALE: case UCL_EPI_PER_COL_SCALE:
+    case UCL_EPI_ROW_BROADCAST: case UCL_EPI_COL_BROADCAST: case UCL_EPI_AUX_STORE:
+        return true;
+    default:
+        return false;
+    }
+}
+bool op_is_matrix(int op) { return op == UCL_EPI_AUX_LOAD || op == UCL_EPI_AUX_STORE; }
+
+// ---- generic description of one launch, filled by the four entry points -------------------------
+struct Launch {
+    int mode = 0;                 // 0 gemm / batched, 1 grouped, 2 conv
+    int64_t batch = 1, M = 0, N = 0, K = 0;
+    int la = 0, lb = 0;           // operand layouts
+    int f16 = 0;
+    int dtD = 0;
+    int groups = 0;
+    const int64_t *M_g = nullptr;
+    int64_t max_Mg = 0, sum_Mg = 0;
+};
+
+// Per-problem selection table.  Rules, in order:
+//   1. only variants built for this (mode, input type, operand layouts) are candidates;
+//   2. take the largest tile that still yields at least ~3/4 of a full wave of workgroups over the
+//      256 CUs (fewer, larger tiles = more reuse per byte staged; too few = idle CUs);
+//      if none does, take the tile giving the most workgroups;
+//   3. among equal tiles take the deepest pipeline the K extent can use (stages - 1 <= K tiles).
+int64_t count_tiles(const Launch &L, int tm, int tn) {
+    const int64_t tiles_n = (L.N + tn - 1) / tn;
+    if (L.mode == 1) {
+        int64_t t = 0;
+        for (int g = 0; g < L.groups; ++g) t += (L.M_g[g] + tm - 1) / tm * tiles_n;
+        return t;
+    }
+    return L.batch * ((L.M + tm - 1) / tm) * tiles_n;
+}
+
+const VariantDesc *select_variant(const Launch &L, const ucl_tuning *tune) {
+    const auto &vs = all_variants();
+    const bool explicit_tune = tune && (tune->tile_m || tune->tile_n || tune->tile_k || tune->stages);
+    const int64_t ktiles = (L.K + kTileK - 1) / kTileK;
+    const VariantDesc *best = nullptr;
+    int64_t best_key = -1;
+    for (const auto &v : vs) {
+        if (v.mode != L.mode || v.f16 != L.f16 || v.la != L.la || v.lb != L.lb) continue;
+        if (explicit_tune) {
+            if (v.tile_m == tune->tile_m && v.tile_n == tune->tile_n && v.stages == tune->stages &&
+                (tune->tile_k == 0 || tune->tile_k == kTileK))
+                return &v;
+            continue;
+        }
+        const int64_t tiles = count_tiles(L, v.tile_m, v.tile_n);
+        const int64_t area = (int64_t)v.tile_m * v.tile_n;
+        const bool fills = tiles >= 192;
+        // wasted rows/columns in edge tiles count against a big tile
+        int64_t key;
+        if (fills) key = (1ll << 40) + area * 16;
+        else key = tiles * 16;
+        const int usable_stages = v.stages - 1 <= ktiles ? v.stages : 0;
+        key += usable_stages;
+        if (key > best_key) { best_key = key; best = &v; }
+    }
+    return best;
+}
+
+int default_raster(const VariantDesc &v, const Launch &L) {
+    (void)L;
+    // bands of ~1024 rows: an XCD's run of 32 consecutive tiles then covers a near-square block
+    int gm = 1024 / v.tile_m;
+    return gm < 1 ? 1 : gm;
+}
+
+ucl_status check_epilogue(const ucl_epilogue *epi, const Launch &L, KParams &kp) {
+    kp.n_steps = 0;
+    if (!epi) return UCL_OK;
+    if (epi->n_steps < 0 || epi->n_steps > UCL_MAX_EPI_STEPS)
+        return fail(UCL_ERR_INVALID_ARG, "epilogue has %d steps; the chain holds 0..%d", epi->n_steps, UCL_MAX_EPI_STEPS);
+    for (int i = 0; i < epi->n_steps; ++i) {
+        const ucl_epi_step &s = epi->steps[i];
+        if (s.op < UCL_EPI_SCALE || s.op > UCL_EPI_AUX_STORE)
+            return fail(UCL_ERR_INVALID_ARG, "epilogue step %d: unknown op code %d", i, s.op);
+        EpiStepDev &d = kp.steps[i];
+        d.op = s.op; d.dtype = s.dtype; d.p0 = s.p0; d.p1 = s.p1; d.ptr = s.ptr; d.ld = s.ld; d.bs = s.bs;
+        if (op_has_tensor(s.op)) {
+            if (!s.ptr) return fail(UCL_ERR_INVALID_ARG, "epilogue step %d needs a tensor operand but ptr is NULL", i);
+            if (!valid_dtype(s.dtype)) return fail(UCL_ERR_INVALID_ARG, "epilogue step %d: bad tensor dtype %d", i, s.dtype);
+            const int per16 = 4;   // 4-element vector accesses
+            bool vec = true;
+            if (L.mode == 1) {
+                // per-group pointers live on the device: alignment cannot be checked here; vector
+                // access is used only if the strides allow it and the caller's pointers are assumed
+                // 16-byte aligned (documented in ucl.h for every tensor operand).
+                vec = true;
+            } else {
+                vec = (reinterpret_cast<uintptr_t>(s.ptr) % (per16 * elem_size(s.dtype))) == 0;
+            }
+            if (op_is_matrix(s.op)) {
+                if (s.ld < L.N) return fail(UCL_ERR_INVALID_ARG, "epilogue step %d: ld=%lld is smaller than N=%lld", i, (long long)s.ld, (long long)L.N);
+                vec = vec && (s.ld % per16 == 0) && (s.bs % per16 == 0);
+            }
+            if (vec) d.dtype |= 0x100;
+        }
+        if (s.op == UCL_EPI_CLAMP && !(s.p0 <= s.p1))
+            return fail(UCL_ERR_INVALID_ARG, "epilogue step %d: clamp(min=%g, max=%g) has min > max", i, s.p0, s.p1);
+    }
+    kp.n_steps = epi->n_steps;
+    return UCL_OK;
+}
+
+// Layout of a 16-bit operand from its two strides: *layout = 0 (contiguous along K) or 1
+// (contiguous along its M / N extent), *ld = stride of the other dimension.
+ucl_status classify(const char *name, const void *ptr, int64_t k_stride, int64_t mn_stride, int64_t mn_extent,
+                    int64_t K, int *layout, int64_t *ld) {
+    if (!aligned16(ptr))
+        return fail(UCL_ERR_UNSUPPORTED, "%s base pointer %p is not 16-byte aligned; 128-bit loads need (alignment * element_size) %% 16 == 0", name, ptr);
+    if (k_stride != 1 && mn_stride != 1)
+        return fail(UCL_ERR_UNSUPPORTED, "%s has strides (%lld, %lld): one of them must be 1 (RowMajor or ColumnMajor)", name,
+                    (long long)mn_stride, (long long)k_stride);
+    if (k_stride == 1 && mn_stride == 1 && mn_extent > 1 && K > 1)
+        return fail(UCL_ERR_INVALID_ARG, "%s has both strides 1 with both extents > 1: elements would overlap", name);
+    if (k_stride == 1 && (mn_stride != 1 || K % 8 == 0)) {
+        if (K % 8 != 0)
+            return fail(UCL_ERR_UNSUPPORTED, "%s is contiguous along K but K=%lld is not a multiple of 8 (alignment 8 x 2 bytes = 16)", name, (long long)K);
+        if (mn_extent > 1) {
+            if (mn_stride % 8 != 0)
+                return fail(UCL_ERR_UNSUPPORTED, "%s leading stride %lld is not a multiple of 8 elements", name, (long long)mn_stride);
+            if (mn_stride < K)
+                return fail(UCL_ERR_INVALID_ARG, "%s leading stride %lld is smaller than its contiguous extent K=%lld", name, (long long)mn_stride, (long long)K);
+        }
+        *layout = 0;
+        *ld = mn_extent > 1 ? mn_stride : K;
+        return UCL_OK;
+    }
+    if (mn_extent % 8 != 0)
+        return fail(UCL_ERR_UNSUPPORTED, "%s is contiguous along its M/N extent %lld, which is not a multiple of 8", name, (long long)mn_extent);
+    if (K > 1) {
+        if (k_stride % 8 != 0)
+            return fail(UCL_ERR_UNSUPPORTED, "%s leading stride %lld is not a multiple of 8 elements", name, (long long)k_stride);
+        if (k_stride < mn_extent)
+            return fail(UCL_ERR_INVALID_ARG, "%s leading stride %lld is smaller than its contiguous extent %lld", name, (long long)k_stride, (long long)mn_extent);
+    }
+    *layout = 1;
+    *ld = K > 1 ? k_stride : mn_extent;
+    return UCL_OK;
+}
+
+ucl_status check_common(int64_t M, int64_t N, int64_t K, int dtA, int dtB, int dtD, const void *A, const void *B,
+                        const void *D) {
+    if (M <= 0 || N <= 0 || K <= 0)
+        return fail(UCL_ERR_INVALID_ARG, "extents must be positive, got M=%lld N=%lld K=%lld", (long long)M, (long long)N, (long long)K);
+    if (M >= (1ll << 31) || N >= (1ll << 31) || K >= (1ll << 31))
+        return fail(UCL_ERR_UNSUPPORTED, "extents must be below 2^31");
+    if (!A || !B || !D) return fail(UCL_ERR_INVALID_ARG, "A, B and D must be non-NULL device pointers");
+    if (!is16(dtA) || dtA != dtB)
+        return fail(UCL_ERR_UNSUPPORTED, "inputs must both be bf16 or both fp16 (got %s, %s); accumulation is fp32", dtype_name(dtA), dtype_name(dtB));
+    if (!valid_dtype(dtD)) return fail(UCL_ERR_INVALID_ARG, "bad output dtype %d", dtD);
+    return UCL_OK;
+}
+
+ucl_status run(const Launch &L, KParams &kp, const GroupTable *gt_in, const ucl_tuning *tune, void *stream) {
+    const VariantDesc *v = select_variant(L, tune);
+    if (!v) {
+        if (tune && (tune->tile_m || tune->tile_n || tune->stages)) {
+            if (tune->tile_k != 0 && tune->tile_k != kTileK)
+                return fail(UCL_ERR_UNSUPPORTED, "tile_k=%d: every built kernel stages K in steps of %d", tune->tile_k, kTileK);
+            const int64_t lds = (int64_t)(tune->tile_m + tune->tile_n) * kTileK * 2 * tune->stages;
+            if (lds > kLdsBytesPerCU)
+                return fail(UCL_ERR_WORKSPACE, "tile %dx%dx%d with %d stages needs %lld bytes of LDS; a CU has %d",
+                            tune->tile_m, tune->tile_n, kTileK, tune->stages, (long long)lds, kLdsBytesPerCU);
+            return fail(UCL_ERR_UNSUPPORTED, "no kernel built for tile %dx%dx%d, %d stages with these types/layouts; see ucl_variant()",
+                        tune->tile_m, tune->tile_n, kTileK, tune->stages);
+        }
+        return fail(UCL_ERR_UNSUPPORTED, "no kernel built for this combination of operation, input type and layouts");
+    }
+    int raster = tune ? tune->raster : 0;
+    if (raster < 0 || raster > 64) return fail(UCL_ERR_INVALID_ARG, "raster=%d must be in 0..64", raster);
+    if (raster == 0) raster = default_raster(*v, L);
+    kp.raster = raster;
+    kp.tiles_n = (int32_t)((L.N + v->tile_n - 1) / v->tile_n);
+    GroupTable gt;
+    int64_t total;
+    if (L.mode == 1) {
+        int64_t acc = 0;
+        for (int g = 0; g < L.groups; ++g) {
+            gt.m[g] = (int32_t)L.M_g[g];
+            gt.tile_start[g] = (int32_t)acc;
+            acc += (L.M_g[g] + v->tile_m - 1) / v->tile_m * kp.tiles_n;
+        }
+        for (int g = L.groups; g <= UCL_MAX_GROUPS; ++g) gt.tile_start[g] = (int32_t)acc;
+        for (int g = L.groups; g < UCL_MAX_GROUPS; ++g) gt.m[g] = 0;
+        total = acc;
+        kp.tiles_m = 0;
+        kp.tiles_per_batch = 0;
+    } else {
+        kp.tiles_m = (int32_t)((L.M + v->tile_m - 1) / v->tile_m);
+        kp.tiles_per_batch = kp.tiles_m * kp.tiles_n;
+        total = (int64_t)kp.tiles_per_batch * L.batch;
+    }
+    if (total >= (1ll << 31)) return fail(UCL_ERR_UNSUPPORTED, "problem needs %lld tiles; the grid is limited to 2^31-1", (long long)total);
+    kp.total_tiles = (int32_t)total;
+    if (total == 0) return UCL_OK;     // grouped with every M_g == 0: nothing to do
+    (void)gt_in;
+    hipError_t e = v->launch(kp, L.mode == 1 ? &gt : nullptr, (int)total, (hipStream_t)stream);
+    if (e != hipSuccess) return fail(UCL_ERR_LAUNCH, "kernel launch failed: %s", hipGetErrorString(e));
+    return UCL_OK;
+}
+
+ucl_status gemm_like(int64_t batch, int64_t M, int64_t N, int64_t K,
+                     const void *A, int dtA, int64_t a_rs, int64_t a_cs, int64_t a_bs,
+                     const void *B, int dtB, int64_t b_rs, int64_t b_cs, int64_t b_bs,
+                     void *D, int dtD, int64_t d_rs, int64_t d_cs, int64_t d_bs,
+                     const ucl_epilogue *epi, const ucl_tuning *tune, void *stream) {
+    g_err[0] = 0;
+    if (batch <= 0) return fail(UCL_ERR_INVALID_ARG, "batch=%lld must be positive", (long long)batch);
+    if (ucl_status st = check_common(M, N, K, dtA, dtB, dtD, A, B, D)) return st;
+    if (d_cs != 1)
+        return fail(UCL_ERR_UNSUPPORTED, "D must be row-major (d_cs == 1, got %lld); for a column-major D swap the operands' roles: (A.B)^T = B^T.A^T", (long long)d_cs);
+    if (d_rs < N && M > 1) return fail(UCL_ERR_INVALID_ARG, "d_rs=%lld is smaller than N=%lld", (long long)d_rs, (long long)N);
+    if (batch > 1 && ((a_bs % 8) || (b_bs % 8)))
+        return fail(UCL_ERR_UNSUPPORTED, "batch strides of A and B must be multiples of 8 elements (16-byte alignment of every batch)");
+    Launch L;
+    L.mode = 0; L.batch = batch; L.M = M; L.N = N; L.K = K; L.f16 = dtA == UCL_F16; L.dtD = dtD;
+    KParams kp;
+    memset(&kp, 0, sizeof(kp));
+    if (ucl_status st = classify("A", A, a_cs, a_rs, M, K, &L.la, &kp.lda)) return st;
+    if (ucl_status st = classify("B", B, b_rs, b_cs, N, K, &L.lb, &kp.ldb)) return st;
+    if (ucl_status st = check_epilogue(epi, L, kp)) return st;
+    kp.A = A; kp.B = B; kp.D = D;
+    kp.ldd = d_rs; kp.a_bs = a_bs; kp.b_bs = b_bs; kp.d_bs = d_bs;
+    kp.M = (int32_t)M; kp.N = (int32_t)N; kp.K = (int32_t)K;
+    kp.dtD = dtD;
+    kp.d_vec = (reinterpret_cast<uintptr_t>(D) % (4 * elem_size(dtD)) == 0) && (d_rs % 4 == 0) && (d_bs % 4 == 0);
+    return run(L, kp, nullptr, tune, stream);
+}
+
+// ---- SOL ---------------------------------------------------------------------------------------
+
+int64_t conv_out(int64_t in, int64_t pad, int64_t dil, int64_t ker, int64_t stride) {
+    return (in + 2 * pad - dil * (ker - 1) - 1) / stride + 1;
+}
+
+ucl_status characterise(const ucl_problem *p, double *flops, double *bytes, int64_t *M_out, int64_t *N_out) {
+    if (!p) return fail(UCL_ERR_INVALID_ARG, "problem is NULL");
+    if (!valid_dtype(p->dt_in) || !valid_dtype(p->dt_out)) return fail(UCL_ERR_INVALID_ARG, "bad dtype in problem");
+    const double si = elem_size(p->dt_in), so = elem_size(p->dt_out);
+    double rows = 0, N = 0, batch = 1;
+    switch (p->op) {
+    case UCL_OP_GEMM:
+    case UCL_OP_BATCHED_GEMM: {
+        batch = p->op == UCL_OP_GEMM ? 1 : (double)p->batch;
+        if (p->M <= 0 || p->N <= 0 || p->K <= 0 || batch <= 0) return fail(UCL_ERR_INVALID_ARG, "extents must be positive");
+        rows = (double)p->M; N = (double)p->N;
+        *flops = 2.0 * batch * p->M * p->N * p->K;
+        *bytes = batch * ((double)p->M * p->K + (double)p->K * p->N) * si + batch * (double)p->M * p->N * so;
+        break;
+    }
+    case UCL_OP_GROUPED_GEMM: {
+        if (p->groups <= 0 || !p->M_g || p->N <= 0 || p->K <= 0) return fail(UCL_ERR_INVALID_ARG, "grouped problem needs groups > 0, M_g, N, K");
+        double sumM = 0;
+        for (int g = 0; g < p->groups; ++g) {
+            if (p->M_g[g] < 0) return fail(UCL_ERR_INVALID_ARG, "M_g[%d] is negative", g);
+            sumM += (double)p->M_g[g];
+        }
+        rows = sumM; N = (double)p->N;
+        *flops = 2.0 * sumM * p->N * p->K;
+        // every group's A, B and D once
+        *bytes = (sumM * p->K + (double)p->groups * p->K * p->N) * si + sumM * p->N * so;
+        break;
+    }
+    case UCL_OP_CONV2D_FPROP: {
+        if (p->cN <= 0 || p->cH <= 0 || p->cW <= 0 || p->cC <= 0 || p->cKout <= 0 || p->cR <= 0 || p->cS <= 0 ||
+            p->stride_h <= 0 || p->stride_w <= 0 || p->dil_h <= 0 || p->dil_w <= 0 || p->pad_h < 0 || p->pad_w < 0)
+            return fail(UCL_ERR_INVALID_ARG, "conv geometry must be positive (pads non-negative)");
+        const int64_t P = conv_out(p->cH, p->pad_h, p->dil_h, p->cR, p->stride_h);
+        const int64_t Q = conv_out(p->cW, p->pad_w, p->dil_w, p->cS, p->stride_w);
+        if (P <= 0 || Q <= 0) return fail(UCL_ERR_INVALID_ARG, "conv output is empty");
+        rows = (double)p->cN * P * Q; N = (double)p->cKout;
+        // padded taps are counted, as a dense implicit GEMM executes them
+        *flops = 2.0 * rows * N * (double)(p->cR * p->cS * p->cC);
+        *bytes = ((double)p->cN * p->cH * p->cW * p->cC + (double)p->cKout * p->cR * p->cS * p->cC) * si + rows * N * so;
+        break;
+    }
+    default:
+        return fail(UCL_ERR_INVALID_ARG, "unknown op kind %d", p->op);
+    }
+    if (p->epi) {
+        if (p->epi->n_steps < 0 || p->epi->n_steps > UCL_MAX_EPI_STEPS) return fail(UCL_ERR_INVALID_ARG, "bad epilogue length");
+        for (int i = 0; i < p->epi->n_steps; ++i) {
+            const ucl_epi_step &s = p->epi->steps[i];
+            if (!op_has_tensor(s.op)) continue;
+            const double se = elem_size(s.dtype);
+            const double groups = p->op == UCL_OP_GROUPED_GEMM ? p->groups : 1;
+            if (op_is_matrix(s.op)) *bytes += batch * rows * N * se;
+            else if (s.op == UCL_EPI_PER_ROW_SCALE || s.op == UCL_EPI_COL_BROADCAST) *bytes += rows * se;
+            else *bytes += groups * N * se;
+        }
+    }
+    if (M_out) *M_out = (int64_t)rows;
+    if (N_out) *N_out = (int64_t)N;
+    return UCL_OK;
+}
+
+}  // namespace
+}  // namespace ucl
+
+using namespace ucl;
+
+extern "C" {
+
+ucl_status ucl_gemm(int64_t M, int64_t N, int64_t K, const void *A, int32_t dtA, int64_t a_rs, int64_t a_cs,
+                    const void *B, int32_t dtB, int64_t b_rs, int64_t b_cs, void *D, int32_t dtD, int64_t d_rs,
+                    int64_t d_cs, const ucl_epilogue *epi, const ucl_tuning *tune, void *stream) {
+    return gemm_like(1, M, N, K, A, dtA, a_rs, a_cs, 0, B, dtB, b_rs, b_cs, 0, D, dtD, d_rs, d_cs, 0, epi, tune, stream);
+}
+
+ucl_status ucl_batched_gemm(int64_t batch, int64_t M, int64_t N, int64_t K, const void *A, int32_t dtA, int64_t a_rs,
+                            int64_t a_cs, int64_t a_bs, const void *B, int32_t dtB, int64_t b_rs, int64_t b_cs,
+                            int64_t b_bs, void *D, int32_t dtD, int64_t d_rs, int64_t d_cs, int64_t d_bs,
+                            const ucl_epilogue *epi, const ucl_tuning *tune, void *stream) {
+    return gemm_like(batch, M, N, K, A, dtA, a_rs, a_cs, a_bs, B, dtB, b_rs, b_cs, b_bs, D, dtD, d_rs, d_cs, d_bs, epi,
+                     tune, stream);
+}
+
+ucl_status ucl_grouped_gemm(int32_t groups, const int64_t *M_g, int64_t N, int64_t K, const void *const *A_g,
+                            int32_t dtA, int64_t a_rs, int64_t a_cs, const void *const *B_g, int32_t dtB, int64_t b_rs,
+                            int64_t b_cs, void *const *D_g, int32_t dtD, int64_t d_rs, int64_t d_cs,
+                            const ucl_epilogue *epi, const ucl_tuning *tune, void *stream) {
+    g_err[0] = 0;
+    if (groups <= 0 || groups > UCL_MAX_GROUPS)
+        return fail(UCL_ERR_INVALID_ARG, "groups=%d must be in 1..%d", groups, UCL_MAX_GROUPS);
+    if (!M_g) return fail(UCL_ERR_INVALID_ARG, "M_g (host array of group sizes) is NULL");
+    Launch L;
+    L.mode = 1; L.groups = groups; L.M_g = M_g; L.N = N; L.K = K; L.f16 = dtA == UCL_F16; L.dtD = dtD;
+    for (int g = 0; g < groups; ++g) {
+        if (M_g[g] < 0 || M_g[g] >= (1ll << 31)) return fail(UCL_ERR_INVALID_ARG, "M_g[%d]=%lld must be in [0, 2^31)", g, (long long)M_g[g]);
+        L.sum_Mg += M_g[g];
+        if (M_g[g] > L.max_Mg) L.max_Mg = M_g[g];
+    }
+    if (ucl_status st = check_common(1, N, K, dtA, dtB, dtD, A_g, B_g, D_g)) return st;
+    if (a_cs != 1 || b_rs != 1)
+        return fail(UCL_ERR_UNSUPPORTED, "grouped_gemm is built for A row-major (a_cs == 1) and B column-major (b_rs == 1), i.e. both contiguous along K");
+    if (K % 8 || a_rs % 8 || b_cs % 8 || a_rs < K || b_cs < K)
+        return fail(UCL_ERR_UNSUPPORTED, "K=%lld and the leading strides (%lld, %lld) must be multiples of 8 and at least K", (long long)K, (long long)a_rs, (long long)b_cs);
+    if (d_cs != 1 || d_rs < N) return fail(UCL_ERR_UNSUPPORTED, "D must be row-major with d_rs >= N");
+    KParams kp;
+    memset(&kp, 0, sizeof(kp));
+    if (ucl_status st = check_epilogue(epi, L, kp)) return st;
+    kp.A_g = A_g; kp.B_g = B_g; kp.D_g = D_g;
+    kp.lda = a_rs; kp.ldb = b_cs; kp.ldd = d_rs;
+    kp.N = (int32_t)N; kp.K = (int32_t)K; kp.groups = groups; kp.dtD = dtD;
+    kp.d_vec = d_rs % 4 == 0;      // group base pointers are required to be 16-byte aligned
+    return run(L, kp, nullptr, tune, stream);
+}
+
+ucl_status ucl_conv2d_fprop(int64_t N, int64_t H, int64_t W, int64_t C, int64_t Kout, int64_t R, int64_t S,
+                            int64_t pad_h, int64_t pad_w, int64_t stride_h, int64_t stride_w, int64_t dil_h,
+                            int64_t dil_w, const void *x, int32_t dtX, const void *w, int32_t dtW, void *y, int32_t dtY,
+                            const ucl_epilogue *epi, const ucl_tuning *tune, void *stream) {
+    g_err[0] = 0;
+    if (N <= 0 || H <= 0 || W <= 0 || C <= 0 || Kout <= 0 || R <= 0 || S <= 0)
+        return fail(UCL_ERR_INVALID_ARG, "conv extents must be positive");
+    if (pad_h < 0 || pad_w < 0 || stride_h <= 0 || stride_w <= 0 || dil_h <= 0 || dil_w <= 0)
+        return fail(UCL_ERR_INVALID_ARG, "pads must be >= 0, strides and dilations > 0");
+    const int64_t P = conv_out(H, pad_h, dil_h, R, stride_h), Q = conv_out(W, pad_w, dil_w, S, stride_w);
+    if (P <= 0 || Q <= 0) return fail(UCL_ERR_INVALID_ARG, "conv output is empty (P=%lld, Q=%lld)", (long long)P, (long long)Q);
+    const int64_t M = N * P * Q, Kg = R * S * C;
+    if (ucl_status st = check_common(M, Kout, Kg, dtX, dtW, dtY, x, w, y)) return st;
+    if (C % 8) return fail(UCL_ERR_UNSUPPORTED, "C=%lld must be a multiple of 8 so that a 128-bit load never straddles a filter tap", (long long)C);
+    if (!aligned16(x) || !aligned16(w)) return fail(UCL_ERR_UNSUPPORTED, "x and w must be 16-byte aligned");
+    if (N * H * W * C >= (1ll << 40)) return fail(UCL_ERR_UNSUPPORTED, "activation tensor too large");
+    if (H >= (1 << 24) || W >= (1 << 24) || pad_h >= (1 << 24) || pad_w >= (1 << 24))
+        return fail(UCL_ERR_UNSUPPORTED, "image extents / pads must be below 2^24");
+    Launch L;
+    L.mode = 2; L.M = M; L.N = Kout; L.K = Kg; L.la = 2; L.lb = 0; L.f16 = dtX == UCL_F16; L.dtD = dtY;
+    KParams kp;
+    memset(&kp, 0, sizeof(kp));
+    if (ucl_status st = check_epilogue(epi, L, kp)) return st;
+    kp.A = x; kp.B = w; kp.D = y;
+    kp.lda = 0; kp.ldb = Kg; kp.ldd = Kout;
+    kp.M = (int32_t)M; kp.N = (int32_t)Kout; kp.K = (int32_t)Kg; kp.dtD = dtY;
+    kp.cH = (int32_t)H; kp.cW = (int32_t)W; kp.cC = (int32_t)C; kp.cS = (int32_t)S; kp.cP = (int32_t)P; kp.cQ = (int32_t)Q;
+    kp.pad_h = (int32_t)pad_h; kp.pad_w = (int32_t)pad_w; kp.str_h = (int32_t)stride_h; kp.str_w = (int32_t)stride_w;
+    kp.dil_h = (int32_t)dil_h; kp.dil_w = (int32_t)dil_w;
+    kp.d_vec = (reinterpret_cast<uintptr_t>(y) % (4 * elem_size(dtY)) == 0) && (Kout % 4 == 0);
+    return run(L, kp, nullptr, tune, stream);
+}
+
+ucl_status ucl_sol_bound(const ucl_problem *p, const ucl_hw *hw, ucl_sol_report *out) {
+    g_err[0] = 0;
+    if (!out) return fail(UCL_ERR_INVALID_ARG, "report pointer is NULL");
+    double flops = 0, bytes = 0;
+    if (ucl_status st = characterise(p, &flops, &bytes, nullptr, nullptr)) return st;
+    // Hardware limits: published peaks, scaled linearly by the clock ratios.
+    ucl_hw mi355x = {2516.6e12, 157.3e12, 8.0e12, 1.0, 1.0};
+    const ucl_hw &h = hw ? *hw : mi355x;
+    if (!(h.peak_bw > 0) || !(h.compute_clock_ratio > 0) || !(h.memory_clock_ratio > 0))
+        return fail(UCL_ERR_INVALID_ARG, "hardware descriptor needs positive peaks and clock ratios");
+    const double peak = (p->dt_in == UCL_F32 ? h.peak_flops_f32 : h.peak_flops_16bit) * h.compute_clock_ratio;
+    if (!(peak > 0)) return fail(UCL_ERR_INVALID_ARG, "hardware descriptor has no compute peak for %s inputs", dtype_name(p->dt_in));
+    const double bw = h.peak_bw * h.memory_clock_ratio;
+    out->flops = flops;
+    out->bytes = bytes;
+    out->peak_flops = peak;
+    out->peak_bw = bw;
+    out->ai = flops / bytes;
+    out->ridge = peak / bw;
+    out->t_compute = flops / peak;
+    out->t_mem = bytes / bw;
+    out->t_sol = out->t_compute > out->t_mem ? out->t_compute : out->t_mem;
+    out->compute_bound = out->ai >= out->ridge ? 1 : 0;
+    out->reserved = 0;
+    return UCL_OK;
+}
+
+ucl_status ucl_select_tuning(const ucl_problem *p, ucl_tuning *out) {
+    g_err[0] = 0;
+    if (!out) return fail(UCL_ERR_INVALID_ARG, "output pointer is NULL");
+    double f, b;
+    int64_t M = 0, N = 0;
+    if (ucl_status st = characterise(p, &f, &b, &M, &N)) return st;
+    if (!is16(p->dt_in)) return fail(UCL_ERR_UNSUPPORTED, "kernels take bf16 or fp16 inputs");
+    Launch L;
+    L.mode = p->op == UCL_OP_GROUPED_GEMM ? 1 : p->op == UCL_OP_CONV2D_FPROP ? 2 : 0;
+    L.batch = p->op == UCL_OP_BATCHED_GEMM ? p->batch : 1;
+    L.M = M; L.N = N;
+    L.K = p->op == UCL_OP_CONV2D_FPROP ? p->cR * p->cS * p->cC : p->K;
+    L.groups = p->groups; L.M_g = p->M_g;
+    L.la = L.mode == 2 ? 2 : 0; L.lb = 0;
+    L.f16 = p->dt_in == UCL_F16;
+    const VariantDesc *v = select_variant(L, nullptr);
+    if (!v) return fail(UCL_ERR_UNSUPPORTED, "no kernel built for this problem");
+    memset(out, 0, sizeof(*out));
+    out->tile_m = v->tile_m; out->tile_n = v->tile_n; out->tile_k = kTileK; out->stages = v->stages;
+    out->raster = default_raster(*v, L);
+    return UCL_OK;
+}
+
+ucl_status ucl_tile_map(int32_t groups, const int32_t *tiles_m, int32_t tiles_n, int32_t raster, int32_t wg,
+                        int32_t *group, int32_t *tile_m, int32_t *tile_n) {
+    g_err[0] = 0;
+    if (groups <= 0 || !tiles_m || tiles_n <= 0 || raster <= 0 || !group || !tile_m || !tile_n)
+        return fail(UCL_ERR_INVALID_ARG, "bad arguments to ucl_tile_map");
+    std::vector<int32_t> start(groups + 1, 0);
+    for (int g = 0; g < groups; ++g) {
+        if (tiles_m[g] < 0) return fail(UCL_ERR_INVALID_ARG, "tiles_m[%d] is negative", g);
+        start[g + 1] = start[g] + tiles_m[g] * tiles_n;
+    }
+    const int total = start[groups];
+    if (wg < 0 || wg >= total) return fail(UCL_ERR_INVALID_ARG, "wg=%d outside [0, %d)", wg, total);
+    int t = xcd_remap(wg, total);
+    const int g = find_group(start.data(), groups, t);
+    t -= start[g];
+    int tm, tn;
+    band_raster(t, tiles_m[g], tiles_n, raster, tm, tn);
+    *group = g; *tile_m = tm; *tile_n = tn;
+    return UCL_OK;
+}
+
+int32_t ucl_num_variants(void) { return (int32_t)all_variants().size(); }
+
+ucl_status ucl_variant(int32_t i, ucl_tuning *out) {
+    const auto &vs = all_variants();
+    if (i < 0 || i >= (int)vs.size() || !out) return fail(UCL_ERR_INVALID_ARG, "variant index %d outside [0, %d)", i, (int)vs.size());
+    memset(out, 0, sizeof(*out));
+    out->tile_m = vs[i].tile_m; out->tile_n = vs[i].tile_n; out->tile_k = kTileK; out->stages = vs[i].stages;
+    // reserved[0..2]: which problems the variant serves (mode, 16-bit type, operand layouts)
+    out->reserved[0] = vs[i].mode; out->reserved[1] = vs[i].f16; out->reserved[2] = vs[i].la * 4 + vs[i].lb;
+    return UCL_OK;
+}
+
+const char *ucl_status_string(ucl_status s) {
+    switch (s) {
+    case UCL_OK: return "UCL_OK";
+    case UCL_ERR_INVALID_ARG: return "UCL_ERR_INVALID_ARG";
+    case UCL_ERR_UNSUPPORTED: return "UCL_ERR_UNSUPPORTED";
+    case UCL_ERR_WORKSPACE: return "UCL_ERR_WORKSPACE";
+    case UCL_ERR_LAUNCH: return "UCL_ERR_LAUNCH";
+    }
+    return "UCL_ERR_?";
+}
+
+const char *ucl_last_error(void) { return g_err; }
+const char *ucl_version(void) { return "ucl 0.1 (gfx950)"; }
+
+}  // extern "C"

@@ -1,0 +1,86 @@
+// Types shared by the host launch code and the gfx950 kernels of this library.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/ucl.h"
+
+namespace ucl {
+
+constexpr int kTileK = 64;            // K extent of one LDS stage, elements (= 128 bytes of bf16/fp16)
+constexpr int kThreads = 256;         // 4 wavefronts of 64 lanes, one per SIMD of a CU
+constexpr int kLdsBytesPerCU = 160 * 1024;
+
+struct EpiStepDev {
+    int32_t op;
+    int32_t dtype;
+    float p0, p1;
+    const void *ptr;
+    int64_t ld;
+    int64_t bs;
+};
+
+// Kernel arguments, passed by value (kernarg segment).
+struct KParams {
+    const void *A;
+    const void *B;
+    void *D;
+    const void *const *A_g;           // grouped: device tables of per-group pointers
+    const void *const *B_g;
+    void *const *D_g;
+    int64_t lda, ldb, ldd;            // element stride of the non-contiguous dimension
+    int64_t a_bs, b_bs, d_bs;         // batch strides (elements)
+    int32_t M, N, K;                  // grouped: M unused (per-group table)
+    int32_t tiles_m, tiles_n;         // per batch (non-grouped)
+    int32_t tiles_per_batch, total_tiles;
+    int32_t raster;                   // band width in tile rows
+    int32_t dtD;                      // ucl_dtype of D
+    int32_t d_vec;                    // 1: D (and aux tensors) may be accessed with 4-element vectors
+    int32_t groups;
+    // conv2d geometry (implicit-GEMM A operand): x [N,H,W,C]
+    int32_t cH, cW, cC, cS, cP, cQ;
+    int32_t pad_h, pad_w, str_h, str_w, dil_h, dil_w;
+    int32_t n_steps;
+    int32_t pad_;
+    EpiStepDev steps[UCL_MAX_EPI_STEPS];
+};
+
+struct GroupTable {
+    int32_t m[UCL_MAX_GROUPS];              // rows of each group
+    int32_t tile_start[UCL_MAX_GROUPS + 1]; // prefix sum of tiles per group
+};
+struct NoGroupTable {};
+
+// ---- tile schedule: the same code runs on the host (tests, introspection) and in the kernels ----
+
+// Workgroups are dealt to the 8 XCDs round-robin by id, and each XCD has its own L2.  Give XCD x
+// one contiguous run of the tile sequence so that the tiles resident on an XCD at the same time
+// are neighbours and share A / B panels through that L2.  Bijective on [0, total).
+__host__ __device__ inline int xcd_remap(int wg, int total) {
+    const int q = total >> 3, r = total & 7;
+    const int x = wg & 7, loc = wg >> 3;
+    return x * q + (x < r ? x : r) + loc;
+}
+
+// Walk a tiles_m x tiles_n grid in bands of `gm` tile rows, column by column inside a band.
+__host__ __device__ inline void band_raster(int t, int tiles_m, int tiles_n, int gm, int &tm, int &tn) {
+    const int per_band = gm * tiles_n;
+    const int band = t / per_band;
+    const int first = band * gm;
+    const int rows = (tiles_m - first) < gm ? (tiles_m - first) : gm;
+    const int r = t - band * per_band;
+    tm = first + r % rows;
+    tn = r / rows;
+}
+
+// Largest g with tile_start[g] <= t  (tile_start[0] = 0, tile_start[groups] = total > t).
+__host__ __device__ inline int find_group(const int32_t *tile_start, int groups, int t) {
+    int lo = 0, hi = groups;          // invariant: tile_start[lo] <= t < tile_start[hi]
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (tile_start[mid] <= t) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+}  // namespace ucl

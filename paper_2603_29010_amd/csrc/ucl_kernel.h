@@ -1,0 +1,587 @@
+// The one mainloop of the library: an MFMA tile kernel for gfx950 (CDNA4, wave64), shared by
+// gemm / batched_gemm / grouped_gemm / conv2d_fprop.  Included only by the instantiation units.
+//
+// Structure of a workgroup (256 threads = 4 waves, one per SIMD):
+//   tile schedule  : workgroup id -> (batch or group, tile row, tile column), XCD-aware
+//   staging        : global -> LDS, `STAGES` buffers deep.  Operands that are contiguous along K
+//                    (and the implicit-GEMM view of NHWC activations) go straight from HBM/L2 into
+//                    LDS with 128-bit `global_load_lds` (no VGPR round trip); operands contiguous
+//                    along M / N are loaded 128-bit into VGPRs and transposed on the way into LDS.
+//   LDS layout     : [rows][64 elements] = 128-byte rows of eight 16-byte chunks, chunk index XORed
+//                    with a function of the row so that the 16-byte-per-lane MFMA fragment reads of
+//                    32 consecutive rows spread over all banks.
+//   mainloop       : v_mfma_f32_32x32x16_{bf16,f16}, fp32 accumulators held in registers,
+//                    wave tile (TM/2) x (TN/2).
+//   epilogue       : the `>>` chain interpreted on the accumulator registers (fp32), one rounding
+//                    to the output type, vector stores straight from registers.
+#pragma once
+#include <type_traits>
+#include <utility>
+
+#include "ucl_device.h"
+
+namespace ucl {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_t;
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
+
+#define UCL_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
+#define UCL_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
+
+enum OperandLayout { kKContig = 0, kMNContig = 1, kIm2col = 2 };
+
+// Compile-time loop: register arrays (accumulators, fragments) must only ever be indexed by
+// constants, or the compiler moves them to scratch memory.
+template <class F, int... I>
+__device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, I...>) {
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F &&f) {
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
+// s_waitcnt immediate (gfx9 encoding) that waits only on the vector-memory counter.
+__device__ constexpr int vmcnt_imm(int n) { return (n & 0xF) | ((n >> 4) << 14) | (0x7 << 4) | (0xF << 8); }
+
+// XOR pattern of the LDS layout; depends on row mod 16 only, so any multiple-of-32 row offset
+// (wave tile, MFMA block) leaves it unchanged.
+__device__ __forceinline__ int lds_swz(int row) { return (row & 7) ^ ((row >> 3) & 1); }
+
+__device__ __forceinline__ float bits_to_f32(uint32_t raw16, int dtype) {
+    if (dtype == UCL_BF16) return __uint_as_float(raw16 << 16);
+    union { uint16_t u; _Float16 h; } c;
+    c.u = (uint16_t)raw16;
+    return (float)c.h;
+}
+
+// Four consecutive elements starting at element index idx; lanes with nvalid < 4 read only what exists.
+__device__ __forceinline__ f32x4_t load4(const void *base, int dtype, int64_t idx, bool vec, int nvalid) {
+    f32x4_t r = {0.f, 0.f, 0.f, 0.f};
+    if (nvalid <= 0) return r;
+    if (dtype == UCL_F32) {
+        const float *p = (const float *)base + idx;
+        if (vec && nvalid >= 4) {
+            r = *(const f32x4_t *)p;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (e < nvalid) r[e] = p[e];
+        }
+    } else {
+        const uint16_t *p = (const uint16_t *)base + idx;
+        if (vec && nvalid >= 4) {
+            const u32x2_t w = *(const u32x2_t *)p;
+            r[0] = bits_to_f32(w[0] & 0xffffu, dtype);
+            r[1] = bits_to_f32(w[0] >> 16, dtype);
+            r[2] = bits_to_f32(w[1] & 0xffffu, dtype);
+            r[3] = bits_to_f32(w[1] >> 16, dtype);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (e < nvalid) r[e] = bits_to_f32(p[e], dtype);
+        }
+    }
+    return r;
+}
+
+__device__ __forceinline__ uint32_t f32_to_bits16(float v, int dtype) {
+    if (dtype == UCL_BF16) {
+        union { __bf16 b; uint16_t u; } c;
+        c.b = (__bf16)v;                  // round to nearest even
+        return c.u;
+    }
+    union { _Float16 h; uint16_t u; } c;
+    c.h = (_Float16)v;                    // round to nearest even
+    return c.u;
+}
+
+__device__ __forceinline__ void store4(void *base, int dtype, int64_t idx, f32x4_t v, bool vec, int nvalid) {
+    if (nvalid <= 0) return;
+    if (dtype == UCL_F32) {
+        float *p = (float *)base + idx;
+        if (vec && nvalid >= 4) {
+            *(f32x4_t *)p = v;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (e < nvalid) p[e] = v[e];
+        }
+    } else {
+        uint16_t *p = (uint16_t *)base + idx;
+        const uint32_t b0 = f32_to_bits16(v[0], dtype), b1 = f32_to_bits16(v[1], dtype);
+        const uint32_t b2 = f32_to_bits16(v[2], dtype), b3 = f32_to_bits16(v[3], dtype);
+        if (vec && nvalid >= 4) {
+            u32x2_t w;
+            w[0] = b0 | (b1 << 16);
+            w[1] = b2 | (b3 << 16);
+            *(u32x2_t *)p = w;
+        } else {
+            const uint32_t b[4] = {b0, b1, b2, b3};
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (e < nvalid) p[e] = (uint16_t)b[e];
+        }
+    }
+}
+
+__device__ __forceinline__ float sigmoid_f32(float u) { return 1.0f / (1.0f + __expf(-u)); }
+
+// One step of the chain on the 16 accumulators a lane holds for one 32x32 block:
+// element j <-> output (m, n_base + 8*(j/4) + (j%4)), n_base already includes 4*(lane/32).
+struct EpiCtx {
+    int64_t m;          // row within the (sub)problem
+    int n_base;         // column of element 0
+    int m_ok;           // row < M
+    int N;
+    int batch;          // batch index (bs multiplier)
+    int group;          // grouped: index into per-group pointer tables, else -1
+};
+
+__device__ __forceinline__ const void *step_ptr(const EpiStepDev &s, const EpiCtx &c) {
+    if (c.group >= 0) return ((const void *const *)s.ptr)[c.group];
+    return s.ptr;
+}
+
+__device__ __forceinline__ void apply_step(float (&v)[16], const EpiStepDev &s, const EpiCtx &c) {
+    const int dt = s.dtype & 0xff;
+    const bool vec = (s.dtype & 0x100) != 0;
+    switch (s.op) {
+    case UCL_EPI_SCALE:
+#pragma unroll
+        for (int j = 0; j < 16; ++j) v[j] *= s.p0;
+        break;
+    case UCL_EPI_BIAS:
+    case UCL_EPI_ROW_BROADCAST:
+    case UCL_EPI_PER_COL_SCALE: {
+        const void *base = step_ptr(s, c);
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int n = c.n_base + 8 * g;
+            const f32x4_t t = load4(base, dt, n, vec, c.N - n);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (s.op == UCL_EPI_PER_COL_SCALE) v[4 * g + e] *= t[e];
+                else v[4 * g + e] += t[e];
+            }
+        }
+        break;
+    }
+    case UCL_EPI_PER_ROW_SCALE:
+    case UCL_EPI_COL_BROADCAST: {
+        float t = 0.f;
+        if (c.m_ok) {
+            const void *base = step_ptr(s, c);
+            t = dt == UCL_F32 ? ((const float *)base)[c.m] : bits_to_f32(((const uint16_t *)base)[c.m], dt);
+        }
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            if (s.op == UCL_EPI_PER_ROW_SCALE) v[j] *= t;
+            else v[j] += t;
+        }
+        break;
+    }
+    case UCL_EPI_AUX_LOAD: {
+        const void *base = step_ptr(s, c);
+        const int64_t row = (int64_t)c.batch * s.bs + c.m * s.ld;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int n = c.n_base + 8 * g;
+            const f32x4_t t = load4(base, dt, row + n, vec, c.m_ok ? c.N - n : 0);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[4 * g + e] += s.p0 * t[e];
+        }
+        break;
+    }
+    case UCL_EPI_AUX_STORE: {
+        void *base = (void *)step_ptr(s, c);
+        const int64_t row = (int64_t)c.batch * s.bs + c.m * s.ld;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int n = c.n_base + 8 * g;
+            const f32x4_t t = {v[4 * g], v[4 * g + 1], v[4 * g + 2], v[4 * g + 3]};
+            store4(base, dt, row + n, t, vec, c.m_ok ? c.N - n : 0);
+        }
+        break;
+    }
+    case UCL_EPI_RELU:
+#pragma unroll
+        for (int j = 0; j < 16; ++j) v[j] = fmaxf(v[j], 0.f);
+        break;
+    case UCL_EPI_LEAKY_RELU:
+#pragma unroll
+        for (int j = 0; j < 16; ++j) v[j] = v[j] > 0.f ? v[j] : s.p0 * v[j];
+        break;
+    case UCL_EPI_CLAMP:
+#pragma unroll
+        for (int j = 0; j < 16; ++j) v[j] = fminf(fmaxf(v[j], s.p0), s.p1);
+        break;
+    case UCL_EPI_HARDSWISH:
+#pragma unroll
+        for (int j = 0; j < 16; ++j) v[j] = v[j] * fminf(fmaxf(v[j] + 3.f, 0.f), 6.f) * (1.f / 6.f);
+        break;
+    case UCL_EPI_GELU_TANH:
+        // 0.5 (1 + tanh u) = sigmoid(2u),  u = sqrt(2/pi) (v + 0.044715 v^3)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const float x = v[j];
+            const float u = 1.5957691216057308f * (x + 0.044715f * x * x * x);
+            v[j] = x * sigmoid_f32(u);
+        }
+        break;
+    case UCL_EPI_SILU:
+#pragma unroll
+        for (int j = 0; j < 16; ++j) v[j] = v[j] * sigmoid_f32(v[j]);
+        break;
+    case UCL_EPI_SIGMOID:
+#pragma unroll
+        for (int j = 0; j < 16; ++j) v[j] = sigmoid_f32(v[j]);
+        break;
+    case UCL_EPI_TANH:
+#pragma unroll
+        for (int j = 0; j < 16; ++j) v[j] = tanhf(v[j]);
+        break;
+    case UCL_EPI_GELU_ERF:
+#pragma unroll
+        for (int j = 0; j < 16; ++j) v[j] = 0.5f * v[j] * (1.f + erff(v[j] * 0.7071067811865476f));
+        break;
+    case UCL_EPI_MISH:
+        // tanh(log(1 + e^x)) = w (w + 2) / (w (w + 2) + 2) with w = e^x; for large x the factor is 1
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const float x = v[j];
+            const float w = __expf(fminf(x, 20.f));
+            const float q = w * (w + 2.f);
+            v[j] = x > 20.f ? x : x * (q / (q + 2.f));
+        }
+        break;
+    case UCL_EPI_ELU:
+#pragma unroll
+        for (int j = 0; j < 16; ++j) v[j] = v[j] > 0.f ? v[j] : s.p0 * expm1f(v[j]);
+        break;
+    default:
+        break;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+
+template <int TM_, int TN_, int STAGES_, bool F16_, int MODE_ /*0 gemm+batched, 1 grouped, 2 conv*/,
+          int LA_ /*OperandLayout of A*/, int LB_ /*OperandLayout of B*/>
+struct KernelCfg {
+    static constexpr int TM = TM_, TN = TN_, TK = kTileK, STAGES = STAGES_, MODE = MODE_, LA = LA_, LB = LB_;
+    static constexpr bool F16 = F16_;
+    static constexpr int WAVES_M = 2, WAVES_N = 2;
+    static constexpr int WTM = TM / WAVES_M, WTN = TN / WAVES_N;  // wave tile
+    static constexpr int MI = WTM / 32, NI = WTN / 32;            // 32x32 MFMA blocks per wave
+    static constexpr int A_BYTES = TM * TK * 2, B_BYTES = TN * TK * 2;
+    static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+    static constexpr int LDS_BYTES = STAGES * STAGE_BYTES;
+    static constexpr int A_ITERS = TM * (TK / 8) / kThreads;      // 16-byte chunks per thread per stage
+    static constexpr int B_ITERS = TN * (TK / 8) / kThreads;
+    static_assert(TM % 64 == 0 && TN % 64 == 0, "wave tile is a multiple of 32x32");
+    static_assert(LDS_BYTES <= kLdsBytesPerCU, "stages x tile exceed LDS");
+    using Groups = typename std::conditional<MODE == 1, GroupTable, NoGroupTable>::type;
+};
+
+template <bool F16>
+__device__ __forceinline__ f32x16_t mfma32(const u32x4_t &a, const u32x4_t &b, const f32x16_t &c) {
+    if constexpr (F16) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b),
+                                                      c, 0, 0, 0);
+    } else {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a),
+                                                       __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+    }
+}
+
+template <class Cfg>
+__global__ __launch_bounds__(kThreads) void ucl_tile_kernel(const KParams p, const typename Cfg::Groups gt) {
+    constexpr int TM = Cfg::TM, TN = Cfg::TN, TK = Cfg::TK, STAGES = Cfg::STAGES;
+    constexpr int MI = Cfg::MI, NI = Cfg::NI, MODE = Cfg::MODE, LA = Cfg::LA, LB = Cfg::LB;
+    constexpr int A_ITERS = Cfg::A_ITERS, B_ITERS = Cfg::B_ITERS;
+    constexpr bool kAnyReg = (LA == kMNContig) || (LB == kMNContig);
+    constexpr int DMA_PER_TILE = (LA != kMNContig ? A_ITERS : 0) + (LB != kMNContig ? B_ITERS : 0);
+
+    __shared__ __attribute__((aligned(1024))) char smem[Cfg::LDS_BYTES];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / Cfg::WAVES_N, wn = wave % Cfg::WAVES_N;
+
+    // ---- tile schedule ---------------------------------------------------------------------
+    int t = xcd_remap(blockIdx.x, p.total_tiles);
+    int batch = 0, group = -1, tm, tn;
+    int Mloc = p.M;
+    const char *Ab = (const char *)p.A;
+    const char *Bb = (const char *)p.B;
+    char *Db = (char *)p.D;
+    if constexpr (MODE == 1) {
+        group = find_group(gt.tile_start, p.groups, t);
+        t -= gt.tile_start[group];
+        Mloc = gt.m[group];
+        band_raster(t, (Mloc + TM - 1) / TM, p.tiles_n, p.raster, tm, tn);
+        Ab = (const char *)p.A_g[group];
+        Bb = (const char *)p.B_g[group];
+        Db = (char *)p.D_g[group];
+    } else {
+        batch = t / p.tiles_per_batch;
+        t -= batch * p.tiles_per_batch;
+        band_raster(t, p.tiles_m, p.tiles_n, p.raster, tm, tn);
+        Ab += (int64_t)batch * p.a_bs * 2;
+        Bb += (int64_t)batch * p.b_bs * 2;
+    }
+    const int m0 = tm * TM, n0 = tn * TN;
+    const int K = p.K;
+    const int KT = (K + TK - 1) / TK;
+
+    // ---- loader set-up -----------------------------------------------------------------------
+    const int l_row = tid >> 3;                          // row of this thread's slot within a 32-row slab
+    const int l_chunk = (tid & 7) ^ lds_swz(l_row);      // source chunk held by that slot
+    const int l_kc = l_chunk * 8;
+
+    const char *a_ptr[LA == kMNContig ? 1 : A_ITERS];
+    int a_h0[LA == kIm2col ? A_ITERS : 1], a_w0[LA == kIm2col ? A_ITERS : 1];
+    int a_ci = 0, a_r = 0, a_s = 0;                      // im2col: decomposition of k = l_kc + kt*TK
+    const char *b_ptr[LB == kMNContig ? 1 : B_ITERS];
+    u32x4_t a_stage[LA == kMNContig ? A_ITERS : 1], b_stage[LB == kMNContig ? B_ITERS : 1];
+
+    if constexpr (LA == kKContig) {
+#pragma unroll
+        for (int i = 0; i < A_ITERS; ++i) {
+            int row = m0 + i * 32 + l_row;
+            row = row < Mloc ? row : Mloc - 1;
+            a_ptr[i] = Ab + ((int64_t)row * p.lda + l_kc) * 2;
+        }
+    } else if constexpr (LA == kIm2col) {
+#pragma unroll
+        for (int i = 0; i < A_ITERS; ++i) {
+            int row = m0 + i * 32 + l_row;
+            row = row < Mloc ? row : Mloc - 1;
+            const int q = row % p.cQ;
+            const int pq = row / p.cQ;
+            const int pp = pq % p.cP;
+            const int nb = pq / p.cP;
+            a_h0[i] = pp * p.str_h - p.pad_h;
+            a_w0[i] = q * p.str_w - p.pad_w;
+            a_ptr[i] = Ab + (int64_t)nb * p.cH * p.cW * p.cC * 2;
+        }
+        a_ci = l_kc % p.cC;
+        const int tap = l_kc / p.cC;
+        a_r = tap / p.cS;
+        a_s = tap % p.cS;
+    }
+    if constexpr (LB == kKContig) {
+#pragma unroll
+        for (int i = 0; i < B_ITERS; ++i) {
+            int row = n0 + i * 32 + l_row;
+            row = row < p.N ? row : p.N - 1;
+            b_ptr[i] = Bb + ((int64_t)row * p.ldb + l_kc) * 2;
+        }
+    }
+
+    // Issue the copies of k-tile `kt` into LDS stage buffer `buf` (DMA operands), or fetch them into
+    // registers (M/N-contiguous operands; written to LDS later by commit_regs).
+    auto issue_tile = [&](int kt, int buf) {
+        char *sA = smem + buf * Cfg::STAGE_BYTES;
+        char *sB = sA + Cfg::A_BYTES;
+        const int k0 = kt * TK;
+        if constexpr (LA == kKContig) {
+            const bool kok = k0 + l_kc < K;
+#pragma unroll
+            for (int i = 0; i < A_ITERS; ++i) {
+                char *dst = sA + (i * kThreads + wave * 64) * 16;      // wave-uniform; lane L lands at dst + 16 L
+                if (kok)
+                    __builtin_amdgcn_global_load_lds(UCL_GLOBAL_PTR(a_ptr[i] + (int64_t)k0 * 2), UCL_LDS_PTR(dst), 16, 0, 0);
+                else
+                    *(u32x4_t *)(dst + lane * 16) = u32x4_t{0, 0, 0, 0};
+            }
+        } else if constexpr (LA == kIm2col) {
+            const bool kok = k0 + l_kc < K;
+            const int dh = a_r * p.dil_h, dw = a_s * p.dil_w;
+            const int64_t tap_off = (((int64_t)dh * p.cW + dw) * p.cC + a_ci) * 2;
+#pragma unroll
+            for (int i = 0; i < A_ITERS; ++i) {
+                char *dst = sA + (i * kThreads + wave * 64) * 16;
+                const int h = a_h0[i] + dh, w = a_w0[i] + dw;
+                const bool ok = kok && (unsigned)h < (unsigned)p.cH && (unsigned)w < (unsigned)p.cW;
+                if (ok) {
+                    const char *src = a_ptr[i] + ((int64_t)a_h0[i] * p.cW + a_w0[i]) * p.cC * 2 + tap_off;
+                    __builtin_amdgcn_global_load_lds(UCL_GLOBAL_PTR(src), UCL_LDS_PTR(dst), 16, 0, 0);
+                } else {
+                    *(u32x4_t *)(dst + lane * 16) = u32x4_t{0, 0, 0, 0};
+                }
+            }
+            // advance k by one k-tile: (ci, s, r) += TK channels
+            a_ci += TK;
+            while (a_ci >= p.cC) {
+                a_ci -= p.cC;
+                if (++a_s == p.cS) { a_s = 0; ++a_r; }
+            }
+        } else {   // A contiguous along M: element (m, k) at k*lda + m
+#pragma unroll
+            for (int i = 0; i < A_ITERS; ++i) {
+                const int s = i * kThreads + tid;
+                const int krow = s / (TM / 8), mc = s % (TM / 8);
+                int m = m0 + mc * 8;
+                m = m + 8 <= Mloc ? m : Mloc - 8;                  // Mloc % 8 == 0 (validated)
+                const int k = k0 + krow;
+                a_stage[i] = k < K ? *(const u32x4_t *)(Ab + ((int64_t)k * p.lda + m) * 2) : u32x4_t{0, 0, 0, 0};
+            }
+        }
+        if constexpr (LB == kKContig) {
+            const bool kok = k0 + l_kc < K;
+#pragma unroll
+            for (int i = 0; i < B_ITERS; ++i) {
+                char *dst = sB + (i * kThreads + wave * 64) * 16;
+                if (kok)
+                    __builtin_amdgcn_global_load_lds(UCL_GLOBAL_PTR(b_ptr[i] + (int64_t)k0 * 2), UCL_LDS_PTR(dst), 16, 0, 0);
+                else
+                    *(u32x4_t *)(dst + lane * 16) = u32x4_t{0, 0, 0, 0};
+            }
+        } else {   // B contiguous along N: element (k, n) at k*ldb + n
+#pragma unroll
+            for (int i = 0; i < B_ITERS; ++i) {
+                const int s = i * kThreads + tid;
+                const int krow = s / (TN / 8), nc = s % (TN / 8);
+                int n = n0 + nc * 8;
+                n = n + 8 <= p.N ? n : p.N - 8;                    // N % 8 == 0 (validated)
+                const int k = k0 + krow;
+                b_stage[i] = k < K ? *(const u32x4_t *)(Bb + ((int64_t)k * p.ldb + n) * 2) : u32x4_t{0, 0, 0, 0};
+            }
+        }
+    };
+
+    // Transposing write of the register-staged operands into stage buffer `buf`.
+    auto commit_regs = [&](int buf) {
+        char *sA = smem + buf * Cfg::STAGE_BYTES;
+        char *sB = sA + Cfg::A_BYTES;
+        if constexpr (LA == kMNContig) {
+#pragma unroll
+            for (int i = 0; i < A_ITERS; ++i) {
+                const int s = i * kThreads + tid;
+                const int krow = s / (TM / 8), mc = s % (TM / 8);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const int row = mc * 8 + j;
+                    const uint32_t w = a_stage[i][j >> 1];
+                    const uint16_t e = (j & 1) ? (uint16_t)(w >> 16) : (uint16_t)(w & 0xffffu);
+                    *(uint16_t *)(sA + row * 128 + (((krow >> 3) ^ lds_swz(row)) << 4) + (krow & 7) * 2) = e;
+                }
+            }
+        }
+        if constexpr (LB == kMNContig) {
+#pragma unroll
+            for (int i = 0; i < B_ITERS; ++i) {
+                const int s = i * kThreads + tid;
+                const int krow = s / (TN / 8), nc = s % (TN / 8);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const int row = nc * 8 + j;
+                    const uint32_t w = b_stage[i][j >> 1];
+                    const uint16_t e = (j & 1) ? (uint16_t)(w >> 16) : (uint16_t)(w & 0xffffu);
+                    *(uint16_t *)(sB + row * 128 + (((krow >> 3) ^ lds_swz(row)) << 4) + (krow & 7) * 2) = e;
+                }
+            }
+        }
+    };
+
+    // ---- accumulators and fragment addressing -----------------------------------------------
+    f32x16_t acc[MI][NI];
+    static_for<MI>([&](auto mi) {
+        static_for<NI>([&](auto ni) {
+#pragma unroll
+            for (int j = 0; j < 16; ++j) acc[mi][ni][j] = 0.f;
+        });
+    });
+
+    const int f_row = lane & 31, f_half = lane >> 5;
+    // byte offset of this lane's fragment chunk inside its 128-byte row, for k-step 0;
+    // k-step kk XORs it with kk*32 (chunk index 2kk + half, XOR swz(row))
+    const int f_x = (f_half ^ lds_swz(f_row)) << 4;
+    const int a_frag_base = (wm * Cfg::WTM + f_row) * 128;
+    const int b_frag_base = Cfg::A_BYTES + (wn * Cfg::WTN + f_row) * 128;
+
+    // ---- prologue -----------------------------------------------------------------------------
+    if constexpr (kAnyReg) {
+        issue_tile(0, 0);
+        commit_regs(0);
+    } else {
+#pragma unroll
+        for (int s = 0; s < STAGES - 1; ++s)
+            if (s < KT) issue_tile(s, s);
+    }
+
+    // ---- mainloop -----------------------------------------------------------------------------
+    for (int kt = 0; kt < KT; ++kt) {
+        const int buf = kt % STAGES;
+        if constexpr (kAnyReg) {
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+        } else {
+            // tiles issued so far: min(KT, kt + STAGES - 1); all but the newest STAGES-2 must have landed
+            if (KT - kt - 1 >= STAGES - 2) __builtin_amdgcn_s_waitcnt(vmcnt_imm((STAGES - 2) * DMA_PER_TILE));
+            else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+        }
+        __syncthreads();
+        if constexpr (kAnyReg) {
+            if (kt + 1 < KT) issue_tile(kt + 1, (kt + 1) % STAGES);
+        } else {
+            if (kt + STAGES - 1 < KT) issue_tile(kt + STAGES - 1, (kt + STAGES - 1) % STAGES);
+        }
+
+        const char *sbase = smem + buf * Cfg::STAGE_BYTES;
+        static_for<TK / 16>([&](auto kk_) {
+            constexpr int kk = decltype(kk_)::value;
+            u32x4_t af[MI], bf[NI];
+            const int xo = f_x ^ (kk * 32);
+            static_for<MI>([&](auto mi) {
+                af[mi] = *(const u32x4_t *)(sbase + a_frag_base + mi * 32 * 128 + xo);
+            });
+            static_for<NI>([&](auto ni) {
+                bf[ni] = *(const u32x4_t *)(sbase + b_frag_base + ni * 32 * 128 + xo);
+            });
+            // B fragment as the MFMA's first operand: the lane then holds 4 consecutive n per
+            // accumulator quad, which is what the row-major store wants.
+            static_for<MI>([&](auto mi) {
+                static_for<NI>([&](auto ni) { acc[mi][ni] = mfma32<Cfg::F16>(bf[ni], af[mi], acc[mi][ni]); });
+            });
+        });
+        if constexpr (kAnyReg) {
+            if (kt + 1 < KT) commit_regs((kt + 1) % STAGES);
+        }
+    }
+
+    // ---- epilogue: chain on registers, round once, store ----------------------------------------
+    const int dtD = p.dtD;
+    const bool dvec = p.d_vec != 0;
+    static_for<MI>([&](auto mi) {
+        const int m = m0 + wm * Cfg::WTM + mi * 32 + f_row;
+        EpiCtx c;
+        c.m = m;
+        c.m_ok = m < Mloc;
+        c.N = p.N;
+        c.batch = batch;
+        c.group = group;
+        const int64_t drow = (MODE == 1 ? 0 : (int64_t)batch * p.d_bs) + (int64_t)m * p.ldd;
+        static_for<NI>([&](auto ni) {
+            c.n_base = n0 + wn * Cfg::WTN + ni * 32 + 4 * f_half;
+            float v[16];
+#pragma unroll
+            for (int j = 0; j < 16; ++j) v[j] = acc[mi][ni][j];
+            for (int s = 0; s < p.n_steps; ++s) apply_step(v, p.steps[s], c);
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int n = c.n_base + 8 * g;
+                const f32x4_t o = {v[4 * g], v[4 * g + 1], v[4 * g + 2], v[4 * g + 3]};
+                store4(Db, dtD, drow + n, o, dvec, c.m_ok ? p.N - n : 0);
+            }
+        });
+    });
+}
+
+}  // namespace ucl

@@ -1,0 +1,29 @@
+// Registry of the built kernel variants: every instantiation unit contributes a table of these.
+#pragma once
+#include "ucl_device.h"
+
+namespace ucl {
+
+struct VariantDesc {
+    int tile_m, tile_n, stages;
+    int f16;            // 1: fp16 inputs, 0: bf16 inputs
+    int mode;           // 0 gemm / batched, 1 grouped, 2 conv2d fprop
+    int la, lb;         // 0: operand contiguous along K, 1: contiguous along M / N, 2: im2col (A only)
+    int lds_bytes;
+    hipError_t (*launch)(const KParams &p, const GroupTable *gt, int grid, hipStream_t stream);
+};
+
+struct VariantList {
+    const VariantDesc *v;
+    int n;
+};
+
+// one per instantiation unit
+VariantList variants_gemm_kk_bf16();
+VariantList variants_gemm_kk_f16();
+VariantList variants_gemm_mn_bf16();
+VariantList variants_gemm_mn_f16();
+VariantList variants_grouped();
+VariantList variants_conv();
+
+}  // namespace ucl

@@ -1,0 +1,227 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 oracle, element by element."""
+import math
+
+import numpy as np
+import pytest
+
+from paper_2603_29010_amd import synth
+from paper_2603_29010_amd.binding import Tuning
+
+import parity
+
+pytestmark = pytest.mark.gpu
+
+
+def T(tm, tn, st, raster=0):
+    return Tuning(tm, tn, 64, st, raster)
+
+
+KK_TILES = [(256, 256, 2), (256, 128, 2), (128, 128, 2), (128, 128, 3), (64, 64, 2), (64, 64, 4)]
+
+
+# ---------------------------------------------------------------- exact (integer) indexing tests
+
+@pytest.mark.parametrize("tile", KK_TILES)
+@pytest.mark.parametrize("dt", ["bf16", "f16"])
+def test_gemm_exact_every_tile(tile, dt):
+    # ragged in M and N, K tail (K = 200 = 3*64 + 8), several tiles in each direction
+    spec = synth.gemm_spec(328, 264, 200, dt_in=dt, dt_out="f32", epilogue=(), integer=True)
+    parity.check_exact(spec, T(*tile), label=f"tile{tile}")
+
+
+@pytest.mark.parametrize("a_layout,b_layout", [("row", "row"), ("col", "col"), ("col", "row")])
+@pytest.mark.parametrize("tile", [(128, 128, 2), (64, 64, 2)])
+def test_gemm_exact_transposed_layouts(a_layout, b_layout, tile):
+    spec = synth.gemm_spec(200, 136, 72, dt_out="f32", a_layout=a_layout, b_layout=b_layout, epilogue=(),
+                           integer=True)
+    parity.check_exact(spec, T(*tile), label=f"{a_layout}/{b_layout}")
+
+
+@pytest.mark.parametrize("shape", [(1, 8, 8), (8, 1, 8), (7, 5, 16), (64, 64, 64), (65, 63, 64), (1, 1, 8)])
+def test_gemm_exact_degenerate_shapes(shape):
+    M, N, K = shape
+    spec = synth.gemm_spec(M, N, K, dt_out="f32", epilogue=(), integer=True)
+    parity.check_exact(spec, label=str(shape))
+
+
+def test_gemm_exact_bf16_output_and_odd_n():
+    # N = 77 forces the scalar-store path for the ragged last columns; |values| small enough for bf16
+    spec = synth.gemm_spec(96, 77, 16, dt_out="bf16", epilogue=(), integer=True)
+    parity.check_exact(spec)
+
+
+@pytest.mark.parametrize("raster", [1, 2, 8, 16])
+def test_gemm_exact_raster_orders(raster):
+    spec = synth.gemm_spec(640, 448, 64, dt_out="f32", epilogue=(), integer=True)
+    parity.check_exact(spec, T(64, 64, 2, raster), label=f"raster{raster}")
+
+
+def test_batched_exact():
+    spec = synth.batched_spec(5, 136, 72, 24, dt_out="f32", epilogue=(), integer=True)
+    parity.check_exact(spec)
+    parity.check_exact(spec, T(64, 64, 2))
+
+
+def test_grouped_exact_ragged_offsets():
+    M_g = [64, 0, 200, 8, 321, 0, 128, 1]
+    spec = synth.grouped_spec(M_g, 136, 72, dt_out="f32", epilogue=(), integer=True)
+    for tile in [(256, 256, 2), (128, 128, 3), (64, 64, 2)]:
+        parity.check_exact(spec, T(*tile), label=f"grouped{tile}")
+
+
+@pytest.mark.parametrize("geom", [
+    dict(Nb=2, H=9, W=7, C=16, Ko=24, R=3, S=3, pad=(1, 1)),
+    dict(Nb=1, H=12, W=10, C=8, Ko=8, R=5, S=3, pad=(2, 0), stride=(2, 1)),
+    dict(Nb=3, H=8, W=8, C=24, Ko=40, R=3, S=3, pad=(2, 2), dil=(2, 2)),
+    dict(Nb=2, H=6, W=6, C=64, Ko=16, R=1, S=1, pad=(0, 0)),
+    dict(Nb=1, H=1, W=40, C=8, Ko=8, R=1, S=5, pad=(0, 2)),           # conv1d as H = 1
+    dict(Nb=2, H=7, W=9, C=72, Ko=136, R=3, S=2, pad=(1, 1), stride=(2, 3)),
+])
+def test_conv_exact_every_halo_position(geom):
+    spec = synth.conv_spec(dt_out="f32", epilogue=(), integer=True, **geom)
+    for tile in [(256, 128, 2), (128, 128, 3), (64, 64, 2)]:
+        parity.check_exact(spec, T(*tile), label=f"conv{tile}")
+
+
+# ---------------------------------------------------------------- floating-point parity
+
+@pytest.mark.parametrize("tile", KK_TILES)
+def test_gemm_parity_every_tile(tile):
+    spec = synth.gemm_spec(520, 392, 264, epilogue=("bias", "gelu_tanh"))
+    parity.check(spec, T(*tile), label=f"tile{tile}")
+
+
+ALL_CHAINS = [
+    ("bias", "relu"),
+    ("bias", "gelu_tanh"),
+    ("gelu_erf",),
+    ("silu",),
+    (("scale", 0.125), "sigmoid"),
+    ("tanh",),
+    ("mish",),
+    ("hardswish",),
+    (("leaky_relu", 0.1),),
+    (("elu", 1.5),),
+    ("bias", ("clamp", -0.5, 0.75)),
+    ("per_row_scale", "per_col_scale"),
+    ("row_broadcast", "column_broadcast", "relu"),
+    (("scale", 2.0), ("aux_load", -0.5), "relu"),
+    ("bias", "aux_load", "relu", ("scale", 3.0), "tanh", ("clamp", 0.0, 6.0), "silu", "hardswish"),
+]
+
+
+@pytest.mark.parametrize("chain", ALL_CHAINS, ids=lambda c: "-".join(s if isinstance(s, str) else s[0] for s in c))
+@pytest.mark.parametrize("dt_out", ["bf16", "f32"])
+def test_epilogue_vocabulary(chain, dt_out):
+    spec = synth.gemm_spec(136, 200, 128, dt_out=dt_out, dist="normal", scale=0.25, epilogue=chain)
+    parity.check(spec, label=str(chain))
+
+
+def test_aux_store_captures_mid_chain_value():
+    import oracle
+    from paper_2603_29010_amd.workload import DeviceWorkload
+    spec = synth.gemm_spec(72, 136, 64, dt_out="bf16", epilogue=("bias", "relu"))
+    spec["epilogue"].insert(1, ("aux_store", "pre_act", "f32"))
+    w = DeviceWorkload(spec)
+    w.run()
+    got = w.result()
+    pre = w.aux_result("pre_act")
+    base = dict(spec)
+    base["epilogue"] = [spec["epilogue"][0]]
+    ref_pre, s1 = parity.oracle_result(base)
+    parity.compare(pre, ref_pre, s1, dict(base, dt_out="f32"), "aux_store")
+    base["epilogue"] = [spec["epilogue"][0], spec["epilogue"][2]]
+    ref, s2 = parity.oracle_result(base)
+    parity.compare(got, ref, s2, base, "after aux_store")
+
+
+@pytest.mark.parametrize("dt_in,dt_out", [("f16", "f16"), ("f16", "f32"), ("bf16", "f16")])
+def test_gemm_dtype_combinations(dt_in, dt_out):
+    spec = synth.gemm_spec(200, 136, 136, dt_in=dt_in, dt_out=dt_out, epilogue=("bias", "silu"))
+    parity.check(spec)
+
+
+def test_batched_parity_with_residual():
+    spec = synth.batched_spec(3, 136, 200, 72, dt_out="f16", epilogue=[("scale", 0.5), "aux_load", "relu"])
+    parity.check(spec)
+
+
+def test_grouped_parity_silu():
+    spec = synth.grouped_spec([192, 64, 0, 448, 128], 264, 136)
+    for tile in [(256, 256, 2), (128, 128, 3)]:
+        parity.check(spec, T(*tile))
+
+
+def test_conv_parity_bias_residual_relu():
+    spec = synth.conv_spec(3, 14, 14, 64, 128, 3, 3)
+    for tile in [(256, 128, 2), (128, 128, 3), (64, 64, 2)]:
+        parity.check(spec, T(*tile), label=f"conv{tile}")
+
+
+# ---------------------------------------------------------------- the benchmark configurations
+
+def test_config1_full():
+    parity.check(synth.config(1), label="config1")
+
+
+def test_config2_shrunk_and_default_selection():
+    parity.check(synth.config(2, shrink=8), label="config2/8")
+
+
+def test_config3_shrunk():
+    parity.check(synth.config(3, shrink=16), label="config3/16")
+
+
+def test_config4_shrunk():
+    parity.check(synth.config(4, shrink=8), label="config4/8")
+
+
+def test_config5_shrunk():
+    parity.check(synth.config(5, shrink=16), label="config5/16")
+
+
+def _sample_rows(M, n, seed):
+    rng = np.random.default_rng(seed)
+    rows = set(rng.integers(0, M, n).tolist()) | {0, M - 1}
+    return sorted(rows)
+
+
+def test_config2_full_size_sampled_rows():
+    spec = synth.config(2)
+    rows = _sample_rows(spec["M"], 24, 2)
+    parity.check(spec, rows=rows, label="config2 full")
+
+
+def test_config3_full_size():
+    parity.check(synth.config(3), label="config3 full")
+
+
+def test_config4_full_size_sampled_rows():
+    import oracle
+    from paper_2603_29010_amd.workload import DeviceWorkload
+    spec = synth.config(4)
+    w = DeviceWorkload(spec)
+    w.run()
+    got = w.result()
+    offs = np.concatenate([[0], np.cumsum(spec["M_g"])])
+    # first, last and a few random rows of every group, each a GEMM row against that group's B
+    rng = np.random.default_rng(4)
+    for g, m in enumerate(spec["M_g"]):
+        rows = sorted({0, m - 1, *rng.integers(0, m, 2).tolist()})
+        A_g = np.ascontiguousarray(spec["A"][offs[g]:offs[g + 1]])
+        ref, s = oracle.gemm(A_g, "bf16", spec["a_strides"], np.ascontiguousarray(spec["B"][g]), "bf16",
+                             spec["b_strides"], m, spec["N"], spec["K"], chain=[("silu",)], rows=rows, want_abs=True)
+        parity.compare(got[offs[g] + np.asarray(rows)], ref, s, spec, f"config4 group {g}")
+
+
+def test_config5_full_size_sampled_rows():
+    spec = synth.config(5)
+    rows = _sample_rows(spec["M"], 400, 5)
+    # add every halo class of the first and last image
+    P, Q = spec["P"], spec["Q"]
+    for n in (0, spec["Nb"] - 1):
+        for p in (0, 1, P - 1):
+            for q in (0, 1, Q - 1):
+                rows.append((n * P + p) * Q + q)
+    rows = sorted(set(rows))
+    parity.check(spec, rows=rows, label="config5 full")
