@@ -31,7 +31,7 @@ WORKLOAD_NAMES = {
 }
 
 
-def time_workload(cfg, steps, warmup, copies=None):
+def time_workload(cfg, steps, warmup, copies=None, use_graph=True):
     """Time `steps` back-to-back launches with HIP events on the launch stream."""
     import torch
     from paper_2603_29010_amd import synth
@@ -44,15 +44,34 @@ def time_workload(cfg, steps, warmup, copies=None):
         # served from the 256 MB last-level cache left warm by the previous one
         copies = 1 if sol["compute_bound"] else max(2, int(768e6 // sol["bytes"]) + 1)
     sets = [probe] + [DeviceWorkload(spec, poison=False) for _ in range(copies - 1)]
-    stream = torch.cuda.current_stream()
     for i in range(warmup):
         sets[i % copies].run()
     torch.cuda.synchronize()
     start = torch.cuda.Event(enable_timing=True)
     stop = torch.cuda.Event(enable_timing=True)
+    launch = "eager"
+    graph = None
+    if use_graph:
+        # record the K launches once into a HIP graph (kernel nodes only: the library issues no memset
+        # or copy), so that the host's per-call cost cannot limit back-to-back short kernels
+        try:
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                for i in range(steps):
+                    sets[i % copies].run()
+            graph.replay()                       # untimed first replay
+            torch.cuda.synchronize()
+            launch = "hipgraph"
+        except Exception as e:                   # capture unsupported: fall back to plain launches
+            print(f"bench.py: graph capture failed ({e}); timing eager launches", file=sys.stderr)
+            graph = None
+    stream = torch.cuda.current_stream()
     start.record(stream)
-    for i in range(steps):
-        sets[i % copies].run()
+    if graph is not None:
+        graph.replay()
+    else:
+        for i in range(steps):
+            sets[i % copies].run()
     stop.record(stream)
     torch.cuda.synchronize()
     ms = start.elapsed_time(stop) / steps
@@ -61,7 +80,7 @@ def time_workload(cfg, steps, warmup, copies=None):
         "workload": WORKLOAD_NAMES[cfg], "ms_per_step": ms, "tflops": sol["flops"] / t / 1e12,
         "gbps": sol["bytes"] / t / 1e9, "flops": sol["flops"], "bytes": sol["bytes"],
         "t_sol_us": sol["t_sol"] * 1e6, "frac_of_sol": sol["t_sol"] / t,
-        "bound": "mfma" if sol["compute_bound"] else "hbm", "buffer_sets": copies,
+        "bound": "mfma" if sol["compute_bound"] else "hbm", "buffer_sets": copies, "launch": launch,
     }
     if spec["op"] == "grouped_gemm":
         res["sum_M"] = int(sum(spec["M_g"]))
@@ -113,6 +132,7 @@ def main():
     ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--all", action="store_true", help="also time the other four workloads")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--eager", action="store_true", help="plain launches instead of one captured HIP graph")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU (the hot path is one kernel on one GPU's share of the "
@@ -127,7 +147,7 @@ def main():
         print("bench.py: libucl.so is not built (python -m paper_2603_29010_amd.build)", file=sys.stderr)
         sys.exit(1)
 
-    res, spec, _ = time_workload(args.config, args.steps, args.warmup)
+    res, spec, _ = time_workload(args.config, args.steps, args.warmup, use_graph=not args.eager)
     mfma = res["bound"] == "mfma"
     roofline = {
         "bound": res["bound"],
@@ -143,7 +163,7 @@ def main():
         "ms_per_step": res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16" if spec["dt_in"] == "f16" else "bf16", "data": "synthetic",
         "config": {"workload": res["workload"], "frac_of_sol": res["frac_of_sol"], "t_sol_us": res["t_sol_us"],
-                   "buffer_sets": res["buffer_sets"]},
+                   "buffer_sets": res["buffer_sets"], "launch": res["launch"]},
         "roofline": roofline,
     }
     if not args.no_cpu_baseline:
@@ -154,7 +174,7 @@ def main():
             if c == args.config:
                 out["configs"][str(c)] = res
                 continue
-            r, _, _ = time_workload(c, args.steps, args.warmup)
+            r, _, _ = time_workload(c, args.steps, args.warmup, use_graph=not args.eager)
             out["configs"][str(c)] = r
     print(json.dumps(out))
 

@@ -78,6 +78,10 @@ def _load():
             raise RuntimeError(
                 f"{_LIB_PATH} is missing: build it with `python -m paper_2603_29010_amd.build` "
                 "(hipcc, gfx950). There is no fallback implementation.")
+        # Device memory and streams come from PyTorch-ROCm, which ships its own copy of the HIP
+        # runtime.  Import it first so that the process holds ONE runtime (the one that owns the
+        # caller's allocations and streams) and libucl.so binds to it.
+        import torch  # noqa: F401
         lib = C.CDLL(_LIB_PATH)
         i32, i64, vp = C.c_int32, C.c_int64, C.c_void_p
         lib.ucl_gemm.restype = C.c_int

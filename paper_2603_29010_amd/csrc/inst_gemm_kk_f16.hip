@@ -1,13 +1,12 @@
-// gemm / batched_gemm, both operands contiguous along K, f16 inputs.
+// gemm / batched_gemm, both operands contiguous along K, fp16 inputs.
 #include "ucl_launch.h"
 namespace ucl {
 static const VariantDesc kTable[] = {
-    describe<KernelCfg<256, 256, 2, true, 0, kKContig, kKContig>>(),
-    describe<KernelCfg<256, 128, 2, true, 0, kKContig, kKContig>>(),
-    describe<KernelCfg<128, 128, 2, true, 0, kKContig, kKContig>>(),
-    describe<KernelCfg<128, 128, 3, true, 0, kKContig, kKContig>>(),
-    describe<KernelCfg<64, 64, 2, true, 0, kKContig, kKContig>>(),
-    describe<KernelCfg<64, 64, 4, true, 0, kKContig, kKContig>>(),
+    describe<KernelCfg<256, 256, 32, 4, true, 0, kKContig, kKContig>>(),
+    describe<KernelCfg<256, 128, 32, 4, true, 0, kKContig, kKContig>>(),
+    describe<KernelCfg<128, 128, 64, 3, true, 0, kKContig, kKContig>>(),
+    describe<KernelCfg<128, 128, 32, 4, true, 0, kKContig, kKContig>>(),
+    describe<KernelCfg<64, 64, 64, 2, true, 0, kKContig, kKContig>>(),
 };
 VariantList variants_gemm_kk_f16() { return {kTable, (int)(sizeof(kTable) / sizeof(kTable[0]))}; }
 }  // namespace ucl

@@ -24,7 +24,7 @@ ucl_status fail(ucl_status st, const char *fmt, ...) {
 const std::vector<VariantDesc> &all_variants() {
     static const std::vector<VariantDesc> v = [] {
         std::vector<VariantDesc> out;
-        for (VariantList l : {variants_gemm_kk_bf16(), variants_gemm_kk_f16(), variants_gemm_mn_bf16(),
+        for (VariantList l : {variants_gemm_kk_bf16_a(), variants_gemm_kk_bf16_b(), variants_gemm_kk_f16(), variants_gemm_mn_bf16(),
                               variants_gemm_mn_f16(), variants_grouped(), variants_conv()})
             for (int i = 0; i < l.n; ++i) out.push_back(l.v[i]);
         return out;
@@ -80,26 +80,26 @@ int64_t count_tiles(const Launch &L, int tm, int tn) {
 const VariantDesc *select_variant(const Launch &L, const ucl_tuning *tune) {
     const auto &vs = all_variants();
     const bool explicit_tune = tune && (tune->tile_m || tune->tile_n || tune->tile_k || tune->stages);
-    const int64_t ktiles = (L.K + kTileK - 1) / kTileK;
     const VariantDesc *best = nullptr;
     int64_t best_key = -1;
     for (const auto &v : vs) {
         if (v.mode != L.mode || v.f16 != L.f16 || v.la != L.la || v.lb != L.lb) continue;
         if (explicit_tune) {
             if (v.tile_m == tune->tile_m && v.tile_n == tune->tile_n && v.stages == tune->stages &&
-                (tune->tile_k == 0 || tune->tile_k == kTileK))
+                v.tile_k == tune->tile_k)
                 return &v;
             continue;
         }
         const int64_t tiles = count_tiles(L, v.tile_m, v.tile_n);
         const int64_t area = (int64_t)v.tile_m * v.tile_n;
+        const int64_t ktiles = (L.K + v.tile_k - 1) / v.tile_k;
         const bool fills = tiles >= 192;
-        // wasted rows/columns in edge tiles count against a big tile
         int64_t key;
-        if (fills) key = (1ll << 40) + area * 16;
-        else key = tiles * 16;
-        const int usable_stages = v.stages - 1 <= ktiles ? v.stages : 0;
-        key += usable_stages;
+        if (fills) key = (1ll << 40) + area * 1024;
+        else key = tiles * 1024;
+        // prefer the pipeline with the most bytes in flight that the K extent can fill
+        const int64_t depth = v.stages <= ktiles ? (int64_t)(v.stages - 1) * v.tile_k : 0;
+        key += depth;
         if (key > best_key) { best_key = key; best = &v; }
     }
     return best;
@@ -203,14 +203,14 @@ ucl_status run(const Launch &L, KParams &kp, const GroupTable *gt_in, const ucl_
     const VariantDesc *v = select_variant(L, tune);
     if (!v) {
         if (tune && (tune->tile_m || tune->tile_n || tune->stages)) {
-            if (tune->tile_k != 0 && tune->tile_k != kTileK)
-                return fail(UCL_ERR_UNSUPPORTED, "tile_k=%d: every built kernel stages K in steps of %d", tune->tile_k, kTileK);
-            const int64_t lds = (int64_t)(tune->tile_m + tune->tile_n) * kTileK * 2 * tune->stages;
+            if (tune->tile_k != 32 && tune->tile_k != 64)
+                return fail(UCL_ERR_UNSUPPORTED, "tile_k=%d: the built kernels stage K in steps of 32 or 64", tune->tile_k);
+            const int64_t lds = (int64_t)(tune->tile_m + tune->tile_n) * tune->tile_k * 2 * tune->stages;
             if (lds > kLdsBytesPerCU)
                 return fail(UCL_ERR_WORKSPACE, "tile %dx%dx%d with %d stages needs %lld bytes of LDS; a CU has %d",
-                            tune->tile_m, tune->tile_n, kTileK, tune->stages, (long long)lds, kLdsBytesPerCU);
+                            tune->tile_m, tune->tile_n, tune->tile_k, tune->stages, (long long)lds, kLdsBytesPerCU);
             return fail(UCL_ERR_UNSUPPORTED, "no kernel built for tile %dx%dx%d, %d stages with these types/layouts; see ucl_variant()",
-                        tune->tile_m, tune->tile_n, kTileK, tune->stages);
+                        tune->tile_m, tune->tile_n, tune->tile_k, tune->stages);
         }
         return fail(UCL_ERR_UNSUPPORTED, "no kernel built for this combination of operation, input type and layouts");
     }
@@ -472,7 +472,7 @@ ucl_status ucl_select_tuning(const ucl_problem *p, ucl_tuning *out) {
     const VariantDesc *v = select_variant(L, nullptr);
     if (!v) return fail(UCL_ERR_UNSUPPORTED, "no kernel built for this problem");
     memset(out, 0, sizeof(*out));
-    out->tile_m = v->tile_m; out->tile_n = v->tile_n; out->tile_k = kTileK; out->stages = v->stages;
+    out->tile_m = v->tile_m; out->tile_n = v->tile_n; out->tile_k = v->tile_k; out->stages = v->stages;
     out->raster = default_raster(*v, L);
     return UCL_OK;
 }
@@ -504,7 +504,7 @@ ucl_status ucl_variant(int32_t i, ucl_tuning *out) {
     const auto &vs = all_variants();
     if (i < 0 || i >= (int)vs.size() || !out) return fail(UCL_ERR_INVALID_ARG, "variant index %d outside [0, %d)", i, (int)vs.size());
     memset(out, 0, sizeof(*out));
-    out->tile_m = vs[i].tile_m; out->tile_n = vs[i].tile_n; out->tile_k = kTileK; out->stages = vs[i].stages;
+    out->tile_m = vs[i].tile_m; out->tile_n = vs[i].tile_n; out->tile_k = vs[i].tile_k; out->stages = vs[i].stages;
     // reserved[0..2]: which problems the variant serves (mode, 16-bit type, operand layouts)
     out->reserved[0] = vs[i].mode; out->reserved[1] = vs[i].f16; out->reserved[2] = vs[i].la * 4 + vs[i].lb;
     return UCL_OK;

@@ -7,7 +7,6 @@
 
 namespace ucl {
 
-constexpr int kTileK = 64;            // K extent of one LDS stage, elements (= 128 bytes of bf16/fp16)
 constexpr int kThreads = 256;         // 4 wavefronts of 64 lanes, one per SIMD of a CU
 constexpr int kLdsBytesPerCU = 160 * 1024;
 

@@ -7,9 +7,9 @@
 //                    (and the implicit-GEMM view of NHWC activations) go straight from HBM/L2 into
 //                    LDS with 128-bit `global_load_lds` (no VGPR round trip); operands contiguous
 //                    along M / N are loaded 128-bit into VGPRs and transposed on the way into LDS.
-//   LDS layout     : [rows][64 elements] = 128-byte rows of eight 16-byte chunks, chunk index XORed
-//                    with a function of the row so that the 16-byte-per-lane MFMA fragment reads of
-//                    32 consecutive rows spread over all banks.
+//   LDS layout     : [rows][TK elements] (TK = 64 or 32: 128- or 64-byte rows of 16-byte chunks), chunk
+//                    index XORed with a function of the row so that the 16-byte-per-lane MFMA
+//                    fragment reads of 32 consecutive rows spread over all banks.
 //   mainloop       : v_mfma_f32_32x32x16_{bf16,f16}, fp32 accumulators held in registers,
 //                    wave tile (TM/2) x (TN/2).
 //   epilogue       : the `>>` chain interpreted on the accumulator registers (fp32), one rounding
@@ -48,9 +48,15 @@ __device__ __forceinline__ void static_for(F &&f) {
 // s_waitcnt immediate (gfx9 encoding) that waits only on the vector-memory counter.
 __device__ constexpr int vmcnt_imm(int n) { return (n & 0xF) | ((n >> 4) << 14) | (0x7 << 4) | (0xF << 8); }
 
-// XOR pattern of the LDS layout; depends on row mod 16 only, so any multiple-of-32 row offset
-// (wave tile, MFMA block) leaves it unchanged.
-__device__ __forceinline__ int lds_swz(int row) { return (row & 7) ^ ((row >> 3) & 1); }
+// XOR pattern of the LDS layout, for rows of CPR 16-byte chunks.  It depends on row mod 16 only, so
+// any multiple-of-32 row offset (wave tile, MFMA block) leaves it unchanged.  Chosen so that 16
+// consecutive rows reading the same logical chunk hit 16 different 16-byte bank groups of a 256-byte
+// LDS line, and 8 consecutive rows 8 different groups of a 128-byte half line.
+template <int CPR>
+__device__ __forceinline__ int lds_swz(int row) {
+    if constexpr (CPR == 8) return (row & 7) ^ ((row >> 3) & 1);
+    else return ((row >> 1) ^ (row >> 3)) & 3;
+}
 
 __device__ __forceinline__ float bits_to_f32(uint32_t raw16, int dtype) {
     if (dtype == UCL_BF16) return __uint_as_float(raw16 << 16);
@@ -270,10 +276,13 @@ __device__ __forceinline__ void apply_step(float (&v)[16], const EpiStepDev &s, 
 
 // ------------------------------------------------------------------------------------------------
 
-template <int TM_, int TN_, int STAGES_, bool F16_, int MODE_ /*0 gemm+batched, 1 grouped, 2 conv*/,
+template <int TM_, int TN_, int TK_, int STAGES_, bool F16_, int MODE_ /*0 gemm+batched, 1 grouped, 2 conv*/,
           int LA_ /*OperandLayout of A*/, int LB_ /*OperandLayout of B*/>
 struct KernelCfg {
-    static constexpr int TM = TM_, TN = TN_, TK = kTileK, STAGES = STAGES_, MODE = MODE_, LA = LA_, LB = LB_;
+    static constexpr int TM = TM_, TN = TN_, TK = TK_, STAGES = STAGES_, MODE = MODE_, LA = LA_, LB = LB_;
+    static constexpr int CPR = TK / 8;                            // 16-byte chunks per LDS row
+    static constexpr int ROW_BYTES = TK * 2;
+    static_assert(TK == 32 || TK == 64, "k-tile of 32 or 64 elements");
     static constexpr bool F16 = F16_;
     static constexpr int WAVES_M = 2, WAVES_N = 2;
     static constexpr int WTM = TM / WAVES_M, WTN = TN / WAVES_N;  // wave tile
@@ -281,12 +290,17 @@ struct KernelCfg {
     static constexpr int A_BYTES = TM * TK * 2, B_BYTES = TN * TK * 2;
     static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
     static constexpr int LDS_BYTES = STAGES * STAGE_BYTES;
-    static constexpr int A_ITERS = TM * (TK / 8) / kThreads;      // 16-byte chunks per thread per stage
-    static constexpr int B_ITERS = TN * (TK / 8) / kThreads;
+    static constexpr int A_ITERS = TM * CPR / kThreads;           // 16-byte chunks per thread per stage
+    static constexpr int B_ITERS = TN * CPR / kThreads;
+    static constexpr int ROWS_PER_ITER = kThreads / CPR;          // rows covered by one 256-thread copy
     static_assert(TM % 64 == 0 && TN % 64 == 0, "wave tile is a multiple of 32x32");
     static_assert(LDS_BYTES <= kLdsBytesPerCU, "stages x tile exceed LDS");
     using Groups = typename std::conditional<MODE == 1, GroupTable, NoGroupTable>::type;
 };
+
+// Source of the 16 zero bytes that stand in for out-of-range chunks (K tail, conv halo): the copy
+// stays one unconditional 128-bit global -> LDS load per slot, only its address is selected.
+static __device__ __attribute__((aligned(16))) const uint32_t g_zero_chunk[4] = {0u, 0u, 0u, 0u};
 
 template <bool F16>
 __device__ __forceinline__ f32x16_t mfma32(const u32x4_t &a, const u32x4_t &b, const f32x16_t &c) {
@@ -306,6 +320,8 @@ __global__ __launch_bounds__(kThreads) void ucl_tile_kernel(const KParams p, con
     constexpr int A_ITERS = Cfg::A_ITERS, B_ITERS = Cfg::B_ITERS;
     constexpr bool kAnyReg = (LA == kMNContig) || (LB == kMNContig);
     constexpr int DMA_PER_TILE = (LA != kMNContig ? A_ITERS : 0) + (LB != kMNContig ? B_ITERS : 0);
+    constexpr int KSTEPS = TK / 16;
+    constexpr int CPR = Cfg::CPR, ROW_BYTES = Cfg::ROW_BYTES, RPI = Cfg::ROWS_PER_ITER;
 
     __shared__ __attribute__((aligned(1024))) char smem[Cfg::LDS_BYTES];
 
@@ -339,11 +355,15 @@ __global__ __launch_bounds__(kThreads) void ucl_tile_kernel(const KParams p, con
     const int m0 = tm * TM, n0 = tn * TN;
     const int K = p.K;
     const int KT = (K + TK - 1) / TK;
+    const bool k_tail = (K % TK) != 0;
 
     // ---- loader set-up -----------------------------------------------------------------------
-    const int l_row = tid >> 3;                          // row of this thread's slot within a 32-row slab
-    const int l_chunk = (tid & 7) ^ lds_swz(l_row);      // source chunk held by that slot
-    const int l_kc = l_chunk * 8;
+    // Slot s = i*256 + tid of a stage holds row s/CPR = i*RPI + tid/CPR, chunk position tid%CPR; the
+    // source chunk is that position XOR swz(row), the same for every i (RPI is a multiple of 16).
+    const int l_row = tid / CPR;
+    const int l_chunk = (tid % CPR) ^ lds_swz<CPR>(l_row);
+    const int l_kc = l_chunk * 8;                        // first k of this thread's chunk within a k-tile
+    const char *const zero_src = (const char *)g_zero_chunk;
 
     const char *a_ptr[LA == kMNContig ? 1 : A_ITERS];
     int a_h0[LA == kIm2col ? A_ITERS : 1], a_w0[LA == kIm2col ? A_ITERS : 1];
@@ -354,14 +374,14 @@ __global__ __launch_bounds__(kThreads) void ucl_tile_kernel(const KParams p, con
     if constexpr (LA == kKContig) {
 #pragma unroll
         for (int i = 0; i < A_ITERS; ++i) {
-            int row = m0 + i * 32 + l_row;
+            int row = m0 + i * RPI + l_row;
             row = row < Mloc ? row : Mloc - 1;
             a_ptr[i] = Ab + ((int64_t)row * p.lda + l_kc) * 2;
         }
     } else if constexpr (LA == kIm2col) {
 #pragma unroll
         for (int i = 0; i < A_ITERS; ++i) {
-            int row = m0 + i * 32 + l_row;
+            int row = m0 + i * RPI + l_row;
             row = row < Mloc ? row : Mloc - 1;
             const int q = row % p.cQ;
             const int pq = row / p.cQ;
@@ -369,7 +389,8 @@ __global__ __launch_bounds__(kThreads) void ucl_tile_kernel(const KParams p, con
             const int nb = pq / p.cP;
             a_h0[i] = pp * p.str_h - p.pad_h;
             a_w0[i] = q * p.str_w - p.pad_w;
-            a_ptr[i] = Ab + (int64_t)nb * p.cH * p.cW * p.cC * 2;
+            // address of x[nb, h0, w0, 0]; only dereferenced at taps that fall inside the image
+            a_ptr[i] = Ab + (((int64_t)nb * p.cH + a_h0[i]) * p.cW + a_w0[i]) * p.cC * 2;
         }
         a_ci = l_kc % p.cC;
         const int tap = l_kc / p.cC;
@@ -379,30 +400,31 @@ __global__ __launch_bounds__(kThreads) void ucl_tile_kernel(const KParams p, con
     if constexpr (LB == kKContig) {
 #pragma unroll
         for (int i = 0; i < B_ITERS; ++i) {
-            int row = n0 + i * 32 + l_row;
+            int row = n0 + i * RPI + l_row;
             row = row < p.N ? row : p.N - 1;
             b_ptr[i] = Bb + ((int64_t)row * p.ldb + l_kc) * 2;
         }
     }
 
-    // Issue the copies of k-tile `kt` into LDS stage buffer `buf` (DMA operands), or fetch them into
-    // registers (M/N-contiguous operands; written to LDS later by commit_regs).
-    auto issue_tile = [&](int kt, int buf) {
+    // Issue the copies of k-tile `kt` into stage buffer `buf`.  K-contiguous and im2col operands:
+    // one 128-bit global -> LDS load per slot (lane L of a wave lands at dst + 16 L).  M/N-contiguous
+    // operands: 128-bit loads into registers, written (transposed) by commit_regs.  CHECK_K adds the
+    // K-tail test; full k-tiles skip it.
+    auto issue_tile = [&](auto check_k_, int kt, int buf) {
+        constexpr bool CHECK_K = decltype(check_k_)::value;
         char *sA = smem + buf * Cfg::STAGE_BYTES;
         char *sB = sA + Cfg::A_BYTES;
         const int k0 = kt * TK;
+        const bool kok = !CHECK_K || (k0 + l_kc < K);
         if constexpr (LA == kKContig) {
-            const bool kok = k0 + l_kc < K;
 #pragma unroll
             for (int i = 0; i < A_ITERS; ++i) {
-                char *dst = sA + (i * kThreads + wave * 64) * 16;      // wave-uniform; lane L lands at dst + 16 L
-                if (kok)
-                    __builtin_amdgcn_global_load_lds(UCL_GLOBAL_PTR(a_ptr[i] + (int64_t)k0 * 2), UCL_LDS_PTR(dst), 16, 0, 0);
-                else
-                    *(u32x4_t *)(dst + lane * 16) = u32x4_t{0, 0, 0, 0};
+                char *dst = sA + (i * kThreads + wave * 64) * 16;
+                const char *src = a_ptr[i] + (int64_t)k0 * 2;
+                if constexpr (CHECK_K) src = kok ? src : zero_src;
+                __builtin_amdgcn_global_load_lds(UCL_GLOBAL_PTR(src), UCL_LDS_PTR(dst), 16, 0, 0);
             }
         } else if constexpr (LA == kIm2col) {
-            const bool kok = k0 + l_kc < K;
             const int dh = a_r * p.dil_h, dw = a_s * p.dil_w;
             const int64_t tap_off = (((int64_t)dh * p.cW + dw) * p.cC + a_ci) * 2;
 #pragma unroll
@@ -410,12 +432,8 @@ __global__ __launch_bounds__(kThreads) void ucl_tile_kernel(const KParams p, con
                 char *dst = sA + (i * kThreads + wave * 64) * 16;
                 const int h = a_h0[i] + dh, w = a_w0[i] + dw;
                 const bool ok = kok && (unsigned)h < (unsigned)p.cH && (unsigned)w < (unsigned)p.cW;
-                if (ok) {
-                    const char *src = a_ptr[i] + ((int64_t)a_h0[i] * p.cW + a_w0[i]) * p.cC * 2 + tap_off;
-                    __builtin_amdgcn_global_load_lds(UCL_GLOBAL_PTR(src), UCL_LDS_PTR(dst), 16, 0, 0);
-                } else {
-                    *(u32x4_t *)(dst + lane * 16) = u32x4_t{0, 0, 0, 0};
-                }
+                const char *src = ok ? a_ptr[i] + tap_off : zero_src;
+                __builtin_amdgcn_global_load_lds(UCL_GLOBAL_PTR(src), UCL_LDS_PTR(dst), 16, 0, 0);
             }
             // advance k by one k-tile: (ci, s, r) += TK channels
             a_ci += TK;
@@ -435,14 +453,12 @@ __global__ __launch_bounds__(kThreads) void ucl_tile_kernel(const KParams p, con
             }
         }
         if constexpr (LB == kKContig) {
-            const bool kok = k0 + l_kc < K;
 #pragma unroll
             for (int i = 0; i < B_ITERS; ++i) {
                 char *dst = sB + (i * kThreads + wave * 64) * 16;
-                if (kok)
-                    __builtin_amdgcn_global_load_lds(UCL_GLOBAL_PTR(b_ptr[i] + (int64_t)k0 * 2), UCL_LDS_PTR(dst), 16, 0, 0);
-                else
-                    *(u32x4_t *)(dst + lane * 16) = u32x4_t{0, 0, 0, 0};
+                const char *src = b_ptr[i] + (int64_t)k0 * 2;
+                if constexpr (CHECK_K) src = kok ? src : zero_src;
+                __builtin_amdgcn_global_load_lds(UCL_GLOBAL_PTR(src), UCL_LDS_PTR(dst), 16, 0, 0);
             }
         } else {   // B contiguous along N: element (k, n) at k*ldb + n
 #pragma unroll
@@ -455,6 +471,11 @@ __global__ __launch_bounds__(kThreads) void ucl_tile_kernel(const KParams p, con
                 b_stage[i] = k < K ? *(const u32x4_t *)(Bb + ((int64_t)k * p.ldb + n) * 2) : u32x4_t{0, 0, 0, 0};
             }
         }
+    };
+    // only the last k-tile can be partial
+    auto issue = [&](int kt, int buf) {
+        if (k_tail && kt == KT - 1) issue_tile(std::true_type{}, kt, buf);
+        else issue_tile(std::false_type{}, kt, buf);
     };
 
     // Transposing write of the register-staged operands into stage buffer `buf`.
@@ -471,7 +492,7 @@ __global__ __launch_bounds__(kThreads) void ucl_tile_kernel(const KParams p, con
                     const int row = mc * 8 + j;
                     const uint32_t w = a_stage[i][j >> 1];
                     const uint16_t e = (j & 1) ? (uint16_t)(w >> 16) : (uint16_t)(w & 0xffffu);
-                    *(uint16_t *)(sA + row * 128 + (((krow >> 3) ^ lds_swz(row)) << 4) + (krow & 7) * 2) = e;
+                    *(uint16_t *)(sA + row * ROW_BYTES + (((krow >> 3) ^ lds_swz<CPR>(row)) << 4) + (krow & 7) * 2) = e;
                 }
             }
         }
@@ -485,7 +506,7 @@ __global__ __launch_bounds__(kThreads) void ucl_tile_kernel(const KParams p, con
                     const int row = nc * 8 + j;
                     const uint32_t w = b_stage[i][j >> 1];
                     const uint16_t e = (j & 1) ? (uint16_t)(w >> 16) : (uint16_t)(w & 0xffffu);
-                    *(uint16_t *)(sB + row * 128 + (((krow >> 3) ^ lds_swz(row)) << 4) + (krow & 7) * 2) = e;
+                    *(uint16_t *)(sB + row * ROW_BYTES + (((krow >> 3) ^ lds_swz<CPR>(row)) << 4) + (krow & 7) * 2) = e;
                 }
             }
         }
@@ -501,59 +522,134 @@ __global__ __launch_bounds__(kThreads) void ucl_tile_kernel(const KParams p, con
     });
 
     const int f_row = lane & 31, f_half = lane >> 5;
-    // byte offset of this lane's fragment chunk inside its 128-byte row, for k-step 0;
+    // byte offset of this lane's fragment chunk inside its LDS row, for k-step 0;
     // k-step kk XORs it with kk*32 (chunk index 2kk + half, XOR swz(row))
-    const int f_x = (f_half ^ lds_swz(f_row)) << 4;
-    const int a_frag_base = (wm * Cfg::WTM + f_row) * 128;
-    const int b_frag_base = Cfg::A_BYTES + (wn * Cfg::WTN + f_row) * 128;
+    const int f_x = (f_half ^ lds_swz<CPR>(f_row)) << 4;
+    const int a_frag_base = (wm * Cfg::WTM + f_row) * ROW_BYTES;
+    const int b_frag_base = Cfg::A_BYTES + (wn * Cfg::WTN + f_row) * ROW_BYTES;
 
-    // ---- prologue -----------------------------------------------------------------------------
-    if constexpr (kAnyReg) {
-        issue_tile(0, 0);
-        commit_regs(0);
-    } else {
-#pragma unroll
-        for (int s = 0; s < STAGES - 1; ++s)
-            if (s < KT) issue_tile(s, s);
-    }
-
-    // ---- mainloop -----------------------------------------------------------------------------
-    for (int kt = 0; kt < KT; ++kt) {
-        const int buf = kt % STAGES;
-        if constexpr (kAnyReg) {
-            __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-        } else {
-            // tiles issued so far: min(KT, kt + STAGES - 1); all but the newest STAGES-2 must have landed
-            if (KT - kt - 1 >= STAGES - 2) __builtin_amdgcn_s_waitcnt(vmcnt_imm((STAGES - 2) * DMA_PER_TILE));
-            else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-        }
-        __syncthreads();
-        if constexpr (kAnyReg) {
-            if (kt + 1 < KT) issue_tile(kt + 1, (kt + 1) % STAGES);
-        } else {
-            if (kt + STAGES - 1 < KT) issue_tile(kt + STAGES - 1, (kt + STAGES - 1) % STAGES);
-        }
-
-        const char *sbase = smem + buf * Cfg::STAGE_BYTES;
-        static_for<TK / 16>([&](auto kk_) {
-            constexpr int kk = decltype(kk_)::value;
-            u32x4_t af[MI], bf[NI];
-            const int xo = f_x ^ (kk * 32);
-            static_for<MI>([&](auto mi) {
-                af[mi] = *(const u32x4_t *)(sbase + a_frag_base + mi * 32 * 128 + xo);
-            });
+    // two register sets of MFMA fragments: one feeds the matrix cores while the other is being filled
+    u32x4_t af[2][MI], bf[2][NI];
+    auto read_frags = [&](auto set_, auto kk_, const char *sbase) {
+        constexpr int set = decltype(set_)::value, kk = decltype(kk_)::value;
+        const int xo = f_x ^ (kk * 32);
+        static_for<MI>([&](auto mi) {
+            af[set][mi] = *(const u32x4_t *)(sbase + a_frag_base + mi * 32 * ROW_BYTES + xo);
+        });
+        static_for<NI>([&](auto ni) {
+            bf[set][ni] = *(const u32x4_t *)(sbase + b_frag_base + ni * 32 * ROW_BYTES + xo);
+        });
+    };
+    auto mfma_step = [&](auto set_) {
+        constexpr int set = decltype(set_)::value;
+        // B fragment as the MFMA's first operand: the lane then holds 4 consecutive n per
+        // accumulator quad, which is what the row-major store wants.
+        static_for<MI>([&](auto mi) {
             static_for<NI>([&](auto ni) {
-                bf[ni] = *(const u32x4_t *)(sbase + b_frag_base + ni * 32 * 128 + xo);
-            });
-            // B fragment as the MFMA's first operand: the lane then holds 4 consecutive n per
-            // accumulator quad, which is what the row-major store wants.
-            static_for<MI>([&](auto mi) {
-                static_for<NI>([&](auto ni) { acc[mi][ni] = mfma32<Cfg::F16>(bf[ni], af[mi], acc[mi][ni]); });
+                acc[mi][ni] = mfma32<Cfg::F16>(bf[set][ni], af[set][mi], acc[mi][ni]);
             });
         });
-        if constexpr (kAnyReg) {
+    };
+    // Scheduling hints for one k-step (MI*NI MFMAs): spread the LDS fragment reads, and at the tile
+    // boundary the global -> LDS loads, between the MFMAs instead of ahead of them, so the matrix
+    // pipe keeps issuing while the wave's other instructions go out in its shadow.
+    constexpr int kMfmaPerStep = MI * NI, kDsPerStep = MI + NI;
+    auto interleave_ds_mfma = [&]() {
+#pragma unroll
+        for (int i = 0; i < kDsPerStep; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, (kMfmaPerStep + kDsPerStep - 1) / kDsPerStep > 2 ? 2 : 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, kMfmaPerStep, 0);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    // Tile boundary: the compiler must keep the next tile's fragment reads behind the global -> LDS
+    // loads (it cannot tell that they touch different stage buffers), so the loads go out under the
+    // first MFMAs of the step and the fragment reads under the rest.
+    auto interleave_all = [&]() {
+        constexpr int kVmemSlots = kMfmaPerStep > kDsPerStep ? kMfmaPerStep - kDsPerStep : 1;
+        constexpr int kPerSlot = (DMA_PER_TILE + kVmemSlots - 1) / kVmemSlots;
+#pragma unroll
+        for (int i = 0; i < kVmemSlots; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x020, kPerSlot, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < kDsPerStep; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, kMfmaPerStep, 0);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
+
+    if constexpr (kAnyReg) {
+        // ---- simple loop for operands that need the register transpose: prefetch distance 1 -----
+        issue(0, 0);
+        commit_regs(0);
+        for (int kt = 0; kt < KT; ++kt) {
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+            __syncthreads();
+            if (kt + 1 < KT) issue(kt + 1, (kt + 1) % STAGES);
+            const char *sbase = smem + (kt % STAGES) * Cfg::STAGE_BYTES;
+            static_for<KSTEPS>([&](auto kk) {
+                read_frags(I0{}, kk, sbase);
+                mfma_step(I0{});
+            });
             if (kt + 1 < KT) commit_regs((kt + 1) % STAGES);
         }
+    } else {
+        // ---- software-pipelined loop ---------------------------------------------------------------
+        // All STAGES buffers are filled up front.  Within a k-tile, the fragments of k-step kk+1 are
+        // read from LDS while the MFMAs of k-step kk run.  The one barrier per k-tile sits before the
+        // LAST k-step: by then this wave has issued every LDS read of the tile, so after the barrier
+        // the buffer can be refilled (k-tile kt+STAGES) and the next tile's first fragments fetched,
+        // both hidden under the MFMAs of the last k-step.
+        static_assert(KSTEPS % 2 == 0, "fragment sets alternate per k-step and must realign per stage");
+#pragma unroll
+        for (int s = 0; s < STAGES; ++s)
+            if (s < KT) issue(s, s);
+        if (KT > STAGES - 1) __builtin_amdgcn_s_waitcnt(vmcnt_imm((STAGES - 1) * DMA_PER_TILE));
+        else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+        __syncthreads();
+        read_frags(I0{}, I0{}, smem);
+        // all k-steps of a stage but the last: fragments of step kk+1 stream in under the MFMAs of step kk
+        auto head_steps = [&](const char *sbase) {
+            static_for<KSTEPS - 1>([&](auto kk_) {
+                constexpr int kk = decltype(kk_)::value;
+                read_frags(std::integral_constant<int, (kk + 1) & 1>{}, std::integral_constant<int, kk + 1>{}, sbase);
+                mfma_step(std::integral_constant<int, kk & 1>{});
+                interleave_ds_mfma();
+            });
+        };
+        // Steady state: every boundary refills the buffer it releases.  Kept as one straight-line
+        // block (no branch around MFMAs: 256 live accumulators do not survive control-flow joins
+        // without copies), hence the always-on K-tail test inside issue_tile.
+        int kt = 0;
+        for (; kt + STAGES < KT; ++kt) {
+            const int buf = kt % STAGES;
+            head_steps(smem + buf * Cfg::STAGE_BYTES);
+            // k-tile kt+1 must have landed; tiles kt+2 .. kt+STAGES-1 may still be in flight
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm((STAGES - 2) * DMA_PER_TILE));
+            __syncthreads();
+            issue_tile(std::true_type{}, kt + STAGES, buf);
+            read_frags(I0{}, I0{}, smem + ((kt + 1) % STAGES) * Cfg::STAGE_BYTES);
+            mfma_step(I1{});
+            interleave_all();
+        }
+        // Drain: nothing left to fetch.
+        for (; kt < KT - 1; ++kt) {
+            head_steps(smem + (kt % STAGES) * Cfg::STAGE_BYTES);
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+            __syncthreads();
+            read_frags(I0{}, I0{}, smem + ((kt + 1) % STAGES) * Cfg::STAGE_BYTES);
+            mfma_step(I1{});
+            interleave_ds_mfma();
+        }
+        head_steps(smem + ((KT - 1) % STAGES) * Cfg::STAGE_BYTES);
+        mfma_step(I1{});
     }
 
     // ---- epilogue: chain on registers, round once, store ----------------------------------------

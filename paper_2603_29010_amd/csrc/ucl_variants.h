@@ -5,7 +5,7 @@
 namespace ucl {
 
 struct VariantDesc {
-    int tile_m, tile_n, stages;
+    int tile_m, tile_n, tile_k, stages;
     int f16;            // 1: fp16 inputs, 0: bf16 inputs
     int mode;           // 0 gemm / batched, 1 grouped, 2 conv2d fprop
     int la, lb;         // 0: operand contiguous along K, 1: contiguous along M / N, 2: im2col (A only)
@@ -19,7 +19,8 @@ struct VariantList {
 };
 
 // one per instantiation unit
-VariantList variants_gemm_kk_bf16();
+VariantList variants_gemm_kk_bf16_a();
+VariantList variants_gemm_kk_bf16_b();
 VariantList variants_gemm_kk_f16();
 VariantList variants_gemm_mn_bf16();
 VariantList variants_gemm_mn_f16();

@@ -12,17 +12,32 @@ import parity
 pytestmark = pytest.mark.gpu
 
 
-def T(tm, tn, st, raster=0):
-    return Tuning(tm, tn, 64, st, raster)
+import paper_2603_29010_amd as ucl
 
 
-KK_TILES = [(256, 256, 2), (256, 128, 2), (128, 128, 2), (128, 128, 3), (64, 64, 2), (64, 64, 4)]
+def T(tm, tn, tk, st, raster=0):
+    return Tuning(tm, tn, tk, st, raster)
+
+
+def built(mode, f16=0, la=None, lb=0):
+    """(tile_m, tile_n, tile_k, stages) of every kernel variant built for a problem class."""
+    la = (2 if mode == 2 else 0) if la is None else la
+    out = []
+    for i in range(ucl.ucl_num_variants()):
+        v = ucl.ucl_variant(i)
+        if (v["mode"], v["f16"], v["la"], v["lb"]) == (mode, f16, la, lb):
+            out.append((v["tile_m"], v["tile_n"], v["tile_k"], v["stages"]))
+    assert out
+    return out
+
+
+KK_TILES = built(0)
+KK_TILES_F16 = built(0, f16=1)
 
 
 # ---------------------------------------------------------------- exact (integer) indexing tests
 
-@pytest.mark.parametrize("tile", KK_TILES)
-@pytest.mark.parametrize("dt", ["bf16", "f16"])
+@pytest.mark.parametrize("tile,dt", [(t, "bf16") for t in KK_TILES] + [(t, "f16") for t in KK_TILES_F16])
 def test_gemm_exact_every_tile(tile, dt):
     # ragged in M and N, K tail (K = 200 = 3*64 + 8), several tiles in each direction
     spec = synth.gemm_spec(328, 264, 200, dt_in=dt, dt_out="f32", epilogue=(), integer=True)
@@ -30,11 +45,12 @@ def test_gemm_exact_every_tile(tile, dt):
 
 
 @pytest.mark.parametrize("a_layout,b_layout", [("row", "row"), ("col", "col"), ("col", "row")])
-@pytest.mark.parametrize("tile", [(128, 128, 2), (64, 64, 2)])
-def test_gemm_exact_transposed_layouts(a_layout, b_layout, tile):
-    spec = synth.gemm_spec(200, 136, 72, dt_out="f32", a_layout=a_layout, b_layout=b_layout, epilogue=(),
+@pytest.mark.parametrize("dt", ["bf16", "f16"])
+def test_gemm_exact_transposed_layouts(a_layout, b_layout, dt):
+    spec = synth.gemm_spec(200, 136, 72, dt_in=dt, dt_out="f32", a_layout=a_layout, b_layout=b_layout, epilogue=(),
                            integer=True)
-    parity.check_exact(spec, T(*tile), label=f"{a_layout}/{b_layout}")
+    for tile in built(0, f16=int(dt == "f16"), la=int(a_layout == "col"), lb=int(b_layout == "row")):
+        parity.check_exact(spec, T(*tile), label=f"{a_layout}/{b_layout}{tile}")
 
 
 @pytest.mark.parametrize("shape", [(1, 8, 8), (8, 1, 8), (7, 5, 16), (64, 64, 64), (65, 63, 64), (1, 1, 8)])
@@ -53,19 +69,20 @@ def test_gemm_exact_bf16_output_and_odd_n():
 @pytest.mark.parametrize("raster", [1, 2, 8, 16])
 def test_gemm_exact_raster_orders(raster):
     spec = synth.gemm_spec(640, 448, 64, dt_out="f32", epilogue=(), integer=True)
-    parity.check_exact(spec, T(64, 64, 2, raster), label=f"raster{raster}")
+    parity.check_exact(spec, T(64, 64, 64, 2, raster), label=f"raster{raster}")
 
 
 def test_batched_exact():
     spec = synth.batched_spec(5, 136, 72, 24, dt_out="f32", epilogue=(), integer=True)
     parity.check_exact(spec)
-    parity.check_exact(spec, T(64, 64, 2))
+    for tile in KK_TILES_F16:
+        parity.check_exact(spec, T(*tile), label=f"batched{tile}")
 
 
 def test_grouped_exact_ragged_offsets():
     M_g = [64, 0, 200, 8, 321, 0, 128, 1]
     spec = synth.grouped_spec(M_g, 136, 72, dt_out="f32", epilogue=(), integer=True)
-    for tile in [(256, 256, 2), (128, 128, 3), (64, 64, 2)]:
+    for tile in built(1):
         parity.check_exact(spec, T(*tile), label=f"grouped{tile}")
 
 
@@ -79,7 +96,7 @@ def test_grouped_exact_ragged_offsets():
 ])
 def test_conv_exact_every_halo_position(geom):
     spec = synth.conv_spec(dt_out="f32", epilogue=(), integer=True, **geom)
-    for tile in [(256, 128, 2), (128, 128, 3), (64, 64, 2)]:
+    for tile in built(2):
         parity.check_exact(spec, T(*tile), label=f"conv{tile}")
 
 
@@ -148,14 +165,20 @@ def test_batched_parity_with_residual():
 
 def test_grouped_parity_silu():
     spec = synth.grouped_spec([192, 64, 0, 448, 128], 264, 136)
-    for tile in [(256, 256, 2), (128, 128, 3)]:
-        parity.check(spec, T(*tile))
+    for tile in built(1):
+        parity.check(spec, T(*tile), label=f"grouped{tile}")
+    spec16 = synth.grouped_spec([192, 64, 0, 448, 128], 264, 136, dt_in="f16", dt_out="f16")
+    for tile in built(1, f16=1):
+        parity.check(spec16, T(*tile), label=f"grouped f16 {tile}")
 
 
 def test_conv_parity_bias_residual_relu():
     spec = synth.conv_spec(3, 14, 14, 64, 128, 3, 3)
-    for tile in [(256, 128, 2), (128, 128, 3), (64, 64, 2)]:
+    for tile in built(2):
         parity.check(spec, T(*tile), label=f"conv{tile}")
+    spec16 = synth.conv_spec(3, 14, 14, 64, 128, 3, 3, dt_in="f16", dt_out="f32")
+    for tile in built(2, f16=1):
+        parity.check(spec16, T(*tile), label=f"conv f16 {tile}")
 
 
 # ---------------------------------------------------------------- the benchmark configurations
