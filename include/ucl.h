@@ -24,9 +24,11 @@
  *     grammar notes, constraint 3): A and B base pointers are 16-byte aligned,
  *     one of their two strides is 1 and the other a multiple of 8, and K (for
  *     K-contiguous operands) or M / N (for operands contiguous along M / N) is
- *     a multiple of 8.  D may have any N; it is written with 128-bit stores
- *     when its leading stride is a multiple of 4 and its base 16-byte aligned,
- *     with scalar stores otherwise.
+ *     a multiple of 8.  D and the epilogue's tensor operands may have any N and
+ *     any strides; they are accessed with 128-bit loads / stores when base and
+ *     row starts are 16-byte aligned (leading and batch strides multiples of 8
+ *     for 16-bit types, of 4 for fp32), element by element otherwise.  In
+ *     ucl_grouped_gemm every per-group pointer must be 16-byte aligned.
  *   - Errors: a nonzero ucl_status is returned BEFORE anything is launched;
  *     ucl_last_error() gives a thread-local sentence saying what was wrong and
  *     why (the paper's compiler explains failed validation the same way,

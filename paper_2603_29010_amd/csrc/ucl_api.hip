@@ -114,6 +114,8 @@ int default_raster(const VariantDesc &v, const Launch &L) {
 
 ucl_status check_epilogue(const ucl_epilogue *epi, const Launch &L, KParams &kp) {
     kp.n_steps = 0;
+    memset(&kp.fused, 0, sizeof(kp.fused));
+    kp.fused.enabled = 1;             // the empty chain is the trivial fused form
     if (!epi) return UCL_OK;
     if (epi->n_steps < 0 || epi->n_steps > UCL_MAX_EPI_STEPS)
         return fail(UCL_ERR_INVALID_ARG, "epilogue has %d steps; the chain holds 0..%d", epi->n_steps, UCL_MAX_EPI_STEPS);
@@ -126,16 +128,11 @@ ucl_status check_epilogue(const ucl_epilogue *epi, const Launch &L, KParams &kp)
         if (op_has_tensor(s.op)) {
             if (!s.ptr) return fail(UCL_ERR_INVALID_ARG, "epilogue step %d needs a tensor operand but ptr is NULL", i);
             if (!valid_dtype(s.dtype)) return fail(UCL_ERR_INVALID_ARG, "epilogue step %d: bad tensor dtype %d", i, s.dtype);
-            const int per16 = 4;   // 4-element vector accesses
+            // 128-bit accesses of 8 (16-bit) or 4 (fp32) elements need 16-byte aligned rows
+            const int per16 = 16 / elem_size(s.dtype);
             bool vec = true;
-            if (L.mode == 1) {
-                // per-group pointers live on the device: alignment cannot be checked here; vector
-                // access is used only if the strides allow it and the caller's pointers are assumed
-                // 16-byte aligned (documented in ucl.h for every tensor operand).
-                vec = true;
-            } else {
-                vec = (reinterpret_cast<uintptr_t>(s.ptr) % (per16 * elem_size(s.dtype))) == 0;
-            }
+            if (L.mode != 1) vec = aligned16(s.ptr);
+            // (grouped: the per-group pointers live on the device and are required to be 16-byte aligned)
             if (op_is_matrix(s.op)) {
                 if (s.ld < L.N) return fail(UCL_ERR_INVALID_ARG, "epilogue step %d: ld=%lld is smaller than N=%lld", i, (long long)s.ld, (long long)L.N);
                 vec = vec && (s.ld % per16 == 0) && (s.bs % per16 == 0);
@@ -146,6 +143,32 @@ ucl_status check_epilogue(const ucl_epilogue *epi, const Launch &L, KParams &kp)
             return fail(UCL_ERR_INVALID_ARG, "epilogue step %d: clamp(min=%g, max=%g) has min > max", i, s.p0, s.p1);
     }
     kp.n_steps = epi->n_steps;
+    // Recognise  [scale] [bias | row_broadcast] [aux_load] [one activation]  in that order.
+    FusedEpi f;
+    memset(&f, 0, sizeof(f));
+    int i = 0;
+    const int n = epi->n_steps;
+    if (i < n && kp.steps[i].op == UCL_EPI_SCALE) { f.has_scale = 1; f.alpha = kp.steps[i].p0; ++i; }
+    if (i < n && (kp.steps[i].op == UCL_EPI_BIAS || kp.steps[i].op == UCL_EPI_ROW_BROADCAST)) {
+        f.has_bias = 1; f.bias = kp.steps[i].ptr; f.bias_dt = kp.steps[i].dtype; ++i;
+    }
+    if (i < n && kp.steps[i].op == UCL_EPI_AUX_LOAD) {
+        f.has_res = 1; f.res = kp.steps[i].ptr; f.res_dt = kp.steps[i].dtype; f.beta = kp.steps[i].p0;
+        f.res_ld = kp.steps[i].ld; f.res_bs = kp.steps[i].bs; ++i;
+    }
+    if (i < n) {
+        switch (kp.steps[i].op) {
+        case UCL_EPI_RELU: case UCL_EPI_GELU_TANH: case UCL_EPI_GELU_ERF: case UCL_EPI_SILU: case UCL_EPI_SIGMOID:
+        case UCL_EPI_TANH: case UCL_EPI_MISH: case UCL_EPI_HARDSWISH: case UCL_EPI_LEAKY_RELU: case UCL_EPI_ELU:
+        case UCL_EPI_CLAMP:
+            f.act = kp.steps[i].op; f.act_p0 = kp.steps[i].p0; f.act_p1 = kp.steps[i].p1; ++i;
+            break;
+        default:
+            break;
+        }
+    }
+    f.enabled = (i == n);
+    kp.fused = f;
     return UCL_OK;
 }
 
@@ -271,7 +294,7 @@ ucl_status gemm_like(int64_t batch, int64_t M, int64_t N, int64_t K,
     kp.ldd = d_rs; kp.a_bs = a_bs; kp.b_bs = b_bs; kp.d_bs = d_bs;
     kp.M = (int32_t)M; kp.N = (int32_t)N; kp.K = (int32_t)K;
     kp.dtD = dtD;
-    kp.d_vec = (reinterpret_cast<uintptr_t>(D) % (4 * elem_size(dtD)) == 0) && (d_rs % 4 == 0) && (d_bs % 4 == 0);
+    kp.d_vec = aligned16(D) && (d_rs % (16 / elem_size(dtD)) == 0) && (d_bs % (16 / elem_size(dtD)) == 0);
     return run(L, kp, nullptr, tune, stream);
 }
 
@@ -390,7 +413,7 @@ ucl_status ucl_grouped_gemm(int32_t groups, const int64_t *M_g, int64_t N, int64
     kp.A_g = A_g; kp.B_g = B_g; kp.D_g = D_g;
     kp.lda = a_rs; kp.ldb = b_cs; kp.ldd = d_rs;
     kp.N = (int32_t)N; kp.K = (int32_t)K; kp.groups = groups; kp.dtD = dtD;
-    kp.d_vec = d_rs % 4 == 0;      // group base pointers are required to be 16-byte aligned
+    kp.d_vec = d_rs % (16 / elem_size(dtD)) == 0;      // group base pointers are required to be 16-byte aligned
     return run(L, kp, nullptr, tune, stream);
 }
 
@@ -423,7 +446,7 @@ ucl_status ucl_conv2d_fprop(int64_t N, int64_t H, int64_t W, int64_t C, int64_t 
     kp.cH = (int32_t)H; kp.cW = (int32_t)W; kp.cC = (int32_t)C; kp.cS = (int32_t)S; kp.cP = (int32_t)P; kp.cQ = (int32_t)Q;
     kp.pad_h = (int32_t)pad_h; kp.pad_w = (int32_t)pad_w; kp.str_h = (int32_t)stride_h; kp.str_w = (int32_t)stride_w;
     kp.dil_h = (int32_t)dil_h; kp.dil_w = (int32_t)dil_w;
-    kp.d_vec = (reinterpret_cast<uintptr_t>(y) % (4 * elem_size(dtY)) == 0) && (Kout % 4 == 0);
+    kp.d_vec = aligned16(y) && (Kout % (16 / elem_size(dtY)) == 0);
     return run(L, kp, nullptr, tune, stream);
 }
 

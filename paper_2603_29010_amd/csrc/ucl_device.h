@@ -19,6 +19,21 @@ struct EpiStepDev {
     int64_t bs;
 };
 
+// A chain of the common shape  act( alpha * acc + bias[n] + beta * R[m,n] )  -- any of the four parts
+// optional, in that order -- is recognised on the host and runs through straight-line epilogue code;
+// every other chain is interpreted step by step.
+struct FusedEpi {
+    int32_t enabled;
+    int32_t has_scale, has_bias, has_res;
+    int32_t act;                      // ucl_epi_op of the activation, 0 = none
+    int32_t bias_dt, res_dt;          // ucl_dtype | 0x100 if 128-bit access is allowed
+    int32_t pad_;
+    float alpha, beta, act_p0, act_p1;
+    const void *bias;                 // grouped: device table of per-group pointers
+    const void *res;
+    int64_t res_ld, res_bs;
+};
+
 // Kernel arguments, passed by value (kernarg segment).
 struct KParams {
     const void *A;
@@ -41,7 +56,8 @@ struct KParams {
     int32_t pad_h, pad_w, str_h, str_w, dil_h, dil_w;
     int32_t n_steps;
     int32_t pad_;
-    EpiStepDev steps[UCL_MAX_EPI_STEPS];
+    EpiStepDev steps[UCL_MAX_EPI_STEPS];   // must stay addressable as offsetof(KParams, steps)
+    FusedEpi fused;
 };
 
 struct GroupTable {

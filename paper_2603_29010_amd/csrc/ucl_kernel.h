@@ -15,6 +15,7 @@
 //   epilogue       : the `>>` chain interpreted on the accumulator registers (fp32), one rounding
 //                    to the output type, vector stores straight from registers.
 #pragma once
+#include <cstddef>
 #include <type_traits>
 #include <utility>
 
@@ -65,34 +66,63 @@ __device__ __forceinline__ float bits_to_f32(uint32_t raw16, int dtype) {
     return (float)c.h;
 }
 
-// Four consecutive elements starting at element index idx; lanes with nvalid < 4 read only what exists.
-__device__ __forceinline__ f32x4_t load4(const void *base, int dtype, int64_t idx, bool vec, int nvalid) {
-    f32x4_t r = {0.f, 0.f, 0.f, 0.f};
+// ---- epilogue operand access: 8 consecutive elements along n per lane ---------------------------
+
+// Raw result of an 8-element load, decoded later so that several loads can be in flight at once.
+struct Raw8 {
+    u32x4_t lo, hi;     // packed: eight 16-bit patterns in lo.  Otherwise eight fp32 values in lo, hi.
+    bool packed;
+};
+
+// Elements [idx, idx+8) of a tensor of type dtype; lanes with nvalid < 8 read only what exists
+// (the rest decode to 0).  `vec`: base + idx is 16-byte aligned for every lane (host-checked).
+__device__ __forceinline__ Raw8 load8(const void *base, int dtype, int64_t idx, bool vec, int nvalid) {
+    Raw8 r;
+    r.lo = u32x4_t{0, 0, 0, 0};
+    r.hi = u32x4_t{0, 0, 0, 0};
+    r.packed = false;
     if (nvalid <= 0) return r;
-    if (dtype == UCL_F32) {
-        const float *p = (const float *)base + idx;
-        if (vec && nvalid >= 4) {
-            r = *(const f32x4_t *)p;
+    if (vec && nvalid >= 8) {
+        if (dtype == UCL_F32) {
+            const u32x4_t *p = (const u32x4_t *)((const float *)base + idx);
+            r.lo = p[0];
+            r.hi = p[1];
         } else {
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-                if (e < nvalid) r[e] = p[e];
+            r.lo = *(const u32x4_t *)((const uint16_t *)base + idx);
+            r.packed = true;
         }
-    } else {
-        const uint16_t *p = (const uint16_t *)base + idx;
-        if (vec && nvalid >= 4) {
-            const u32x2_t w = *(const u32x2_t *)p;
-            r[0] = bits_to_f32(w[0] & 0xffffu, dtype);
-            r[1] = bits_to_f32(w[0] >> 16, dtype);
-            r[2] = bits_to_f32(w[1] & 0xffffu, dtype);
-            r[3] = bits_to_f32(w[1] >> 16, dtype);
-        } else {
+        return r;
+    }
+    float t[8];
 #pragma unroll
-            for (int e = 0; e < 4; ++e)
-                if (e < nvalid) r[e] = bits_to_f32(p[e], dtype);
-        }
+    for (int e = 0; e < 8; ++e) {
+        t[e] = 0.f;
+        if (e < nvalid)
+            t[e] = dtype == UCL_F32 ? ((const float *)base)[idx + e]
+                                    : bits_to_f32(((const uint16_t *)base)[idx + e], dtype);
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        r.lo[e] = __float_as_uint(t[e]);
+        r.hi[e] = __float_as_uint(t[4 + e]);
     }
     return r;
+}
+
+__device__ __forceinline__ void decode8(const Raw8 &r, int dtype, float (&out)[8]) {
+    if (r.packed) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            out[2 * e] = bits_to_f32(r.lo[e] & 0xffffu, dtype);
+            out[2 * e + 1] = bits_to_f32(r.lo[e] >> 16, dtype);
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            out[e] = __uint_as_float(r.lo[e]);
+            out[4 + e] = __uint_as_float(r.hi[e]);
+        }
+    }
 }
 
 __device__ __forceinline__ uint32_t f32_to_bits16(float v, int dtype) {
@@ -106,30 +136,29 @@ __device__ __forceinline__ uint32_t f32_to_bits16(float v, int dtype) {
     return c.u;
 }
 
-__device__ __forceinline__ void store4(void *base, int dtype, int64_t idx, f32x4_t v, bool vec, int nvalid) {
+// One rounding to the stored type, then 128-bit stores where alignment allows.
+__device__ __forceinline__ void store8(void *base, int dtype, int64_t idx, const float (&v)[8], bool vec, int nvalid) {
     if (nvalid <= 0) return;
     if (dtype == UCL_F32) {
         float *p = (float *)base + idx;
-        if (vec && nvalid >= 4) {
-            *(f32x4_t *)p = v;
+        if (vec && nvalid >= 8) {
+            ((f32x4_t *)p)[0] = f32x4_t{v[0], v[1], v[2], v[3]};
+            ((f32x4_t *)p)[1] = f32x4_t{v[4], v[5], v[6], v[7]};
         } else {
 #pragma unroll
-            for (int e = 0; e < 4; ++e)
+            for (int e = 0; e < 8; ++e)
                 if (e < nvalid) p[e] = v[e];
         }
     } else {
         uint16_t *p = (uint16_t *)base + idx;
-        const uint32_t b0 = f32_to_bits16(v[0], dtype), b1 = f32_to_bits16(v[1], dtype);
-        const uint32_t b2 = f32_to_bits16(v[2], dtype), b3 = f32_to_bits16(v[3], dtype);
-        if (vec && nvalid >= 4) {
-            u32x2_t w;
-            w[0] = b0 | (b1 << 16);
-            w[1] = b2 | (b3 << 16);
-            *(u32x2_t *)p = w;
-        } else {
-            const uint32_t b[4] = {b0, b1, b2, b3};
+        uint32_t b[8];
 #pragma unroll
-            for (int e = 0; e < 4; ++e)
+        for (int e = 0; e < 8; ++e) b[e] = f32_to_bits16(v[e], dtype);
+        if (vec && nvalid >= 8) {
+            *(u32x4_t *)p = u32x4_t{b[0] | (b[1] << 16), b[2] | (b[3] << 16), b[4] | (b[5] << 16), b[6] | (b[7] << 16)};
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
                 if (e < nvalid) p[e] = (uint16_t)b[e];
         }
     }
@@ -137,137 +166,139 @@ __device__ __forceinline__ void store4(void *base, int dtype, int64_t idx, f32x4
 
 __device__ __forceinline__ float sigmoid_f32(float u) { return 1.0f / (1.0f + __expf(-u)); }
 
-// One step of the chain on the 16 accumulators a lane holds for one 32x32 block:
-// element j <-> output (m, n_base + 8*(j/4) + (j%4)), n_base already includes 4*(lane/32).
+// The element-wise activations of the vocabulary, fp32.
+template <int OP>
+__device__ __forceinline__ float act_f32(float x, float p0, float p1) {
+    if constexpr (OP == UCL_EPI_RELU) return fmaxf(x, 0.f);
+    else if constexpr (OP == UCL_EPI_LEAKY_RELU) return x > 0.f ? x : p0 * x;
+    else if constexpr (OP == UCL_EPI_CLAMP) return fminf(fmaxf(x, p0), p1);
+    else if constexpr (OP == UCL_EPI_HARDSWISH) return x * fminf(fmaxf(x + 3.f, 0.f), 6.f) * (1.f / 6.f);
+    else if constexpr (OP == UCL_EPI_GELU_TANH) {
+        // 0.5 (1 + tanh u) = sigmoid(2u),  u = sqrt(2/pi) (x + 0.044715 x^3)
+        return x * sigmoid_f32(1.5957691216057308f * (x + 0.044715f * x * x * x));
+    } else if constexpr (OP == UCL_EPI_SILU) return x * sigmoid_f32(x);
+    else if constexpr (OP == UCL_EPI_SIGMOID) return sigmoid_f32(x);
+    else if constexpr (OP == UCL_EPI_TANH) return tanhf(x);
+    else if constexpr (OP == UCL_EPI_GELU_ERF) return 0.5f * x * (1.f + erff(x * 0.7071067811865476f));
+    else if constexpr (OP == UCL_EPI_MISH) {
+        // tanh(log(1 + e^x)) = w (w + 2) / (w (w + 2) + 2) with w = e^x; for large x the factor is 1
+        const float w = __expf(fminf(x, 20.f));
+        const float q = w * (w + 2.f);
+        return x > 20.f ? x : x * (q / (q + 2.f));
+    } else if constexpr (OP == UCL_EPI_ELU) return x > 0.f ? x : p0 * expm1f(x);
+    else return x;
+}
+
+// Where a lane stands in the output while it runs the chain: 8 consecutive columns of one row.
 struct EpiCtx {
     int64_t m;          // row within the (sub)problem
-    int n_base;         // column of element 0
-    int m_ok;           // row < M
-    int N;
+    int n;              // first of the lane's 8 columns
+    int nvalid;         // how many of them exist (<= 0: none; row out of range counts as none)
     int batch;          // batch index (bs multiplier)
     int group;          // grouped: index into per-group pointer tables, else -1
 };
 
-__device__ __forceinline__ const void *step_ptr(const EpiStepDev &s, const EpiCtx &c) {
-    if (c.group >= 0) return ((const void *const *)s.ptr)[c.group];
+__device__ __forceinline__ const void *step_ptr(const EpiStepDev &s, int group) {
+    if (group >= 0) return ((const void *const *)s.ptr)[group];
     return s.ptr;
 }
 
-__device__ __forceinline__ void apply_step(float (&v)[16], const EpiStepDev &s, const EpiCtx &c) {
+__device__ __forceinline__ bool op_is_nvec(int op) {
+    return op == UCL_EPI_BIAS || op == UCL_EPI_ROW_BROADCAST || op == UCL_EPI_PER_COL_SCALE;
+}
+
+// One step of the chain on the lane's 8 values.  If has_pre, `pre` is the step's tensor operand
+// already fetched for exactly this position: an n-indexed vector or an AUX_LOAD row segment.
+__device__ __forceinline__ void apply_step(float (&v)[8], const EpiStepDev &s, const EpiCtx &c, const Raw8 &pre,
+                                           bool has_pre) {
     const int dt = s.dtype & 0xff;
     const bool vec = (s.dtype & 0x100) != 0;
     switch (s.op) {
     case UCL_EPI_SCALE:
 #pragma unroll
-        for (int j = 0; j < 16; ++j) v[j] *= s.p0;
+        for (int j = 0; j < 8; ++j) v[j] *= s.p0;
         break;
     case UCL_EPI_BIAS:
     case UCL_EPI_ROW_BROADCAST:
     case UCL_EPI_PER_COL_SCALE: {
-        const void *base = step_ptr(s, c);
+        float t[8];
+        if (has_pre) decode8(pre, dt, t);
+        else decode8(load8(step_ptr(s, c.group), dt, c.n, vec, c.nvalid), dt, t);
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const int n = c.n_base + 8 * g;
-            const f32x4_t t = load4(base, dt, n, vec, c.N - n);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                if (s.op == UCL_EPI_PER_COL_SCALE) v[4 * g + e] *= t[e];
-                else v[4 * g + e] += t[e];
-            }
+        for (int j = 0; j < 8; ++j) {
+            if (s.op == UCL_EPI_PER_COL_SCALE) v[j] *= t[j];
+            else v[j] += t[j];
         }
         break;
     }
     case UCL_EPI_PER_ROW_SCALE:
     case UCL_EPI_COL_BROADCAST: {
         float t = 0.f;
-        if (c.m_ok) {
-            const void *base = step_ptr(s, c);
+        if (c.nvalid > 0) {
+            const void *base = step_ptr(s, c.group);
             t = dt == UCL_F32 ? ((const float *)base)[c.m] : bits_to_f32(((const uint16_t *)base)[c.m], dt);
         }
 #pragma unroll
-        for (int j = 0; j < 16; ++j) {
+        for (int j = 0; j < 8; ++j) {
             if (s.op == UCL_EPI_PER_ROW_SCALE) v[j] *= t;
             else v[j] += t;
         }
         break;
     }
     case UCL_EPI_AUX_LOAD: {
-        const void *base = step_ptr(s, c);
-        const int64_t row = (int64_t)c.batch * s.bs + c.m * s.ld;
+        float t[8];
+        if (has_pre) decode8(pre, dt, t);
+        else decode8(load8(step_ptr(s, c.group), dt, (int64_t)c.batch * s.bs + c.m * s.ld + c.n, vec, c.nvalid), dt, t);
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const int n = c.n_base + 8 * g;
-            const f32x4_t t = load4(base, dt, row + n, vec, c.m_ok ? c.N - n : 0);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) v[4 * g + e] += s.p0 * t[e];
-        }
+        for (int j = 0; j < 8; ++j) v[j] += s.p0 * t[j];
         break;
     }
-    case UCL_EPI_AUX_STORE: {
-        void *base = (void *)step_ptr(s, c);
-        const int64_t row = (int64_t)c.batch * s.bs + c.m * s.ld;
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const int n = c.n_base + 8 * g;
-            const f32x4_t t = {v[4 * g], v[4 * g + 1], v[4 * g + 2], v[4 * g + 3]};
-            store4(base, dt, row + n, t, vec, c.m_ok ? c.N - n : 0);
-        }
+    case UCL_EPI_AUX_STORE:
+        store8((void *)step_ptr(s, c.group), dt, (int64_t)c.batch * s.bs + c.m * s.ld + c.n, v, vec, c.nvalid);
         break;
-    }
     case UCL_EPI_RELU:
 #pragma unroll
-        for (int j = 0; j < 16; ++j) v[j] = fmaxf(v[j], 0.f);
+        for (int j = 0; j < 8; ++j) v[j] = act_f32<UCL_EPI_RELU>(v[j], s.p0, s.p1);
         break;
     case UCL_EPI_LEAKY_RELU:
 #pragma unroll
-        for (int j = 0; j < 16; ++j) v[j] = v[j] > 0.f ? v[j] : s.p0 * v[j];
+        for (int j = 0; j < 8; ++j) v[j] = act_f32<UCL_EPI_LEAKY_RELU>(v[j], s.p0, s.p1);
         break;
     case UCL_EPI_CLAMP:
 #pragma unroll
-        for (int j = 0; j < 16; ++j) v[j] = fminf(fmaxf(v[j], s.p0), s.p1);
+        for (int j = 0; j < 8; ++j) v[j] = act_f32<UCL_EPI_CLAMP>(v[j], s.p0, s.p1);
         break;
     case UCL_EPI_HARDSWISH:
 #pragma unroll
-        for (int j = 0; j < 16; ++j) v[j] = v[j] * fminf(fmaxf(v[j] + 3.f, 0.f), 6.f) * (1.f / 6.f);
+        for (int j = 0; j < 8; ++j) v[j] = act_f32<UCL_EPI_HARDSWISH>(v[j], s.p0, s.p1);
         break;
     case UCL_EPI_GELU_TANH:
-        // 0.5 (1 + tanh u) = sigmoid(2u),  u = sqrt(2/pi) (v + 0.044715 v^3)
 #pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            const float x = v[j];
-            const float u = 1.5957691216057308f * (x + 0.044715f * x * x * x);
-            v[j] = x * sigmoid_f32(u);
-        }
+        for (int j = 0; j < 8; ++j) v[j] = act_f32<UCL_EPI_GELU_TANH>(v[j], s.p0, s.p1);
         break;
     case UCL_EPI_SILU:
 #pragma unroll
-        for (int j = 0; j < 16; ++j) v[j] = v[j] * sigmoid_f32(v[j]);
+        for (int j = 0; j < 8; ++j) v[j] = act_f32<UCL_EPI_SILU>(v[j], s.p0, s.p1);
         break;
     case UCL_EPI_SIGMOID:
 #pragma unroll
-        for (int j = 0; j < 16; ++j) v[j] = sigmoid_f32(v[j]);
+        for (int j = 0; j < 8; ++j) v[j] = act_f32<UCL_EPI_SIGMOID>(v[j], s.p0, s.p1);
         break;
     case UCL_EPI_TANH:
 #pragma unroll
-        for (int j = 0; j < 16; ++j) v[j] = tanhf(v[j]);
+        for (int j = 0; j < 8; ++j) v[j] = act_f32<UCL_EPI_TANH>(v[j], s.p0, s.p1);
         break;
     case UCL_EPI_GELU_ERF:
 #pragma unroll
-        for (int j = 0; j < 16; ++j) v[j] = 0.5f * v[j] * (1.f + erff(v[j] * 0.7071067811865476f));
+        for (int j = 0; j < 8; ++j) v[j] = act_f32<UCL_EPI_GELU_ERF>(v[j], s.p0, s.p1);
         break;
     case UCL_EPI_MISH:
-        // tanh(log(1 + e^x)) = w (w + 2) / (w (w + 2) + 2) with w = e^x; for large x the factor is 1
 #pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            const float x = v[j];
-            const float w = __expf(fminf(x, 20.f));
-            const float q = w * (w + 2.f);
-            v[j] = x > 20.f ? x : x * (q / (q + 2.f));
-        }
+        for (int j = 0; j < 8; ++j) v[j] = act_f32<UCL_EPI_MISH>(v[j], s.p0, s.p1);
         break;
     case UCL_EPI_ELU:
 #pragma unroll
-        for (int j = 0; j < 16; ++j) v[j] = v[j] > 0.f ? v[j] : s.p0 * expm1f(v[j]);
+        for (int j = 0; j < 8; ++j) v[j] = act_f32<UCL_EPI_ELU>(v[j], s.p0, s.p1);
         break;
     default:
         break;
@@ -289,7 +320,11 @@ struct KernelCfg {
     static constexpr int MI = WTM / 32, NI = WTN / 32;            // 32x32 MFMA blocks per wave
     static constexpr int A_BYTES = TM * TK * 2, B_BYTES = TN * TK * 2;
     static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
-    static constexpr int LDS_BYTES = STAGES * STAGE_BYTES;
+    static constexpr int PIPE_BYTES = STAGES * STAGE_BYTES;
+    // epilogue staging: per wave 32 rows x (WTN + 4) fp32 (16 bytes of padding per row)
+    static constexpr int EPI_LD = TN / 2 + 4;
+    static constexpr int EPI_BYTES = 4 * 32 * EPI_LD * 4;
+    static constexpr int LDS_BYTES = PIPE_BYTES > EPI_BYTES ? PIPE_BYTES : EPI_BYTES;
     static constexpr int A_ITERS = TM * CPR / kThreads;           // 16-byte chunks per thread per stage
     static constexpr int B_ITERS = TN * CPR / kThreads;
     static constexpr int ROWS_PER_ITER = kThreads / CPR;          // rows covered by one 256-thread copy
@@ -303,7 +338,7 @@ struct KernelCfg {
 static __device__ __attribute__((aligned(16))) const uint32_t g_zero_chunk[4] = {0u, 0u, 0u, 0u};
 
 template <bool F16>
-__device__ __forceinline__ f32x16_t mfma32(const u32x4_t &a, const u32x4_t &b, const f32x16_t &c) {
+__device__ __forceinline__ f32x16_t mfma32(u32x4_t a, u32x4_t b, f32x16_t c) {
     if constexpr (F16) {
         return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b),
                                                       c, 0, 0, 0);
@@ -652,32 +687,233 @@ __global__ __launch_bounds__(kThreads) void ucl_tile_kernel(const KParams p, con
         mfma_step(I1{});
     }
 
-    // ---- epilogue: chain on registers, round once, store ----------------------------------------
+    // ---- epilogue ---------------------------------------------------------------------------------
+    // The accumulators leave the MFMA layout (a lane holds 4 consecutive n of ONE row per quad)
+    // through a wave-private LDS patch, one 32-row block at a time, and come back as 8 consecutive
+    // n per lane with the lanes of a row side by side.  The chain then runs on registers in that
+    // layout, so bias / residual loads and the output stores are all full 128-bit accesses that
+    // cover whole contiguous row segments.
+    constexpr int WTN = Cfg::WTN, EPI_LD = Cfg::EPI_LD;
+    constexpr int LPR = WTN / 8;              // lanes per staged row
+    constexpr int RPP = 64 / LPR;             // rows per pass
+    constexpr int PASSES = 32 / RPP;
+    constexpr int kMaxNVec = 4, kMaxMat = 2;  // tensor operands fetched ahead of use; others load in place
+    __syncthreads();                          // every wave is done with the pipeline buffers
+    // The chain is walked with a run-time step index.  Steps are read straight from the kernel
+    // argument segment (constant address space, uniform index => scalar loads into SGPRs); `p` is
+    // the kernel's first argument, so its step table sits at offsetof(KParams, steps).
+    typedef const __attribute__((address_space(4))) EpiStepDev ConstStep;
+    ConstStep *const ksteps = (ConstStep *)((const __attribute__((address_space(4))) char *)
+                                                __builtin_amdgcn_kernarg_segment_ptr() + offsetof(KParams, steps));
+    auto get_step = [&](int s) __attribute__((always_inline)) {
+        EpiStepDev st;
+        st.op = ksteps[s].op;
+        st.dtype = ksteps[s].dtype;
+        st.p0 = ksteps[s].p0;
+        st.p1 = ksteps[s].p1;
+        st.ptr = ksteps[s].ptr;
+        st.ld = ksteps[s].ld;
+        st.bs = ksteps[s].bs;
+        return st;
+    };
+    float *stg = (float *)smem + wave * 32 * EPI_LD;
+    const int e_row = lane / LPR, e_col = (lane % LPR) * 8;
     const int dtD = p.dtD;
     const bool dvec = p.d_vec != 0;
-    static_for<MI>([&](auto mi) {
-        const int m = m0 + wm * Cfg::WTM + mi * 32 + f_row;
-        EpiCtx c;
-        c.m = m;
-        c.m_ok = m < Mloc;
-        c.N = p.N;
-        c.batch = batch;
-        c.group = group;
-        const int64_t drow = (MODE == 1 ? 0 : (int64_t)batch * p.d_bs) + (int64_t)m * p.ldd;
-        static_for<NI>([&](auto ni) {
-            c.n_base = n0 + wn * Cfg::WTN + ni * 32 + 4 * f_half;
-            float v[16];
+    const int n_steps = p.n_steps;
+
+    EpiCtx c;
+    c.batch = batch;
+    c.group = group;
+    c.n = n0 + wn * WTN + e_col;
+    const int n_left = p.N - c.n;
+
+    constexpr int GRP = PASSES < 4 ? PASSES : 4;
+
+    // accumulators of 32-row block `mi` -> this wave's staging patch (fp32).  acc needs constant
+    // indices, and is only ever touched by code written directly in the kernel body (a closure that
+    // holds a reference to it and is itself captured by another closure keeps it out of registers).
+#define UCL_STAGE_BLOCK(mi)                                                                             \
+    static_for<MI>([&](auto mj) {                                                                       \
+        if ((mi) == mj) {                                                                               \
+            static_for<NI>([&](auto ni) {                                                               \
+                static_for<4>([&](auto g) {                                                             \
+                    const f32x4_t q = {acc[mj][ni][4 * g], acc[mj][ni][4 * g + 1], acc[mj][ni][4 * g + 2], \
+                                       acc[mj][ni][4 * g + 3]};                                         \
+                    *(f32x4_t *)(stg + f_row * EPI_LD + ni * 32 + 8 * g + 4 * f_half) = q;              \
+                });                                                                                     \
+            });                                                                                         \
+        }                                                                                               \
+    })
+    auto staged_row = [&](int row, float (&v)[8]) __attribute__((always_inline)) {
+        const f32x4_t lo = *(const f32x4_t *)(stg + row * EPI_LD + e_col);
+        const f32x4_t hi = *(const f32x4_t *)(stg + row * EPI_LD + e_col + 4);
 #pragma unroll
-            for (int j = 0; j < 16; ++j) v[j] = acc[mi][ni][j];
-            for (int s = 0; s < p.n_steps; ++s) apply_step(v, p.steps[s], c);
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int n = c.n_base + 8 * g;
-                const f32x4_t o = {v[4 * g], v[4 * g + 1], v[4 * g + 2], v[4 * g + 3]};
-                store4(Db, dtD, drow + n, o, dvec, c.m_ok ? p.N - n : 0);
+        for (int e = 0; e < 4; ++e) {
+            v[e] = lo[e];
+            v[4 + e] = hi[e];
+        }
+    };
+    const int64_t d_batch_off = MODE == 1 ? 0 : (int64_t)batch * p.d_bs;
+
+    // ---- fused form: act(alpha * acc + bias[n] + beta * R[m,n]) as straight-line code ---------------
+    // All block / pass loops of the epilogue are REAL loops: their bodies are re-executed from the
+    // instruction cache instead of existing once per pass.
+    // (one 32-row block; the caller stages the block and loops over blocks, so that the accumulator
+    // registers are read at exactly one place in the code)
+    const FusedEpi &f = p.fused;
+    float bias8[8];
+    const char *res_base = nullptr;
+    float alpha = 1.f;
+    auto fused_block = [&](auto act_, int mi) __attribute__((always_inline)) {
+        constexpr int ACT = decltype(act_)::value;
+        const int m_blk = m0 + wm * Cfg::WTM + mi * 32;
+#pragma clang loop unroll(disable)
+        for (int pg = 0; pg < PASSES; pg += GRP) {
+            // the residual segments of a whole group of passes are requested before any is used
+            Raw8 res[GRP];
+            if (f.has_res) {
+                static_for<GRP>([&](auto u) {
+                    const int m = m_blk + (pg + u) * RPP + e_row;
+                    res[u] = load8(res_base, f.res_dt & 0xff, (int64_t)m * f.res_ld, (f.res_dt & 0x100) != 0,
+                                   m < Mloc ? n_left : 0);
+                });
             }
-        });
-    });
+            static_for<GRP>([&](auto u) {
+                const int row = (pg + u) * RPP + e_row;
+                const int m = m_blk + row;
+                float v[8];
+                staged_row(row, v);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[e] = v[e] * alpha + bias8[e];
+                if (f.has_res) {
+                    float t[8];
+                    decode8(res[u], f.res_dt & 0xff, t);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) v[e] += f.beta * t[e];
+                }
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[e] = act_f32<ACT>(v[e], f.act_p0, f.act_p1);
+                store8(Db, dtD, d_batch_off + (int64_t)m * p.ldd + c.n, v, dvec, m < Mloc ? n_left : 0);
+            });
+        }
+    };
+
+    if (f.enabled) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) bias8[e] = 0.f;
+        if (f.has_bias) {
+            const void *bp = group >= 0 ? ((const void *const *)f.bias)[group] : f.bias;
+            decode8(load8(bp, f.bias_dt & 0xff, c.n, (f.bias_dt & 0x100) != 0, n_left), f.bias_dt & 0xff, bias8);
+        }
+        if (f.has_res) {
+            const void *rp = group >= 0 ? ((const void *const *)f.res)[group] : f.res;
+            res_base = (const char *)rp + ((int64_t)batch * f.res_bs + c.n) * ((f.res_dt & 0xff) == UCL_F32 ? 4 : 2);
+        }
+        if (f.has_scale) alpha = f.alpha;
+        // All block / pass loops of the epilogue are REAL loops: their bodies are re-executed from
+        // the instruction cache instead of existing once per pass.
+#pragma clang loop unroll(disable)
+        for (int mi = 0; mi < MI; ++mi) {
+            UCL_STAGE_BLOCK(mi);
+            switch (f.act) {
+#define UCL_FUSED_CASE(OP) case OP: fused_block(std::integral_constant<int, OP>{}, mi); break;
+                UCL_FUSED_CASE(UCL_EPI_RELU)
+                UCL_FUSED_CASE(UCL_EPI_GELU_TANH)
+                UCL_FUSED_CASE(UCL_EPI_GELU_ERF)
+                UCL_FUSED_CASE(UCL_EPI_SILU)
+                UCL_FUSED_CASE(UCL_EPI_SIGMOID)
+                UCL_FUSED_CASE(UCL_EPI_TANH)
+                UCL_FUSED_CASE(UCL_EPI_MISH)
+                UCL_FUSED_CASE(UCL_EPI_HARDSWISH)
+                UCL_FUSED_CASE(UCL_EPI_LEAKY_RELU)
+                UCL_FUSED_CASE(UCL_EPI_ELU)
+                UCL_FUSED_CASE(UCL_EPI_CLAMP)
+#undef UCL_FUSED_CASE
+            default: fused_block(std::integral_constant<int, 0>{}, mi); break;
+            }
+        }
+    } else {
+    // ---- any other chain: interpreted step by step ----------------------------------------------------
+        // n-indexed vectors (bias, column scale): the lane's 8 columns never change, fetch them once.
+        // (All indexing of these small register arrays goes through static_for: constant indices only.)
+        Raw8 nvec[kMaxNVec];
+        int nvec_step[kMaxNVec], mat_step[kMaxMat];
+        const char *mat_base[kMaxMat];            // AUX_LOAD operands: row-0 address of this lane's columns
+        int64_t mat_ld[kMaxMat];
+        int mat_dt[kMaxMat];
+        int n_nvec = 0, n_mat = 0;
+        static_for<kMaxNVec>([&](auto j) { nvec_step[j] = -1; });
+        static_for<kMaxMat>([&](auto j) { mat_step[j] = -1; });
+        for (int s = 0; s < n_steps; ++s) {
+            const EpiStepDev st = get_step(s);
+            const int op = st.op;
+            if (op_is_nvec(op) && n_nvec < kMaxNVec) {
+                static_for<kMaxNVec>([&](auto j) {
+                    if (j == n_nvec) {
+                        nvec_step[j] = s;
+                        nvec[j] = load8(step_ptr(st, group), st.dtype & 0xff, c.n, (st.dtype & 0x100) != 0, n_left);
+                    }
+                });
+                ++n_nvec;
+            } else if (op == UCL_EPI_AUX_LOAD && n_mat < kMaxMat) {
+                static_for<kMaxMat>([&](auto j) {
+                    if (j == n_mat) {
+                        const int esz = (st.dtype & 0xff) == UCL_F32 ? 4 : 2;
+                        mat_step[j] = s;
+                        mat_dt[j] = st.dtype;
+                        mat_ld[j] = st.ld;
+                        mat_base[j] = (const char *)step_ptr(st, group) + ((int64_t)batch * st.bs + c.n) * esz;
+                    }
+                });
+                ++n_mat;
+            }
+        }
+
+#pragma clang loop unroll(disable)
+        for (int mi = 0; mi < MI; ++mi) {
+            UCL_STAGE_BLOCK(mi);
+            const int m_blk = m0 + wm * Cfg::WTM + mi * 32;
+            // passes run in groups: the matrix operands (residual) of a whole group are requested first,
+            // so several row segments are in flight while the chain runs
+#pragma clang loop unroll(disable)
+            for (int pg = 0; pg < PASSES; pg += GRP) {
+                Raw8 mat[GRP][kMaxMat];
+                static_for<GRP>([&](auto u) {
+                    const int m = m_blk + (pg + u) * RPP + e_row;
+                    const int nv = m < Mloc ? n_left : 0;
+                    static_for<kMaxMat>([&](auto j) {
+                        if (j < n_mat)
+                            mat[u][j] = load8(mat_base[j], mat_dt[j] & 0xff, (int64_t)m * mat_ld[j], (mat_dt[j] & 0x100) != 0, nv);
+                    });
+                });
+                static_for<GRP>([&](auto u) {
+                    const int row = (pg + u) * RPP + e_row;
+                    const int m = m_blk + row;
+                    c.m = m;
+                    c.nvalid = m < Mloc ? n_left : 0;
+                    float v[8];
+                    staged_row(row, v);
+                    for (int s = 0; s < n_steps; ++s) {
+                        Raw8 pre;
+                        pre.lo = u32x4_t{0, 0, 0, 0};
+                        pre.hi = u32x4_t{0, 0, 0, 0};
+                        pre.packed = false;
+                        bool has_pre = false;
+                        static_for<kMaxNVec>([&](auto j) {
+                            if (nvec_step[j] == s) { pre = nvec[j]; has_pre = true; }
+                        });
+                        static_for<kMaxMat>([&](auto j) {
+                            if (mat_step[j] == s) { pre = mat[u][j]; has_pre = true; }
+                        });
+                        apply_step(v, get_step(s), c, pre, has_pre);
+                    }
+                    store8(Db, dtD, d_batch_off + (int64_t)m * p.ldd + c.n, v, dvec, c.nvalid);
+                });
+            }
+        }
+    }
+#undef UCL_STAGE_BLOCK
 }
 
 }  // namespace ucl
