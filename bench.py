@@ -133,6 +133,9 @@ def main():
     ap.add_argument("--all", action="store_true", help="also time the other four workloads")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--eager", action="store_true", help="plain launches instead of one captured HIP graph")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run 10 plain device copies of 256 MiB and exit (reference reading for the "
+                         "FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU (the hot path is one kernel on one GPU's share of the "
@@ -142,6 +145,14 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
+    if args.copy_calibration:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": 256 << 20, "copy_bytes_written": 256 << 20, "copies": 10}))
+        return
     import paper_2603_29010_amd as ucl
     if not os.path.exists(ucl.library_path()):
         print("bench.py: libucl.so is not built (python -m paper_2603_29010_amd.build)", file=sys.stderr)
