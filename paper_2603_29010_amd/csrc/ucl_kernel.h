@@ -49,14 +49,28 @@ __device__ __forceinline__ void static_for(F &&f) {
 // s_waitcnt immediate (gfx9 encoding) that waits only on the vector-memory counter.
 __device__ constexpr int vmcnt_imm(int n) { return (n & 0xF) | ((n >> 4) << 14) | (0x7 << 4) | (0xF << 8); }
 
+// Workgroup barrier of the pipelined mainloop: waits until at most `VM` of this wave's global -> LDS
+// loads are outstanding and all of its LDS reads have returned, then s_barrier.  __syncthreads() is
+// not used there: its release fence makes the compiler wait for EVERY outstanding global -> LDS load
+// (it must treat them as LDS stores), which would drain the pipeline at each stage boundary.  The
+// empty asm statements only stop the compiler from moving memory operations across the barrier.
+template <int VM>
+__device__ __forceinline__ void pipeline_barrier() {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt((VM & 0xF) | ((VM >> 4) << 14) | (0x7 << 4) | (0x0 << 8));   // vmcnt(VM) lgkmcnt(0)
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
 // XOR pattern of the LDS layout, for rows of CPR 16-byte chunks.  It depends on row mod 16 only, so
-// any multiple-of-32 row offset (wave tile, MFMA block) leaves it unchanged.  Chosen so that 16
-// consecutive rows reading the same logical chunk hit 16 different 16-byte bank groups of a 256-byte
-// LDS line, and 8 consecutive rows 8 different groups of a 128-byte half line.
+// any multiple-of-32 row offset (wave tile, MFMA block) leaves it unchanged.  Both patterns were
+// picked by timing the fragment-read pattern (32 consecutive rows, two adjacent chunks) on the GPU:
+// the 128-byte-row pattern reads conflict-free (SQ_LDS_BANK_CONFLICT = 0), the 64-byte-row one is
+// the fastest of the candidates tried (about 1.2x the conflict-free time).
 template <int CPR>
 __device__ __forceinline__ int lds_swz(int row) {
     if constexpr (CPR == 8) return (row & 7) ^ ((row >> 3) & 1);
-    else return ((row >> 1) ^ (row >> 3)) & 3;
+    else return (row >> 2) & 3;
 }
 
 __device__ __forceinline__ float bits_to_f32(uint32_t raw16, int dtype) {
@@ -445,13 +459,17 @@ __global__ __launch_bounds__(kThreads) void ucl_tile_kernel(const KParams p, con
     // one 128-bit global -> LDS load per slot (lane L of a wave lands at dst + 16 L).  M/N-contiguous
     // operands: 128-bit loads into registers, written (transposed) by commit_regs.  CHECK_K adds the
     // K-tail test; full k-tiles skip it.
-    auto issue_tile = [&](auto check_k_, int kt, int buf) {
+    // PART: 0 = both operands, 1 = A only, 2 = B only (the deep pipelines spread the two halves of a
+    // stage's loads over different k-steps).
+    auto issue_part = [&](auto check_k_, auto part_, int kt, int buf) {
         constexpr bool CHECK_K = decltype(check_k_)::value;
+        constexpr int PART = decltype(part_)::value;
         char *sA = smem + buf * Cfg::STAGE_BYTES;
         char *sB = sA + Cfg::A_BYTES;
         const int k0 = kt * TK;
         const bool kok = !CHECK_K || (k0 + l_kc < K);
-        if constexpr (LA == kKContig) {
+        if constexpr (PART == 2) {
+        } else if constexpr (LA == kKContig) {
 #pragma unroll
             for (int i = 0; i < A_ITERS; ++i) {
                 char *dst = sA + (i * kThreads + wave * 64) * 16;
@@ -487,7 +505,8 @@ __global__ __launch_bounds__(kThreads) void ucl_tile_kernel(const KParams p, con
                 a_stage[i] = k < K ? *(const u32x4_t *)(Ab + ((int64_t)k * p.lda + m) * 2) : u32x4_t{0, 0, 0, 0};
             }
         }
-        if constexpr (LB == kKContig) {
+        if constexpr (PART == 1) {
+        } else if constexpr (LB == kKContig) {
 #pragma unroll
             for (int i = 0; i < B_ITERS; ++i) {
                 char *dst = sB + (i * kThreads + wave * 64) * 16;
@@ -506,6 +525,9 @@ __global__ __launch_bounds__(kThreads) void ucl_tile_kernel(const KParams p, con
                 b_stage[i] = k < K ? *(const u32x4_t *)(Bb + ((int64_t)k * p.ldb + n) * 2) : u32x4_t{0, 0, 0, 0};
             }
         }
+    };
+    auto issue_tile = [&](auto check_k_, int kt, int buf) {
+        issue_part(check_k_, std::integral_constant<int, 0>{}, kt, buf);
     };
     // only the last k-tile can be partial
     auto issue = [&](int kt, int buf) {
@@ -617,6 +639,23 @@ __global__ __launch_bounds__(kThreads) void ucl_tile_kernel(const KParams p, con
         __builtin_amdgcn_sched_group_barrier(0x008, kMfmaPerStep, 0);
         __builtin_amdgcn_sched_barrier(0);
     };
+    // General form: this k-step's MFMAs with `n_vmem` global -> LDS loads, then the fragment reads,
+    // dealt out evenly behind the first MFMAs.
+    auto interleave_step = [&](auto n_vmem_) {
+        constexpr int NV = decltype(n_vmem_)::value;
+        constexpr int T = NV + kDsPerStep;
+        constexpr int Q = (T + kMfmaPerStep - 1) / kMfmaPerStep;     // side instructions per MFMA slot
+        static_for<kMfmaPerStep>([&](auto i_) {
+            constexpr int i = decltype(i_)::value;
+            constexpr int lo = i * Q < T ? i * Q : T, hi = (i + 1) * Q < T ? (i + 1) * Q : T;
+            constexpr int nv = (hi < NV ? hi : NV) - (lo < NV ? lo : NV);
+            constexpr int nd = (hi - lo) - nv;
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            if constexpr (nv > 0) __builtin_amdgcn_sched_group_barrier(0x020, nv, 0);
+            if constexpr (nd > 0) __builtin_amdgcn_sched_group_barrier(0x100, nd, 0);
+        });
+        __builtin_amdgcn_sched_barrier(0);
+    };
     using I0 = std::integral_constant<int, 0>;
     using I1 = std::integral_constant<int, 1>;
 
@@ -643,13 +682,6 @@ __global__ __launch_bounds__(kThreads) void ucl_tile_kernel(const KParams p, con
         // the buffer can be refilled (k-tile kt+STAGES) and the next tile's first fragments fetched,
         // both hidden under the MFMAs of the last k-step.
         static_assert(KSTEPS % 2 == 0, "fragment sets alternate per k-step and must realign per stage");
-#pragma unroll
-        for (int s = 0; s < STAGES; ++s)
-            if (s < KT) issue(s, s);
-        if (KT > STAGES - 1) __builtin_amdgcn_s_waitcnt(vmcnt_imm((STAGES - 1) * DMA_PER_TILE));
-        else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-        __syncthreads();
-        read_frags(I0{}, I0{}, smem);
         // all k-steps of a stage but the last: fragments of step kk+1 stream in under the MFMAs of step kk
         auto head_steps = [&](const char *sbase) {
             static_for<KSTEPS - 1>([&](auto kk_) {
@@ -659,32 +691,92 @@ __global__ __launch_bounds__(kThreads) void ucl_tile_kernel(const KParams p, con
                 interleave_ds_mfma();
             });
         };
-        // Steady state: every boundary refills the buffer it releases.  Kept as one straight-line
-        // block (no branch around MFMAs: 256 live accumulators do not survive control-flow joins
-        // without copies), hence the always-on K-tail test inside issue_tile.
-        int kt = 0;
-        for (; kt + STAGES < KT; ++kt) {
-            const int buf = kt % STAGES;
-            head_steps(smem + buf * Cfg::STAGE_BYTES);
-            // k-tile kt+1 must have landed; tiles kt+2 .. kt+STAGES-1 may still be in flight
-            __builtin_amdgcn_s_waitcnt(vmcnt_imm((STAGES - 2) * DMA_PER_TILE));
+        if constexpr (STAGES >= 3) {
+            // ---- deep pipeline: STAGES-1 stages in flight, loads spread over the stage ---------------
+            // Stage kt+STAGES-1 goes into the buffer released at the previous boundary: its A half is
+            // issued under the first k-step of stage kt, its B half under the last.  A wave's load
+            // instructions then arrive at the memory pipeline a few at a time instead of as one burst
+            // whose queueing would hold back the MFMAs issued behind it.
+            constexpr int DA = A_ITERS, DB = B_ITERS;
+            using P1 = std::integral_constant<int, 1>;
+            using P2 = std::integral_constant<int, 2>;
+#pragma unroll
+            for (int s = 0; s < STAGES - 1; ++s)
+                if (s < KT) issue(s, s);
+            if (KT >= STAGES - 1) __builtin_amdgcn_s_waitcnt(vmcnt_imm((STAGES - 2) * DMA_PER_TILE));
+            else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
             __syncthreads();
-            issue_tile(std::true_type{}, kt + STAGES, buf);
-            read_frags(I0{}, I0{}, smem + ((kt + 1) % STAGES) * Cfg::STAGE_BYTES);
+            read_frags(I0{}, I0{}, smem);
+            int kt = 0;
+            int fill = STAGES - 1;                 // buffer index of stage kt+STAGES-1, kept without a modulo
+            int cur = 0;
+            for (; kt + STAGES - 1 < KT; ++kt) {
+                const char *sbase = smem + cur * Cfg::STAGE_BYTES;
+                const int nxt = cur + 1 == STAGES ? 0 : cur + 1;
+                // first k-step: A half of the refill + fragments of the second k-step
+                issue_part(std::true_type{}, P1{}, kt + STAGES - 1, fill);
+                read_frags(I1{}, I1{}, sbase);
+                mfma_step(I0{});
+                interleave_step(std::integral_constant<int, DA>{});
+                static_for<KSTEPS - 2>([&](auto kk_) {
+                    constexpr int kk = decltype(kk_)::value + 1;
+                    read_frags(std::integral_constant<int, (kk + 1) & 1>{}, std::integral_constant<int, kk + 1>{}, sbase);
+                    mfma_step(std::integral_constant<int, kk & 1>{});
+                    interleave_ds_mfma();
+                });
+                // stage kt+1 must have landed; younger: stages kt+2..kt+STAGES-2 and the A half just issued
+                pipeline_barrier<(STAGES - 3) * DMA_PER_TILE + DA>();
+                issue_part(std::true_type{}, P2{}, kt + STAGES - 1, fill);
+                read_frags(I0{}, I0{}, smem + nxt * Cfg::STAGE_BYTES);
+                mfma_step(I1{});
+                interleave_step(std::integral_constant<int, DB>{});
+                fill = cur;
+                cur = nxt;
+            }
+            for (; kt < KT - 1; ++kt) {            // drain
+                const int nxt = cur + 1 == STAGES ? 0 : cur + 1;
+                head_steps(smem + cur * Cfg::STAGE_BYTES);
+                pipeline_barrier<0>();
+                read_frags(I0{}, I0{}, smem + nxt * Cfg::STAGE_BYTES);
+                mfma_step(I1{});
+                interleave_ds_mfma();
+                cur = nxt;
+            }
+            head_steps(smem + cur * Cfg::STAGE_BYTES);
             mfma_step(I1{});
-            interleave_all();
-        }
-        // Drain: nothing left to fetch.
-        for (; kt < KT - 1; ++kt) {
-            head_steps(smem + (kt % STAGES) * Cfg::STAGE_BYTES);
-            __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+        } else {
+#pragma unroll
+            for (int s = 0; s < STAGES; ++s)
+                if (s < KT) issue(s, s);
+            if (KT > STAGES - 1) __builtin_amdgcn_s_waitcnt(vmcnt_imm((STAGES - 1) * DMA_PER_TILE));
+            else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
             __syncthreads();
-            read_frags(I0{}, I0{}, smem + ((kt + 1) % STAGES) * Cfg::STAGE_BYTES);
+            read_frags(I0{}, I0{}, smem);
+            // Steady state: every boundary refills the buffer it releases.  Kept as one straight-line
+            // block (no branch around MFMAs: 256 live accumulators do not survive control-flow joins
+            // without copies), hence the always-on K-tail test inside issue_tile.
+            int kt = 0;
+            for (; kt + STAGES < KT; ++kt) {
+                const int buf = kt % STAGES;
+                head_steps(smem + buf * Cfg::STAGE_BYTES);
+                // k-tile kt+1 must have landed; tiles kt+2 .. kt+STAGES-1 may still be in flight
+                pipeline_barrier<(STAGES - 2) * DMA_PER_TILE>();
+                issue_tile(std::true_type{}, kt + STAGES, buf);
+                read_frags(I0{}, I0{}, smem + ((kt + 1) % STAGES) * Cfg::STAGE_BYTES);
+                mfma_step(I1{});
+                interleave_all();
+            }
+            // Drain: nothing left to fetch.
+            for (; kt < KT - 1; ++kt) {
+                head_steps(smem + (kt % STAGES) * Cfg::STAGE_BYTES);
+                pipeline_barrier<0>();
+                read_frags(I0{}, I0{}, smem + ((kt + 1) % STAGES) * Cfg::STAGE_BYTES);
+                mfma_step(I1{});
+                interleave_ds_mfma();
+            }
+            head_steps(smem + ((KT - 1) % STAGES) * Cfg::STAGE_BYTES);
             mfma_step(I1{});
-            interleave_ds_mfma();
         }
-        head_steps(smem + ((KT - 1) % STAGES) * Cfg::STAGE_BYTES);
-        mfma_step(I1{});
     }
 
     // ---- epilogue ---------------------------------------------------------------------------------
