@@ -262,6 +262,11 @@ ucl_status run(const Launch &L, KParams &kp, const GroupTable *gt_in, const ucl_
         total = (int64_t)kp.tiles_per_batch * L.batch;
     }
     if (total >= (1ll << 31)) return fail(UCL_ERR_UNSUPPORTED, "problem needs %lld tiles; the grid is limited to 2^31-1", (long long)total);
+    // operand panels are addressed with 32-bit byte offsets inside range-checked buffer resources
+    if (v->la == 0 && ((int64_t)v->tile_m * kp.lda + L.K) * 2 >= (1ll << 31))
+        return fail(UCL_ERR_UNSUPPORTED, "A leading stride %lld too large: a %d-row panel must span less than 2 GiB", (long long)kp.lda, v->tile_m);
+    if (v->lb == 0 && ((int64_t)v->tile_n * kp.ldb + L.K) * 2 >= (1ll << 31))
+        return fail(UCL_ERR_UNSUPPORTED, "B leading stride %lld too large: a %d-row panel must span less than 2 GiB", (long long)kp.ldb, v->tile_n);
     kp.total_tiles = (int32_t)total;
     if (total == 0) return UCL_OK;     // grouped with every M_g == 0: nothing to do
     (void)gt_in;
@@ -432,7 +437,7 @@ ucl_status ucl_conv2d_fprop(int64_t N, int64_t H, int64_t W, int64_t C, int64_t 
     if (ucl_status st = check_common(M, Kout, Kg, dtX, dtW, dtY, x, w, y)) return st;
     if (C % 8) return fail(UCL_ERR_UNSUPPORTED, "C=%lld must be a multiple of 8 so that a 128-bit load never straddles a filter tap", (long long)C);
     if (!aligned16(x) || !aligned16(w)) return fail(UCL_ERR_UNSUPPORTED, "x and w must be 16-byte aligned");
-    if (N * H * W * C >= (1ll << 40)) return fail(UCL_ERR_UNSUPPORTED, "activation tensor too large");
+    if (N * H * W * C * 2 >= (1ll << 31)) return fail(UCL_ERR_UNSUPPORTED, "activation tensor must be smaller than 2 GiB (32-bit offsets)");
     if (H >= (1 << 24) || W >= (1 << 24) || pad_h >= (1 << 24) || pad_w >= (1 << 24))
         return fail(UCL_ERR_UNSUPPORTED, "image extents / pads must be below 2^24");
     Launch L;
@@ -441,6 +446,7 @@ ucl_status ucl_conv2d_fprop(int64_t N, int64_t H, int64_t W, int64_t C, int64_t 
     memset(&kp, 0, sizeof(kp));
     if (ucl_status st = check_epilogue(epi, L, kp)) return st;
     kp.A = x; kp.B = w; kp.D = y;
+    kp.a_bytes = N * H * W * C * 2;
     kp.lda = 0; kp.ldb = Kg; kp.ldd = Kout;
     kp.M = (int32_t)M; kp.N = (int32_t)Kout; kp.K = (int32_t)Kg; kp.dtD = dtY;
     kp.cH = (int32_t)H; kp.cW = (int32_t)W; kp.cC = (int32_t)C; kp.cS = (int32_t)S; kp.cP = (int32_t)P; kp.cQ = (int32_t)Q;

@@ -5,7 +5,7 @@
 //   tile schedule  : workgroup id -> (batch or group, tile row, tile column), XCD-aware
 //   staging        : global -> LDS, `STAGES` buffers deep.  Operands that are contiguous along K
 //                    (and the implicit-GEMM view of NHWC activations) go straight from HBM/L2 into
-//                    LDS with 128-bit `global_load_lds` (no VGPR round trip); operands contiguous
+//                    LDS with 128-bit `buffer_load ... lds` (no VGPR round trip); operands contiguous
 //                    along M / N are loaded 128-bit into VGPRs and transposed on the way into LDS.
 //   LDS layout     : [rows][TK elements] (TK = 64 or 32: 128- or 64-byte rows of 16-byte chunks), chunk
 //                    index XORed with a function of the row so that the 16-byte-per-lane MFMA
@@ -30,7 +30,6 @@ typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
 
-#define UCL_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
 #define UCL_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
 
 enum OperandLayout { kKContig = 0, kMNContig = 1, kIm2col = 2 };
@@ -347,9 +346,15 @@ struct KernelCfg {
     using Groups = typename std::conditional<MODE == 1, GroupTable, NoGroupTable>::type;
 };
 
-// Source of the 16 zero bytes that stand in for out-of-range chunks (K tail, conv halo): the copy
-// stays one unconditional 128-bit global -> LDS load per slot, only its address is selected.
-static __device__ __attribute__((aligned(16))) const uint32_t g_zero_chunk[4] = {0u, 0u, 0u, 0u};
+// Buffer resource (4 SGPRs) over `bytes` bytes at `base`: raw buffer, no stride, range-checked.
+// Loads through it whose offset is >= bytes return zero, which is how rows beyond the problem edge,
+// the K tail and the conv halo become zeros in LDS without a branch or a second address.
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+constexpr uint32_t kOobOffset = 0x80000000u;   // never inside a resource (sizes are kept below 2^31)
+__device__ __forceinline__ rsrc_t buffer_rsrc(const void *base, uint32_t bytes) {
+    // word 3: 32-bit data format, raw (unstructured) addressing
+    return __builtin_amdgcn_make_buffer_rsrc((void *)base, (short)0, (int)bytes, 0x00020000);
+}
 
 template <bool F16>
 __device__ __forceinline__ f32x16_t mfma32(u32x4_t a, u32x4_t b, f32x16_t c) {
@@ -412,22 +417,23 @@ __global__ __launch_bounds__(kThreads) void ucl_tile_kernel(const KParams p, con
     const int l_row = tid / CPR;
     const int l_chunk = (tid % CPR) ^ lds_swz<CPR>(l_row);
     const int l_kc = l_chunk * 8;                        // first k of this thread's chunk within a k-tile
-    const char *const zero_src = (const char *)g_zero_chunk;
-
-    const char *a_ptr[LA == kMNContig ? 1 : A_ITERS];
+    // K-contiguous operands: one scalar buffer resource per operand over the tile's row panel, and per
+    // thread one loop-invariant 32-bit byte offset per slot; the k position advances through the
+    // scalar offset of the load, so a load costs no vector ALU instruction in the steady state.
+    rsrc_t a_rsrc = buffer_rsrc(nullptr, 0), b_rsrc = buffer_rsrc(nullptr, 0);
+    uint32_t a_off[LA == kMNContig ? 1 : A_ITERS], b_off[LB == kMNContig ? 1 : B_ITERS];
     int a_h0[LA == kIm2col ? A_ITERS : 1], a_w0[LA == kIm2col ? A_ITERS : 1];
     int a_ci = 0, a_r = 0, a_s = 0;                      // im2col: decomposition of k = l_kc + kt*TK
-    const char *b_ptr[LB == kMNContig ? 1 : B_ITERS];
     u32x4_t a_stage[LA == kMNContig ? A_ITERS : 1], b_stage[LB == kMNContig ? B_ITERS : 1];
 
     if constexpr (LA == kKContig) {
+        const int rows = Mloc - m0 < TM ? Mloc - m0 : TM;              // rows of the panel that exist
+        a_rsrc = buffer_rsrc(Ab + (int64_t)m0 * p.lda * 2, (uint32_t)(((int64_t)(rows - 1) * p.lda + K) * 2));
 #pragma unroll
-        for (int i = 0; i < A_ITERS; ++i) {
-            int row = m0 + i * RPI + l_row;
-            row = row < Mloc ? row : Mloc - 1;
-            a_ptr[i] = Ab + ((int64_t)row * p.lda + l_kc) * 2;
-        }
+        for (int i = 0; i < A_ITERS; ++i)
+            a_off[i] = (uint32_t)(((int64_t)(i * RPI + l_row) * p.lda + l_kc) * 2);   // rows past the edge: out of range
     } else if constexpr (LA == kIm2col) {
+        a_rsrc = buffer_rsrc(Ab, (uint32_t)p.a_bytes);
 #pragma unroll
         for (int i = 0; i < A_ITERS; ++i) {
             int row = m0 + i * RPI + l_row;
@@ -438,8 +444,8 @@ __global__ __launch_bounds__(kThreads) void ucl_tile_kernel(const KParams p, con
             const int nb = pq / p.cP;
             a_h0[i] = pp * p.str_h - p.pad_h;
             a_w0[i] = q * p.str_w - p.pad_w;
-            // address of x[nb, h0, w0, 0]; only dereferenced at taps that fall inside the image
-            a_ptr[i] = Ab + (((int64_t)nb * p.cH + a_h0[i]) * p.cW + a_w0[i]) * p.cC * 2;
+            // byte offset of x[nb, h0, w0, 0] (may be negative); only used at taps inside the image
+            a_off[i] = (uint32_t)(((nb * p.cH + a_h0[i]) * p.cW + a_w0[i]) * p.cC * 2);
         }
         a_ci = l_kc % p.cC;
         const int tap = l_kc / p.cC;
@@ -447,12 +453,11 @@ __global__ __launch_bounds__(kThreads) void ucl_tile_kernel(const KParams p, con
         a_s = tap % p.cS;
     }
     if constexpr (LB == kKContig) {
+        const int rows = p.N - n0 < TN ? p.N - n0 : TN;
+        b_rsrc = buffer_rsrc(Bb + (int64_t)n0 * p.ldb * 2, (uint32_t)(((int64_t)(rows - 1) * p.ldb + K) * 2));
 #pragma unroll
-        for (int i = 0; i < B_ITERS; ++i) {
-            int row = n0 + i * RPI + l_row;
-            row = row < p.N ? row : p.N - 1;
-            b_ptr[i] = Bb + ((int64_t)row * p.ldb + l_kc) * 2;
-        }
+        for (int i = 0; i < B_ITERS; ++i)
+            b_off[i] = (uint32_t)(((int64_t)(i * RPI + l_row) * p.ldb + l_kc) * 2);
     }
 
     // Issue the copies of k-tile `kt` into stage buffer `buf`.  K-contiguous and im2col operands:
@@ -473,20 +478,19 @@ __global__ __launch_bounds__(kThreads) void ucl_tile_kernel(const KParams p, con
 #pragma unroll
             for (int i = 0; i < A_ITERS; ++i) {
                 char *dst = sA + (i * kThreads + wave * 64) * 16;
-                const char *src = a_ptr[i] + (int64_t)k0 * 2;
-                if constexpr (CHECK_K) src = kok ? src : zero_src;
-                __builtin_amdgcn_global_load_lds(UCL_GLOBAL_PTR(src), UCL_LDS_PTR(dst), 16, 0, 0);
+                const uint32_t off = CHECK_K ? (kok ? a_off[i] : kOobOffset) : a_off[i];
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, UCL_LDS_PTR(dst), 16, off, k0 * 2, 0, 0);
             }
         } else if constexpr (LA == kIm2col) {
             const int dh = a_r * p.dil_h, dw = a_s * p.dil_w;
-            const int64_t tap_off = (((int64_t)dh * p.cW + dw) * p.cC + a_ci) * 2;
+            const uint32_t tap_off = (uint32_t)(((dh * p.cW + dw) * p.cC + a_ci) * 2);
 #pragma unroll
             for (int i = 0; i < A_ITERS; ++i) {
                 char *dst = sA + (i * kThreads + wave * 64) * 16;
                 const int h = a_h0[i] + dh, w = a_w0[i] + dw;
                 const bool ok = kok && (unsigned)h < (unsigned)p.cH && (unsigned)w < (unsigned)p.cW;
-                const char *src = ok ? a_ptr[i] + tap_off : zero_src;
-                __builtin_amdgcn_global_load_lds(UCL_GLOBAL_PTR(src), UCL_LDS_PTR(dst), 16, 0, 0);
+                const uint32_t off = ok ? a_off[i] + tap_off : kOobOffset;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, UCL_LDS_PTR(dst), 16, off, 0, 0, 0);
             }
             // advance k by one k-tile: (ci, s, r) += TK channels
             a_ci += TK;
@@ -510,9 +514,8 @@ __global__ __launch_bounds__(kThreads) void ucl_tile_kernel(const KParams p, con
 #pragma unroll
             for (int i = 0; i < B_ITERS; ++i) {
                 char *dst = sB + (i * kThreads + wave * 64) * 16;
-                const char *src = b_ptr[i] + (int64_t)k0 * 2;
-                if constexpr (CHECK_K) src = kok ? src : zero_src;
-                __builtin_amdgcn_global_load_lds(UCL_GLOBAL_PTR(src), UCL_LDS_PTR(dst), 16, 0, 0);
+                const uint32_t off = CHECK_K ? (kok ? b_off[i] : kOobOffset) : b_off[i];
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(b_rsrc, UCL_LDS_PTR(dst), 16, off, k0 * 2, 0, 0);
             }
         } else {   // B contiguous along N: element (k, n) at k*ldb + n
 #pragma unroll
@@ -639,20 +642,23 @@ __global__ __launch_bounds__(kThreads) void ucl_tile_kernel(const KParams p, con
         __builtin_amdgcn_sched_group_barrier(0x008, kMfmaPerStep, 0);
         __builtin_amdgcn_sched_barrier(0);
     };
-    // General form: this k-step's MFMAs with `n_vmem` global -> LDS loads, then the fragment reads,
-    // dealt out evenly behind the first MFMAs.
+    // General form: this k-step's MFMAs with the fragment reads first (the next k-step needs them
+    // soonest), then `n_vmem` global -> LDS loads, dealt out evenly behind the first MFMAs.  The
+    // source order must be the same (reads, then loads): the compiler keeps LDS reads and LDS-writing
+    // loads in program order because it cannot tell that they touch different stage buffers.
     auto interleave_step = [&](auto n_vmem_) {
         constexpr int NV = decltype(n_vmem_)::value;
-        constexpr int T = NV + kDsPerStep;
+        constexpr int ND = kDsPerStep;
+        constexpr int T = NV + ND;
         constexpr int Q = (T + kMfmaPerStep - 1) / kMfmaPerStep;     // side instructions per MFMA slot
         static_for<kMfmaPerStep>([&](auto i_) {
             constexpr int i = decltype(i_)::value;
             constexpr int lo = i * Q < T ? i * Q : T, hi = (i + 1) * Q < T ? (i + 1) * Q : T;
-            constexpr int nv = (hi < NV ? hi : NV) - (lo < NV ? lo : NV);
-            constexpr int nd = (hi - lo) - nv;
+            constexpr int nd = (hi < ND ? hi : ND) - (lo < ND ? lo : ND);
+            constexpr int nv = (hi - lo) - nd;
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            if constexpr (nv > 0) __builtin_amdgcn_sched_group_barrier(0x020, nv, 0);
             if constexpr (nd > 0) __builtin_amdgcn_sched_group_barrier(0x100, nd, 0);
+            if constexpr (nv > 0) __builtin_amdgcn_sched_group_barrier(0x020, nv, 0);
         });
         __builtin_amdgcn_sched_barrier(0);
     };
@@ -710,12 +716,14 @@ __global__ __launch_bounds__(kThreads) void ucl_tile_kernel(const KParams p, con
             int kt = 0;
             int fill = STAGES - 1;                 // buffer index of stage kt+STAGES-1, kept without a modulo
             int cur = 0;
-            for (; kt + STAGES - 1 < KT; ++kt) {
+            // stages [0, KT_full) are complete k-tiles: their loads skip the K-tail test
+            const int KT_full = k_tail ? KT - 1 : KT;
+            auto deep_iter = [&](auto check_) {
                 const char *sbase = smem + cur * Cfg::STAGE_BYTES;
                 const int nxt = cur + 1 == STAGES ? 0 : cur + 1;
                 // first k-step: A half of the refill + fragments of the second k-step
-                issue_part(std::true_type{}, P1{}, kt + STAGES - 1, fill);
                 read_frags(I1{}, I1{}, sbase);
+                issue_part(check_, P1{}, kt + STAGES - 1, fill);
                 mfma_step(I0{});
                 interleave_step(std::integral_constant<int, DA>{});
                 static_for<KSTEPS - 2>([&](auto kk_) {
@@ -726,13 +734,15 @@ __global__ __launch_bounds__(kThreads) void ucl_tile_kernel(const KParams p, con
                 });
                 // stage kt+1 must have landed; younger: stages kt+2..kt+STAGES-2 and the A half just issued
                 pipeline_barrier<(STAGES - 3) * DMA_PER_TILE + DA>();
-                issue_part(std::true_type{}, P2{}, kt + STAGES - 1, fill);
                 read_frags(I0{}, I0{}, smem + nxt * Cfg::STAGE_BYTES);
+                issue_part(check_, P2{}, kt + STAGES - 1, fill);
                 mfma_step(I1{});
                 interleave_step(std::integral_constant<int, DB>{});
                 fill = cur;
                 cur = nxt;
-            }
+            };
+            for (; kt + STAGES - 1 < KT_full; ++kt) deep_iter(std::false_type{});
+            for (; kt + STAGES - 1 < KT; ++kt) deep_iter(std::true_type{});       // the partial k-tile, if any
             for (; kt < KT - 1; ++kt) {            // drain
                 const int nxt = cur + 1 == STAGES ? 0 : cur + 1;
                 head_steps(smem + cur * Cfg::STAGE_BYTES);
@@ -752,20 +762,24 @@ __global__ __launch_bounds__(kThreads) void ucl_tile_kernel(const KParams p, con
             else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
             __syncthreads();
             read_frags(I0{}, I0{}, smem);
-            // Steady state: every boundary refills the buffer it releases.  Kept as one straight-line
-            // block (no branch around MFMAs: 256 live accumulators do not survive control-flow joins
-            // without copies), hence the always-on K-tail test inside issue_tile.
+            // Steady state: every boundary refills the buffer it releases.  Each iteration is one
+            // straight-line block (no branch around MFMAs: 256 live accumulators do not survive
+            // control-flow joins without copies); the K-tail test lives in a second copy of the loop
+            // that runs for the one partial k-tile only.
             int kt = 0;
-            for (; kt + STAGES < KT; ++kt) {
+            const int KT_full = k_tail ? KT - 1 : KT;
+            auto flat_iter = [&](auto check_) {
                 const int buf = kt % STAGES;
                 head_steps(smem + buf * Cfg::STAGE_BYTES);
                 // k-tile kt+1 must have landed; tiles kt+2 .. kt+STAGES-1 may still be in flight
                 pipeline_barrier<(STAGES - 2) * DMA_PER_TILE>();
-                issue_tile(std::true_type{}, kt + STAGES, buf);
+                issue_tile(check_, kt + STAGES, buf);
                 read_frags(I0{}, I0{}, smem + ((kt + 1) % STAGES) * Cfg::STAGE_BYTES);
                 mfma_step(I1{});
                 interleave_all();
-            }
+            };
+            for (; kt + STAGES < KT_full; ++kt) flat_iter(std::false_type{});
+            for (; kt + STAGES < KT; ++kt) flat_iter(std::true_type{});           // the partial k-tile, if any
             // Drain: nothing left to fetch.
             for (; kt < KT - 1; ++kt) {
                 head_steps(smem + (kt % STAGES) * Cfg::STAGE_BYTES);
