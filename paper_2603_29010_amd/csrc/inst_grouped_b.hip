@@ -1,14 +1,12 @@
-// grouped_gemm (per-group pointer tables, ragged M), operands contiguous along K.
+// grouped_gemm (per-group pointer tables, ragged M), operands contiguous along K, small tiles and fp16.
 #include "ucl_launch.h"
 namespace ucl {
 static const VariantDesc kTable[] = {
-    describe<KernelCfg<256, 256, 32, 4, false, 1, kKContig, kKContig>>(),
-    describe<KernelCfg<256, 128, 32, 4, false, 1, kKContig, kKContig>>(),
     describe<KernelCfg<128, 128, 64, 3, false, 1, kKContig, kKContig>>(),
     describe<KernelCfg<64, 64, 64, 2, false, 1, kKContig, kKContig>>(),
     describe<KernelCfg<256, 256, 32, 4, true, 1, kKContig, kKContig>>(),
     describe<KernelCfg<128, 128, 64, 3, true, 1, kKContig, kKContig>>(),
     describe<KernelCfg<64, 64, 64, 2, true, 1, kKContig, kKContig>>(),
 };
-VariantList variants_grouped() { return {kTable, (int)(sizeof(kTable) / sizeof(kTable[0]))}; }
+VariantList variants_grouped_b() { return {kTable, (int)(sizeof(kTable) / sizeof(kTable[0]))}; }
 }  // namespace ucl

@@ -177,7 +177,12 @@ __device__ __forceinline__ void store8(void *base, int dtype, int64_t idx, const
     }
 }
 
-__device__ __forceinline__ float sigmoid_f32(float u) { return 1.0f / (1.0f + __expf(-u)); }
+// 1 / (1 + 2^-t): one exp2 and one reciprocal (both hardware approximations good to ~1 ulp), so an
+// activation built on it costs two quarter-rate instructions per element instead of a full division.
+__device__ __forceinline__ float sigmoid_exp2(float t) {
+    return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-t));
+}
+__device__ __forceinline__ float sigmoid_f32(float u) { return sigmoid_exp2(u * 1.4426950408889634f); }
 
 // The element-wise activations of the vocabulary, fp32.
 template <int OP>
@@ -187,17 +192,18 @@ __device__ __forceinline__ float act_f32(float x, float p0, float p1) {
     else if constexpr (OP == UCL_EPI_CLAMP) return fminf(fmaxf(x, p0), p1);
     else if constexpr (OP == UCL_EPI_HARDSWISH) return x * fminf(fmaxf(x + 3.f, 0.f), 6.f) * (1.f / 6.f);
     else if constexpr (OP == UCL_EPI_GELU_TANH) {
-        // 0.5 (1 + tanh u) = sigmoid(2u),  u = sqrt(2/pi) (x + 0.044715 x^3)
-        return x * sigmoid_f32(1.5957691216057308f * (x + 0.044715f * x * x * x));
+        // 0.5 (1 + tanh u) = sigmoid(2u),  u = sqrt(2/pi) (x + 0.044715 x^3); constants folded with log2(e)
+        const float x2 = x * x;
+        return x * sigmoid_exp2(x * (2.3022082011f + 0.1029432397f * x2));
     } else if constexpr (OP == UCL_EPI_SILU) return x * sigmoid_f32(x);
     else if constexpr (OP == UCL_EPI_SIGMOID) return sigmoid_f32(x);
     else if constexpr (OP == UCL_EPI_TANH) return tanhf(x);
     else if constexpr (OP == UCL_EPI_GELU_ERF) return 0.5f * x * (1.f + erff(x * 0.7071067811865476f));
     else if constexpr (OP == UCL_EPI_MISH) {
         // tanh(log(1 + e^x)) = w (w + 2) / (w (w + 2) + 2) with w = e^x; for large x the factor is 1
-        const float w = __expf(fminf(x, 20.f));
+        const float w = __builtin_amdgcn_exp2f(fminf(x, 20.f) * 1.4426950408889634f);
         const float q = w * (w + 2.f);
-        return x > 20.f ? x : x * (q / (q + 2.f));
+        return x > 20.f ? x : x * (q * __builtin_amdgcn_rcpf(q + 2.f));
     } else if constexpr (OP == UCL_EPI_ELU) return x > 0.f ? x : p0 * expm1f(x);
     else return x;
 }
@@ -343,6 +349,10 @@ struct KernelCfg {
     static constexpr int ROWS_PER_ITER = kThreads / CPR;          // rows covered by one 256-thread copy
     static_assert(TM % 64 == 0 && TN % 64 == 0, "wave tile is a multiple of 32x32");
     static_assert(LDS_BYTES <= kLdsBytesPerCU, "stages x tile exceed LDS");
+    // Register budget: smaller tiles are built to let several workgroups share a CU (512 registers per
+    // lane and SIMD, accumulators included), so that one workgroup's loads and stores overlap another's
+    // MFMAs -- that is what the short-K, bandwidth-bound problems need.
+    static constexpr int MIN_WAVES = TM * TN >= 256 * 256 ? 1 : TM * TN >= 256 * 128 ? 2 : TM * TN >= 128 * 128 ? 3 : 4;
     using Groups = typename std::conditional<MODE == 1, GroupTable, NoGroupTable>::type;
 };
 
@@ -368,7 +378,7 @@ __device__ __forceinline__ f32x16_t mfma32(u32x4_t a, u32x4_t b, f32x16_t c) {
 }
 
 template <class Cfg>
-__global__ __launch_bounds__(kThreads) void ucl_tile_kernel(const KParams p, const typename Cfg::Groups gt) {
+__global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(const KParams p, const typename Cfg::Groups gt) {
     constexpr int TM = Cfg::TM, TN = Cfg::TN, TK = Cfg::TK, STAGES = Cfg::STAGES;
     constexpr int MI = Cfg::MI, NI = Cfg::NI, MODE = Cfg::MODE, LA = Cfg::LA, LB = Cfg::LB;
     constexpr int A_ITERS = Cfg::A_ITERS, B_ITERS = Cfg::B_ITERS;
@@ -803,7 +813,10 @@ __global__ __launch_bounds__(kThreads) void ucl_tile_kernel(const KParams p, con
     constexpr int LPR = WTN / 8;              // lanes per staged row
     constexpr int RPP = 64 / LPR;             // rows per pass
     constexpr int PASSES = 32 / RPP;
-    constexpr int kMaxNVec = 4, kMaxMat = 2;  // tensor operands fetched ahead of use; others load in place
+    // tensor operands of an interpreted chain fetched ahead of use (others load in place); kernels that
+    // share a CU with other workgroups have fewer registers and prefetch less
+    constexpr bool kLean = Cfg::MIN_WAVES >= 2;
+    constexpr int kMaxNVec = kLean ? 2 : 4, kMaxMat = kLean ? 1 : 2;
     __syncthreads();                          // every wave is done with the pipeline buffers
     // The chain is walked with a run-time step index.  Steps are read straight from the kernel
     // argument segment (constant address space, uniform index => scalar loads into SGPRs); `p` is
@@ -834,7 +847,9 @@ __global__ __launch_bounds__(kThreads) void ucl_tile_kernel(const KParams p, con
     c.n = n0 + wn * WTN + e_col;
     const int n_left = p.N - c.n;
 
+    // passes whose residual segments are requested together, ahead of use
     constexpr int GRP = PASSES < 4 ? PASSES : 4;
+    constexpr int GRP_I = Cfg::MIN_WAVES >= 3 ? 1 : (kLean && GRP > 2 ? 2 : GRP);     // pass group of the interpreted chain
 
     // accumulators of 32-row block `mi` -> this wave's staging patch (fp32).  acc needs constant
     // indices, and is only ever touched by code written directly in the kernel body (a closure that
@@ -905,6 +920,70 @@ __global__ __launch_bounds__(kThreads) void ucl_tile_kernel(const KParams p, con
         }
     };
 
+    // Fast form of the same block for the common case (decided once per wave): every lane owns 8
+    // existing columns and every tensor involved allows 128-bit access.  No per-element predicates,
+    // addresses advance by a constant per pass; only the row bound is tested.
+    auto fused_block_fast = [&](auto act_, int mi) __attribute__((always_inline)) {
+        constexpr int ACT = decltype(act_)::value;
+        const int m_first = m0 + wm * Cfg::WTM + mi * 32 + e_row;
+        const int esz = dtD == UCL_F32 ? 4 : 2;
+        char *dp = Db + (d_batch_off + (int64_t)m_first * p.ldd + c.n) * esz;
+        const int64_t dstep = (int64_t)RPP * p.ldd * esz;
+        const int res_dt = f.res_dt & 0xff;
+        const int rsz = res_dt == UCL_F32 ? 4 : 2;
+        const char *rp = res_base + (int64_t)m_first * f.res_ld * rsz;
+        const int64_t rstep = (int64_t)RPP * f.res_ld * rsz;
+        const float beta = f.beta, ap0 = f.act_p0, ap1 = f.act_p1;
+        const bool has_res = f.has_res != 0;
+#pragma clang loop unroll(disable)
+        for (int pg = 0; pg < PASSES; pg += GRP) {
+            u32x4_t r_lo[GRP], r_hi[GRP];
+            if (has_res) {
+                static_for<GRP>([&](auto u) {
+                    r_lo[u] = u32x4_t{0, 0, 0, 0};
+                    r_hi[u] = u32x4_t{0, 0, 0, 0};
+                    if (m_first + (pg + u) * RPP < Mloc) {
+                        r_lo[u] = *(const u32x4_t *)(rp + u * rstep);
+                        if (res_dt == UCL_F32) r_hi[u] = *(const u32x4_t *)(rp + u * rstep + 16);
+                    }
+                });
+            }
+            static_for<GRP>([&](auto u) {
+                const int row = (pg + u) * RPP + e_row;
+                float v[8];
+                staged_row(row, v);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[e] = v[e] * alpha + bias8[e];
+                if (has_res) {
+                    Raw8 r;
+                    r.lo = r_lo[u];
+                    r.hi = r_hi[u];
+                    r.packed = res_dt != UCL_F32;
+                    float t[8];
+                    decode8(r, res_dt, t);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) v[e] += beta * t[e];
+                }
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[e] = act_f32<ACT>(v[e], ap0, ap1);
+                if (m_first + (pg + u) * RPP < Mloc) {
+                    char *q = dp + u * dstep;
+                    if (dtD == UCL_F32) {
+                        ((f32x4_t *)q)[0] = f32x4_t{v[0], v[1], v[2], v[3]};
+                        ((f32x4_t *)q)[1] = f32x4_t{v[4], v[5], v[6], v[7]};
+                    } else {
+                        uint32_t b[8];
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) b[e] = f32_to_bits16(v[e], dtD);
+                        *(u32x4_t *)q = u32x4_t{b[0] | (b[1] << 16), b[2] | (b[3] << 16), b[4] | (b[5] << 16), b[6] | (b[7] << 16)};
+                    }
+                }
+            });
+            dp += GRP * dstep;
+            rp += GRP * rstep;
+        }
+    };
+
     if (f.enabled) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) bias8[e] = 0.f;
@@ -917,13 +996,20 @@ __global__ __launch_bounds__(kThreads) void ucl_tile_kernel(const KParams p, con
             res_base = (const char *)rp + ((int64_t)batch * f.res_bs + c.n) * ((f.res_dt & 0xff) == UCL_F32 ? 4 : 2);
         }
         if (f.has_scale) alpha = f.alpha;
+        // uniform per wave: all 8-column groups of the wave exist and every access may be 128-bit
+        const bool fast_ok = dvec && (n0 + wn * WTN + WTN <= p.N) && (!f.has_res || (f.res_dt & 0x100)) &&
+                             (!f.has_bias || (f.bias_dt & 0x100));
         // All block / pass loops of the epilogue are REAL loops: their bodies are re-executed from
         // the instruction cache instead of existing once per pass.
 #pragma clang loop unroll(disable)
         for (int mi = 0; mi < MI; ++mi) {
             UCL_STAGE_BLOCK(mi);
             switch (f.act) {
-#define UCL_FUSED_CASE(OP) case OP: fused_block(std::integral_constant<int, OP>{}, mi); break;
+#define UCL_FUSED_CASE(OP)                                                         \
+    case OP:                                                                       \
+        if (fast_ok) fused_block_fast(std::integral_constant<int, OP>{}, mi);      \
+        else fused_block(std::integral_constant<int, OP>{}, mi);                   \
+        break;
                 UCL_FUSED_CASE(UCL_EPI_RELU)
                 UCL_FUSED_CASE(UCL_EPI_GELU_TANH)
                 UCL_FUSED_CASE(UCL_EPI_GELU_ERF)
@@ -936,7 +1022,10 @@ __global__ __launch_bounds__(kThreads) void ucl_tile_kernel(const KParams p, con
                 UCL_FUSED_CASE(UCL_EPI_ELU)
                 UCL_FUSED_CASE(UCL_EPI_CLAMP)
 #undef UCL_FUSED_CASE
-            default: fused_block(std::integral_constant<int, 0>{}, mi); break;
+            default:
+                if (fast_ok) fused_block_fast(std::integral_constant<int, 0>{}, mi);
+                else fused_block(std::integral_constant<int, 0>{}, mi);
+                break;
             }
         }
     } else {
@@ -983,9 +1072,9 @@ __global__ __launch_bounds__(kThreads) void ucl_tile_kernel(const KParams p, con
             // passes run in groups: the matrix operands (residual) of a whole group are requested first,
             // so several row segments are in flight while the chain runs
 #pragma clang loop unroll(disable)
-            for (int pg = 0; pg < PASSES; pg += GRP) {
-                Raw8 mat[GRP][kMaxMat];
-                static_for<GRP>([&](auto u) {
+            for (int pg = 0; pg < PASSES; pg += GRP_I) {
+                Raw8 mat[GRP_I][kMaxMat];
+                static_for<GRP_I>([&](auto u) {
                     const int m = m_blk + (pg + u) * RPP + e_row;
                     const int nv = m < Mloc ? n_left : 0;
                     static_for<kMaxMat>([&](auto j) {
@@ -993,7 +1082,7 @@ __global__ __launch_bounds__(kThreads) void ucl_tile_kernel(const KParams p, con
                             mat[u][j] = load8(mat_base[j], mat_dt[j] & 0xff, (int64_t)m * mat_ld[j], (mat_dt[j] & 0x100) != 0, nv);
                     });
                 });
-                static_for<GRP>([&](auto u) {
+                static_for<GRP_I>([&](auto u) {
                     const int row = (pg + u) * RPP + e_row;
                     const int m = m_blk + row;
                     c.m = m;

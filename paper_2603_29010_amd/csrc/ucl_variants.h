@@ -21,10 +21,16 @@ struct VariantList {
 // one per instantiation unit
 VariantList variants_gemm_kk_bf16_a();
 VariantList variants_gemm_kk_bf16_b();
-VariantList variants_gemm_kk_f16();
+VariantList variants_gemm_kk_bf16_c();
+VariantList variants_gemm_kk_bf16_d();
+VariantList variants_gemm_kk_f16_a();
+VariantList variants_gemm_kk_f16_b();
 VariantList variants_gemm_mn_bf16();
 VariantList variants_gemm_mn_f16();
-VariantList variants_grouped();
-VariantList variants_conv();
+VariantList variants_grouped_a();
+VariantList variants_grouped_b();
+VariantList variants_conv_a();
+VariantList variants_conv_b();
+VariantList variants_conv_f16();
 
 }  // namespace ucl
