@@ -76,6 +76,9 @@ int64_t count_tiles(const Launch &L, int tm, int tn) {
     return L.batch * ((L.M + tm - 1) / tm) * tiles_n;
 }
 
+// The wide epilogue path addresses a wave's row panel (up to 128 rows) with 32-bit byte offsets.
+constexpr int64_t kMaxWideLd = 1ll << 21;
+
 const VariantDesc *select_variant(const Launch &L, const ucl_tuning *tune) {
     const auto &vs = all_variants();
     const bool explicit_tune = tune && (tune->tile_m || tune->tile_n || tune->tile_k || tune->stages);
@@ -134,7 +137,7 @@ ucl_status check_epilogue(const ucl_epilogue *epi, const Launch &L, KParams &kp)
             // (grouped: the per-group pointers live on the device and are required to be 16-byte aligned)
             if (op_is_matrix(s.op)) {
                 if (s.ld < L.N) return fail(UCL_ERR_INVALID_ARG, "epilogue step %d: ld=%lld is smaller than N=%lld", i, (long long)s.ld, (long long)L.N);
-                vec = vec && (s.ld % per16 == 0) && (s.bs % per16 == 0);
+                vec = vec && (s.ld % per16 == 0) && (s.bs % per16 == 0) && s.ld <= kMaxWideLd;
             }
             if (vec) d.dtype |= 0x100;
         }
@@ -236,6 +239,7 @@ ucl_status run(const Launch &L, KParams &kp, const GroupTable *gt_in, const ucl_
         }
         return fail(UCL_ERR_UNSUPPORTED, "no kernel built for this combination of operation, input type and layouts");
     }
+    if (kp.ldd > kMaxWideLd) kp.d_vec = 0;
     int raster = tune ? tune->raster : 0;
     if (raster < 0 || raster > 64) return fail(UCL_ERR_INVALID_ARG, "raster=%d must be in 0..64", raster);
     if (raster == 0) raster = default_raster(*v, L);

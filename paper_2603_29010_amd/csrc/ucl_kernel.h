@@ -377,6 +377,28 @@ __device__ __forceinline__ f32x16_t mfma32(u32x4_t a, u32x4_t b, f32x16_t c) {
     }
 }
 
+// Merge order of ND fragment reads and DN copy instructions within a k-step: reads in order, copy j
+// right after the read that completes the j-th equal share of the reads.
+template <int ND, int DN>
+struct SideSeq {
+    bool dma[ND + DN + 1] = {};
+    int which[ND + DN + 1] = {};
+    constexpr SideSeq() {
+        int j = 0, t = 0;
+        for (int r = 0; r < ND; ++r) {
+            dma[t] = false;
+            which[t] = r;
+            ++t;
+            while (j < DN && (j + 1) * ND <= (r + 1) * DN) {
+                dma[t] = true;
+                which[t] = j;
+                ++t;
+                ++j;
+            }
+        }
+    }
+};
+
 template <class Cfg>
 __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(const KParams p, const typename Cfg::Groups gt) {
     constexpr int TM = Cfg::TM, TN = Cfg::TN, TK = Cfg::TK, STAGES = Cfg::STAGES;
@@ -539,6 +561,43 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
             }
         }
     };
+    // One copy instruction of k-tile `kt`: slot IDX counts the A slots first, then the B slots.  The
+    // deep pipeline deals these out one at a time between the MFMAs (K-contiguous / im2col operands).
+    auto issue_one = [&](auto check_k_, auto idx_, int kt, int buf) {
+        constexpr bool CHECK_K = decltype(check_k_)::value;
+        constexpr int IDX = decltype(idx_)::value;
+        char *sA = smem + buf * Cfg::STAGE_BYTES;
+        char *sB = sA + Cfg::A_BYTES;
+        const int k0 = kt * TK;
+        const bool kok = !CHECK_K || (k0 + l_kc < K);
+        if constexpr (IDX < A_ITERS) {
+            constexpr int i = IDX;
+            char *dst = sA + (i * kThreads + wave * 64) * 16;
+            if constexpr (LA == kKContig) {
+                const uint32_t off = CHECK_K ? (kok ? a_off[i] : kOobOffset) : a_off[i];
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, UCL_LDS_PTR(dst), 16, off, k0 * 2, 0, 0);
+            } else {
+                const int dh = a_r * p.dil_h, dw = a_s * p.dil_w;
+                const uint32_t tap_off = (uint32_t)(((dh * p.cW + dw) * p.cC + a_ci) * 2);
+                const int h = a_h0[i] + dh, w = a_w0[i] + dw;
+                const bool ok = kok && (unsigned)h < (unsigned)p.cH && (unsigned)w < (unsigned)p.cW;
+                const uint32_t off = ok ? a_off[i] + tap_off : kOobOffset;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, UCL_LDS_PTR(dst), 16, off, 0, 0, 0);
+                if constexpr (i == A_ITERS - 1) {     // advance k by one k-tile: (ci, s, r) += TK channels
+                    a_ci += TK;
+                    while (a_ci >= p.cC) {
+                        a_ci -= p.cC;
+                        if (++a_s == p.cS) { a_s = 0; ++a_r; }
+                    }
+                }
+            }
+        } else {
+            constexpr int i = IDX - A_ITERS;
+            char *dst = sB + (i * kThreads + wave * 64) * 16;
+            const uint32_t off = CHECK_K ? (kok ? b_off[i] : kOobOffset) : b_off[i];
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(b_rsrc, UCL_LDS_PTR(dst), 16, off, k0 * 2, 0, 0);
+        }
+    };
     auto issue_tile = [&](auto check_k_, int kt, int buf) {
         issue_part(check_k_, std::integral_constant<int, 0>{}, kt, buf);
     };
@@ -672,6 +731,46 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
         });
         __builtin_amdgcn_sched_barrier(0);
     };
+    // Fragment `IDX` of a k-step in order of first use by the MFMAs (A block 0, all B blocks, then the
+    // other A blocks).
+    auto read_one = [&](auto set_, auto kk_, auto idx_, const char *sbase) {
+        constexpr int set = decltype(set_)::value, kk = decltype(kk_)::value, IDX = decltype(idx_)::value;
+        const int xo = f_x ^ (kk * 32);
+        if constexpr (IDX == 0) af[set][0] = *(const u32x4_t *)(sbase + a_frag_base + xo);
+        else if constexpr (IDX <= NI) bf[set][IDX - 1] = *(const u32x4_t *)(sbase + b_frag_base + (IDX - 1) * 32 * ROW_BYTES + xo);
+        else af[set][IDX - NI] = *(const u32x4_t *)(sbase + a_frag_base + (IDX - NI) * 32 * ROW_BYTES + xo);
+    };
+    // A k-step of the deep pipeline: its MI*NI MFMAs (fragment set CS) with, dealt out one per MFMA
+    // in this order, the fragment reads of the following k-step (into set 1-CS, k-step RK of the
+    // stage at rbase) and copy slots [D0, D0+DN) of k-tile kt_load, evenly spaced between the reads.
+    // Source order and scheduling hints name the same sequence: the compiler keeps LDS reads and
+    // LDS-writing loads in program order (it cannot tell that they touch different stage buffers).
+    auto pipelined_step = [&](auto cs_, auto rk_, const char *rbase, auto check_, auto d0_, auto dn_, int kt_load, int fill_buf) {
+        constexpr int CS = decltype(cs_)::value, RK = decltype(rk_)::value;
+        constexpr int D0 = decltype(d0_)::value, DN = decltype(dn_)::value;
+        constexpr int ND = kDsPerStep;
+        constexpr SideSeq<ND, DN> seq{};
+        static_for<ND + DN>([&](auto t_) {
+            constexpr int t = decltype(t_)::value;
+            if constexpr (seq.dma[t]) issue_one(check_, std::integral_constant<int, D0 + seq.which[t]>{}, kt_load, fill_buf);
+            else read_one(std::integral_constant<int, 1 - CS>{}, rk_, std::integral_constant<int, seq.which[t]>{}, rbase);
+        });
+        mfma_step(cs_);
+        constexpr int T = ND + DN;
+        constexpr int Q = (T + kMfmaPerStep - 1) / kMfmaPerStep;         // side instructions per MFMA slot
+        static_for<kMfmaPerStep>([&](auto i_) {
+            constexpr int i = decltype(i_)::value;
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            static_for<Q>([&](auto q_) {
+                constexpr int t = i * Q + decltype(q_)::value;
+                if constexpr (t < T) {
+                    if constexpr (seq.dma[t]) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+                    else __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                }
+            });
+        });
+        __builtin_amdgcn_sched_barrier(0);
+    };
     using I0 = std::integral_constant<int, 0>;
     using I1 = std::integral_constant<int, 1>;
 
@@ -713,9 +812,8 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
             // issued under the first k-step of stage kt, its B half under the last.  A wave's load
             // instructions then arrive at the memory pipeline a few at a time instead of as one burst
             // whose queueing would hold back the MFMAs issued behind it.
-            constexpr int DA = A_ITERS, DB = B_ITERS;
-            using P1 = std::integral_constant<int, 1>;
-            using P2 = std::integral_constant<int, 2>;
+            // Copy slots of a stage are split evenly over its k-steps.
+            constexpr int DPS = (DMA_PER_TILE + KSTEPS - 1) / KSTEPS;
 #pragma unroll
             for (int s = 0; s < STAGES - 1; ++s)
                 if (s < KT) issue(s, s);
@@ -724,35 +822,48 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
             __syncthreads();
             read_frags(I0{}, I0{}, smem);
             int kt = 0;
-            int fill = STAGES - 1;                 // buffer index of stage kt+STAGES-1, kept without a modulo
-            int cur = 0;
             // stages [0, KT_full) are complete k-tiles: their loads skip the K-tail test
             const int KT_full = k_tail ? KT - 1 : KT;
-            auto deep_iter = [&](auto check_) {
+            // One stage.  cur / fill are the buffers of stage kt and of stage kt+STAGES-1 (the one
+            // released at the previous boundary); passed as constants by the unrolled steady loop,
+            // so that every LDS address in it is a loop-invariant register plus an immediate.
+            auto deep_iter = [&](auto check_, auto cur_, auto fill_) {
+                const int cur = cur_, fill = fill_;
                 const char *sbase = smem + cur * Cfg::STAGE_BYTES;
                 const int nxt = cur + 1 == STAGES ? 0 : cur + 1;
-                // first k-step: A half of the refill + fragments of the second k-step
-                read_frags(I1{}, I1{}, sbase);
-                issue_part(check_, P1{}, kt + STAGES - 1, fill);
-                mfma_step(I0{});
-                interleave_step(std::integral_constant<int, DA>{});
-                static_for<KSTEPS - 2>([&](auto kk_) {
-                    constexpr int kk = decltype(kk_)::value + 1;
-                    read_frags(std::integral_constant<int, (kk + 1) & 1>{}, std::integral_constant<int, kk + 1>{}, sbase);
-                    mfma_step(std::integral_constant<int, kk & 1>{});
-                    interleave_ds_mfma();
+                static_for<KSTEPS - 1>([&](auto kk_) {
+                    constexpr int kk = decltype(kk_)::value;
+                    constexpr int d0 = kk * DPS < DMA_PER_TILE ? kk * DPS : DMA_PER_TILE;
+                    constexpr int d1 = (kk + 1) * DPS < DMA_PER_TILE ? (kk + 1) * DPS : DMA_PER_TILE;
+                    pipelined_step(std::integral_constant<int, kk & 1>{}, std::integral_constant<int, kk + 1>{}, sbase, check_,
+                                   std::integral_constant<int, d0>{}, std::integral_constant<int, d1 - d0>{}, kt + STAGES - 1, fill);
                 });
-                // stage kt+1 must have landed; younger: stages kt+2..kt+STAGES-2 and the A half just issued
-                pipeline_barrier<(STAGES - 3) * DMA_PER_TILE + DA>();
-                read_frags(I0{}, I0{}, smem + nxt * Cfg::STAGE_BYTES);
-                issue_part(check_, P2{}, kt + STAGES - 1, fill);
-                mfma_step(I1{});
-                interleave_step(std::integral_constant<int, DB>{});
-                fill = cur;
-                cur = nxt;
+                // stage kt+1 must have landed; younger: stages kt+2..kt+STAGES-2 and this stage's slots so far
+                constexpr int dl0 = (KSTEPS - 1) * DPS < DMA_PER_TILE ? (KSTEPS - 1) * DPS : DMA_PER_TILE;
+                pipeline_barrier<(STAGES - 3) * DMA_PER_TILE + dl0>();
+                pipelined_step(I1{}, I0{}, smem + nxt * Cfg::STAGE_BYTES, check_, std::integral_constant<int, dl0>{},
+                               std::integral_constant<int, DMA_PER_TILE - dl0>{}, kt + STAGES - 1, fill);
             };
-            for (; kt + STAGES - 1 < KT_full; ++kt) deep_iter(std::false_type{});
-            for (; kt + STAGES - 1 < KT; ++kt) deep_iter(std::true_type{});       // the partial k-tile, if any
+            // steady state, unrolled over the ring of stage buffers
+            while (kt + 2 * STAGES - 2 < KT_full) {
+                static_for<STAGES>([&](auto s_) {
+                    constexpr int sb = decltype(s_)::value;
+                    deep_iter(std::false_type{}, std::integral_constant<int, sb>{},
+                              std::integral_constant<int, (sb + STAGES - 1) % STAGES>{});
+                    ++kt;
+                });
+            }
+            int cur = 0, fill = STAGES - 1;        // kt is a multiple of STAGES here
+            for (; kt + STAGES - 1 < KT_full; ++kt) {
+                deep_iter(std::false_type{}, cur, fill);
+                fill = cur;
+                cur = cur + 1 == STAGES ? 0 : cur + 1;
+            }
+            for (; kt + STAGES - 1 < KT; ++kt) {   // the partial k-tile, if any
+                deep_iter(std::true_type{}, cur, fill);
+                fill = cur;
+                cur = cur + 1 == STAGES ? 0 : cur + 1;
+            }
             for (; kt < KT - 1; ++kt) {            // drain
                 const int nxt = cur + 1 == STAGES ? 0 : cur + 1;
                 head_steps(smem + cur * Cfg::STAGE_BYTES);
@@ -884,7 +995,8 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
     // registers are read at exactly one place in the code)
     const FusedEpi &f = p.fused;
     float bias8[8];
-    const char *res_base = nullptr;
+    const char *res_base = nullptr;       // residual, this lane's columns of row 0
+    const char *res_u = nullptr;          // residual, element (0, 0) of this batch / group (wave-uniform)
     float alpha = 1.f;
     auto fused_block = [&](auto act_, int mi) __attribute__((always_inline)) {
         constexpr int ACT = decltype(act_)::value;
@@ -921,67 +1033,87 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
     };
 
     // Fast form of the same block for the common case (decided once per wave): every lane owns 8
-    // existing columns and every tensor involved allows 128-bit access.  No per-element predicates,
-    // addresses advance by a constant per pass; only the row bound is tested.
+    // existing columns and every tensor involved allows 128-bit access.  Rows are bounded by the
+    // range check of buffer resources that cover exactly the wave's existing rows (stores past the
+    // end are dropped, residual loads return zero), so the block is straight-line code: all residual
+    // rows and all staged rows are requested up front and the arithmetic of one pass runs while the
+    // data of the next is still on its way.
+    const int w_rows = Mloc - (m0 + wm * Cfg::WTM) < Cfg::WTM ? Mloc - (m0 + wm * Cfg::WTM) : Cfg::WTM;
+    const int d_esz = dtD == UCL_F32 ? 4 : 2;
+    const int r_dt = f.res_dt & 0xff;
+    const int r_esz = r_dt == UCL_F32 ? 4 : 2;
+    rsrc_t d_rsrc = buffer_rsrc(nullptr, 0), r_rsrc = buffer_rsrc(nullptr, 0);
+    uint32_t d_lane = 0, r_lane = 0, d_row_bytes = 0, r_row_bytes = 0;
+    auto fast_setup = [&]() __attribute__((always_inline)) {
+        const int64_t col0 = n0 + wn * WTN;
+        if (w_rows > 0) {
+            d_rsrc = buffer_rsrc(Db + (d_batch_off + (int64_t)(m0 + wm * Cfg::WTM) * p.ldd + col0) * d_esz,
+                                 (uint32_t)(((int64_t)(w_rows - 1) * p.ldd + WTN) * d_esz));
+            if (f.has_res)
+                r_rsrc = buffer_rsrc(res_u + ((int64_t)(m0 + wm * Cfg::WTM) * f.res_ld + col0) * r_esz,
+                                     (uint32_t)(((int64_t)(w_rows - 1) * f.res_ld + WTN) * r_esz));
+        }
+        d_row_bytes = (uint32_t)(p.ldd * d_esz);
+        r_row_bytes = (uint32_t)(f.res_ld * r_esz);
+        d_lane = e_row * d_row_bytes + e_col * d_esz;
+        r_lane = e_row * r_row_bytes + e_col * r_esz;
+    };
+    // passes whose operands are requested together (all of a block where registers allow)
+    constexpr int FG = Cfg::MIN_WAVES >= 3 && PASSES > 2 ? 2 : PASSES;
     auto fused_block_fast = [&](auto act_, int mi) __attribute__((always_inline)) {
         constexpr int ACT = decltype(act_)::value;
-        const int m_first = m0 + wm * Cfg::WTM + mi * 32 + e_row;
-        const int esz = dtD == UCL_F32 ? 4 : 2;
-        char *dp = Db + (d_batch_off + (int64_t)m_first * p.ldd + c.n) * esz;
-        const int64_t dstep = (int64_t)RPP * p.ldd * esz;
-        const int res_dt = f.res_dt & 0xff;
-        const int rsz = res_dt == UCL_F32 ? 4 : 2;
-        const char *rp = res_base + (int64_t)m_first * f.res_ld * rsz;
-        const int64_t rstep = (int64_t)RPP * f.res_ld * rsz;
         const float beta = f.beta, ap0 = f.act_p0, ap1 = f.act_p1;
         const bool has_res = f.has_res != 0;
-#pragma clang loop unroll(disable)
-        for (int pg = 0; pg < PASSES; pg += GRP) {
-            u32x4_t r_lo[GRP], r_hi[GRP];
+        const uint32_t r0 = r_lane + mi * 32 * r_row_bytes;
+        const uint32_t d0 = d_lane + mi * 32 * d_row_bytes;
+        static_for<PASSES / FG>([&](auto g_) {
+            constexpr int P0 = decltype(g_)::value * FG;
+            u32x4_t r_lo[FG], r_hi[FG];
             if (has_res) {
-                static_for<GRP>([&](auto u) {
-                    r_lo[u] = u32x4_t{0, 0, 0, 0};
-                    r_hi[u] = u32x4_t{0, 0, 0, 0};
-                    if (m_first + (pg + u) * RPP < Mloc) {
-                        r_lo[u] = *(const u32x4_t *)(rp + u * rstep);
-                        if (res_dt == UCL_F32) r_hi[u] = *(const u32x4_t *)(rp + u * rstep + 16);
-                    }
+                static_for<FG>([&](auto u) {
+                    r_lo[u] = __builtin_amdgcn_raw_buffer_load_b128(r_rsrc, r0 + (P0 + u) * RPP * r_row_bytes, 0, 0);
+                    if (r_dt == UCL_F32)
+                        r_hi[u] = __builtin_amdgcn_raw_buffer_load_b128(r_rsrc, r0 + (P0 + u) * RPP * r_row_bytes + 16, 0, 0);
+                    else r_hi[u] = u32x4_t{0, 0, 0, 0};
                 });
             }
-            static_for<GRP>([&](auto u) {
-                const int row = (pg + u) * RPP + e_row;
+            f32x4_t s_lo[FG], s_hi[FG];
+            static_for<FG>([&](auto u) {
+                s_lo[u] = *(const f32x4_t *)(stg + ((P0 + u) * RPP + e_row) * EPI_LD + e_col);
+                s_hi[u] = *(const f32x4_t *)(stg + ((P0 + u) * RPP + e_row) * EPI_LD + e_col + 4);
+            });
+            static_for<FG>([&](auto u) {
                 float v[8];
-                staged_row(row, v);
 #pragma unroll
-                for (int e = 0; e < 8; ++e) v[e] = v[e] * alpha + bias8[e];
+                for (int e = 0; e < 4; ++e) {
+                    v[e] = s_lo[u][e] * alpha + bias8[e];
+                    v[4 + e] = s_hi[u][e] * alpha + bias8[4 + e];
+                }
                 if (has_res) {
                     Raw8 r;
                     r.lo = r_lo[u];
                     r.hi = r_hi[u];
-                    r.packed = res_dt != UCL_F32;
+                    r.packed = r_dt != UCL_F32;
                     float t[8];
-                    decode8(r, res_dt, t);
+                    decode8(r, r_dt, t);
 #pragma unroll
                     for (int e = 0; e < 8; ++e) v[e] += beta * t[e];
                 }
 #pragma unroll
                 for (int e = 0; e < 8; ++e) v[e] = act_f32<ACT>(v[e], ap0, ap1);
-                if (m_first + (pg + u) * RPP < Mloc) {
-                    char *q = dp + u * dstep;
-                    if (dtD == UCL_F32) {
-                        ((f32x4_t *)q)[0] = f32x4_t{v[0], v[1], v[2], v[3]};
-                        ((f32x4_t *)q)[1] = f32x4_t{v[4], v[5], v[6], v[7]};
-                    } else {
-                        uint32_t b[8];
+                const uint32_t off = d0 + (P0 + u) * RPP * d_row_bytes;
+                if (dtD == UCL_F32) {
+                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, f32x4_t{v[0], v[1], v[2], v[3]}), d_rsrc, off, 0, 0);
+                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, f32x4_t{v[4], v[5], v[6], v[7]}), d_rsrc, off + 16, 0, 0);
+                } else {
+                    uint32_t b[8];
 #pragma unroll
-                        for (int e = 0; e < 8; ++e) b[e] = f32_to_bits16(v[e], dtD);
-                        *(u32x4_t *)q = u32x4_t{b[0] | (b[1] << 16), b[2] | (b[3] << 16), b[4] | (b[5] << 16), b[6] | (b[7] << 16)};
-                    }
+                    for (int e = 0; e < 8; ++e) b[e] = f32_to_bits16(v[e], dtD);
+                    __builtin_amdgcn_raw_buffer_store_b128(u32x4_t{b[0] | (b[1] << 16), b[2] | (b[3] << 16), b[4] | (b[5] << 16), b[6] | (b[7] << 16)},
+                                                           d_rsrc, off, 0, 0);
                 }
             });
-            dp += GRP * dstep;
-            rp += GRP * rstep;
-        }
+        });
     };
 
     if (f.enabled) {
@@ -993,12 +1125,14 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
         }
         if (f.has_res) {
             const void *rp = group >= 0 ? ((const void *const *)f.res)[group] : f.res;
-            res_base = (const char *)rp + ((int64_t)batch * f.res_bs + c.n) * ((f.res_dt & 0xff) == UCL_F32 ? 4 : 2);
+            res_u = (const char *)rp + (int64_t)batch * f.res_bs * r_esz;
+            res_base = res_u + (int64_t)c.n * r_esz;
         }
         if (f.has_scale) alpha = f.alpha;
         // uniform per wave: all 8-column groups of the wave exist and every access may be 128-bit
         const bool fast_ok = dvec && (n0 + wn * WTN + WTN <= p.N) && (!f.has_res || (f.res_dt & 0x100)) &&
                              (!f.has_bias || (f.bias_dt & 0x100));
+        if (fast_ok) fast_setup();
         // All block / pass loops of the epilogue are REAL loops: their bodies are re-executed from
         // the instruction cache instead of existing once per pass.
 #pragma clang loop unroll(disable)
