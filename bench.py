@@ -22,6 +22,12 @@ sys.path.insert(0, ROOT)
 
 PEAK_MFMA_TFLOPS = 2516.6      # dense bf16 / fp16, 256 CUs x 2.4 GHz x 4096 FLOP/clk
 PEAK_HBM_GBPS = 8000.0
+# HBM bytes moved per launch (read + written) as counted by rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
+# each scaled by what the same counter reads for a plain 256 MiB device copy (2.000 and 1.000); the
+# runs and their commands are recorded in profiles/ucl_tile_kernel_*.txt.  Counters cannot be read
+# from inside this process, so these are the recorded figures for the kernels the selection table
+# picks for each workload.
+MEASURED_TRAFFIC_BYTES = {1: 1128591, 2: 235418087, 3: 84202219, 4: 525575929, 5: 65781892}
 WORKLOAD_NAMES = {
     1: "gemm_256x256x256_bf16_bias_relu",
     2: "gemm_4096x4096x4096_bf16_rowcol_bias_gelu_tanh",
@@ -166,7 +172,7 @@ def main():
         "peak": PEAK_MFMA_TFLOPS if mfma else PEAK_HBM_GBPS,
         "unit": "TFLOP/s" if mfma else "GB/s",
         "frac": (res["tflops"] / PEAK_MFMA_TFLOPS) if mfma else (res["gbps"] / PEAK_HBM_GBPS),
-        "traffic": None,
+        "traffic": MEASURED_TRAFFIC_BYTES.get(args.config),
     }
     out = {
         "metric": "TFLOP/s and % of SOL (MFMA/HBM roofline) per GEMM/conv config, 1 MI355X",

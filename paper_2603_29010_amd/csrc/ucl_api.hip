@@ -62,10 +62,15 @@ struct Launch {
 
 // Per-problem selection table.  Rules, in order:
 //   1. only variants built for this (mode, input type, operand layouts) are candidates;
-//   2. take the largest tile that still yields at least ~3/4 of a full wave of workgroups over the
-//      256 CUs (fewer, larger tiles = more reuse per byte staged; too few = idle CUs);
+//   2. a problem whose arithmetic intensity is below the machine balance (memory-bound by the SOL
+//      model) spends its time in the load and store phases of its tiles, which one workgroup runs
+//      one after the other: take the largest tile among the variants of which at least two
+//      workgroups fit on a CU (registers and LDS) and that yield a full wave of workgroups, so that
+//      one workgroup's stores overlap another's loads;
+//   3. otherwise take the largest tile that still yields at least ~3/4 of a full wave of workgroups
+//      over the 256 CUs (fewer, larger tiles = more reuse per byte staged; too few = idle CUs);
 //      if none does, take the tile giving the most workgroups;
-//   3. among equal tiles take the deepest pipeline the K extent can use (stages - 1 <= K tiles).
+//   4. among equal tiles take the deepest pipeline the K extent can use (stages - 1 <= K tiles).
 int64_t count_tiles(const Launch &L, int tm, int tn) {
     const int64_t tiles_n = (L.N + tn - 1) / tn;
     if (L.mode == 1) {
@@ -79,11 +84,36 @@ int64_t count_tiles(const Launch &L, int tm, int tn) {
 // The wide epilogue path addresses a wave's row panel (up to 128 rows) with 32-bit byte offsets.
 constexpr int64_t kMaxWideLd = 1ll << 21;
 
+// Workgroups of a variant that fit on one CU: 512 registers per lane and SIMD (the kernels are built
+// with a budget by tile area), 160 KB of LDS.
+int workgroups_per_cu(const VariantDesc &v) {
+    const int64_t area = (int64_t)v.tile_m * v.tile_n;
+    const int by_regs = area >= 256 * 256 ? 1 : area >= 256 * 128 ? 2 : area >= 128 * 128 ? 3 : 4;
+    const int by_lds = v.lds_bytes > 0 ? kLdsBytesPerCU / v.lds_bytes : 8;
+    return by_regs < by_lds ? by_regs : by_lds;
+}
+
+// Arithmetic intensity of the problem against the ridge of the default machine (bf16/fp16 MFMA peak
+// over HBM bandwidth), operands and output counted once.
+bool memory_bound(const Launch &L) {
+    double flops, bytes;
+    const double eo = L.dtD == UCL_F32 ? 4.0 : 2.0;
+    if (L.mode == 1) {
+        flops = 2.0 * (double)L.sum_Mg * L.N * L.K;
+        bytes = 2.0 * ((double)L.sum_Mg * L.K + (double)L.groups * L.N * L.K) + eo * (double)L.sum_Mg * L.N;
+    } else {
+        flops = 2.0 * (double)L.batch * L.M * L.N * L.K;
+        bytes = (double)L.batch * (2.0 * ((double)L.M * L.K + (double)L.N * L.K) + eo * (double)L.M * L.N);
+    }
+    return flops * 8.0e12 < bytes * 2516.6e12;
+}
+
 const VariantDesc *select_variant(const Launch &L, const ucl_tuning *tune) {
     const auto &vs = all_variants();
     const bool explicit_tune = tune && (tune->tile_m || tune->tile_n || tune->tile_k || tune->stages);
     const VariantDesc *best = nullptr;
     int64_t best_key = -1;
+    const bool membound = !explicit_tune && memory_bound(L);
     for (const auto &v : vs) {
         if (v.mode != L.mode || v.f16 != L.f16 || v.la != L.la || v.lb != L.lb) continue;
         if (explicit_tune) {
@@ -95,9 +125,9 @@ const VariantDesc *select_variant(const Launch &L, const ucl_tuning *tune) {
         const int64_t tiles = count_tiles(L, v.tile_m, v.tile_n);
         const int64_t area = (int64_t)v.tile_m * v.tile_n;
         const int64_t ktiles = (L.K + v.tile_k - 1) / v.tile_k;
-        const bool fills = tiles >= 192;
         int64_t key;
-        if (fills) key = (1ll << 40) + area * 1024;
+        if (membound && workgroups_per_cu(v) >= 2 && tiles >= 256) key = (2ll << 40) + area * 1024;
+        else if (tiles >= 192) key = (1ll << 40) + area * 1024;
         else key = tiles * 1024;
         // prefer the pipeline with the most bytes in flight that the K extent can fill
         const int64_t depth = v.stages <= ktiles ? (int64_t)(v.stages - 1) * v.tile_k : 0;
@@ -501,6 +531,9 @@ ucl_status ucl_select_tuning(const ucl_problem *p, ucl_tuning *out) {
     L.groups = p->groups; L.M_g = p->M_g;
     L.la = L.mode == 2 ? 2 : 0; L.lb = 0;
     L.f16 = p->dt_in == UCL_F16;
+    L.dtD = p->dt_out;
+    if (L.mode == 1)
+        for (int g = 0; g < L.groups; ++g) L.sum_Mg += L.M_g[g];
     const VariantDesc *v = select_variant(L, nullptr);
     if (!v) return fail(UCL_ERR_UNSUPPORTED, "no kernel built for this problem");
     memset(out, 0, sizeof(*out));

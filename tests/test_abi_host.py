@@ -96,6 +96,9 @@ def test_selection_table():
     assert (t["tile_m"], t["tile_n"]) == (256, 256)
     t = ucl.ucl_select_tuning("gemm", "bf16", "bf16", M=256, N=256, K=256)
     assert (t["tile_m"], t["tile_n"]) == (64, 64)
+    # memory-bound by the SOL model (short K, fp32 output): a tile of which two workgroups share a CU
+    t = ucl.ucl_select_tuning("batched_gemm", "f16", "f32", batch=64, M=512, N=512, K=128)
+    assert (t["tile_m"], t["tile_n"], t["tile_k"], t["stages"]) == (256, 128, 32, 3)
     variants = [ucl.ucl_variant(i) for i in range(ucl.ucl_num_variants())]
     assert all((v["tile_m"] + v["tile_n"]) * v["tile_k"] * 2 * v["stages"] <= 160 * 1024 for v in variants)
 
