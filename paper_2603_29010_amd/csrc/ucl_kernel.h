@@ -360,6 +360,9 @@ struct KernelCfg {
 // Loads through it whose offset is >= bytes return zero, which is how rows beyond the problem edge,
 // the K tail and the conv halo become zeros in LDS without a branch or a second address.
 typedef __amdgpu_buffer_rsrc_t rsrc_t;
+typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+typedef __attribute__((ext_vector_type(2))) _Float16 f16x2_t;
 constexpr uint32_t kOobOffset = 0x80000000u;   // never inside a resource (sizes are kept below 2^31)
 __device__ __forceinline__ rsrc_t buffer_rsrc(const void *base, uint32_t bytes) {
     // word 3: 32-bit data format, raw (unstructured) addressing
@@ -1060,59 +1063,110 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
     };
     // passes whose operands are requested together (all of a block where registers allow)
     constexpr int FG = Cfg::MIN_WAVES >= 3 && PASSES > 2 ? 2 : PASSES;
-    auto fused_block_fast = [&](auto act_, int mi) __attribute__((always_inline)) {
-        constexpr int ACT = decltype(act_)::value;
+    // The block in three phases, each selected once per pass group by a wave-uniform branch instead of
+    // per element: gather (staged fp32 * alpha + bias + beta * residual, by residual type), activation
+    // (by opcode), conversion + store (by output type).  The values of the whole group stay in
+    // registers between the phases.
+    auto fast_block = [&](auto has_res_, int mi) __attribute__((always_inline)) {
+        constexpr bool HAS_RES = decltype(has_res_)::value;
         const float beta = f.beta, ap0 = f.act_p0, ap1 = f.act_p1;
-        const bool has_res = f.has_res != 0;
         const uint32_t r0 = r_lane + mi * 32 * r_row_bytes;
         const uint32_t d0 = d_lane + mi * 32 * d_row_bytes;
         static_for<PASSES / FG>([&](auto g_) {
             constexpr int P0 = decltype(g_)::value * FG;
+            float v[FG][8];
             u32x4_t r_lo[FG], r_hi[FG];
-            if (has_res) {
+            if constexpr (HAS_RES) {
                 static_for<FG>([&](auto u) {
                     r_lo[u] = __builtin_amdgcn_raw_buffer_load_b128(r_rsrc, r0 + (P0 + u) * RPP * r_row_bytes, 0, 0);
-                    if (r_dt == UCL_F32)
-                        r_hi[u] = __builtin_amdgcn_raw_buffer_load_b128(r_rsrc, r0 + (P0 + u) * RPP * r_row_bytes + 16, 0, 0);
-                    else r_hi[u] = u32x4_t{0, 0, 0, 0};
                 });
+                if (r_dt == UCL_F32) {
+                    static_for<FG>([&](auto u) {
+                        r_hi[u] = __builtin_amdgcn_raw_buffer_load_b128(r_rsrc, r0 + (P0 + u) * RPP * r_row_bytes + 16, 0, 0);
+                    });
+                }
             }
-            f32x4_t s_lo[FG], s_hi[FG];
             static_for<FG>([&](auto u) {
-                s_lo[u] = *(const f32x4_t *)(stg + ((P0 + u) * RPP + e_row) * EPI_LD + e_col);
-                s_hi[u] = *(const f32x4_t *)(stg + ((P0 + u) * RPP + e_row) * EPI_LD + e_col + 4);
-            });
-            static_for<FG>([&](auto u) {
-                float v[8];
+                const f32x4_t lo = *(const f32x4_t *)(stg + ((P0 + u) * RPP + e_row) * EPI_LD + e_col);
+                const f32x4_t hi = *(const f32x4_t *)(stg + ((P0 + u) * RPP + e_row) * EPI_LD + e_col + 4);
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    v[e] = s_lo[u][e] * alpha + bias8[e];
-                    v[4 + e] = s_hi[u][e] * alpha + bias8[4 + e];
-                }
-                if (has_res) {
-                    Raw8 r;
-                    r.lo = r_lo[u];
-                    r.hi = r_hi[u];
-                    r.packed = r_dt != UCL_F32;
-                    float t[8];
-                    decode8(r, r_dt, t);
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) v[e] += beta * t[e];
-                }
-#pragma unroll
-                for (int e = 0; e < 8; ++e) v[e] = act_f32<ACT>(v[e], ap0, ap1);
-                const uint32_t off = d0 + (P0 + u) * RPP * d_row_bytes;
-                if (dtD == UCL_F32) {
-                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, f32x4_t{v[0], v[1], v[2], v[3]}), d_rsrc, off, 0, 0);
-                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, f32x4_t{v[4], v[5], v[6], v[7]}), d_rsrc, off + 16, 0, 0);
-                } else {
-                    uint32_t b[8];
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) b[e] = f32_to_bits16(v[e], dtD);
-                    __builtin_amdgcn_raw_buffer_store_b128(u32x4_t{b[0] | (b[1] << 16), b[2] | (b[3] << 16), b[4] | (b[5] << 16), b[6] | (b[7] << 16)},
-                                                           d_rsrc, off, 0, 0);
+                    v[u][e] = lo[e] * alpha + bias8[e];
+                    v[u][4 + e] = hi[e] * alpha + bias8[4 + e];
                 }
             });
+            if constexpr (HAS_RES) {
+                if (r_dt == UCL_F32) {
+                    static_for<FG>([&](auto u) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            v[u][e] += beta * __builtin_bit_cast(float, r_lo[u][e]);
+                            v[u][4 + e] += beta * __builtin_bit_cast(float, r_hi[u][e]);
+                        }
+                    });
+                } else if (r_dt == UCL_BF16) {
+                    static_for<FG>([&](auto u) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            v[u][2 * e] += beta * __builtin_bit_cast(float, r_lo[u][e] << 16);
+                            v[u][2 * e + 1] += beta * __builtin_bit_cast(float, r_lo[u][e] & 0xffff0000u);
+                        }
+                    });
+                } else {
+                    static_for<FG>([&](auto u) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const f16x2_t h = __builtin_bit_cast(f16x2_t, r_lo[u][e]);
+                            v[u][2 * e] += beta * (float)h[0];
+                            v[u][2 * e + 1] += beta * (float)h[1];
+                        }
+                    });
+                }
+            }
+            switch (f.act) {
+#define UCL_ACT_CASE(OP)                                                                   \
+    case OP:                                                                               \
+        static_for<FG>([&](auto u) {                                                       \
+            _Pragma("unroll") for (int e = 0; e < 8; ++e) v[u][e] = act_f32<OP>(v[u][e], ap0, ap1); \
+        });                                                                                \
+        break;
+                UCL_ACT_CASE(UCL_EPI_RELU)
+                UCL_ACT_CASE(UCL_EPI_GELU_TANH)
+                UCL_ACT_CASE(UCL_EPI_GELU_ERF)
+                UCL_ACT_CASE(UCL_EPI_SILU)
+                UCL_ACT_CASE(UCL_EPI_SIGMOID)
+                UCL_ACT_CASE(UCL_EPI_TANH)
+                UCL_ACT_CASE(UCL_EPI_MISH)
+                UCL_ACT_CASE(UCL_EPI_HARDSWISH)
+                UCL_ACT_CASE(UCL_EPI_LEAKY_RELU)
+                UCL_ACT_CASE(UCL_EPI_ELU)
+                UCL_ACT_CASE(UCL_EPI_CLAMP)
+#undef UCL_ACT_CASE
+            default: break;
+            }
+            if (dtD == UCL_F32) {
+                static_for<FG>([&](auto u) {
+                    const uint32_t off = d0 + (P0 + u) * RPP * d_row_bytes;
+                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, f32x4_t{v[u][0], v[u][1], v[u][2], v[u][3]}), d_rsrc, off, 0, 0);
+                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, f32x4_t{v[u][4], v[u][5], v[u][6], v[u][7]}), d_rsrc, off + 16, 0, 0);
+                });
+            } else if (dtD == UCL_BF16) {
+                static_for<FG>([&](auto u) {
+                    u32x4_t o;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        o[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2_t{v[u][2 * e], v[u][2 * e + 1]}, bf16x2_t));
+                    __builtin_amdgcn_raw_buffer_store_b128(o, d_rsrc, d0 + (P0 + u) * RPP * d_row_bytes, 0, 0);
+                });
+            } else {
+                static_for<FG>([&](auto u) {
+                    u32x4_t o;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        o[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2_t{v[u][2 * e], v[u][2 * e + 1]}, f16x2_t));
+                    __builtin_amdgcn_raw_buffer_store_b128(o, d_rsrc, d0 + (P0 + u) * RPP * d_row_bytes, 0, 0);
+                });
+            }
         });
     };
 
@@ -1132,34 +1186,43 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
         // uniform per wave: all 8-column groups of the wave exist and every access may be 128-bit
         const bool fast_ok = dvec && (n0 + wn * WTN + WTN <= p.N) && (!f.has_res || (f.res_dt & 0x100)) &&
                              (!f.has_bias || (f.bias_dt & 0x100));
-        if (fast_ok) fast_setup();
-        // All block / pass loops of the epilogue are REAL loops: their bodies are re-executed from
-        // the instruction cache instead of existing once per pass.
+        if (fast_ok) {
+            fast_setup();
+            // All block loops of the epilogue are REAL loops: their bodies are re-executed from the
+            // instruction cache instead of existing once per block.
 #pragma clang loop unroll(disable)
-        for (int mi = 0; mi < MI; ++mi) {
-            UCL_STAGE_BLOCK(mi);
-            switch (f.act) {
+            for (int mi = 0; mi < MI; ++mi) {
+                UCL_STAGE_BLOCK(mi);
+                // (two copies: without a residual the block issues no loads at all, so nothing ever
+                // makes it wait for the stores in flight)
+                if (f.has_res) fast_block(std::true_type{}, mi);
+                else fast_block(std::false_type{}, mi);
+            }
+        } else {
+#pragma clang loop unroll(disable)
+            for (int mi = 0; mi < MI; ++mi) {
+                UCL_STAGE_BLOCK(mi);
+                switch (f.act) {
 #define UCL_FUSED_CASE(OP)                                                         \
     case OP:                                                                       \
-        if (fast_ok) fused_block_fast(std::integral_constant<int, OP>{}, mi);      \
-        else fused_block(std::integral_constant<int, OP>{}, mi);                   \
+        fused_block(std::integral_constant<int, OP>{}, mi);                        \
         break;
-                UCL_FUSED_CASE(UCL_EPI_RELU)
-                UCL_FUSED_CASE(UCL_EPI_GELU_TANH)
-                UCL_FUSED_CASE(UCL_EPI_GELU_ERF)
-                UCL_FUSED_CASE(UCL_EPI_SILU)
-                UCL_FUSED_CASE(UCL_EPI_SIGMOID)
-                UCL_FUSED_CASE(UCL_EPI_TANH)
-                UCL_FUSED_CASE(UCL_EPI_MISH)
-                UCL_FUSED_CASE(UCL_EPI_HARDSWISH)
-                UCL_FUSED_CASE(UCL_EPI_LEAKY_RELU)
-                UCL_FUSED_CASE(UCL_EPI_ELU)
-                UCL_FUSED_CASE(UCL_EPI_CLAMP)
+                    UCL_FUSED_CASE(UCL_EPI_RELU)
+                    UCL_FUSED_CASE(UCL_EPI_GELU_TANH)
+                    UCL_FUSED_CASE(UCL_EPI_GELU_ERF)
+                    UCL_FUSED_CASE(UCL_EPI_SILU)
+                    UCL_FUSED_CASE(UCL_EPI_SIGMOID)
+                    UCL_FUSED_CASE(UCL_EPI_TANH)
+                    UCL_FUSED_CASE(UCL_EPI_MISH)
+                    UCL_FUSED_CASE(UCL_EPI_HARDSWISH)
+                    UCL_FUSED_CASE(UCL_EPI_LEAKY_RELU)
+                    UCL_FUSED_CASE(UCL_EPI_ELU)
+                    UCL_FUSED_CASE(UCL_EPI_CLAMP)
 #undef UCL_FUSED_CASE
-            default:
-                if (fast_ok) fused_block_fast(std::integral_constant<int, 0>{}, mi);
-                else fused_block(std::integral_constant<int, 0>{}, mi);
-                break;
+                default:
+                    fused_block(std::integral_constant<int, 0>{}, mi);
+                    break;
+                }
             }
         }
     } else {
