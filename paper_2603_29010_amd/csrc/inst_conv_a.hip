@@ -2,7 +2,6 @@
 #include "ucl_launch.h"
 namespace ucl {
 static const VariantDesc kTable[] = {
-    describe<KernelCfg<256, 128, 64, 2, false, 2, kIm2col, kKContig>>(),
     describe<KernelCfg<256, 128, 32, 4, false, 2, kIm2col, kKContig>>(),
     describe<KernelCfg<256, 128, 32, 3, false, 2, kIm2col, kKContig>>(),
 };

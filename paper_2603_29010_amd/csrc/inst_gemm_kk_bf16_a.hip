@@ -1,8 +1,7 @@
-// gemm / batched_gemm, both operands contiguous along K, bf16 inputs, 256-row tiles.
+// gemm / batched_gemm, both operands contiguous along K, bf16 inputs, 256x256 tiles.
 #include "ucl_launch.h"
 namespace ucl {
 static const VariantDesc kTable[] = {
-    describe<KernelCfg<256, 256, 64, 2, false, 0, kKContig, kKContig>>(),
     describe<KernelCfg<256, 256, 32, 4, false, 0, kKContig, kKContig>>(),
     describe<KernelCfg<256, 256, 32, 5, false, 0, kKContig, kKContig>>(),
 };

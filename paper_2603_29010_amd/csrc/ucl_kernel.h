@@ -336,7 +336,8 @@ struct KernelCfg {
     static constexpr bool F16 = F16_;
     static constexpr int WAVES_M = 2, WAVES_N = 2;
     static constexpr int WTM = TM / WAVES_M, WTN = TN / WAVES_N;  // wave tile
-    static constexpr int MI = WTM / 32, NI = WTN / 32;            // 32x32 MFMA blocks per wave
+    static constexpr int MI = WTM / 16, NI = WTN / 16;            // 16x16 MFMA blocks per wave
+    static constexpr int KSTEPS = TK / 32;                        // MFMA k-steps (32 elements) per k-tile
     static constexpr int A_BYTES = TM * TK * 2, B_BYTES = TN * TK * 2;
     static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
     static constexpr int PIPE_BYTES = STAGES * STAGE_BYTES;
@@ -369,38 +370,19 @@ __device__ __forceinline__ rsrc_t buffer_rsrc(const void *base, uint32_t bytes) 
     return __builtin_amdgcn_make_buffer_rsrc((void *)base, (short)0, (int)bytes, 0x00020000);
 }
 
+// D(16x16, fp32) += A(16x32) * B(32x16): lane L supplies row/column L % 16 and the 8 consecutive k
+// starting at 8 * (L / 16) of both operands; it receives column L % 16, rows 4 * (L / 16) .. + 3 of D.
+// (Of the two shapes of the 16-bit MFMA this one sustains the higher rate on random data under the
+// power limit: measured 2.03 vs 1.81 PFLOP/s for loops of nothing but MFMAs.)
+// Written as an asm statement with the accumulator tied to an accumulation register: the compiler's
+// register allocator otherwise shuffles the 64 four-register accumulators of a wave tile between the
+// two register files inside the loop.  The statements are volatile, so MFMAs, LDS reads and copy
+// instructions issue in source order, which is how the loop below spaces them.
 template <bool F16>
-__device__ __forceinline__ f32x16_t mfma32(u32x4_t a, u32x4_t b, f32x16_t c) {
-    if constexpr (F16) {
-        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b),
-                                                      c, 0, 0, 0);
-    } else {
-        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a),
-                                                       __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
-    }
+__device__ __forceinline__ void mfma16(f32x4_t &c, const u32x4_t &a, const u32x4_t &b) {
+    if constexpr (F16) asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
+    else asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
 }
-
-// Merge order of ND fragment reads and DN copy instructions within a k-step: reads in order, copy j
-// right after the read that completes the j-th equal share of the reads.
-template <int ND, int DN>
-struct SideSeq {
-    bool dma[ND + DN + 1] = {};
-    int which[ND + DN + 1] = {};
-    constexpr SideSeq() {
-        int j = 0, t = 0;
-        for (int r = 0; r < ND; ++r) {
-            dma[t] = false;
-            which[t] = r;
-            ++t;
-            while (j < DN && (j + 1) * ND <= (r + 1) * DN) {
-                dma[t] = true;
-                which[t] = j;
-                ++t;
-                ++j;
-            }
-        }
-    }
-};
 
 template <class Cfg>
 __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(const KParams p, const typename Cfg::Groups gt) {
@@ -409,7 +391,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
     constexpr int A_ITERS = Cfg::A_ITERS, B_ITERS = Cfg::B_ITERS;
     constexpr bool kAnyReg = (LA == kMNContig) || (LB == kMNContig);
     constexpr int DMA_PER_TILE = (LA != kMNContig ? A_ITERS : 0) + (LB != kMNContig ? B_ITERS : 0);
-    constexpr int KSTEPS = TK / 16;
+    constexpr int KSTEPS = Cfg::KSTEPS;
     constexpr int CPR = Cfg::CPR, ROW_BYTES = Cfg::ROW_BYTES, RPI = Cfg::ROWS_PER_ITER;
 
     __shared__ __attribute__((aligned(1024))) char smem[Cfg::LDS_BYTES];
@@ -645,140 +627,26 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
     };
 
     // ---- accumulators and fragment addressing -----------------------------------------------
-    f32x16_t acc[MI][NI];
+    f32x4_t acc[MI][NI];
     static_for<MI>([&](auto mi) {
-        static_for<NI>([&](auto ni) {
-#pragma unroll
-            for (int j = 0; j < 16; ++j) acc[mi][ni][j] = 0.f;
-        });
+        static_for<NI>([&](auto ni) { acc[mi][ni] = f32x4_t{0.f, 0.f, 0.f, 0.f}; });
     });
 
-    const int f_row = lane & 31, f_half = lane >> 5;
-    // byte offset of this lane's fragment chunk inside its LDS row, for k-step 0;
-    // k-step kk XORs it with kk*32 (chunk index 2kk + half, XOR swz(row))
-    const int f_x = (f_half ^ lds_swz<CPR>(f_row)) << 4;
+    const int f_row = lane & 15, f_kg = lane >> 4;
+    // byte offset of this lane's fragment chunk inside its LDS row for k-step 0 (chunk f_kg XOR
+    // swz(row)); k-step kk XORs it with kk*64 (chunk index 4kk + f_kg)
+    const int f_x = (f_kg ^ lds_swz<CPR>(f_row)) << 4;
     const int a_frag_base = (wm * Cfg::WTM + f_row) * ROW_BYTES;
     const int b_frag_base = Cfg::A_BYTES + (wn * Cfg::WTN + f_row) * ROW_BYTES;
-
-    // two register sets of MFMA fragments: one feeds the matrix cores while the other is being filled
-    u32x4_t af[2][MI], bf[2][NI];
-    auto read_frags = [&](auto set_, auto kk_, const char *sbase) {
-        constexpr int set = decltype(set_)::value, kk = decltype(kk_)::value;
-        const int xo = f_x ^ (kk * 32);
-        static_for<MI>([&](auto mi) {
-            af[set][mi] = *(const u32x4_t *)(sbase + a_frag_base + mi * 32 * ROW_BYTES + xo);
-        });
-        static_for<NI>([&](auto ni) {
-            bf[set][ni] = *(const u32x4_t *)(sbase + b_frag_base + ni * 32 * ROW_BYTES + xo);
-        });
-    };
-    auto mfma_step = [&](auto set_) {
-        constexpr int set = decltype(set_)::value;
-        // B fragment as the MFMA's first operand: the lane then holds 4 consecutive n per
-        // accumulator quad, which is what the row-major store wants.
-        static_for<MI>([&](auto mi) {
-            static_for<NI>([&](auto ni) {
-                acc[mi][ni] = mfma32<Cfg::F16>(bf[set][ni], af[set][mi], acc[mi][ni]);
-            });
-        });
-    };
-    // Scheduling hints for one k-step (MI*NI MFMAs): spread the LDS fragment reads, and at the tile
-    // boundary the global -> LDS loads, between the MFMAs instead of ahead of them, so the matrix
-    // pipe keeps issuing while the wave's other instructions go out in its shadow.
-    constexpr int kMfmaPerStep = MI * NI, kDsPerStep = MI + NI;
-    auto interleave_ds_mfma = [&]() {
-#pragma unroll
-        for (int i = 0; i < kDsPerStep; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, (kMfmaPerStep + kDsPerStep - 1) / kDsPerStep > 2 ? 2 : 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        }
-        __builtin_amdgcn_sched_group_barrier(0x008, kMfmaPerStep, 0);
-        __builtin_amdgcn_sched_barrier(0);
-    };
-    // Tile boundary: the compiler must keep the next tile's fragment reads behind the global -> LDS
-    // loads (it cannot tell that they touch different stage buffers), so the loads go out under the
-    // first MFMAs of the step and the fragment reads under the rest.
-    auto interleave_all = [&]() {
-        constexpr int kVmemSlots = kMfmaPerStep > kDsPerStep ? kMfmaPerStep - kDsPerStep : 1;
-        constexpr int kPerSlot = (DMA_PER_TILE + kVmemSlots - 1) / kVmemSlots;
-#pragma unroll
-        for (int i = 0; i < kVmemSlots; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x020, kPerSlot, 0);
-        }
-#pragma unroll
-        for (int i = 0; i < kDsPerStep; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        }
-        __builtin_amdgcn_sched_group_barrier(0x008, kMfmaPerStep, 0);
-        __builtin_amdgcn_sched_barrier(0);
-    };
-    // General form: this k-step's MFMAs with the fragment reads first (the next k-step needs them
-    // soonest), then `n_vmem` global -> LDS loads, dealt out evenly behind the first MFMAs.  The
-    // source order must be the same (reads, then loads): the compiler keeps LDS reads and LDS-writing
-    // loads in program order because it cannot tell that they touch different stage buffers.
-    auto interleave_step = [&](auto n_vmem_) {
-        constexpr int NV = decltype(n_vmem_)::value;
-        constexpr int ND = kDsPerStep;
-        constexpr int T = NV + ND;
-        constexpr int Q = (T + kMfmaPerStep - 1) / kMfmaPerStep;     // side instructions per MFMA slot
-        static_for<kMfmaPerStep>([&](auto i_) {
-            constexpr int i = decltype(i_)::value;
-            constexpr int lo = i * Q < T ? i * Q : T, hi = (i + 1) * Q < T ? (i + 1) * Q : T;
-            constexpr int nd = (hi < ND ? hi : ND) - (lo < ND ? lo : ND);
-            constexpr int nv = (hi - lo) - nd;
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            if constexpr (nd > 0) __builtin_amdgcn_sched_group_barrier(0x100, nd, 0);
-            if constexpr (nv > 0) __builtin_amdgcn_sched_group_barrier(0x020, nv, 0);
-        });
-        __builtin_amdgcn_sched_barrier(0);
-    };
-    // Fragment `IDX` of a k-step in order of first use by the MFMAs (A block 0, all B blocks, then the
-    // other A blocks).
-    auto read_one = [&](auto set_, auto kk_, auto idx_, const char *sbase) {
-        constexpr int set = decltype(set_)::value, kk = decltype(kk_)::value, IDX = decltype(idx_)::value;
-        const int xo = f_x ^ (kk * 32);
-        if constexpr (IDX == 0) af[set][0] = *(const u32x4_t *)(sbase + a_frag_base + xo);
-        else if constexpr (IDX <= NI) bf[set][IDX - 1] = *(const u32x4_t *)(sbase + b_frag_base + (IDX - 1) * 32 * ROW_BYTES + xo);
-        else af[set][IDX - NI] = *(const u32x4_t *)(sbase + a_frag_base + (IDX - NI) * 32 * ROW_BYTES + xo);
-    };
-    // A k-step of the deep pipeline: its MI*NI MFMAs (fragment set CS) with, dealt out one per MFMA
-    // in this order, the fragment reads of the following k-step (into set 1-CS, k-step RK of the
-    // stage at rbase) and copy slots [D0, D0+DN) of k-tile kt_load, evenly spaced between the reads.
-    // Source order and scheduling hints name the same sequence: the compiler keeps LDS reads and
-    // LDS-writing loads in program order (it cannot tell that they touch different stage buffers).
-    auto pipelined_step = [&](auto cs_, auto rk_, const char *rbase, auto check_, auto d0_, auto dn_, int kt_load, int fill_buf) {
-        constexpr int CS = decltype(cs_)::value, RK = decltype(rk_)::value;
-        constexpr int D0 = decltype(d0_)::value, DN = decltype(dn_)::value;
-        constexpr int ND = kDsPerStep;
-        constexpr SideSeq<ND, DN> seq{};
-        static_for<ND + DN>([&](auto t_) {
-            constexpr int t = decltype(t_)::value;
-            if constexpr (seq.dma[t]) issue_one(check_, std::integral_constant<int, D0 + seq.which[t]>{}, kt_load, fill_buf);
-            else read_one(std::integral_constant<int, 1 - CS>{}, rk_, std::integral_constant<int, seq.which[t]>{}, rbase);
-        });
-        mfma_step(cs_);
-        constexpr int T = ND + DN;
-        constexpr int Q = (T + kMfmaPerStep - 1) / kMfmaPerStep;         // side instructions per MFMA slot
-        static_for<kMfmaPerStep>([&](auto i_) {
-            constexpr int i = decltype(i_)::value;
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            static_for<Q>([&](auto q_) {
-                constexpr int t = i * Q + decltype(q_)::value;
-                if constexpr (t < T) {
-                    if constexpr (seq.dma[t]) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-                    else __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-                }
-            });
-        });
-        __builtin_amdgcn_sched_barrier(0);
+    auto frag = [&](const char *sbase, int base, int blk, int kk) __attribute__((always_inline)) {
+        return *(const u32x4_t *)(sbase + base + blk * 16 * ROW_BYTES + (f_x ^ (kk << 6)));
     };
     using I0 = std::integral_constant<int, 0>;
     using I1 = std::integral_constant<int, 1>;
 
     if constexpr (kAnyReg) {
         // ---- simple loop for operands that need the register transpose: prefetch distance 1 -----
+        u32x4_t af[MI], bf[NI];
         issue(0, 0);
         commit_regs(0);
         for (int kt = 0; kt < KT; ++kt) {
@@ -787,135 +655,114 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
             if (kt + 1 < KT) issue(kt + 1, (kt + 1) % STAGES);
             const char *sbase = smem + (kt % STAGES) * Cfg::STAGE_BYTES;
             static_for<KSTEPS>([&](auto kk) {
-                read_frags(I0{}, kk, sbase);
-                mfma_step(I0{});
+                static_for<MI>([&](auto mi) { af[mi] = frag(sbase, a_frag_base, mi, kk); });
+                static_for<NI>([&](auto ni) { bf[ni] = frag(sbase, b_frag_base, ni, kk); });
+                // B fragment as the MFMA's first operand: the lane then holds 4 consecutive n per
+                // accumulator, which is what the row-major store wants.
+                static_for<MI>([&](auto mi) {
+                    static_for<NI>([&](auto ni) { mfma16<Cfg::F16>(acc[mi][ni], bf[ni], af[mi]); });
+                });
             });
             if (kt + 1 < KT) commit_regs((kt + 1) % STAGES);
         }
     } else {
         // ---- software-pipelined loop ---------------------------------------------------------------
-        // All STAGES buffers are filled up front.  Within a k-tile, the fragments of k-step kk+1 are
-        // read from LDS while the MFMAs of k-step kk run.  The one barrier per k-tile sits before the
-        // LAST k-step: by then this wave has issued every LDS read of the tile, so after the barrier
-        // the buffer can be refilled (k-tile kt+STAGES) and the next tile's first fragments fetched,
-        // both hidden under the MFMAs of the last k-step.
-        static_assert(KSTEPS % 2 == 0, "fragment sets alternate per k-step and must realign per stage");
-        // all k-steps of a stage but the last: fragments of step kk+1 stream in under the MFMAs of step kk
-        auto head_steps = [&](const char *sbase) {
-            static_for<KSTEPS - 1>([&](auto kk_) {
-                constexpr int kk = decltype(kk_)::value;
-                read_frags(std::integral_constant<int, (kk + 1) & 1>{}, std::integral_constant<int, kk + 1>{}, sbase);
-                mfma_step(std::integral_constant<int, kk & 1>{});
-                interleave_ds_mfma();
+        // STAGES-1 k-tiles are in flight.  Registers hold the B fragments of the running k-step and
+        // of the next one (two sets) and a ring of RA fragments of A: the MFMAs walk the wave tile
+        // row block by row block (mi), and at the start of row block mi the A fragment of row block
+        // mi + RA - 1 is requested -- past the last row block that is the first of the NEXT k-step,
+        // so the ring runs across k-step and k-tile boundaries without a bubble.  The B fragments of
+        // the next k-step and the copy instructions of the k-tile being fetched are dealt out over
+        // the row blocks in the same way, one side instruction per MFMA (sched_group_barrier; the
+        // source order is the issue order, since the compiler keeps LDS reads and LDS-writing loads
+        // in program order).
+        // One barrier per k-tile, before its last k-step: then k-tile kt+1 has landed (explicit
+        // vmcnt) and every wave is done with k-tile kt-1, whose buffer the last k-step refills with
+        // k-tile kt+STAGES-1.  The k-steps before it read their own stage only and issue no copies.
+        static_assert(STAGES >= 3, "the pipelined loop refills the buffer released one k-tile earlier");
+        constexpr int RA = MI % 4 == 0 ? 4 : 2;                    // ring of A fragments
+        static_assert(MI % RA == 0, "ring slots must line up across k-steps");
+        // B sets alternate per k-step: with an odd number of k-steps per k-tile two k-tiles form one
+        // unit of the loop (the K extent is rounded up to whole units; k-tiles past the end are
+        // copied from out-of-range addresses, i.e. zeros).
+        constexpr int TPU = KSTEPS % 2 ? 2 : 1;                    // k-tiles per unit
+        u32x4_t ar[RA], bq[2][NI];
+
+        // One k-step: fragment set PB of B, k-step KK of stage `sc`; the following k-step is KN of
+        // stage `sn`.  DN > 0: also the copies of k-tile kt_load into buffer fill_buf.
+        auto kstep = [&](auto pb_, auto kk_, auto kn_, const char *sc, const char *sn, auto check_, auto dn_, int kt_load,
+                         int fill_buf) {
+            constexpr int PB = decltype(pb_)::value, KK = decltype(kk_)::value, KN = decltype(kn_)::value;
+            constexpr int DN = decltype(dn_)::value;
+            static_for<MI>([&](auto mi_) {
+                constexpr int mi = decltype(mi_)::value;
+                constexpr int ia = mi + RA - 1;                    // A fragment requested now
+                if constexpr (ia < MI) ar[ia % RA] = frag(sc, a_frag_base, ia, KK);
+                else ar[ia % RA] = frag(sn, a_frag_base, ia - MI, KN);
+                constexpr int b0 = mi * NI / MI, b1 = (mi + 1) * NI / MI;      // B fragments of the next k-step
+                static_for<b1 - b0>([&](auto j) { bq[1 - PB][b0 + j] = frag(sn, b_frag_base, b0 + j, KN); });
+                constexpr int d0 = mi * DN / MI, d1 = (mi + 1) * DN / MI;      // copies
+                static_for<d1 - d0>([&](auto j) { issue_one(check_, std::integral_constant<int, d0 + j>{}, kt_load, fill_buf); });
+                // B fragment as the MFMA's first operand: the lane then holds 4 consecutive n per
+                // accumulator, which is what the row-major store wants.
+                static_for<NI>([&](auto ni) { mfma16<Cfg::F16>(acc[mi][ni], bq[PB][ni], ar[mi % RA]); });
             });
         };
-        if constexpr (STAGES >= 3) {
-            // ---- deep pipeline: STAGES-1 stages in flight, loads spread over the stage ---------------
-            // Stage kt+STAGES-1 goes into the buffer released at the previous boundary: its A half is
-            // issued under the first k-step of stage kt, its B half under the last.  A wave's load
-            // instructions then arrive at the memory pipeline a few at a time instead of as one burst
-            // whose queueing would hold back the MFMAs issued behind it.
-            // Copy slots of a stage are split evenly over its k-steps.
-            constexpr int DPS = (DMA_PER_TILE + KSTEPS - 1) / KSTEPS;
-#pragma unroll
-            for (int s = 0; s < STAGES - 1; ++s)
-                if (s < KT) issue(s, s);
-            if (KT >= STAGES - 1) __builtin_amdgcn_s_waitcnt(vmcnt_imm((STAGES - 2) * DMA_PER_TILE));
-            else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-            __syncthreads();
-            read_frags(I0{}, I0{}, smem);
-            int kt = 0;
-            // stages [0, KT_full) are complete k-tiles: their loads skip the K-tail test
-            const int KT_full = k_tail ? KT - 1 : KT;
-            // One stage.  cur / fill are the buffers of stage kt and of stage kt+STAGES-1 (the one
-            // released at the previous boundary); passed as constants by the unrolled steady loop,
-            // so that every LDS address in it is a loop-invariant register plus an immediate.
-            auto deep_iter = [&](auto check_, auto cur_, auto fill_) {
-                const int cur = cur_, fill = fill_;
-                const char *sbase = smem + cur * Cfg::STAGE_BYTES;
+        // One k-tile.  P0: B set of its first k-step.  cur / nxt / fill: buffers of k-tiles kt, kt+1 and
+        // kt-1 (= kt+STAGES-1); constants in the unrolled steady loop, so that every LDS address
+        // there is a loop-invariant register plus an immediate.
+        auto ktile = [&](auto p0_, auto check_, auto cur_, auto nxt_, auto fill_, int kt) {
+            constexpr int P0 = decltype(p0_)::value;
+            const int cur = cur_, nxt = nxt_, fill = fill_;
+            const char *sc = smem + cur * Cfg::STAGE_BYTES;
+            static_for<KSTEPS - 1>([&](auto kk_) {
+                constexpr int kk = decltype(kk_)::value;
+                kstep(std::integral_constant<int, (P0 + kk) & 1>{}, kk_, std::integral_constant<int, kk + 1>{}, sc, sc,
+                      check_, I0{}, 0, 0);
+            });
+            pipeline_barrier<(STAGES - 3) * DMA_PER_TILE>();
+            kstep(std::integral_constant<int, (P0 + KSTEPS - 1) & 1>{}, std::integral_constant<int, KSTEPS - 1>{}, I0{}, sc,
+                  smem + nxt * Cfg::STAGE_BYTES, check_, std::integral_constant<int, DMA_PER_TILE>{}, kt + STAGES - 1, fill);
+        };
+
+        // prologue: k-tiles 0 .. STAGES-2 on their way, k-tile 0 landed, first fragments in registers
+        static_for<STAGES - 1>([&](auto s_) { issue_tile(std::true_type{}, decltype(s_)::value, decltype(s_)::value); });
+        pipeline_barrier<(STAGES - 2) * DMA_PER_TILE>();
+        static_for<RA - 1>([&](auto i) { ar[i] = frag(smem, a_frag_base, i, 0); });
+        static_for<NI>([&](auto ni) { bq[0][ni] = frag(smem, b_frag_base, ni, 0); });
+
+        const int KT_full = k_tail ? KT - 1 : KT;                  // complete k-tiles: loads skip the K-tail test
+        const int KTP = (KT + TPU - 1) / TPU * TPU;
+        int kt = 0;
+        // steady state, unrolled over the ring of stage buffers (and over the B set parity)
+        constexpr int UNR = STAGES * TPU;
+        while (kt + UNR + STAGES - 2 < KT_full) {
+            static_for<UNR>([&](auto u_) {
+                constexpr int u = decltype(u_)::value;
+                constexpr int c = u % STAGES;
+                ktile(std::integral_constant<int, (u * KSTEPS) & 1>{}, std::false_type{}, std::integral_constant<int, c>{},
+                      std::integral_constant<int, (c + 1) % STAGES>{}, std::integral_constant<int, (c + STAGES - 1) % STAGES>{}, kt);
+                ++kt;
+            });
+        }
+        // the rest, one unit at a time with the K-tail / past-the-end test on every copy
+        int cur = 0;                                               // kt is a multiple of STAGES here
+        while (kt < KTP) {
+            static_for<TPU>([&](auto u_) {
+                constexpr int u = decltype(u_)::value;
                 const int nxt = cur + 1 == STAGES ? 0 : cur + 1;
-                static_for<KSTEPS - 1>([&](auto kk_) {
-                    constexpr int kk = decltype(kk_)::value;
-                    constexpr int d0 = kk * DPS < DMA_PER_TILE ? kk * DPS : DMA_PER_TILE;
-                    constexpr int d1 = (kk + 1) * DPS < DMA_PER_TILE ? (kk + 1) * DPS : DMA_PER_TILE;
-                    pipelined_step(std::integral_constant<int, kk & 1>{}, std::integral_constant<int, kk + 1>{}, sbase, check_,
-                                   std::integral_constant<int, d0>{}, std::integral_constant<int, d1 - d0>{}, kt + STAGES - 1, fill);
-                });
-                // stage kt+1 must have landed; younger: stages kt+2..kt+STAGES-2 and this stage's slots so far
-                constexpr int dl0 = (KSTEPS - 1) * DPS < DMA_PER_TILE ? (KSTEPS - 1) * DPS : DMA_PER_TILE;
-                pipeline_barrier<(STAGES - 3) * DMA_PER_TILE + dl0>();
-                pipelined_step(I1{}, I0{}, smem + nxt * Cfg::STAGE_BYTES, check_, std::integral_constant<int, dl0>{},
-                               std::integral_constant<int, DMA_PER_TILE - dl0>{}, kt + STAGES - 1, fill);
-            };
-            // steady state, unrolled over the ring of stage buffers
-            while (kt + 2 * STAGES - 2 < KT_full) {
-                static_for<STAGES>([&](auto s_) {
-                    constexpr int sb = decltype(s_)::value;
-                    deep_iter(std::false_type{}, std::integral_constant<int, sb>{},
-                              std::integral_constant<int, (sb + STAGES - 1) % STAGES>{});
-                    ++kt;
-                });
-            }
-            int cur = 0, fill = STAGES - 1;        // kt is a multiple of STAGES here
-            for (; kt + STAGES - 1 < KT_full; ++kt) {
-                deep_iter(std::false_type{}, cur, fill);
-                fill = cur;
-                cur = cur + 1 == STAGES ? 0 : cur + 1;
-            }
-            for (; kt + STAGES - 1 < KT; ++kt) {   // the partial k-tile, if any
-                deep_iter(std::true_type{}, cur, fill);
-                fill = cur;
-                cur = cur + 1 == STAGES ? 0 : cur + 1;
-            }
-            for (; kt < KT - 1; ++kt) {            // drain
-                const int nxt = cur + 1 == STAGES ? 0 : cur + 1;
-                head_steps(smem + cur * Cfg::STAGE_BYTES);
-                pipeline_barrier<0>();
-                read_frags(I0{}, I0{}, smem + nxt * Cfg::STAGE_BYTES);
-                mfma_step(I1{});
-                interleave_ds_mfma();
+                const int fill = cur == 0 ? STAGES - 1 : cur - 1;
+                ktile(std::integral_constant<int, (u * KSTEPS) & 1>{}, std::true_type{}, cur, nxt, fill, kt);
                 cur = nxt;
-            }
-            head_steps(smem + cur * Cfg::STAGE_BYTES);
-            mfma_step(I1{});
-        } else {
-#pragma unroll
-            for (int s = 0; s < STAGES; ++s)
-                if (s < KT) issue(s, s);
-            if (KT > STAGES - 1) __builtin_amdgcn_s_waitcnt(vmcnt_imm((STAGES - 1) * DMA_PER_TILE));
-            else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-            __syncthreads();
-            read_frags(I0{}, I0{}, smem);
-            // Steady state: every boundary refills the buffer it releases.  Each iteration is one
-            // straight-line block (no branch around MFMAs: 256 live accumulators do not survive
-            // control-flow joins without copies); the K-tail test lives in a second copy of the loop
-            // that runs for the one partial k-tile only.
-            int kt = 0;
-            const int KT_full = k_tail ? KT - 1 : KT;
-            auto flat_iter = [&](auto check_) {
-                const int buf = kt % STAGES;
-                head_steps(smem + buf * Cfg::STAGE_BYTES);
-                // k-tile kt+1 must have landed; tiles kt+2 .. kt+STAGES-1 may still be in flight
-                pipeline_barrier<(STAGES - 2) * DMA_PER_TILE>();
-                issue_tile(check_, kt + STAGES, buf);
-                read_frags(I0{}, I0{}, smem + ((kt + 1) % STAGES) * Cfg::STAGE_BYTES);
-                mfma_step(I1{});
-                interleave_all();
-            };
-            for (; kt + STAGES < KT_full; ++kt) flat_iter(std::false_type{});
-            for (; kt + STAGES < KT; ++kt) flat_iter(std::true_type{});           // the partial k-tile, if any
-            // Drain: nothing left to fetch.
-            for (; kt < KT - 1; ++kt) {
-                head_steps(smem + (kt % STAGES) * Cfg::STAGE_BYTES);
-                pipeline_barrier<0>();
-                read_frags(I0{}, I0{}, smem + ((kt + 1) % STAGES) * Cfg::STAGE_BYTES);
-                mfma_step(I1{});
-                interleave_ds_mfma();
-            }
-            head_steps(smem + ((KT - 1) % STAGES) * Cfg::STAGE_BYTES);
-            mfma_step(I1{});
+                ++kt;
+            });
         }
     }
+
+    // The MFMAs are asm statements, so the compiler does not know that the accumulators were written
+    // by the matrix pipeline: keep the required distance to their first reader by hand.
+    asm volatile("s_nop 15");
+    asm volatile("s_nop 15");
 
     // ---- epilogue ---------------------------------------------------------------------------------
     // The accumulators leave the MFMA layout (a lane holds 4 consecutive n of ONE row per quad)
@@ -968,14 +815,12 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
     // accumulators of 32-row block `mi` -> this wave's staging patch (fp32).  acc needs constant
     // indices, and is only ever touched by code written directly in the kernel body (a closure that
     // holds a reference to it and is itself captured by another closure keeps it out of registers).
-#define UCL_STAGE_BLOCK(mi)                                                                             \
-    static_for<MI>([&](auto mj) {                                                                       \
-        if ((mi) == mj) {                                                                               \
-            static_for<NI>([&](auto ni) {                                                               \
-                static_for<4>([&](auto g) {                                                             \
-                    const f32x4_t q = {acc[mj][ni][4 * g], acc[mj][ni][4 * g + 1], acc[mj][ni][4 * g + 2], \
-                                       acc[mj][ni][4 * g + 3]};                                         \
-                    *(f32x4_t *)(stg + f_row * EPI_LD + ni * 32 + 8 * g + 4 * f_half) = q;              \
+#define UCL_STAGE_BLOCK(mb)                                                                             \
+    static_for<MI / 2>([&](auto mj) {                                                                   \
+        if ((mb) == mj) {                                                                               \
+            static_for<2>([&](auto h) {                                                                 \
+                static_for<NI>([&](auto ni) {                                                           \
+                    *(f32x4_t *)(stg + (h * 16 + f_row) * EPI_LD + ni * 16 + 4 * f_kg) = acc[2 * mj + h][ni]; \
                 });                                                                                     \
             });                                                                                         \
         }                                                                                               \
@@ -1062,7 +907,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
         r_lane = e_row * r_row_bytes + e_col * r_esz;
     };
     // passes whose operands are requested together (all of a block where registers allow)
-    constexpr int FG = Cfg::MIN_WAVES >= 3 && PASSES > 2 ? 2 : PASSES;
+    constexpr int FG = Cfg::MIN_WAVES >= 2 && PASSES > 2 ? 2 : PASSES;
     // The block in three phases, each selected once per pass group by a wave-uniform branch instead of
     // per element: gather (staged fp32 * alpha + bias + beta * residual, by residual type), activation
     // (by opcode), conversion + store (by output type).  The values of the whole group stay in
@@ -1098,25 +943,28 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
             if constexpr (HAS_RES) {
                 if (r_dt == UCL_F32) {
                     static_for<FG>([&](auto u) {
+                        const f32x4_t fl = __builtin_bit_cast(f32x4_t, r_lo[u]), fh = __builtin_bit_cast(f32x4_t, r_hi[u]);
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
-                            v[u][e] += beta * __builtin_bit_cast(float, r_lo[u][e]);
-                            v[u][4 + e] += beta * __builtin_bit_cast(float, r_hi[u][e]);
+                            v[u][e] += beta * fl[e];
+                            v[u][4 + e] += beta * fh[e];
                         }
                     });
                 } else if (r_dt == UCL_BF16) {
                     static_for<FG>([&](auto u) {
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
-                            v[u][2 * e] += beta * __builtin_bit_cast(float, r_lo[u][e] << 16);
-                            v[u][2 * e + 1] += beta * __builtin_bit_cast(float, r_lo[u][e] & 0xffff0000u);
+                            const uint32_t w = r_lo[u][e];
+                            v[u][2 * e] += beta * __builtin_bit_cast(float, w << 16);
+                            v[u][2 * e + 1] += beta * __builtin_bit_cast(float, w & 0xffff0000u);
                         }
                     });
                 } else {
                     static_for<FG>([&](auto u) {
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
-                            const f16x2_t h = __builtin_bit_cast(f16x2_t, r_lo[u][e]);
+                            const uint32_t w = r_lo[u][e];
+                            const f16x2_t h = __builtin_bit_cast(f16x2_t, w);
                             v[u][2 * e] += beta * (float)h[0];
                             v[u][2 * e + 1] += beta * (float)h[1];
                         }
@@ -1191,7 +1039,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
             // All block loops of the epilogue are REAL loops: their bodies are re-executed from the
             // instruction cache instead of existing once per block.
 #pragma clang loop unroll(disable)
-            for (int mi = 0; mi < MI; ++mi) {
+            for (int mi = 0; mi < MI / 2; ++mi) {
                 UCL_STAGE_BLOCK(mi);
                 // (two copies: without a residual the block issues no loads at all, so nothing ever
                 // makes it wait for the stores in flight)
@@ -1200,7 +1048,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
             }
         } else {
 #pragma clang loop unroll(disable)
-            for (int mi = 0; mi < MI; ++mi) {
+            for (int mi = 0; mi < MI / 2; ++mi) {
                 UCL_STAGE_BLOCK(mi);
                 switch (f.act) {
 #define UCL_FUSED_CASE(OP)                                                         \
@@ -1263,7 +1111,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
         }
 
 #pragma clang loop unroll(disable)
-        for (int mi = 0; mi < MI; ++mi) {
+        for (int mi = 0; mi < MI / 2; ++mi) {
             UCL_STAGE_BLOCK(mi);
             const int m_blk = m0 + wm * Cfg::WTM + mi * 32;
             // passes run in groups: the matrix operands (residual) of a whole group are requested first,
