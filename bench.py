@@ -27,7 +27,7 @@ PEAK_HBM_GBPS = 8000.0
 # runs and their commands are recorded in profiles/ucl_tile_kernel_*.txt.  Counters cannot be read
 # from inside this process, so these are the recorded figures for the kernels the selection table
 # picks for each workload.
-MEASURED_TRAFFIC_BYTES = {1: 1128591, 2: 235418087, 3: 84202219, 4: 525575929, 5: 65781892}
+MEASURED_TRAFFIC_BYTES = {1: 1149965, 2: 235397255, 3: 84200333, 4: 525560923, 5: 65831608}
 WORKLOAD_NAMES = {
     1: "gemm_256x256x256_bf16_bias_relu",
     2: "gemm_4096x4096x4096_bf16_rowcol_bias_gelu_tanh",
@@ -101,7 +101,7 @@ def cpu_baseline(spec, cfg):
     import numpy as np
     if spec["op"] in ("gemm", "conv2d_fprop"):
         M = spec["M"]
-        n = {1: M, 2: 1024, 5: 12544}.get(cfg, min(M, 1024))
+        n = {1: M, 2: 4096, 5: 50176}.get(cfg, min(M, 1024))
         rows = list(range(0, M, max(1, M // n)))[:n]
         t0 = time.perf_counter()
         run_spec.run(spec, rows=rows)
