@@ -9,11 +9,12 @@
 //                    along M / N are loaded 128-bit into VGPRs and transposed on the way into LDS.
 //   LDS layout     : [rows][TK elements] (TK = 64 or 32: 128- or 64-byte rows of 16-byte chunks), chunk
 //                    index XORed with a function of the row so that the 16-byte-per-lane MFMA
-//                    fragment reads of 32 consecutive rows spread over all banks.
-//   mainloop       : v_mfma_f32_32x32x16_{bf16,f16}, fp32 accumulators held in registers,
+//                    fragment reads of 16 consecutive rows spread over all banks.
+//   mainloop       : v_mfma_f32_16x16x32_{bf16,f16}, fp32 accumulators held in registers,
 //                    wave tile (TM/2) x (TN/2).
-//   epilogue       : the `>>` chain interpreted on the accumulator registers (fp32), one rounding
-//                    to the output type, vector stores straight from registers.
+//   epilogue       : accumulators pass through a wave-private LDS patch to a row-contiguous layout;
+//                    the `>>` chain runs on them in fp32 registers, one rounding to the output type,
+//                    128-bit stores of whole row segments.
 #pragma once
 #include <cstddef>
 #include <type_traits>
@@ -62,10 +63,11 @@ __device__ __forceinline__ void pipeline_barrier() {
 }
 
 // XOR pattern of the LDS layout, for rows of CPR 16-byte chunks.  It depends on row mod 16 only, so
-// any multiple-of-32 row offset (wave tile, MFMA block) leaves it unchanged.  Both patterns were
-// picked by timing the fragment-read pattern (32 consecutive rows, two adjacent chunks) on the GPU:
-// the 128-byte-row pattern reads conflict-free (SQ_LDS_BANK_CONFLICT = 0), the 64-byte-row one is
-// the fastest of the candidates tried (about 1.2x the conflict-free time).
+// any multiple-of-16 row offset (wave tile, MFMA block) leaves it unchanged.  An MFMA fragment read
+// has 16 consecutive lanes on 16 consecutive rows at one logical chunk: with rows of 64 bytes the
+// 16-byte slots hit are (row mod 4) * 4 + (chunk ^ swz), with rows of 128 bytes (row mod 2) * 8 +
+// (chunk ^ swz), modulo the 16 slots of the banks -- both patterns make these 16 values distinct
+// (measured: SQ_LDS_BANK_CONFLICT = 0).
 template <int CPR>
 __device__ __forceinline__ int lds_swz(int row) {
     if constexpr (CPR == 8) return (row & 7) ^ ((row >> 3) & 1);
@@ -348,7 +350,7 @@ struct KernelCfg {
     static constexpr int A_ITERS = TM * CPR / kThreads;           // 16-byte chunks per thread per stage
     static constexpr int B_ITERS = TN * CPR / kThreads;
     static constexpr int ROWS_PER_ITER = kThreads / CPR;          // rows covered by one 256-thread copy
-    static_assert(TM % 64 == 0 && TN % 64 == 0, "wave tile is a multiple of 32x32");
+    static_assert(TM % 64 == 0 && TN % 64 == 0, "wave tile is a multiple of 32x32 (two 16-row MFMA blocks per staged epilogue block)");
     static_assert(LDS_BYTES <= kLdsBytesPerCU, "stages x tile exceed LDS");
     // Register budget: smaller tiles are built to let several workgroups share a CU (512 registers per
     // lane and SIMD, accumulators included), so that one workgroup's loads and stores overlap another's
