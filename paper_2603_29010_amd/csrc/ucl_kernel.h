@@ -698,16 +698,31 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
             constexpr int DN = decltype(dn_)::value;
             static_for<MI>([&](auto mi_) {
                 constexpr int mi = decltype(mi_)::value;
-                constexpr int ia = mi + RA - 1;                    // A fragment requested now
-                if constexpr (ia < MI) ar[ia % RA] = frag(sc, a_frag_base, ia, KK);
-                else ar[ia % RA] = frag(sn, a_frag_base, ia - MI, KN);
-                constexpr int b0 = mi * NI / MI, b1 = (mi + 1) * NI / MI;      // B fragments of the next k-step
-                static_for<b1 - b0>([&](auto j) { bq[1 - PB][b0 + j] = frag(sn, b_frag_base, b0 + j, KN); });
-                constexpr int d0 = mi * DN / MI, d1 = (mi + 1) * DN / MI;      // copies
-                static_for<d1 - d0>([&](auto j) { issue_one(check_, std::integral_constant<int, d0 + j>{}, kt_load, fill_buf); });
+                constexpr int ia = mi + RA - 1;                    // A fragment requested in this row block
+                constexpr int b0 = mi * NI / MI, nb = (mi + 1) * NI / MI - b0;   // B fragments of the next k-step
+                constexpr int d0 = mi * DN / MI, nd = (mi + 1) * DN / MI - d0;   // copies
+                constexpr int NS = 1 + nb + nd;                    // side instructions of this row block
+                auto side = [&](auto s_) __attribute__((always_inline)) {
+                    constexpr int sx = decltype(s_)::value;
+                    if constexpr (sx == 0) {
+                        if constexpr (ia < MI) ar[ia % RA] = frag(sc, a_frag_base, ia, KK);
+                        else ar[ia % RA] = frag(sn, a_frag_base, ia - MI, KN);
+                    } else if constexpr (sx <= nb) {
+                        bq[1 - PB][b0 + sx - 1] = frag(sn, b_frag_base, b0 + sx - 1, KN);
+                    } else {
+                        issue_one(check_, std::integral_constant<int, d0 + sx - 1 - nb>{}, kt_load, fill_buf);
+                    }
+                };
                 // B fragment as the MFMA's first operand: the lane then holds 4 consecutive n per
-                // accumulator, which is what the row-major store wants.
-                static_for<NI>([&](auto ni) { mfma16<Cfg::F16>(acc[mi][ni], bq[PB][ni], ar[mi % RA]); });
+                // accumulator, which is what the row-major store wants.  The side instructions go
+                // out one (or their even share) behind each MFMA, so that none of the gaps between
+                // two MFMAs grows longer than the MFMA itself.
+                static_for<NI>([&](auto ni_) {
+                    constexpr int ni = decltype(ni_)::value;
+                    mfma16<Cfg::F16>(acc[mi][ni], bq[PB][ni], ar[mi % RA]);
+                    constexpr int s0 = ni * NS / NI, s1 = (ni + 1) * NS / NI;
+                    static_for<s1 - s0>([&](auto j) { side(std::integral_constant<int, s0 + decltype(j)::value>{}); });
+                });
             });
         };
         // One k-tile.  P0: B set of its first k-step.  cur / nxt / fill: buffers of k-tiles kt, kt+1 and
