@@ -44,6 +44,15 @@ def test_gemm_exact_every_tile(tile, dt):
     parity.check_exact(spec, T(*tile), label=f"tile{tile}")
 
 
+@pytest.mark.parametrize("K", [8, 40, 96, 160, 416])
+def test_gemm_exact_short_k_every_tile(K):
+    # K shorter than a k-tile, fewer k-tiles than pipeline stages, odd numbers of k-tiles (the loop
+    # works in units of two k-tiles where a k-tile is one MFMA k-step), K tails of 8 and 32
+    spec = synth.gemm_spec(264, 136, K, dt_out="f32", epilogue=(), integer=True)
+    for tile in KK_TILES:
+        parity.check_exact(spec, T(*tile), label=f"K{K} tile{tile}")
+
+
 @pytest.mark.parametrize("a_layout,b_layout", [("row", "row"), ("col", "col"), ("col", "row")])
 @pytest.mark.parametrize("dt", ["bf16", "f16"])
 def test_gemm_exact_transposed_layouts(a_layout, b_layout, dt):
