@@ -257,3 +257,29 @@ def test_config5_full_size_sampled_rows():
                 rows.append((n * P + p) * Q + q)
     rows = sorted(set(rows))
     parity.check(spec, rows=rows, label="config5 full")
+
+
+def test_hip_graph_replays_match_eager_launch():
+    """bench.py times launches recorded in a HIP graph: every replay must give the eager result.
+    The library issues kernel nodes only (no memset or copy nodes); the replays are separated by
+    eager work and synchronisation of the program's own."""
+    import torch
+    from paper_2603_29010_amd.workload import DeviceWorkload
+    spec = synth.config(2, shrink=8)
+    w = DeviceWorkload(spec)
+    w.run()
+    torch.cuda.synchronize()
+    eager = w.result().copy()
+    ref, absacc = parity.oracle_result(spec)
+    parity.compare(eager.reshape(ref.shape), ref, absacc, spec, "eager")
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        w.run()
+        w.run()
+    for rep in range(3):
+        w.D.zero_()                       # eager work between replays; also wipes the previous result
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        got = w.result()
+        assert np.array_equal(got, eager), f"replay {rep} differs from the eager launch"
