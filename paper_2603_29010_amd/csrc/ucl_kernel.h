@@ -386,6 +386,13 @@ __device__ __forceinline__ void mfma16(f32x4_t &c, const u32x4_t &a, const u32x4
     else asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
 }
 
+// First of the n items dealt to row block mi when they are spread over the first half of the
+// mblocks row blocks.
+constexpr int bshare(int mi, int mblocks, int n) {
+    const int h = mblocks >= 2 ? mblocks / 2 : 1;
+    return (mi < h ? mi : h) * n / h;
+}
+
 template <class Cfg>
 __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(const KParams p, const typename Cfg::Groups gt) {
     constexpr int TM = Cfg::TM, TN = Cfg::TN, TK = Cfg::TK, STAGES = Cfg::STAGES;
@@ -667,6 +674,78 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
             });
             if (kt + 1 < KT) commit_regs((kt + 1) % STAGES);
         }
+    } else if constexpr (STAGES == 2) {
+        // ---- two stage buffers, k-tiles of two k-steps --------------------------------------------
+        // For tiles whose stage is too large for three buffers.  One k-tile is multiplied while the
+        // next is in flight.  k-step 0 takes its A fragments through the ring (see below) and, beside
+        // its MFMAs, reads ALL fragments of k-step 1; then the barrier: this wave has issued every
+        // read of the tile, the next k-tile has landed (vmcnt 0), every wave is past its reads -- so
+        // k-step 1, beside its MFMAs, refills the tile's own buffer with k-tile kt+2 and reads the
+        // first fragments of k-tile kt+1.
+        static_assert(KSTEPS == 2, "the two-buffer loop is written for k-tiles of two k-steps");
+        constexpr int RA = MI % 4 == 0 ? 4 : 2;
+        static_assert(MI % RA == 0, "ring slots must line up across k-tiles");
+        u32x4_t ar[RA], af[MI], bq[2][NI];
+        // the side instructions of a row block go out one (or their even share) behind each MFMA
+        auto row_block = [&](auto mi_, const u32x4_t &a, auto pb_, auto ns_, auto &&side) __attribute__((always_inline)) {
+            constexpr int mi = decltype(mi_)::value, PB = decltype(pb_)::value, NS = decltype(ns_)::value;
+            static_for<NI>([&](auto ni_) {
+                constexpr int ni = decltype(ni_)::value;
+                mfma16<Cfg::F16>(acc[mi][ni], bq[PB][ni], a);
+                constexpr int s0 = ni * NS / NI, s1 = (ni + 1) * NS / NI;
+                static_for<s1 - s0>([&](auto j) { side(std::integral_constant<int, s0 + decltype(j)::value>{}); });
+            });
+        };
+        auto first_step = [&](const char *sc) {
+            static_for<MI>([&](auto mi_) {
+                constexpr int mi = decltype(mi_)::value;
+                constexpr int ia = mi + RA - 1;
+                constexpr int b0 = bshare(mi, MI, NI), nb = bshare(mi + 1, MI, NI) - b0;
+                constexpr int na = ia < MI ? 1 : 0;
+                auto side = [&](auto s_) __attribute__((always_inline)) {
+                    constexpr int sx = decltype(s_)::value;
+                    if constexpr (sx < na) ar[ia % RA] = frag(sc, a_frag_base, ia, 0);
+                    else if constexpr (sx == na) af[mi] = frag(sc, a_frag_base, mi, 1);
+                    else bq[1][b0 + sx - na - 1] = frag(sc, b_frag_base, b0 + sx - na - 1, 1);
+                };
+                row_block(mi_, ar[mi % RA], I0{}, std::integral_constant<int, na + 1 + nb>{}, side);
+            });
+        };
+        auto last_step = [&](auto check_, const char *sn, int kt_load, int buf) {
+            static_for<MI>([&](auto mi_) {
+                constexpr int mi = decltype(mi_)::value;
+                constexpr int ih = mi - (MI - (RA - 1));           // ring head of the next k-tile
+                constexpr int na = ih >= 0 ? 1 : 0;
+                constexpr int b0 = bshare(mi, MI, NI), nb = bshare(mi + 1, MI, NI) - b0;
+                constexpr int d0 = mi * DMA_PER_TILE / MI, nd = (mi + 1) * DMA_PER_TILE / MI - d0;
+                auto side = [&](auto s_) __attribute__((always_inline)) {
+                    constexpr int sx = decltype(s_)::value;
+                    if constexpr (sx < na) ar[ih] = frag(sn, a_frag_base, ih, 0);
+                    else if constexpr (sx < na + nb) bq[0][b0 + sx - na] = frag(sn, b_frag_base, b0 + sx - na, 0);
+                    else issue_one(check_, std::integral_constant<int, d0 + sx - na - nb>{}, kt_load, buf);
+                };
+                row_block(mi_, af[mi], I1{}, std::integral_constant<int, na + nb + nd>{}, side);
+            });
+        };
+        issue_tile(std::true_type{}, 0, 0);
+        issue_tile(std::true_type{}, 1, 1);
+        pipeline_barrier<DMA_PER_TILE>();
+        static_for<RA - 1>([&](auto i) { ar[i] = frag(smem, a_frag_base, i, 0); });
+        static_for<NI>([&](auto ni) { bq[0][ni] = frag(smem, b_frag_base, ni, 0); });
+        const int KT_full = k_tail ? KT - 1 : KT;
+        int kt = 0;
+        auto ktile2 = [&](auto check_, auto cur_) {
+            const int cur = cur_;
+            first_step(smem + cur * Cfg::STAGE_BYTES);
+            pipeline_barrier<0>();
+            last_step(check_, smem + (cur ^ 1) * Cfg::STAGE_BYTES, kt + 2, cur);
+            ++kt;
+        };
+        while (kt + 3 < KT_full) {                                 // steady state over the two buffers
+            ktile2(std::false_type{}, I0{});
+            ktile2(std::false_type{}, I1{});
+        }
+        while (kt < KT) ktile2(std::true_type{}, kt & 1);
     } else {
         // ---- software-pipelined loop ---------------------------------------------------------------
         // STAGES-1 k-tiles are in flight.  Registers hold the B fragments of the running k-step and
@@ -699,7 +778,8 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
             static_for<MI>([&](auto mi_) {
                 constexpr int mi = decltype(mi_)::value;
                 constexpr int ia = mi + RA - 1;                    // A fragment requested in this row block
-                constexpr int b0 = mi * NI / MI, nb = (mi + 1) * NI / MI - b0;   // B fragments of the next k-step
+                // B fragments of the next k-step: all in the first half of the row blocks (its first MFMAs need them)
+                constexpr int b0 = bshare(mi, MI, NI), nb = bshare(mi + 1, MI, NI) - b0;
                 constexpr int d0 = mi * DN / MI, nd = (mi + 1) * DN / MI - d0;   // copies
                 constexpr int NS = 1 + nb + nd;                    // side instructions of this row block
                 auto side = [&](auto s_) __attribute__((always_inline)) {
