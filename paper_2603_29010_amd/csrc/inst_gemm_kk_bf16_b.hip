@@ -4,6 +4,7 @@ namespace ucl {
 static const VariantDesc kTable[] = {
     describe<KernelCfg<256, 128, 32, 4, false, 0, kKContig, kKContig>>(),
     describe<KernelCfg<256, 128, 32, 3, false, 0, kKContig, kKContig>>(),
+    describe<KernelCfg<256, 128, 64, 2, false, 0, kKContig, kKContig>>(),
 };
 VariantList variants_gemm_kk_bf16_b() { return {kTable, (int)(sizeof(kTable) / sizeof(kTable[0]))}; }
 }  // namespace ucl

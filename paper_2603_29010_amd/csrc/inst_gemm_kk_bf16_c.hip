@@ -5,6 +5,7 @@ static const VariantDesc kTable[] = {
     describe<KernelCfg<128, 128, 64, 3, false, 0, kKContig, kKContig>>(),
     describe<KernelCfg<128, 128, 32, 4, false, 0, kKContig, kKContig>>(),
     describe<KernelCfg<128, 128, 32, 3, false, 0, kKContig, kKContig>>(),
+    describe<KernelCfg<128, 128, 64, 2, false, 0, kKContig, kKContig>>(),
 };
 VariantList variants_gemm_kk_bf16_c() { return {kTable, (int)(sizeof(kTable) / sizeof(kTable[0]))}; }
 }  // namespace ucl

@@ -3,6 +3,7 @@
 namespace ucl {
 static const VariantDesc kTable[] = {
     describe<KernelCfg<256, 256, 32, 4, true, 0, kKContig, kKContig>>(),
+    describe<KernelCfg<256, 256, 64, 2, true, 0, kKContig, kKContig>>(),
     describe<KernelCfg<256, 128, 32, 4, true, 0, kKContig, kKContig>>(),
     describe<KernelCfg<256, 128, 32, 3, true, 0, kKContig, kKContig>>(),
 };

@@ -4,6 +4,7 @@ namespace ucl {
 static const VariantDesc kTable[] = {
     describe<KernelCfg<256, 256, 32, 4, false, 1, kKContig, kKContig>>(),
     describe<KernelCfg<256, 256, 32, 5, false, 1, kKContig, kKContig>>(),
+    describe<KernelCfg<256, 256, 64, 2, false, 1, kKContig, kKContig>>(),
     describe<KernelCfg<256, 128, 32, 4, false, 1, kKContig, kKContig>>(),
     describe<KernelCfg<256, 128, 32, 3, false, 1, kKContig, kKContig>>(),
 };

@@ -3,8 +3,10 @@
 namespace ucl {
 static const VariantDesc kTable[] = {
     describe<KernelCfg<128, 128, 64, 3, false, 1, kKContig, kKContig>>(),
+    describe<KernelCfg<128, 128, 64, 2, false, 1, kKContig, kKContig>>(),
     describe<KernelCfg<64, 64, 32, 3, false, 1, kKContig, kKContig>>(),
     describe<KernelCfg<256, 256, 32, 4, true, 1, kKContig, kKContig>>(),
+    describe<KernelCfg<256, 256, 64, 2, true, 1, kKContig, kKContig>>(),
     describe<KernelCfg<128, 128, 64, 3, true, 1, kKContig, kKContig>>(),
     describe<KernelCfg<64, 64, 32, 3, true, 1, kKContig, kKContig>>(),
 };

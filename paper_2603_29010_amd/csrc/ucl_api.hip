@@ -70,7 +70,8 @@ struct Launch {
 //   3. otherwise take the largest tile that still yields at least ~3/4 of a full wave of workgroups
 //      over the 256 CUs (fewer, larger tiles = more reuse per byte staged; too few = idle CUs);
 //      if none does, take the tile giving the most workgroups;
-//   4. among equal tiles take the deepest pipeline the K extent can use (stages - 1 <= K tiles).
+//   4. among equal tiles take the two-buffer loop over 64-wide k-tiles if built, else the deepest
+//      pipeline of 32-wide k-tiles the K extent can use.
 int64_t count_tiles(const Launch &L, int tm, int tn) {
     const int64_t tiles_n = (L.N + tn - 1) / tn;
     if (L.mode == 1) {
@@ -129,9 +130,13 @@ const VariantDesc *select_variant(const Launch &L, const ucl_tuning *tune) {
         if (membound && workgroups_per_cu(v) >= 2 && tiles >= 256) key = (2ll << 40) + area * 1024;
         else if (tiles >= 192) key = (1ll << 40) + area * 1024;
         else key = tiles * 1024;
-        // prefer the pipeline with the most bytes in flight that the K extent can fill
-        const int64_t depth = v.stages <= ktiles ? (int64_t)(v.stages - 1) * v.tile_k : 0;
-        key += depth;
+        // among the variants of a tile: the two-buffer loop over 64-wide k-tiles measured fastest,
+        // then the 32-wide k-tiles by depth (as far as the K extent can fill the pipeline)
+        int64_t pref;
+        if (v.stages == 2 && v.tile_k == 64 && v.lb == 0) pref = 900;
+        else if (v.tile_k == 32) pref = 100 + (v.stages <= ktiles + 1 ? v.stages : 0);
+        else pref = v.stages;
+        key += pref;
         if (key > best_key) { best_key = key; best = &v; }
     }
     return best;
