@@ -700,15 +700,18 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
             static_for<MI>([&](auto mi_) {
                 constexpr int mi = decltype(mi_)::value;
                 constexpr int ia = mi + RA - 1;
+                // everything of k-step 1 is requested in the first half of the row blocks, so that the
+                // barrier behind this k-step does not wait for LDS latency
                 constexpr int b0 = bshare(mi, MI, NI), nb = bshare(mi + 1, MI, NI) - b0;
+                constexpr int f0 = bshare(mi, MI, MI), nf = bshare(mi + 1, MI, MI) - f0;
                 constexpr int na = ia < MI ? 1 : 0;
                 auto side = [&](auto s_) __attribute__((always_inline)) {
                     constexpr int sx = decltype(s_)::value;
                     if constexpr (sx < na) ar[ia % RA] = frag(sc, a_frag_base, ia, 0);
-                    else if constexpr (sx == na) af[mi] = frag(sc, a_frag_base, mi, 1);
-                    else bq[1][b0 + sx - na - 1] = frag(sc, b_frag_base, b0 + sx - na - 1, 1);
+                    else if constexpr (sx < na + nf) af[f0 + sx - na] = frag(sc, a_frag_base, f0 + sx - na, 1);
+                    else bq[1][b0 + sx - na - nf] = frag(sc, b_frag_base, b0 + sx - na - nf, 1);
                 };
-                row_block(mi_, ar[mi % RA], I0{}, std::integral_constant<int, na + 1 + nb>{}, side);
+                row_block(mi_, ar[mi % RA], I0{}, std::integral_constant<int, na + nf + nb>{}, side);
             });
         };
         auto last_step = [&](auto check_, const char *sn, int kt_load, int buf) {
