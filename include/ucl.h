@@ -108,8 +108,10 @@ typedef struct ucl_epilogue {
 
 /* Explicit kernel choice (`.with_tile`, `.with_stages`, `.with_swizzle`).
  * tile_k (K extent of one LDS stage) is 32 or 64; stages is the number of LDS stage
- * buffers, at least 3 for operands contiguous along K (stages - 1 k-tiles are in
- * flight while one is being multiplied), 2 for the register-transposed layouts.
+ * buffers: 3 or more for operands contiguous along K (stages - 1 k-tiles are in
+ * flight while one is being multiplied), or 2 with tile_k = 64 (each half of a
+ * buffer is refilled as soon as it has been read); 2 for the register-transposed
+ * layouts.
  * Only built combinations are accepted (ucl_variant()).  raster = width, in tile rows, of the
  * bands the tile order walks column by column (1, 2, 4, 8, 16; the swizzle
  * knob's Identity1..8), 0 = table default.  The order is also XCD-aware:

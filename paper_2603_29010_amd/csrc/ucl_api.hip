@@ -60,18 +60,15 @@ struct Launch {
     int64_t max_Mg = 0, sum_Mg = 0;
 };
 
-// Per-problem selection table.  Rules, in order:
-//   1. only variants built for this (mode, input type, operand layouts) are candidates;
-//   2. a problem whose arithmetic intensity is below the machine balance (memory-bound by the SOL
-//      model) spends its time in the load and store phases of its tiles, which one workgroup runs
-//      one after the other: take the largest tile among the variants of which at least two
-//      workgroups fit on a CU (registers and LDS) and that yield a full wave of workgroups, so that
-//      one workgroup's stores overlap another's loads;
-//   3. otherwise take the largest tile that still yields at least ~3/4 of a full wave of workgroups
-//      over the 256 CUs (fewer, larger tiles = more reuse per byte staged; too few = idle CUs);
-//      if none does, take the tile giving the most workgroups;
-//   4. among equal tiles take the two-buffer loop over 64-wide k-tiles if built, else the deepest
-//      pipeline of 32-wide k-tiles the K extent can use.
+// Per-problem selection table: of the variants built for this (mode, input type, operand layouts)
+// take the one with the smallest estimated time
+//     ceil(tiles / 256) * ( tile FLOPs / (rate of a busy CU with this variant)
+//                           + (fixed cost of a tile) / (workgroups of the variant that share a CU) ),
+// i.e. the tiles dealt to the busiest CU one after the other, each paying its MFMA time at the rate
+// measured for the variant (4096^3 bf16 problem, relative to the best variant) and its un-overlapped
+// prologue + store time unless a co-resident workgroup hides it.  Large compute-bound problems thus get
+// 256x256 tiles and the two-buffer loop, short-K / wide-output problems get the largest tile of which
+// two workgroups fit on a CU, small problems the tile that fills the chip.
 int64_t count_tiles(const Launch &L, int tm, int tn) {
     const int64_t tiles_n = (L.N + tn - 1) / tn;
     if (L.mode == 1) {
@@ -94,27 +91,43 @@ int workgroups_per_cu(const VariantDesc &v) {
     return by_regs < by_lds ? by_regs : by_lds;
 }
 
-// Arithmetic intensity of the problem against the ridge of the default machine (bf16/fp16 MFMA peak
-// over HBM bandwidth), operands and output counted once.
-bool memory_bound(const Launch &L) {
-    double flops, bytes;
-    const double eo = L.dtD == UCL_F32 ? 4.0 : 2.0;
-    if (L.mode == 1) {
-        flops = 2.0 * (double)L.sum_Mg * L.N * L.K;
-        bytes = 2.0 * ((double)L.sum_Mg * L.K + (double)L.groups * L.N * L.K) + eo * (double)L.sum_Mg * L.N;
-    } else {
-        flops = 2.0 * (double)L.batch * L.M * L.N * L.K;
-        bytes = (double)L.batch * (2.0 * ((double)L.M * L.K + (double)L.N * L.K) + eo * (double)L.M * L.N);
-    }
-    return flops * 8.0e12 < bytes * 2516.6e12;
+// Rate of a CU that is busy with variant v, relative to the best variant (measured, see above).
+double relative_rate(const VariantDesc &v) {
+    const int64_t area = (int64_t)v.tile_m * v.tile_n;
+    const bool two_buf = v.stages == 2 && v.tile_k == 64 && v.lb == 0 && v.la != 1;
+    if (v.la == 1 || v.lb == 1) return area >= 128 * 128 ? 0.30 : 0.20;     // register-transposed operands
+    if (area >= 256 * 256) return two_buf ? 1.00 : v.stages >= 5 ? 0.92 : 0.90;
+    if (area >= 256 * 128) return two_buf ? 0.81 : v.stages == 3 ? 0.80 : 0.73;
+    if (area >= 128 * 128) return two_buf ? 0.86 : v.tile_k == 32 ? (v.stages >= 4 ? 0.67 : 0.65) : 0.58;
+    return v.tile_k == 64 ? 0.49 : v.stages == 3 ? 0.41 : 0.37;
+}
+
+double estimate_seconds(const VariantDesc &v, const Launch &L) {
+    const double kCuRate = 1.38e15 / 256;            // FLOP/s of one CU at the best variant's measured rate
+    const double kCuStore = 4.6e12 / 256;            // B/s of output one CU gets when all CUs store
+    const int wg = workgroups_per_cu(v);
+    const int64_t tiles = count_tiles(L, v.tile_m, v.tile_n);
+    const int64_t slots = 256 * (int64_t)wg;
+    // tiles the busiest CU works through: they run wg at a time, a new set starting when slots free up
+    const double per_cu = tiles <= slots ? (double)((tiles + 255) / 256) : (double)((tiles + slots - 1) / slots * wg);
+    // the chip is power-limited: CUs run faster when fewer of them are busy (measured ~1.5x at 144 of 256)
+    const double active = tiles / per_cu < 256.0 ? tiles / per_cu : 256.0;
+    double boost = pow(256.0 / (active < 1.0 ? 1.0 : active), 0.7);
+    if (boost > 1.5) boost = 1.5;
+    const double tile_flops = 2.0 * v.tile_m * v.tile_n * (double)L.K;
+    const double out_bytes = (double)v.tile_m * v.tile_n * (L.dtD == UCL_F32 ? 4.0 : 2.0);
+    const double fixed = 2.0e-6 + out_bytes / kCuStore;
+    // co-resident workgroups hide about half of what perfect overlap of one's fixed cost with the
+    // others' MFMA time would; a CU with a single tile has nothing to overlap with
+    const double exposed = per_cu > 1.0 ? 0.5 * (1.0 + 1.0 / wg) : 1.0;
+    return per_cu * (tile_flops / (relative_rate(v) * kCuRate * boost) + fixed * exposed);
 }
 
 const VariantDesc *select_variant(const Launch &L, const ucl_tuning *tune) {
     const auto &vs = all_variants();
     const bool explicit_tune = tune && (tune->tile_m || tune->tile_n || tune->tile_k || tune->stages);
     const VariantDesc *best = nullptr;
-    int64_t best_key = -1;
-    const bool membound = !explicit_tune && memory_bound(L);
+    double best_t = 0;
     for (const auto &v : vs) {
         if (v.mode != L.mode || v.f16 != L.f16 || v.la != L.la || v.lb != L.lb) continue;
         if (explicit_tune) {
@@ -123,21 +136,8 @@ const VariantDesc *select_variant(const Launch &L, const ucl_tuning *tune) {
                 return &v;
             continue;
         }
-        const int64_t tiles = count_tiles(L, v.tile_m, v.tile_n);
-        const int64_t area = (int64_t)v.tile_m * v.tile_n;
-        const int64_t ktiles = (L.K + v.tile_k - 1) / v.tile_k;
-        int64_t key;
-        if (membound && workgroups_per_cu(v) >= 2 && tiles >= 256) key = (2ll << 40) + area * 1024;
-        else if (tiles >= 192) key = (1ll << 40) + area * 1024;
-        else key = tiles * 1024;
-        // among the variants of a tile: the two-buffer loop over 64-wide k-tiles measured fastest,
-        // then the 32-wide k-tiles by depth (as far as the K extent can fill the pipeline)
-        int64_t pref;
-        if (v.stages == 2 && v.tile_k == 64 && v.lb == 0) pref = 900;
-        else if (v.tile_k == 32) pref = 100 + (v.stages <= ktiles + 1 ? v.stages : 0);
-        else pref = v.stages;
-        key += pref;
-        if (key > best_key) { best_key = key; best = &v; }
+        const double t = estimate_seconds(v, L);
+        if (!best || t < best_t) { best_t = t; best = &v; }
     }
     return best;
 }
