@@ -106,7 +106,18 @@ typedef struct ucl_epilogue {
     ucl_epi_step steps[UCL_MAX_EPI_STEPS];
 } ucl_epilogue;
 
-/* Explicit kernel choice (`.with_tile`, `.with_stages`, `.with_swizzle`).
+/* How conv2d_fprop reads the activations (`.with_iterator`).  ANALYTIC gathers every
+ * filter tap from global memory and serves every geometry.  FIXED_STRIDE_DILATION
+ * (3x3 filter, unit stride and dilation, pad 1, C = 64, W <= 58) copies the pixels a
+ * tile needs into LDS once and reads all nine taps from there.  DEFAULT: the table
+ * takes the second where it applies. */
+typedef enum ucl_conv_iterator {
+    UCL_ITER_DEFAULT = 0,
+    UCL_ITER_ANALYTIC = 1,
+    UCL_ITER_FIXED_STRIDE_DILATION = 2
+} ucl_conv_iterator;
+
+/* Explicit kernel choice (`.with_tile`, `.with_stages`, `.with_swizzle`, `.with_iterator`).
  * tile_k (K extent of one LDS stage) is 32 or 64; stages is the number of LDS stage
  * buffers: 3 or more for operands contiguous along K (stages - 1 k-tiles are in
  * flight while one is being multiplied), or 2 with tile_k = 64 (each half of a
@@ -115,10 +126,12 @@ typedef struct ucl_epilogue {
  * Only built combinations are accepted (ucl_variant()).  raster = width, in tile rows, of the
  * bands the tile order walks column by column (1, 2, 4, 8, 16; the swizzle
  * knob's Identity1..8), 0 = table default.  The order is also XCD-aware:
- * workgroup ids that land on the same XCD (id mod 8) get neighbouring tiles. */
+ * workgroup ids that land on the same XCD (id mod 8) get neighbouring tiles.
+ * iterator is a ucl_conv_iterator and is ignored by the GEMM entry points. */
 typedef struct ucl_tuning {
     int32_t tile_m, tile_n, tile_k, stages, raster;
-    int32_t reserved[3];
+    int32_t iterator;
+    int32_t reserved[2];
 } ucl_tuning;
 
 /* D[m,n] = E( sum_k A[m*a_rs + k*a_cs] * B[k*b_rs + n*b_cs] ), written to
@@ -226,8 +239,8 @@ ucl_status ucl_select_tuning(const ucl_problem *p, ucl_tuning *out);
 ucl_status ucl_tile_map(int32_t groups, const int32_t *tiles_m, int32_t tiles_n, int32_t raster,
                         int32_t wg, int32_t *group, int32_t *tile_m, int32_t *tile_n);
 
-/* Number of kernel variants built in, and the (tile_m, tile_n, tile_k, stages)
- * of variant i; explicit ucl_tuning must name one of these. */
+/* Number of kernel variants built in, and the (tile_m, tile_n, tile_k, stages,
+ * iterator) of variant i; explicit ucl_tuning must name one of these. */
 int32_t ucl_num_variants(void);
 ucl_status ucl_variant(int32_t i, ucl_tuning *out);
 

@@ -38,7 +38,7 @@ class _Epilogue(C.Structure):
 
 class _Tuning(C.Structure):
     _fields_ = [("tile_m", C.c_int32), ("tile_n", C.c_int32), ("tile_k", C.c_int32),
-                ("stages", C.c_int32), ("raster", C.c_int32), ("reserved", C.c_int32 * 3)]
+                ("stages", C.c_int32), ("raster", C.c_int32), ("iterator", C.c_int32), ("reserved", C.c_int32 * 2)]
 
 
 class _Problem(C.Structure):
@@ -155,14 +155,14 @@ class Epilogue:
 
 
 class Tuning:
-    def __init__(self, tile_m=0, tile_n=0, tile_k=0, stages=0, raster=0):
-        self.c = _Tuning(tile_m, tile_n, tile_k, stages, raster)
+    def __init__(self, tile_m=0, tile_n=0, tile_k=0, stages=0, raster=0, iterator=0):
+        self.c = _Tuning(tile_m, tile_n, tile_k, stages, raster, iterator)
 
     def ref(self):
         return C.byref(self.c)
 
     def as_dict(self):
-        return {k: getattr(self.c, k) for k in ("tile_m", "tile_n", "tile_k", "stages", "raster")}
+        return {k: getattr(self.c, k) for k in ("tile_m", "tile_n", "tile_k", "stages", "raster", "iterator")}
 
 
 def _opt(x):
@@ -252,8 +252,8 @@ def ucl_variant(i):
     t = Tuning()
     _check(_load().ucl_variant(i, t.ref()))
     d = t.as_dict()
-    d["mode"], d["f16"], lay = t.c.reserved[0], t.c.reserved[1], t.c.reserved[2]
-    d["la"], d["lb"] = lay // 4, lay % 4
+    d["mode"], lay = t.c.reserved[0], t.c.reserved[1]
+    d["f16"], d["la"], d["lb"] = lay // 16, lay // 4 % 4, lay % 4
     return d
 
 

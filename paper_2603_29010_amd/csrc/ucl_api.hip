@@ -24,7 +24,7 @@ ucl_status fail(ucl_status st, const char *fmt, ...) {
 const std::vector<VariantDesc> &all_variants() {
     static const std::vector<VariantDesc> v = [] {
         std::vector<VariantDesc> out;
-        for (VariantList l : {variants_gemm_kk_bf16_a(), variants_gemm_kk_bf16_b(), variants_gemm_kk_bf16_c(), variants_gemm_kk_bf16_d(), variants_gemm_kk_f16_a(), variants_gemm_kk_f16_b(), variants_gemm_mn_bf16(), variants_gemm_mn_f16(), variants_grouped_a(), variants_grouped_b(), variants_conv_a(), variants_conv_b(), variants_conv_f16()})
+        for (VariantList l : {variants_gemm_kk_bf16_a(), variants_gemm_kk_bf16_b(), variants_gemm_kk_bf16_c(), variants_gemm_kk_bf16_d(), variants_gemm_kk_f16_a(), variants_gemm_kk_f16_b(), variants_gemm_mn_bf16(), variants_gemm_mn_f16(), variants_grouped_a(), variants_grouped_b(), variants_conv_a(), variants_conv_b(), variants_conv_f16(), variants_conv_halo()})
             for (int i = 0; i < l.n; ++i) out.push_back(l.v[i]);
         return out;
     }();
@@ -58,7 +58,16 @@ struct Launch {
     int groups = 0;
     const int64_t *M_g = nullptr;
     int64_t max_Mg = 0, sum_Mg = 0;
+    bool patch_ok = false;        // conv: the problem fits the resident-patch kernels
 };
+
+// The resident-patch conv kernels hold 64-channel pixels and address the taps of a 3x3 filter at unit
+// stride / dilation with one pad pixel, the image row (plus one pixel) on either side of a tile in LDS.
+bool conv_patch_ok(int64_t W, int64_t C, int64_t R, int64_t S, int64_t pad_h, int64_t pad_w, int64_t str_h,
+                   int64_t str_w, int64_t dil_h, int64_t dil_w) {
+    return C == 64 && R == 3 && S == 3 && pad_h == 1 && pad_w == 1 && str_h == 1 && str_w == 1 && dil_h == 1 &&
+           dil_w == 1 && W + 1 <= 59;
+}
 
 // Per-problem selection table: of the variants built for this (mode, input type, operand layouts)
 // take the one with the smallest estimated time
@@ -96,6 +105,7 @@ double relative_rate(const VariantDesc &v) {
     const int64_t area = (int64_t)v.tile_m * v.tile_n;
     const bool two_buf = v.stages == 2 && v.tile_k == 64 && v.lb == 0 && v.la != 1;
     if (v.la == 1 || v.lb == 1) return area >= 128 * 128 ? 0.30 : 0.20;     // register-transposed operands
+    if (v.la == 3) return 0.85;                                             // conv from a resident patch: above the gather kernels
     if (area >= 256 * 256) return two_buf ? 1.00 : v.stages >= 5 ? 0.92 : 0.90;
     if (area >= 256 * 128) return two_buf ? 0.81 : v.stages == 3 ? 0.80 : 0.73;
     if (area >= 128 * 128) return two_buf ? 0.86 : v.tile_k == 32 ? (v.stages >= 4 ? 0.67 : 0.65) : 0.58;
@@ -129,11 +139,19 @@ const VariantDesc *select_variant(const Launch &L, const ucl_tuning *tune) {
     const VariantDesc *best = nullptr;
     double best_t = 0;
     for (const auto &v : vs) {
-        if (v.mode != L.mode || v.f16 != L.f16 || v.la != L.la || v.lb != L.lb) continue;
+        if (v.mode != L.mode || v.f16 != L.f16 || v.lb != L.lb) continue;
+        if (L.mode == 2) {
+            // conv: the iterator knob picks between the per-tap gather (la 2) and the resident patch (la 3)
+            const int it = tune ? tune->iterator : 0;
+            if (v.la == 3 ? (!L.patch_ok || it == UCL_ITER_ANALYTIC) : (v.la != 2 || it == UCL_ITER_FIXED_STRIDE_DILATION)) continue;
+        } else if (v.la != L.la) {
+            continue;
+        }
         if (explicit_tune) {
-            if (v.tile_m == tune->tile_m && v.tile_n == tune->tile_n && v.stages == tune->stages &&
-                v.tile_k == tune->tile_k)
-                return &v;
+            if (v.tile_m != tune->tile_m || v.tile_n != tune->tile_n || v.stages != tune->stages || v.tile_k != tune->tile_k)
+                continue;
+            if (v.la == 3) return &v;                       // of two kernels with the named shape the patch one
+            if (!best) best = &v;
             continue;
         }
         const double t = estimate_seconds(v, L);
@@ -260,6 +278,10 @@ ucl_status check_common(int64_t M, int64_t N, int64_t K, int dtA, int dtB, int d
 }
 
 ucl_status run(const Launch &L, KParams &kp, const GroupTable *gt_in, const ucl_tuning *tune, void *stream) {
+    if (tune && (tune->iterator < 0 || tune->iterator > UCL_ITER_FIXED_STRIDE_DILATION))
+        return fail(UCL_ERR_INVALID_ARG, "iterator=%d is not a ucl_conv_iterator", tune->iterator);
+    if (tune && tune->iterator == UCL_ITER_FIXED_STRIDE_DILATION && !(L.mode == 2 && L.patch_ok))
+        return fail(UCL_ERR_UNSUPPORTED, "the fixed_stride_dilation iterator serves conv2d_fprop with a 3x3 filter, unit stride and dilation, pad 1, 64 channels and W <= 58");
     const VariantDesc *v = select_variant(L, tune);
     if (!v) {
         if (tune && (tune->tile_m || tune->tile_n || tune->stages)) {
@@ -480,6 +502,7 @@ ucl_status ucl_conv2d_fprop(int64_t N, int64_t H, int64_t W, int64_t C, int64_t 
         return fail(UCL_ERR_UNSUPPORTED, "image extents / pads must be below 2^24");
     Launch L;
     L.mode = 2; L.M = M; L.N = Kout; L.K = Kg; L.la = 2; L.lb = 0; L.f16 = dtX == UCL_F16; L.dtD = dtY;
+    L.patch_ok = conv_patch_ok(W, C, R, S, pad_h, pad_w, stride_h, stride_w, dil_h, dil_w);
     KParams kp;
     memset(&kp, 0, sizeof(kp));
     if (ucl_status st = check_epilogue(epi, L, kp)) return st;
@@ -537,6 +560,8 @@ ucl_status ucl_select_tuning(const ucl_problem *p, ucl_tuning *out) {
     L.la = L.mode == 2 ? 2 : 0; L.lb = 0;
     L.f16 = p->dt_in == UCL_F16;
     L.dtD = p->dt_out;
+    if (L.mode == 2)
+        L.patch_ok = conv_patch_ok(p->cW, p->cC, p->cR, p->cS, p->pad_h, p->pad_w, p->stride_h, p->stride_w, p->dil_h, p->dil_w);
     if (L.mode == 1)
         for (int g = 0; g < L.groups; ++g) L.sum_Mg += L.M_g[g];
     const VariantDesc *v = select_variant(L, nullptr);
@@ -544,6 +569,7 @@ ucl_status ucl_select_tuning(const ucl_problem *p, ucl_tuning *out) {
     memset(out, 0, sizeof(*out));
     out->tile_m = v->tile_m; out->tile_n = v->tile_n; out->tile_k = v->tile_k; out->stages = v->stages;
     out->raster = default_raster(*v, L);
+    out->iterator = v->la == 3 ? UCL_ITER_FIXED_STRIDE_DILATION : v->la == 2 ? UCL_ITER_ANALYTIC : UCL_ITER_DEFAULT;
     return UCL_OK;
 }
 
@@ -575,8 +601,9 @@ ucl_status ucl_variant(int32_t i, ucl_tuning *out) {
     if (i < 0 || i >= (int)vs.size() || !out) return fail(UCL_ERR_INVALID_ARG, "variant index %d outside [0, %d)", i, (int)vs.size());
     memset(out, 0, sizeof(*out));
     out->tile_m = vs[i].tile_m; out->tile_n = vs[i].tile_n; out->tile_k = vs[i].tile_k; out->stages = vs[i].stages;
-    // reserved[0..2]: which problems the variant serves (mode, 16-bit type, operand layouts)
-    out->reserved[0] = vs[i].mode; out->reserved[1] = vs[i].f16; out->reserved[2] = vs[i].la * 4 + vs[i].lb;
+    out->iterator = vs[i].la == 3 ? UCL_ITER_FIXED_STRIDE_DILATION : vs[i].la == 2 ? UCL_ITER_ANALYTIC : UCL_ITER_DEFAULT;
+    // reserved[0..1]: which problems the variant serves (mode; 16-bit type and operand layouts)
+    out->reserved[0] = vs[i].mode; out->reserved[1] = vs[i].f16 * 16 + vs[i].la * 4 + vs[i].lb;
     return UCL_OK;
 }
 

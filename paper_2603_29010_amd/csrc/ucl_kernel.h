@@ -33,7 +33,10 @@ typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
 
 #define UCL_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
 
-enum OperandLayout { kKContig = 0, kMNContig = 1, kIm2col = 2 };
+// kIm2col gathers every filter tap of the activations from global memory again; kHalo (3x3 filter,
+// unit stride and dilation, pad 1, 64 channels) copies the pixels a tile needs -- its rows plus one
+// image row and one pixel on either side -- into LDS once and reads every tap from there.
+enum OperandLayout { kKContig = 0, kMNContig = 1, kIm2col = 2, kHalo = 3 };
 
 // Compile-time loop: register arrays (accumulators, fragments) must only ever be indexed by
 // constants, or the compiler moves them to scratch memory.
@@ -340,14 +343,22 @@ struct KernelCfg {
     static constexpr int WTM = TM / WAVES_M, WTN = TN / WAVES_N;  // wave tile
     static constexpr int MI = WTM / 16, NI = WTN / 16;            // 16x16 MFMA blocks per wave
     static constexpr int KSTEPS = TK / 32;                        // MFMA k-steps (32 elements) per k-tile
-    static constexpr int A_BYTES = TM * TK * 2, B_BYTES = TN * TK * 2;
+    static constexpr bool HALO = LA_ == kHalo;
+    // kHalo: the stage buffers hold B only; A is a resident patch of PATCH_ROWS pixels (rows of 64
+    // channels = 128 bytes) behind them, whose last row stays zero for padded taps to read.
+    static constexpr int A_BYTES = HALO ? 0 : TM * TK * 2, B_BYTES = TN * TK * 2;
     static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
     static constexpr int PIPE_BYTES = STAGES * STAGE_BYTES;
+    static constexpr int HALO_MAX = 59;                           // pixels kept before and behind the tile's own
+    static constexpr int PATCH_ROWS = TM + 2 * HALO_MAX + 2;      // a whole number of 8-row wave copies
+    static constexpr int PATCH_BYTES = HALO ? PATCH_ROWS * 128 : 0;
+    static_assert(PATCH_ROWS % 8 == 0, "one copy instruction of a wave fills 8 patch rows");
+    static_assert(!HALO || (TK == 32 && STAGES >= 3 && MODE_ == 2 && LB_ == kKContig), "patch kernels: pipelined loop, k-tiles of half a tap");
     // epilogue staging: per wave 32 rows x (WTN + 4) fp32 (16 bytes of padding per row)
     static constexpr int EPI_LD = TN / 2 + 4;
     static constexpr int EPI_BYTES = 4 * 32 * EPI_LD * 4;
-    static constexpr int LDS_BYTES = PIPE_BYTES > EPI_BYTES ? PIPE_BYTES : EPI_BYTES;
-    static constexpr int A_ITERS = TM * CPR / kThreads;           // 16-byte chunks per thread per stage
+    static constexpr int LDS_BYTES = PIPE_BYTES + PATCH_BYTES > EPI_BYTES ? PIPE_BYTES + PATCH_BYTES : EPI_BYTES;
+    static constexpr int A_ITERS = HALO ? 0 : TM * CPR / kThreads;   // 16-byte chunks per thread per stage
     static constexpr int B_ITERS = TN * CPR / kThreads;
     static constexpr int ROWS_PER_ITER = kThreads / CPR;          // rows covered by one 256-thread copy
     static_assert(TM % 64 == 0 && TN % 64 == 0, "wave tile is a multiple of 32x32 (two 16-row MFMA blocks per staged epilogue block)");
@@ -447,7 +458,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
     // thread one loop-invariant 32-bit byte offset per slot; the k position advances through the
     // scalar offset of the load, so a load costs no vector ALU instruction in the steady state.
     rsrc_t a_rsrc = buffer_rsrc(nullptr, 0), b_rsrc = buffer_rsrc(nullptr, 0);
-    uint32_t a_off[LA == kMNContig ? 1 : A_ITERS], b_off[LB == kMNContig ? 1 : B_ITERS];
+    uint32_t a_off[LA == kMNContig || LA == kHalo ? 1 : A_ITERS], b_off[LB == kMNContig ? 1 : B_ITERS];
     int a_h0[LA == kIm2col ? A_ITERS : 1], a_w0[LA == kIm2col ? A_ITERS : 1];
     int a_ci = 0, a_r = 0, a_s = 0;                      // im2col: decomposition of k = l_kc + kt*TK
     u32x4_t a_stage[LA == kMNContig ? A_ITERS : 1], b_stage[LB == kMNContig ? B_ITERS : 1];
@@ -486,6 +497,64 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
             b_off[i] = (uint32_t)(((int64_t)(i * RPI + l_row) * p.ldb + l_kc) * 2);
     }
 
+    // Resident activation patch (kHalo).  Output pixel m of a 3x3 / stride 1 / pad 1 convolution reads
+    // input pixels m + dy*W + dx of the flattened [N*H*W] pixel sequence, except where the tap leaves
+    // the image.  Patch row r holds pixel m0 - (W + 1) + r (one contiguous global range, rows outside
+    // the tensor are zero-filled by the range check), its 16-byte chunks XOR-swizzled like a 128-byte
+    // stage row.  Per 16-row MFMA block and lane, four bits say whether the lane's pixel sits in the
+    // first / last column or row of its image; a tap that would leave the image reads the zero row.
+    constexpr int kPatchOff = Cfg::PIPE_BYTES, kZeroRow = Cfg::PIPE_BYTES + (Cfg::PATCH_ROWS - 1) * 128;
+    uint32_t h_flags = 0;
+    int h_r0 = 0;
+    if constexpr (LA == kHalo) {
+        a_rsrc = buffer_rsrc(Ab, (uint32_t)p.a_bytes);
+        const int halo = p.cW + 1;
+        const int f_row_ = lane & 15;
+        h_r0 = wm * Cfg::WTM + f_row_ + halo;
+#pragma unroll
+        for (int blk = 0; blk < MI; ++blk) {
+            int pix = m0 + wm * Cfg::WTM + blk * 16 + f_row_;
+            pix = pix < Mloc ? pix : Mloc - 1;
+            const int w = pix % p.cW, h = (pix / p.cW) % p.cH;
+            const uint32_t f = (w == 0 ? 1u : 0u) | (w == p.cW - 1 ? 2u : 0u) | (h == 0 ? 4u : 0u) | (h == p.cH - 1 ? 8u : 0u);
+            h_flags |= f << (4 * blk);
+        }
+        constexpr int CHUNKS = Cfg::PATCH_ROWS * 8, SLOTS = (CHUNKS + kThreads - 1) / kThreads;
+        static_assert(MI <= 8, "4 flag bits per row block");
+        // rows the tile does not need (the last one among them: TM + 2 halo < PATCH_ROWS) are copied
+        // from an out-of-range offset, i.e. zero-filled
+#pragma unroll
+        for (int i = 0; i < SLOTS; ++i) {
+            if (i * kThreads + wave * 64 < CHUNKS) {             // wave-uniform: the last slot may be partial
+                const int q = i * kThreads + tid;                // 16-byte slot of the patch
+                const int r = q >> 3;
+                const int chunk = (q & 7) ^ lds_swz<8>(r);
+                const int pix = m0 - halo + r;
+                const bool ok = pix >= 0 && pix < Mloc && r < TM + 2 * halo;
+                const uint32_t off = ok ? (uint32_t)(pix * 8 + chunk) * 16u : kOobOffset;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, UCL_LDS_PTR(smem + kPatchOff + (i * kThreads + wave * 64) * 16), 16, off, 0, 0, 0);
+            }
+        }
+    }
+    // Patch addressing of k-tile kt (half a tap: 32 of the 64 channels): byte address of this lane's
+    // fragment chunk for row block 0, and the flag bits that void the tap.
+    auto halo_desc = [&](int kt, int &base, uint32_t &mask) __attribute__((always_inline)) {
+        int tap = kt >> 1;
+        tap = tap < 8 ? tap : 8;                                 // k-tiles past the end multiply zeros of B
+        const int dy = tap / 3 - 1, dx = tap - (dy + 1) * 3 - 1;
+        const int r = h_r0 + dy * p.cW + dx;
+        const int chunk = ((kt & 1) << 2) | (lane >> 4);
+        base = kPatchOff + r * 128 + ((chunk ^ lds_swz<8>(r)) << 4);
+        mask = (dx < 0 ? 1u : dx > 0 ? 2u : 0u) | (dy < 0 ? 4u : dy > 0 ? 8u : 0u);
+    };
+    auto halo_frag = [&](int base, uint32_t mask, int blk) __attribute__((always_inline)) {
+        const bool dead = (h_flags & (mask << (4 * blk))) != 0;
+        const int addr = dead ? kZeroRow : base + blk * 2048;
+        return *(const u32x4_t *)(smem + addr);
+    };
+    int hb_c = 0, hb_n = 0;                                      // descriptors of the running and the next k-tile
+    uint32_t hm_c = 0, hm_n = 0;
+
     // Issue the copies of k-tile `kt` into stage buffer `buf`.  K-contiguous and im2col operands:
     // one 128-bit global -> LDS load per slot (lane L of a wave lands at dst + 16 L).  M/N-contiguous
     // operands: 128-bit loads into registers, written (transposed) by commit_regs.  CHECK_K adds the
@@ -499,7 +568,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
         char *sB = sA + Cfg::A_BYTES;
         const int k0 = kt * TK;
         const bool kok = !CHECK_K || (k0 + l_kc < K);
-        if constexpr (PART == 2) {
+        if constexpr (PART == 2 || LA == kHalo) {
         } else if constexpr (LA == kKContig) {
 #pragma unroll
             for (int i = 0; i < A_ITERS; ++i) {
@@ -788,7 +857,10 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
                 auto side = [&](auto s_) __attribute__((always_inline)) {
                     constexpr int sx = decltype(s_)::value;
                     if constexpr (sx == 0) {
-                        if constexpr (ia < MI) ar[ia % RA] = frag(sc, a_frag_base, ia, KK);
+                        if constexpr (LA == kHalo) {
+                            if constexpr (ia < MI) ar[ia % RA] = halo_frag(hb_c, hm_c, ia);
+                            else ar[ia % RA] = halo_frag(hb_n, hm_n, ia - MI);
+                        } else if constexpr (ia < MI) ar[ia % RA] = frag(sc, a_frag_base, ia, KK);
                         else ar[ia % RA] = frag(sn, a_frag_base, ia - MI, KN);
                     } else if constexpr (sx <= nb) {
                         bq[1 - PB][b0 + sx - 1] = frag(sn, b_frag_base, b0 + sx - 1, KN);
@@ -815,6 +887,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
             constexpr int P0 = decltype(p0_)::value;
             const int cur = cur_, nxt = nxt_, fill = fill_;
             const char *sc = smem + cur * Cfg::STAGE_BYTES;
+            if constexpr (LA == kHalo) halo_desc(kt + 1, hb_n, hm_n);
             static_for<KSTEPS - 1>([&](auto kk_) {
                 constexpr int kk = decltype(kk_)::value;
                 kstep(std::integral_constant<int, (P0 + kk) & 1>{}, kk_, std::integral_constant<int, kk + 1>{}, sc, sc,
@@ -823,12 +896,18 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
             pipeline_barrier<(STAGES - 3) * DMA_PER_TILE>();
             kstep(std::integral_constant<int, (P0 + KSTEPS - 1) & 1>{}, std::integral_constant<int, KSTEPS - 1>{}, I0{}, sc,
                   smem + nxt * Cfg::STAGE_BYTES, check_, std::integral_constant<int, DMA_PER_TILE>{}, kt + STAGES - 1, fill);
+            if constexpr (LA == kHalo) { hb_c = hb_n; hm_c = hm_n; }
         };
 
         // prologue: k-tiles 0 .. STAGES-2 on their way, k-tile 0 landed, first fragments in registers
         static_for<STAGES - 1>([&](auto s_) { issue_tile(std::true_type{}, decltype(s_)::value, decltype(s_)::value); });
         pipeline_barrier<(STAGES - 2) * DMA_PER_TILE>();
-        static_for<RA - 1>([&](auto i) { ar[i] = frag(smem, a_frag_base, i, 0); });
+        if constexpr (LA == kHalo) {
+            halo_desc(0, hb_c, hm_c);
+            static_for<RA - 1>([&](auto i) { ar[i] = halo_frag(hb_c, hm_c, i); });
+        } else {
+            static_for<RA - 1>([&](auto i) { ar[i] = frag(smem, a_frag_base, i, 0); });
+        }
         static_for<NI>([&](auto ni) { bq[0][ni] = frag(smem, b_frag_base, ni, 0); });
 
         const int KT_full = k_tail ? KT - 1 : KT;                  // complete k-tiles: loads skip the K-tail test

@@ -15,8 +15,11 @@ pytestmark = pytest.mark.gpu
 import paper_2603_29010_amd as ucl
 
 
-def T(tm, tn, tk, st, raster=0):
-    return Tuning(tm, tn, tk, st, raster)
+def T(tm, tn, tk, st, raster=0, iterator=0):
+    return Tuning(tm, tn, tk, st, raster, iterator)
+
+
+ANALYTIC, PATCH = 1, 2      # ucl_conv_iterator
 
 
 def built(mode, f16=0, la=None, lb=0):
@@ -106,7 +109,38 @@ def test_grouped_exact_ragged_offsets():
 def test_conv_exact_every_halo_position(geom):
     spec = synth.conv_spec(dt_out="f32", epilogue=(), integer=True, **geom)
     for tile in built(2):
-        parity.check_exact(spec, T(*tile), label=f"conv{tile}")
+        parity.check_exact(spec, T(*tile, iterator=ANALYTIC), label=f"conv{tile}")
+
+
+# 3x3 / stride 1 / pad 1 / 64 channels: geometries the resident-patch kernels accept.  Tiles of 256
+# pixels that start and end mid-row and cross image boundaries, one-pixel-wide and one-row-high
+# images, the widest row the patch holds, ragged M and N tails; the per-tap gather runs beside it.
+@pytest.mark.parametrize("geom", [
+    dict(Nb=3, H=13, W=11, Ko=72),
+    dict(Nb=2, H=20, W=58, Ko=128),
+    dict(Nb=5, H=1, W=1, Ko=8),
+    dict(Nb=2, H=9, W=1, Ko=24),
+    dict(Nb=2, H=1, W=37, Ko=136),
+    dict(Nb=7, H=6, W=6, Ko=16),
+    dict(Nb=1, H=56, W=56, Ko=128),
+])
+def test_conv_patch_iterator_exact(geom):
+    spec = synth.conv_spec(C=64, R=3, S=3, dt_out="f32", epilogue=(), integer=True, **geom)
+    for tile in built(2, la=3):
+        parity.check_exact(spec, T(*tile, iterator=PATCH), label=f"conv patch {tile}")
+    parity.check_exact(spec, T(256, 128, 32, 3, iterator=ANALYTIC), label="conv gather")
+    parity.check_exact(spec, None, label="conv table choice")
+
+
+def test_conv_patch_iterator_refuses_other_geometries():
+    for kw in (dict(C=32), dict(R=1, S=1, pad=(0, 0)), dict(stride=(2, 2)), dict(dil=(2, 2), pad=(2, 2)), dict(W=59), dict(pad=(0, 0))):
+        g = dict(Nb=1, H=8, W=8, C=64, Ko=16, R=3, S=3)
+        g.update(kw)
+        spec = synth.conv_spec(dt_out="f32", epilogue=(), integer=True, **g)
+        with pytest.raises(ucl.UclError) as e:
+            parity.gpu_result(spec, T(0, 0, 0, 0, iterator=PATCH))
+        assert e.value.status == "UCL_ERR_UNSUPPORTED" and "fixed_stride_dilation" in str(e.value)
+        parity.check_exact(spec, None, label=f"conv {kw}")
 
 
 # ---------------------------------------------------------------- floating-point parity
@@ -184,10 +218,14 @@ def test_grouped_parity_silu():
 def test_conv_parity_bias_residual_relu():
     spec = synth.conv_spec(3, 14, 14, 64, 128, 3, 3)
     for tile in built(2):
-        parity.check(spec, T(*tile), label=f"conv{tile}")
+        parity.check(spec, T(*tile, iterator=ANALYTIC), label=f"conv{tile}")
+    for tile in built(2, la=3):
+        parity.check(spec, T(*tile, iterator=PATCH), label=f"conv patch {tile}")
     spec16 = synth.conv_spec(3, 14, 14, 64, 128, 3, 3, dt_in="f16", dt_out="f32")
     for tile in built(2, f16=1):
-        parity.check(spec16, T(*tile), label=f"conv f16 {tile}")
+        parity.check(spec16, T(*tile, iterator=ANALYTIC), label=f"conv f16 {tile}")
+    for tile in built(2, f16=1, la=3):
+        parity.check(spec16, T(*tile, iterator=PATCH), label=f"conv f16 patch {tile}")
 
 
 # ---------------------------------------------------------------- the benchmark configurations
