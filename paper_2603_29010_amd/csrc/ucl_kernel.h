@@ -397,6 +397,9 @@ __device__ __forceinline__ void mfma16(f32x4_t &c, const u32x4_t &a, const u32x4
     else asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
 }
 
+// Forces the accumulator to hold its value in an accumulation register at this point of the program.
+__device__ __forceinline__ void pin_acc(f32x4_t &c) { asm volatile("" : "+a"(c)); }
+
 // First of the n items dealt to row block mi when they are spread over the first half of the
 // mblocks row blocks.
 constexpr int bshare(int mi, int mblocks, int n) {
@@ -501,10 +504,11 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
     // input pixels m + dy*W + dx of the flattened [N*H*W] pixel sequence, except where the tap leaves
     // the image.  Patch row r holds pixel m0 - (W + 1) + r (one contiguous global range, rows outside
     // the tensor are zero-filled by the range check), its 16-byte chunks XOR-swizzled like a 128-byte
-    // stage row.  Per 16-row MFMA block and lane, four bits say whether the lane's pixel sits in the
-    // first / last column or row of its image; a tap that would leave the image reads the zero row.
+    // stage row.  Per 16-row MFMA block and lane, one byte says for each of the eight outer taps
+    // whether it leaves the image at the lane's pixel (first / last column, first / last row, and the
+    // four corner combinations); such a tap reads the zero row.
     constexpr int kPatchOff = Cfg::PIPE_BYTES, kZeroRow = Cfg::PIPE_BYTES + (Cfg::PATCH_ROWS - 1) * 128;
-    uint32_t h_flags = 0;
+    uint32_t h_flags[2] = {0u, 0u};                              // row blocks 0-3, 4-7
     int h_r0 = 0;
     if constexpr (LA == kHalo) {
         a_rsrc = buffer_rsrc(Ab, (uint32_t)p.a_bytes);
@@ -516,11 +520,13 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
             int pix = m0 + wm * Cfg::WTM + blk * 16 + f_row_;
             pix = pix < Mloc ? pix : Mloc - 1;
             const int w = pix % p.cW, h = (pix / p.cW) % p.cH;
-            const uint32_t f = (w == 0 ? 1u : 0u) | (w == p.cW - 1 ? 2u : 0u) | (h == 0 ? 4u : 0u) | (h == p.cH - 1 ? 8u : 0u);
-            h_flags |= f << (4 * blk);
+            const bool w0 = w == 0, wl = w == p.cW - 1, h0 = h == 0, hl = h == p.cH - 1;
+            const uint32_t f = (w0 ? 1u : 0u) | (wl ? 2u : 0u) | (h0 ? 4u : 0u) | (hl ? 8u : 0u) | (w0 || h0 ? 16u : 0u) |
+                               (wl || h0 ? 32u : 0u) | (w0 || hl ? 64u : 0u) | (wl || hl ? 128u : 0u);
+            h_flags[blk >> 2] |= f << (8 * (blk & 3));
         }
         constexpr int CHUNKS = Cfg::PATCH_ROWS * 8, SLOTS = (CHUNKS + kThreads - 1) / kThreads;
-        static_assert(MI <= 8, "4 flag bits per row block");
+        static_assert(MI <= 8, "one flag byte per row block");
         // rows the tile does not need (the last one among them: TM + 2 halo < PATCH_ROWS) are copied
         // from an out-of-range offset, i.e. zero-filled
 #pragma unroll
@@ -536,24 +542,33 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
             }
         }
     }
-    // Patch addressing of k-tile kt (half a tap: 32 of the 64 channels): byte address of this lane's
-    // fragment chunk for row block 0, and the flag bits that void the tap.
-    auto halo_desc = [&](int kt, int &base, uint32_t &mask) __attribute__((always_inline)) {
-        int tap = kt >> 1;
-        tap = tap < 8 ? tap : 8;                                 // k-tiles past the end multiply zeros of B
-        const int dy = tap / 3 - 1, dx = tap - (dy + 1) * 3 - 1;
+    // Patch addressing of k-tile KT (half a tap: 32 of the 64 channels; dy, dx and the half are
+    // compile-time): byte address of this lane's fragment chunk for row block 0.
+    auto halo_base = [&](auto kt_) __attribute__((always_inline)) {
+        constexpr int KT_ = decltype(kt_)::value, tap = KT_ >> 1, dy = tap / 3 - 1, dx = tap % 3 - 1;
         const int r = h_r0 + dy * p.cW + dx;
-        const int chunk = ((kt & 1) << 2) | (lane >> 4);
-        base = kPatchOff + r * 128 + ((chunk ^ lds_swz<8>(r)) << 4);
-        mask = (dx < 0 ? 1u : dx > 0 ? 2u : 0u) | (dy < 0 ? 4u : dy > 0 ? 8u : 0u);
+        const int chunk = ((KT_ & 1) << 2) | (lane >> 4);
+        return kPatchOff + r * 128 + ((chunk ^ lds_swz<8>(r)) << 4);
     };
-    auto halo_frag = [&](int base, uint32_t mask, int blk) __attribute__((always_inline)) {
-        const bool dead = (h_flags & (mask << (4 * blk))) != 0;
-        const int addr = dead ? kZeroRow : base + blk * 2048;
-        return *(const u32x4_t *)(smem + addr);
+    // Fragment of row block BLK: one vector ALU instruction spreads the tap's flag bit over a register
+    // (-1: the tap leaves the image at this lane's pixel), one merges the zero row's address in under
+    // that mask, then the 128-bit LDS read.  Written as asm so that they stay where they are placed
+    // between the MFMAs.
+    auto halo_test = [&](auto kt_, auto blk_) __attribute__((always_inline)) -> int {
+        constexpr int KT_ = decltype(kt_)::value, BLK = decltype(blk_)::value, tap = KT_ >> 1, dy = tap / 3 - 1, dx = tap % 3 - 1;
+        constexpr int bit = dy == 0 ? (dx < 0 ? 0 : 1) : dx == 0 ? (dy < 0 ? 2 : 3) : 4 + (dx > 0 ? 1 : 0) + (dy > 0 ? 2 : 0);
+        int dead = 0;
+        if constexpr (dx != 0 || dy != 0)
+            asm volatile("v_bfe_i32 %0, %1, %2, 1" : "=v"(dead) : "v"(h_flags[BLK >> 2]), "n"(8 * (BLK & 3) + bit));
+        return dead;
     };
-    int hb_c = 0, hb_n = 0;                                      // descriptors of the running and the next k-tile
-    uint32_t hm_c = 0, hm_n = 0;
+    auto halo_read = [&](auto kt_, auto blk_, int base, int dead) __attribute__((always_inline)) {
+        constexpr int KT_ = decltype(kt_)::value, BLK = decltype(blk_)::value, tap = KT_ >> 1, dy = tap / 3 - 1, dx = tap % 3 - 1;
+        int addr = base;
+        if constexpr (dx != 0 || dy != 0)                        // the read adds BLK * 2048 as its immediate offset
+            asm volatile("v_bfi_b32 %0, %1, %2, %3" : "=v"(addr) : "v"(dead), "s"(kZeroRow - BLK * 2048), "v"(base));
+        return *(const u32x4_t *)(smem + addr + BLK * 2048);
+    };
 
     // Issue the copies of k-tile `kt` into stage buffer `buf`.  K-contiguous and im2col operands:
     // one 128-bit global -> LDS load per slot (lane L of a wave lands at dst + 16 L).  M/N-contiguous
@@ -818,6 +833,66 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
             ktile2(std::false_type{}, I1{});
         }
         while (kt < KT) ktile2(std::true_type{}, kt & 1);
+    } else if constexpr (LA == kHalo) {
+        // ---- resident patch: 18 k-tiles (9 taps x 2 channel halves), fully unrolled ------------------
+        // The same ring of A fragments and two B sets as the pipelined loop below, with every buffer
+        // index, tap offset and border test a compile-time constant; only B is copied (k-tile
+        // kt + STAGES - 1 into the buffer released by the barrier of k-tile kt).
+        constexpr int KT_ALL = 18, RA = 4;
+        static_assert(MI % RA == 0 && KSTEPS == 1, "ring slots line up across k-tiles");
+        u32x4_t ar[RA], bq[2][NI];
+        static_for<STAGES - 1>([&](auto s_) { issue_tile(std::false_type{}, decltype(s_)::value, decltype(s_)::value); });
+        // The code below is straight-line, so the compiler would otherwise sink the zeroing of each
+        // accumulator to just in front of its first MFMA -- closer than the matrix pipeline allows
+        // after a register write, which it cannot know of an asm statement.  Pin the zeroing here.
+        static_for<MI>([&](auto mi) {
+            static_for<NI>([&](auto ni) { pin_acc(acc[mi][ni]); });
+        });
+        pipeline_barrier<(STAGES - 2) * DMA_PER_TILE>();
+        int hb_c = halo_base(I0{}), hb_n = 0;
+        static_for<RA - 1>([&](auto i) { ar[i] = halo_read(I0{}, i, hb_c, halo_test(I0{}, i)); });
+        static_for<NI>([&](auto ni) { bq[0][ni] = frag(smem, b_frag_base, ni, 0); });
+        static_for<KT_ALL>([&](auto kt_) {
+            constexpr int kt = decltype(kt_)::value, PB = kt & 1;
+            constexpr bool more = kt + 1 < KT_ALL, load = kt + STAGES - 1 < KT_ALL;
+            constexpr int last_issued = kt + STAGES - 2 < KT_ALL - 1 ? kt + STAGES - 2 : KT_ALL - 1;
+            constexpr int in_flight = last_issued - (kt + 1) > 0 ? last_issued - (kt + 1) : 0;   // k-tiles behind kt + 1
+            using KN = std::integral_constant<int, more ? kt + 1 : kt>;
+            const char *sn = smem + ((kt + 1) % STAGES) * Cfg::STAGE_BYTES;
+            if constexpr (more) hb_n = halo_base(KN{});
+            pipeline_barrier<in_flight * DMA_PER_TILE>();
+            static_for<MI>([&](auto mi_) {
+                constexpr int mi = decltype(mi_)::value;
+                constexpr int ia = mi + RA - 1;
+                constexpr bool a_cur = ia < MI, a_any = a_cur || more;
+                using KA = std::integral_constant<int, a_cur ? kt : KN::value>;
+                using BA = std::integral_constant<int, a_cur ? ia : ia - MI>;
+                constexpr int b0 = more ? bshare(mi, MI, NI) : 0, nb = more ? bshare(mi + 1, MI, NI) - b0 : 0;
+                constexpr int d0 = load ? mi * DMA_PER_TILE / MI : 0, nd = load ? (mi + 1) * DMA_PER_TILE / MI - d0 : 0;
+                constexpr int NS = 2 + nb + nd;
+                int dead = 0;
+                auto side = [&](auto s_) __attribute__((always_inline)) {
+                    constexpr int sx = decltype(s_)::value;
+                    if constexpr (sx == 0) {
+                        if constexpr (a_any) dead = halo_test(KA{}, BA{});
+                    } else if constexpr (sx == 1) {
+                        if constexpr (a_any) ar[ia % RA] = halo_read(KA{}, BA{}, a_cur ? hb_c : hb_n, dead);
+                    } else if constexpr (sx < 2 + nb) {
+                        bq[1 - PB][b0 + sx - 2] = frag(sn, b_frag_base, b0 + sx - 2, 0);
+                    } else {
+                        issue_one(std::false_type{}, std::integral_constant<int, d0 + sx - 2 - nb>{}, kt + STAGES - 1,
+                                  (kt + STAGES - 1) % STAGES);
+                    }
+                };
+                static_for<NI>([&](auto ni_) {
+                    constexpr int ni = decltype(ni_)::value;
+                    mfma16<Cfg::F16>(acc[mi][ni], bq[PB][ni], ar[mi % RA]);
+                    constexpr int s0 = ni * NS / NI, s1 = (ni + 1) * NS / NI;
+                    static_for<s1 - s0>([&](auto j) { side(std::integral_constant<int, s0 + decltype(j)::value>{}); });
+                });
+            });
+            hb_c = hb_n;
+        });
     } else {
         // ---- software-pipelined loop ---------------------------------------------------------------
         // STAGES-1 k-tiles are in flight.  Registers hold the B fragments of the running k-step and
@@ -857,10 +932,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
                 auto side = [&](auto s_) __attribute__((always_inline)) {
                     constexpr int sx = decltype(s_)::value;
                     if constexpr (sx == 0) {
-                        if constexpr (LA == kHalo) {
-                            if constexpr (ia < MI) ar[ia % RA] = halo_frag(hb_c, hm_c, ia);
-                            else ar[ia % RA] = halo_frag(hb_n, hm_n, ia - MI);
-                        } else if constexpr (ia < MI) ar[ia % RA] = frag(sc, a_frag_base, ia, KK);
+                        if constexpr (ia < MI) ar[ia % RA] = frag(sc, a_frag_base, ia, KK);
                         else ar[ia % RA] = frag(sn, a_frag_base, ia - MI, KN);
                     } else if constexpr (sx <= nb) {
                         bq[1 - PB][b0 + sx - 1] = frag(sn, b_frag_base, b0 + sx - 1, KN);
@@ -887,7 +959,6 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
             constexpr int P0 = decltype(p0_)::value;
             const int cur = cur_, nxt = nxt_, fill = fill_;
             const char *sc = smem + cur * Cfg::STAGE_BYTES;
-            if constexpr (LA == kHalo) halo_desc(kt + 1, hb_n, hm_n);
             static_for<KSTEPS - 1>([&](auto kk_) {
                 constexpr int kk = decltype(kk_)::value;
                 kstep(std::integral_constant<int, (P0 + kk) & 1>{}, kk_, std::integral_constant<int, kk + 1>{}, sc, sc,
@@ -896,18 +967,12 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
             pipeline_barrier<(STAGES - 3) * DMA_PER_TILE>();
             kstep(std::integral_constant<int, (P0 + KSTEPS - 1) & 1>{}, std::integral_constant<int, KSTEPS - 1>{}, I0{}, sc,
                   smem + nxt * Cfg::STAGE_BYTES, check_, std::integral_constant<int, DMA_PER_TILE>{}, kt + STAGES - 1, fill);
-            if constexpr (LA == kHalo) { hb_c = hb_n; hm_c = hm_n; }
         };
 
         // prologue: k-tiles 0 .. STAGES-2 on their way, k-tile 0 landed, first fragments in registers
         static_for<STAGES - 1>([&](auto s_) { issue_tile(std::true_type{}, decltype(s_)::value, decltype(s_)::value); });
         pipeline_barrier<(STAGES - 2) * DMA_PER_TILE>();
-        if constexpr (LA == kHalo) {
-            halo_desc(0, hb_c, hm_c);
-            static_for<RA - 1>([&](auto i) { ar[i] = halo_frag(hb_c, hm_c, i); });
-        } else {
-            static_for<RA - 1>([&](auto i) { ar[i] = frag(smem, a_frag_base, i, 0); });
-        }
+        static_for<RA - 1>([&](auto i) { ar[i] = frag(smem, a_frag_base, i, 0); });
         static_for<NI>([&](auto ni) { bq[0][ni] = frag(smem, b_frag_base, ni, 0); });
 
         const int KT_full = k_tail ? KT - 1 : KT;                  // complete k-tiles: loads skip the K-tail test
