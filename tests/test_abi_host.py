@@ -99,6 +99,14 @@ def test_selection_table():
     # memory-bound by the SOL model (short K, fp32 output): a tile of which two workgroups share a CU
     t = ucl.ucl_select_tuning("batched_gemm", "f16", "f32", batch=64, M=512, N=512, K=128)
     assert (t["tile_m"], t["tile_n"], t["tile_k"], t["stages"]) == (256, 128, 32, 3)
+    # conv: 3x3 / stride 1 / pad 1 / 64 channels takes the resident-patch iterator (2), anything else the gather (1)
+    t = ucl.ucl_select_tuning("conv2d_fprop", "bf16", "bf16", conv=(32, 56, 56, 64, 128, 3, 3, 1, 1, 1, 1, 1, 1))
+    assert (t["tile_m"], t["tile_n"], t["tile_k"], t["stages"], t["iterator"]) == (256, 128, 32, 4, 2)
+    t = ucl.ucl_select_tuning("conv2d_fprop", "bf16", "bf16", conv=(32, 56, 56, 64, 128, 3, 3, 1, 1, 2, 2, 1, 1))
+    assert t["iterator"] == 1
+    t = ucl.ucl_select_tuning("conv2d_fprop", "bf16", "bf16", conv=(32, 56, 56, 32, 128, 3, 3, 1, 1, 1, 1, 1, 1))
+    assert t["iterator"] == 1
+    assert ucl.ucl_select_tuning("gemm", "bf16", "bf16", M=512, N=512, K=512)["iterator"] == 0
     variants = [ucl.ucl_variant(i) for i in range(ucl.ucl_num_variants())]
     assert all((v["tile_m"] + v["tile_n"]) * v["tile_k"] * 2 * v["stages"] <= 160 * 1024 for v in variants)
 
