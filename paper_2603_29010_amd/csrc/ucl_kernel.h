@@ -1156,26 +1156,54 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
     // per element: gather (staged fp32 * alpha + bias + beta * residual, by residual type), activation
     // (by opcode), conversion + store (by output type).  The values of the whole group stay in
     // registers between the phases.
-    auto fast_block = [&](auto has_res_, int mi) __attribute__((always_inline)) {
-        constexpr bool HAS_RES = decltype(has_res_)::value;
-        const float beta = f.beta, ap0 = f.act_p0, ap1 = f.act_p1;
+    // The residual segments of a whole block (one 128-bit load per pass, two for fp32) are requested
+    // one block ahead of their use: a load from HBM takes longer than a block's arithmetic, and a wave
+    // that waited for it in every block would spend the epilogue waiting.
+    static_assert(MI / 2 == 1 || (MI / 2) % 2 == 0, "blocks are taken in pairs");
+    // (the registers suffice for the first 16 bytes per pass: the second half of an fp32 residual is
+    // loaded where it is used; kernels with three or more workgroups per CU load everything in place)
+    constexpr bool kResHi = false, kResAhead = Cfg::MIN_WAVES <= 2;
+    struct ResRegs {
+        u32x4_t lo[kResAhead ? PASSES : 1], hi[kResHi ? PASSES : 1];
+    };
+    auto res_issue = [&](int mi, ResRegs &r) __attribute__((always_inline)) {
+        if constexpr (!kResAhead) return;
         const uint32_t r0 = r_lane + mi * 32 * r_row_bytes;
+        static_for<kResAhead ? PASSES : 0>([&](auto u) { r.lo[u] = __builtin_amdgcn_raw_buffer_load_b128(r_rsrc, r0 + u * RPP * r_row_bytes, 0, 0); });
+        if constexpr (kResHi) {
+            if (r_dt == UCL_F32) {
+                static_for<PASSES>([&](auto u) { r.hi[u] = __builtin_amdgcn_raw_buffer_load_b128(r_rsrc, r0 + u * RPP * r_row_bytes + 16, 0, 0); });
+            }
+        }
+    };
+    auto fast_block = [&](auto has_res_, int mi, const ResRegs &rr) __attribute__((always_inline)) {
+        constexpr bool HAS_RES = decltype(has_res_)::value;
+        constexpr int FGX = HAS_RES && FG > 4 ? 4 : FG;       // with a residual in registers: smaller pass groups
+        const float beta = f.beta, ap0 = f.act_p0, ap1 = f.act_p1;
         const uint32_t d0 = d_lane + mi * 32 * d_row_bytes;
-        static_for<PASSES / FG>([&](auto g_) {
-            constexpr int P0 = decltype(g_)::value * FG;
-            float v[FG][8];
-            u32x4_t r_lo[FG], r_hi[FG];
+        static_for<PASSES / FGX>([&](auto g_) {
+            constexpr int P0 = decltype(g_)::value * FGX;
+            float v[FGX][8];
+            u32x4_t r_lo[FGX], r_hi[FGX];
             if constexpr (HAS_RES) {
-                static_for<FG>([&](auto u) {
-                    r_lo[u] = __builtin_amdgcn_raw_buffer_load_b128(r_rsrc, r0 + (P0 + u) * RPP * r_row_bytes, 0, 0);
-                });
-                if (r_dt == UCL_F32) {
-                    static_for<FG>([&](auto u) {
+                if constexpr (kResAhead) {
+                    static_for<FGX>([&](auto u) { r_lo[u] = rr.lo[P0 + u]; });
+                } else {
+                    const uint32_t r0 = r_lane + mi * 32 * r_row_bytes;
+                    static_for<FGX>([&](auto u) {
+                        r_lo[u] = __builtin_amdgcn_raw_buffer_load_b128(r_rsrc, r0 + (P0 + u) * RPP * r_row_bytes, 0, 0);
+                    });
+                }
+                if constexpr (kResHi) {
+                    static_for<FGX>([&](auto u) { r_hi[u] = rr.hi[P0 + u]; });
+                } else if (r_dt == UCL_F32) {
+                    const uint32_t r0 = r_lane + mi * 32 * r_row_bytes;
+                    static_for<FGX>([&](auto u) {
                         r_hi[u] = __builtin_amdgcn_raw_buffer_load_b128(r_rsrc, r0 + (P0 + u) * RPP * r_row_bytes + 16, 0, 0);
                     });
                 }
             }
-            static_for<FG>([&](auto u) {
+            static_for<FGX>([&](auto u) {
                 const f32x4_t lo = *(const f32x4_t *)(stg + ((P0 + u) * RPP + e_row) * EPI_LD + e_col);
                 const f32x4_t hi = *(const f32x4_t *)(stg + ((P0 + u) * RPP + e_row) * EPI_LD + e_col + 4);
 #pragma unroll
@@ -1186,7 +1214,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
             });
             if constexpr (HAS_RES) {
                 if (r_dt == UCL_F32) {
-                    static_for<FG>([&](auto u) {
+                    static_for<FGX>([&](auto u) {
                         const f32x4_t fl = __builtin_bit_cast(f32x4_t, r_lo[u]), fh = __builtin_bit_cast(f32x4_t, r_hi[u]);
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
@@ -1195,7 +1223,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
                         }
                     });
                 } else if (r_dt == UCL_BF16) {
-                    static_for<FG>([&](auto u) {
+                    static_for<FGX>([&](auto u) {
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
                             const uint32_t w = r_lo[u][e];
@@ -1204,7 +1232,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
                         }
                     });
                 } else {
-                    static_for<FG>([&](auto u) {
+                    static_for<FGX>([&](auto u) {
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
                             const uint32_t w = r_lo[u][e];
@@ -1218,7 +1246,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
             switch (f.act) {
 #define UCL_ACT_CASE(OP)                                                                   \
     case OP:                                                                               \
-        static_for<FG>([&](auto u) {                                                       \
+        static_for<FGX>([&](auto u) {                                                       \
             _Pragma("unroll") for (int e = 0; e < 8; ++e) v[u][e] = act_f32<OP>(v[u][e], ap0, ap1); \
         });                                                                                \
         break;
@@ -1237,13 +1265,13 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
             default: break;
             }
             if (dtD == UCL_F32) {
-                static_for<FG>([&](auto u) {
+                static_for<FGX>([&](auto u) {
                     const uint32_t off = d0 + (P0 + u) * RPP * d_row_bytes;
                     __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, f32x4_t{v[u][0], v[u][1], v[u][2], v[u][3]}), d_rsrc, off, 0, 0);
                     __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, f32x4_t{v[u][4], v[u][5], v[u][6], v[u][7]}), d_rsrc, off + 16, 0, 0);
                 });
             } else if (dtD == UCL_BF16) {
-                static_for<FG>([&](auto u) {
+                static_for<FGX>([&](auto u) {
                     u32x4_t o;
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
@@ -1251,7 +1279,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
                     __builtin_amdgcn_raw_buffer_store_b128(o, d_rsrc, d0 + (P0 + u) * RPP * d_row_bytes, 0, 0);
                 });
             } else {
-                static_for<FG>([&](auto u) {
+                static_for<FGX>([&](auto u) {
                     u32x4_t o;
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
@@ -1282,13 +1310,38 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
             fast_setup();
             // All block loops of the epilogue are REAL loops: their bodies are re-executed from the
             // instruction cache instead of existing once per block.
+            // (two copies: without a residual the block issues no loads at all, so nothing ever makes
+            // it wait for the stores in flight)
+            if (f.has_res) {
+                ResRegs ra, rb;
+                res_issue(0, ra);
+                if constexpr (!kResAhead) {
 #pragma clang loop unroll(disable)
-            for (int mi = 0; mi < MI / 2; ++mi) {
-                UCL_STAGE_BLOCK(mi);
-                // (two copies: without a residual the block issues no loads at all, so nothing ever
-                // makes it wait for the stores in flight)
-                if (f.has_res) fast_block(std::true_type{}, mi);
-                else fast_block(std::false_type{}, mi);
+                    for (int mi = 0; mi < MI / 2; ++mi) {
+                        UCL_STAGE_BLOCK(mi);
+                        fast_block(std::true_type{}, mi, ra);
+                    }
+                } else if constexpr (MI / 2 >= 2) {
+#pragma clang loop unroll(disable)
+                    for (int mi = 0; mi < MI / 2; mi += 2) {          // two blocks per trip: the register sets alternate
+                        res_issue(mi + 1, rb);
+                        UCL_STAGE_BLOCK(mi);
+                        fast_block(std::true_type{}, mi, ra);
+                        if (mi + 2 < MI / 2) res_issue(mi + 2, ra);
+                        UCL_STAGE_BLOCK(mi + 1);
+                        fast_block(std::true_type{}, mi + 1, rb);
+                    }
+                } else {
+                    UCL_STAGE_BLOCK(0);
+                    fast_block(std::true_type{}, 0, ra);
+                }
+            } else {
+                ResRegs none;
+#pragma clang loop unroll(disable)
+                for (int mi = 0; mi < MI / 2; ++mi) {
+                    UCL_STAGE_BLOCK(mi);
+                    fast_block(std::false_type{}, mi, none);
+                }
             }
         } else {
 #pragma clang loop unroll(disable)
