@@ -82,6 +82,8 @@ def lib():
         _lib.orc_conv_out_dim.argtypes = [C.c_int64] * 5
         _lib.orc_gemm_flops.restype = C.c_double
         _lib.orc_gemm_flops.argtypes = [C.c_double] * 4
+        _lib.orc_transpose.restype = None
+        _lib.orc_transpose.argtypes = [C.c_int64, C.c_int64, C.c_int64, C.c_void_p, C.c_int, C.c_void_p]
         _lib.orc_sol_bound.restype = None
         _lib.orc_sol_bound.argtypes = [C.c_double] * 6 + [C.c_void_p]
     return _lib
@@ -221,6 +223,17 @@ def conv2d_fprop(x, dtX, w, dtW, Nb, H, W, Cin, Ko, R, S, pad=(0, 0), stride=(1,
                            C.byref(c) if c is not None else None, rp, C.c_int64(nr),
                            _ptr(D), _ptr(Sabs) if want_abs else None)
     return (D, Sabs) if want_abs else D
+
+
+def transpose(src, dtype, batch, rows, cols):
+    """dst[b][c][r] = src[b][r][c] as unrounded float64 (grammar `transpose_op`); round_to() gives
+    what the target type stores."""
+    _check(src, dtype)
+    assert src.size == batch * rows * cols
+    out = np.empty((batch, cols, rows), dtype=np.float64)
+    if out.size:
+        lib().orc_transpose(C.c_int64(batch), C.c_int64(rows), C.c_int64(cols), _ptr(src), DT[dtype], _ptr(out))
+    return out
 
 
 def epilogue(v, m, n, chain):

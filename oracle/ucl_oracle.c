@@ -24,7 +24,9 @@
  * conv, brute-force pure-Python loops on tiny shapes, numpy fp64 matmul,
  * activation values from tests/golden/activations.txt, RNE rounding against
  * exhaustive fp16 round trips and hand-derived ties, and the SOL arithmetic
- * against the worked example the paper prints (Appendix, "Example SOL Report").
+ * against the worked example the paper prints (Appendix, "Example SOL Report");
+ * transpose: numpy's own transposition of the decoded array, a pure-Python index
+ * loop, the involution T(T(x)) = x and rows = 1 / cols = 1 being plain copies.
  */
 #include <math.h>
 #include <stddef.h>
@@ -348,6 +350,16 @@ typedef struct {
 
 /* The four steps of the analysis, given work (flops, bytes) and published peaks
  * (FLOP/s and B/s at max clocks) scaled linearly by clock ratios. */
+/* Transform stage of a `pipeline(...)` program (grammar `transpose_op`): per batch a rows x cols
+ * matrix written transposed, dst[b][c][r] = src[b][r][c], as unrounded doubles (the caller rounds
+ * to the target type with orc_round).  Three plain loops. */
+void orc_transpose(int64_t batch, int64_t rows, int64_t cols, const void *src, int dtype, double *dst) {
+    for (int64_t b = 0; b < batch; ++b)
+        for (int64_t r = 0; r < rows; ++r)
+            for (int64_t c = 0; c < cols; ++c)
+                dst[(b * cols + c) * rows + r] = orc_load(src, dtype, (b * rows + r) * cols + c);
+}
+
 void orc_sol_bound(double flops, double bytes,
                    double peak_flops_at_max, double compute_clock_ratio,
                    double peak_bw_at_max, double mem_clock_ratio, orc_sol *out) {

@@ -384,6 +384,53 @@ def _gold(path):
     return d
 
 
+# ---- transform stage: transpose(tensor, NCL, NLC [, dtype_in, dtype_out]) ------------------------
+
+@pytest.mark.parametrize("dt", ["bf16", "f16", "f32"])
+def test_transpose_matches_numpy_and_index_loop(dt):
+    batch, rows, cols = 3, 5, 7
+    x = bits(synth.normal(11, 1, batch * rows * cols), dt).reshape(batch, rows, cols)
+    got = oracle.transpose(x, dt, batch, rows, cols)
+    assert got.shape == (batch, cols, rows)
+    # numpy's own transposition of the decoded values
+    assert np.array_equal(got, np.swapaxes(val(x, dt), 1, 2))
+    # the definition, index by index
+    v = val(x, dt)
+    for b, r, c in itertools.product(range(batch), range(rows), range(cols)):
+        assert got[b, c, r] == v[b, r, c]
+
+
+def test_transpose_twice_is_identity_and_vectors_are_copies():
+    batch, rows, cols = 2, 6, 4
+    x = synth.normal(12, 1, batch * rows * cols).astype(np.float32).reshape(batch, rows, cols)
+    once = oracle.transpose(x, "f32", batch, rows, cols)
+    twice = oracle.transpose(once.astype(np.float32), "f32", batch, cols, rows)
+    assert np.array_equal(twice, x.astype(np.float64))
+    # a single row or a single column: the element order in memory does not change
+    row = synth.normal(13, 1, 9).astype(np.float32)
+    assert np.array_equal(oracle.transpose(row.reshape(1, 1, 9), "f32", 1, 1, 9).reshape(-1), row)
+    assert np.array_equal(oracle.transpose(row.reshape(1, 9, 1), "f32", 1, 9, 1).reshape(-1), row)
+    # NCHW -> NHWC of a tensor whose value encodes its index (n, c, h, w)
+    N, Cc, H, W = 2, 3, 2, 2
+    idx = np.arange(N * Cc * H * W, dtype=np.float32).reshape(N, Cc, H * W)
+    nhwc = oracle.transpose(idx, "f32", N, Cc, H * W).reshape(N, H, W, Cc)
+    for n, c, h, w in itertools.product(range(N), range(Cc), range(H), range(W)):
+        assert nhwc[n, h, w, c] == ((n * Cc + c) * H + h) * W + w
+    assert oracle.transpose(np.empty((0, 4, 4), np.float32), "f32", 0, 4, 4).size == 0
+
+
+def test_transpose_with_conversion_rounds_once_to_nearest_even():
+    # fp32 -> bf16 / fp16: the unrounded transposition followed by round_to equals the library casts
+    x = (synth.normal(14, 1, 4 * 8) * 3.0).astype(np.float32).reshape(1, 4, 8)
+    t = oracle.transpose(x, "f32", 1, 4, 8)
+    want16 = torch.from_numpy(x).transpose(1, 2).contiguous()
+    assert np.array_equal(oracle.round_to(t, "f16"), want16.to(torch.float16).to(torch.float64).numpy())
+    assert np.array_equal(oracle.round_to(t, "bf16"), want16.to(torch.bfloat16).to(torch.float64).numpy())
+    # a tie: 1 + 2^-8 is halfway between two bf16 values and goes to the even one (1.0)
+    tie = np.array([[[1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8]]], dtype=np.float32)
+    assert list(oracle.round_to(oracle.transpose(tie, "f32", 1, 1, 2), "bf16").reshape(-1)) == [1.0, 1.0 + 2.0 ** -6]
+
+
 def test_sol_reproduces_paper_worked_example():
     g = _gold(os.path.join(GOLD, "sol_report_example.txt"))
     n = int(g["n"])
