@@ -185,6 +185,20 @@ ucl_status ucl_conv2d_fprop(int64_t N, int64_t H, int64_t W, int64_t C, int64_t 
 typedef enum ucl_op_kind { UCL_OP_GEMM = 0, UCL_OP_BATCHED_GEMM = 1, UCL_OP_GROUPED_GEMM = 2,
                            UCL_OP_CONV2D_FPROP = 3 } ucl_op_kind;
 
+/* Transform stage of a `pipeline(...)` program (grammar `transpose_op`:
+ * transpose(tensor, NCL, NLC [, dtype_in, dtype_out]); NCHW <-> NHWC is the same
+ * with H*W flattened into L): src is `batch` packed row-major rows x cols matrices,
+ * dst `batch` packed cols x rows matrices, and
+ *   dst[b][c][r] = convert(src[b][r][c]),
+ * the conversion between fp32 / fp16 / bf16 exact where the target holds the value
+ * and round-to-nearest-even otherwise.  NCL -> NLC: rows = C, cols = L; NHWC -> NCHW:
+ * rows = H*W, cols = C.  src and dst are DEVICE pointers owned by the caller and must
+ * not overlap; any extents are accepted (zero extents do nothing), 16-byte aligned
+ * pointers with cols*size(dt_src) and rows*size(dt_dst) multiples of 16 take the
+ * 128-bit path.  Errors as for the other entry points, nothing is launched then. */
+ucl_status ucl_transpose(int64_t batch, int64_t rows, int64_t cols, const void *src, int32_t dt_src,
+                         void *dst, int32_t dt_dst, void *stream);
+
 /* Problem characterisation input.  GEMM family: batch (1 for gemm), M, N, K;
  * grouped: groups and M_g (HOST), N, K.  Conv: N,H,W,C,Kout,R,S and pads,
  * strides, dilations.  dt_in / dt_out are ucl_dtype.  The epilogue matters

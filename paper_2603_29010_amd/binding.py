@@ -96,6 +96,8 @@ def _load():
         lib.ucl_conv2d_fprop.restype = C.c_int
         lib.ucl_conv2d_fprop.argtypes = [i64] * 13 + [vp, i32, vp, i32, vp, i32, C.POINTER(_Epilogue),
                                                       C.POINTER(_Tuning), vp]
+        lib.ucl_transpose.restype = C.c_int
+        lib.ucl_transpose.argtypes = [i64, i64, i64, vp, i32, vp, i32, vp]
         lib.ucl_sol_bound.restype = C.c_int
         lib.ucl_sol_bound.argtypes = [C.POINTER(_Problem), C.POINTER(_Hw), C.POINTER(_SolReport)]
         lib.ucl_select_tuning.restype = C.c_int
@@ -194,6 +196,10 @@ def ucl_conv2d_fprop(N, H, W, Cin, Kout, R, S, pad_h, pad_w, stride_h, stride_w,
                      y, dtY, epi=None, tune=None, stream=0):
     _check(_load().ucl_conv2d_fprop(N, H, W, Cin, Kout, R, S, pad_h, pad_w, stride_h, stride_w, dil_h, dil_w,
                                     x, _dt(dtX), w, _dt(dtW), y, _dt(dtY), _opt(epi), _opt(tune), stream or None))
+
+
+def ucl_transpose(batch, rows, cols, src, dt_src, dst, dt_dst, stream=0):
+    _check(_load().ucl_transpose(batch, rows, cols, src, _dt(dt_src), dst, _dt(dt_dst), stream or None))
 
 
 def _problem(op, dt_in, dt_out, batch=1, M=0, N=0, K=0, M_g=None, conv=None, epi=None):

@@ -9,6 +9,11 @@
 #include "ucl_variants.h"
 
 namespace ucl {
+// the transform stage lives in its own unit
+ucl_status transpose_run(int64_t batch, int64_t rows, int64_t cols, const void *src, int32_t dt_src, void *dst, int32_t dt_dst,
+                         void *stream);
+const char *transpose_last_error();
+
 namespace {
 
 thread_local char g_err[512] = "";
@@ -515,6 +520,14 @@ ucl_status ucl_conv2d_fprop(int64_t N, int64_t H, int64_t W, int64_t C, int64_t 
     kp.dil_h = (int32_t)dil_h; kp.dil_w = (int32_t)dil_w;
     kp.d_vec = aligned16(y) && (Kout % (16 / elem_size(dtY)) == 0);
     return run(L, kp, nullptr, tune, stream);
+}
+
+ucl_status ucl_transpose(int64_t batch, int64_t rows, int64_t cols, const void *src, int32_t dt_src, void *dst,
+                         int32_t dt_dst, void *stream) {
+    g_err[0] = 0;
+    const ucl_status st = transpose_run(batch, rows, cols, src, dt_src, dst, dt_dst, stream);
+    if (st != UCL_OK) return fail(st, "%s", transpose_last_error());
+    return UCL_OK;
 }
 
 ucl_status ucl_sol_bound(const ucl_problem *p, const ucl_hw *hw, ucl_sol_report *out) {

@@ -1,0 +1,96 @@
+"""GPU parity of the pipeline transform stage (transpose with type conversion) against the oracle: bit for bit."""
+import itertools
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2603_29010_amd as ucl
+from paper_2603_29010_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+DTS = ["f32", "f16", "bf16"]
+
+
+def _dev(bits_arr):
+    import torch
+    a = bits_arr.view(np.int16) if bits_arr.dtype == np.uint16 else bits_arr
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def _run(batch, rows, cols, dt_src, dt_dst, seed=1, offset_src=0, offset_dst=0):
+    """Returns (gpu values as float64, expected values), both [batch, cols, rows]."""
+    import torch
+    n = batch * rows * cols
+    src_bits = synth.to_bits(synth.normal(900 + seed, 1, n + offset_src) * 3.0, dt_src)
+    x = src_bits[offset_src:].reshape(batch, rows, cols)
+    d_src = _dev(src_bits)
+    esz = synth.itemsize(dt_dst)
+    d_dst = torch.full((n + offset_dst + 16,), -1, dtype=torch.int16 if esz == 2 else torch.int32, device="cuda")
+    ucl.ucl_transpose(batch, rows, cols, d_src.data_ptr() + offset_src * synth.itemsize(dt_src), dt_src,
+                      d_dst.data_ptr() + offset_dst * esz, dt_dst)
+    torch.cuda.synchronize()
+    out = d_dst.cpu().numpy()
+    # nothing outside the destination may have been written
+    assert (out[:offset_dst] == -1).all() and (out[offset_dst + n:] == -1).all()
+    body = out[offset_dst:offset_dst + n]
+    got_bits = body.view(np.uint16) if esz == 2 else body.view(np.float32)
+    got = synth.bits_to_f64(got_bits, dt_dst).reshape(batch, cols, rows)
+    want = oracle.round_to(oracle.transpose(np.ascontiguousarray(x), dt_src, batch, rows, cols), dt_dst)
+    return got, want
+
+
+@pytest.mark.parametrize("dt_src,dt_dst", list(itertools.product(DTS, DTS)))
+def test_transpose_every_type_pair(dt_src, dt_dst):
+    # 128-bit loads (cols % 8 == 0), element-wise stores (rows % 4 != 0), several tiles and ragged tails
+    got, want = _run(3, 70, 200, dt_src, dt_dst)
+    assert np.array_equal(got, want)
+    # 128-bit both ways
+    got, want = _run(2, 128, 136, dt_src, dt_dst, seed=2)
+    assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("shape", [(1, 64, 64), (2, 1, 1), (1, 1, 257), (1, 257, 1), (1, 63, 65), (5, 7, 3), (1, 8, 1000), (2, 1000, 8)])
+def test_transpose_shapes(shape):
+    for dt_src, dt_dst in (("f32", "bf16"), ("bf16", "f32"), ("f16", "f16")):
+        got, want = _run(*shape, dt_src, dt_dst, seed=3)
+        assert np.array_equal(got, want), (shape, dt_src, dt_dst)
+
+
+def test_transpose_unaligned_pointers_take_the_element_path():
+    got, want = _run(2, 64, 128, "bf16", "f16", seed=4, offset_src=1, offset_dst=3)
+    assert np.array_equal(got, want)
+    got, want = _run(2, 64, 128, "f32", "f32", seed=5, offset_src=1, offset_dst=1)
+    assert np.array_equal(got, want)
+
+
+def test_transpose_nchw_to_nhwc_activation_tensor():
+    # the activations of the conv workload arriving as fp32 NCHW: [32, 64, 56, 56] -> bf16 NHWC
+    got, want = _run(32, 64, 56 * 56, "f32", "bf16", seed=6)
+    assert np.array_equal(got, want)
+    got, want = _run(32, 56 * 56, 128, "bf16", "f32", seed=7)      # and the output back to fp32 NCHW
+    assert np.array_equal(got, want)
+
+
+def test_transpose_empty_and_rejected_arguments():
+    import torch
+    buf = torch.zeros(64, dtype=torch.float32, device="cuda")
+    out = torch.zeros(64, dtype=torch.float32, device="cuda")
+    for shape in ((0, 4, 4), (2, 0, 4), (2, 4, 0)):
+        ucl.ucl_transpose(*shape, buf.data_ptr(), "f32", out.data_ptr(), "f32")      # nothing to do, no error
+    ucl.ucl_transpose(0, 4, 4, 0, "f32", 0, "f32")                                   # not even pointers are needed
+    with pytest.raises(ucl.UclError) as e:
+        ucl.ucl_transpose(1, 4, 4, buf.data_ptr(), "f32", buf.data_ptr(), "f32")
+    assert e.value.status == "UCL_ERR_UNSUPPORTED"
+    with pytest.raises(ucl.UclError) as e:
+        ucl.ucl_transpose(1, 4, 4, 0, "f32", out.data_ptr(), "f32")
+    assert e.value.status == "UCL_ERR_INVALID_ARG"
+    with pytest.raises(ucl.UclError) as e:
+        ucl.ucl_transpose(1, 4, 4, buf.data_ptr(), 7, out.data_ptr(), "f32")
+    assert e.value.status == "UCL_ERR_INVALID_ARG"
+    with pytest.raises(ucl.UclError) as e:
+        ucl.ucl_transpose(-1, 4, 4, buf.data_ptr(), "f32", out.data_ptr(), "f32")
+    assert e.value.status == "UCL_ERR_INVALID_ARG"
+    torch.cuda.synchronize()
+    assert (out == 0).all()
