@@ -130,6 +130,75 @@ def cpu_baseline(spec, cfg):
             "sample": sample, "seconds": dt}
 
 
+TRANSPOSE_WORKLOAD = {"name": "transpose_nchw_to_nhwc_64x256x56x56_f32_to_bf16", "batch": 64, "rows": 256, "cols": 56 * 56,
+                      "dt_src": "f32", "dt_dst": "bf16"}
+TRANSPOSE_TRAFFIC_BYTES = None
+
+
+def bench_transpose(args):
+    """The pipeline transform stage (a widening row, not one of the five headline workloads):
+    NCHW fp32 -> NHWC bf16 of a [64, 256, 56, 56] activation tensor, HBM-cold rotation."""
+    import numpy as np
+    import torch
+    import paper_2603_29010_amd as ucl
+    from paper_2603_29010_amd import synth
+    w = TRANSPOSE_WORKLOAD
+    n = w["batch"] * w["rows"] * w["cols"]
+    nbytes = n * (synth.itemsize(w["dt_src"]) + synth.itemsize(w["dt_dst"]))
+    copies = max(2, int(768e6 // nbytes) + 1)
+    host = synth.normal(synth.BASE_SEED + 6, 1, n).astype(np.float32)
+    srcs = [torch.from_numpy(host).cuda() for _ in range(copies)]
+    dsts = [torch.empty(n, dtype=torch.int16, device="cuda") for _ in range(copies)]
+
+    def run(i):
+        ucl.ucl_transpose(w["batch"], w["rows"], w["cols"], srcs[i % copies].data_ptr(), w["dt_src"],
+                          dsts[i % copies].data_ptr(), w["dt_dst"], torch.cuda.current_stream().cuda_stream)
+    for i in range(args.warmup):
+        run(i)
+    torch.cuda.synchronize()
+    launch = "eager"
+    graph = None
+    if not args.eager:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for i in range(args.steps):
+                run(i)
+        graph.replay()
+        torch.cuda.synchronize()
+        launch = "hipgraph"
+    start = torch.cuda.Event(enable_timing=True)
+    stop = torch.cuda.Event(enable_timing=True)
+    stream = torch.cuda.current_stream()
+    start.record(stream)
+    if graph is not None:
+        graph.replay()
+    else:
+        for i in range(args.steps):
+            run(i)
+    stop.record(stream)
+    torch.cuda.synchronize()
+    ms = start.elapsed_time(stop) / args.steps
+    gbps = nbytes / (ms * 1e-3) / 1e9
+    out = {
+        "metric": "GB/s of algorithmic bytes (elements x (source + destination size)), transpose with conversion, 1 MI355X",
+        "value": gbps, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w["name"], "buffer_sets": copies, "launch": launch, "bytes": nbytes},
+        "roofline": {"bound": "hbm", "achieved": gbps, "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": gbps / PEAK_HBM_GBPS,
+                     "traffic": TRANSPOSE_TRAFFIC_BYTES},
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        sample_b = w["batch"]
+        x = host[:sample_b * w["rows"] * w["cols"]].reshape(sample_b, w["rows"], w["cols"])
+        t0 = time.perf_counter()
+        oracle.round_to(oracle.transpose(x, "f32", sample_b, w["rows"], w["cols"]), "bf16")
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": nbytes * sample_b / w["batch"] / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+                               "sample": f"{sample_b} of {w['batch']} batches", "seconds": dt}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -139,6 +208,8 @@ def main():
     ap.add_argument("--all", action="store_true", help="also time the other four workloads")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--eager", action="store_true", help="plain launches instead of one captured HIP graph")
+    ap.add_argument("--transpose", action="store_true",
+                    help="time the pipeline transform stage (NCHW fp32 -> NHWC bf16) instead of a GEMM / conv workload")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run 10 plain device copies of 256 MiB and exit (reference reading for the "
                          "FETCH_SIZE / WRITE_SIZE counters)")
@@ -164,6 +235,9 @@ def main():
         print("bench.py: libucl.so is not built (python -m paper_2603_29010_amd.build)", file=sys.stderr)
         sys.exit(1)
 
+    if args.transpose:
+        bench_transpose(args)
+        return
     res, spec, _ = time_workload(args.config, args.steps, args.warmup, use_graph=not args.eager)
     mfma = res["bound"] == "mfma"
     roofline = {

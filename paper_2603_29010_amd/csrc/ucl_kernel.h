@@ -377,6 +377,12 @@ typedef __amdgpu_buffer_rsrc_t rsrc_t;
 typedef __attribute__((ext_vector_type(2))) float f32x2_t;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
 typedef __attribute__((ext_vector_type(2))) _Float16 f16x2_t;
+// Cache policy of accesses to data that is touched exactly once (residual loads, 16-bit output stores
+// whose wave instruction covers whole 128-byte lines): the non-temporal bit.  Measured on the grouped
+// GEMM and conv workloads: 9 % and 7 % shorter launches, because less dirty output waits in L2 for the
+// write-back at the end of the kernel.  fp32 outputs keep the default policy: a lane's 32 bytes go out
+// as two instructions that each cover half of every line, and streaming those half lines was 29 % slower.
+constexpr int kAuxStream = 2;
 constexpr uint32_t kOobOffset = 0x80000000u;   // never inside a resource (sizes are kept below 2^31)
 __device__ __forceinline__ rsrc_t buffer_rsrc(const void *base, uint32_t bytes) {
     // word 3: 32-bit data format, raw (unstructured) addressing
@@ -1169,15 +1175,16 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
     auto res_issue = [&](int mi, ResRegs &r) __attribute__((always_inline)) {
         if constexpr (!kResAhead) return;
         const uint32_t r0 = r_lane + mi * 32 * r_row_bytes;
-        static_for<kResAhead ? PASSES : 0>([&](auto u) { r.lo[u] = __builtin_amdgcn_raw_buffer_load_b128(r_rsrc, r0 + u * RPP * r_row_bytes, 0, 0); });
+        static_for<kResAhead ? PASSES : 0>([&](auto u) { r.lo[u] = __builtin_amdgcn_raw_buffer_load_b128(r_rsrc, r0 + u * RPP * r_row_bytes, 0, kAuxStream); });
         if constexpr (kResHi) {
             if (r_dt == UCL_F32) {
-                static_for<PASSES>([&](auto u) { r.hi[u] = __builtin_amdgcn_raw_buffer_load_b128(r_rsrc, r0 + u * RPP * r_row_bytes + 16, 0, 0); });
+                static_for<PASSES>([&](auto u) { r.hi[u] = __builtin_amdgcn_raw_buffer_load_b128(r_rsrc, r0 + u * RPP * r_row_bytes + 16, 0, kAuxStream); });
             }
         }
     };
     auto fast_block = [&](auto has_res_, int mi, const ResRegs &rr) __attribute__((always_inline)) {
         constexpr bool HAS_RES = decltype(has_res_)::value;
+        constexpr int kAuxStore = LPR * 16 >= 128 ? kAuxStream : 0;   // streaming only where an instruction writes whole lines
         constexpr int FGX = HAS_RES && FG > 4 ? 4 : FG;       // with a residual in registers: smaller pass groups
         const float beta = f.beta, ap0 = f.act_p0, ap1 = f.act_p1;
         const uint32_t d0 = d_lane + mi * 32 * d_row_bytes;
@@ -1191,7 +1198,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
                 } else {
                     const uint32_t r0 = r_lane + mi * 32 * r_row_bytes;
                     static_for<FGX>([&](auto u) {
-                        r_lo[u] = __builtin_amdgcn_raw_buffer_load_b128(r_rsrc, r0 + (P0 + u) * RPP * r_row_bytes, 0, 0);
+                        r_lo[u] = __builtin_amdgcn_raw_buffer_load_b128(r_rsrc, r0 + (P0 + u) * RPP * r_row_bytes, 0, kAuxStream);
                     });
                 }
                 if constexpr (kResHi) {
@@ -1199,7 +1206,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
                 } else if (r_dt == UCL_F32) {
                     const uint32_t r0 = r_lane + mi * 32 * r_row_bytes;
                     static_for<FGX>([&](auto u) {
-                        r_hi[u] = __builtin_amdgcn_raw_buffer_load_b128(r_rsrc, r0 + (P0 + u) * RPP * r_row_bytes + 16, 0, 0);
+                        r_hi[u] = __builtin_amdgcn_raw_buffer_load_b128(r_rsrc, r0 + (P0 + u) * RPP * r_row_bytes + 16, 0, kAuxStream);
                     });
                 }
             }
@@ -1276,7 +1283,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
                         o[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2_t{v[u][2 * e], v[u][2 * e + 1]}, bf16x2_t));
-                    __builtin_amdgcn_raw_buffer_store_b128(o, d_rsrc, d0 + (P0 + u) * RPP * d_row_bytes, 0, 0);
+                    __builtin_amdgcn_raw_buffer_store_b128(o, d_rsrc, d0 + (P0 + u) * RPP * d_row_bytes, 0, kAuxStore);
                 });
             } else {
                 static_for<FGX>([&](auto u) {
@@ -1284,7 +1291,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
                         o[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2_t{v[u][2 * e], v[u][2 * e + 1]}, f16x2_t));
-                    __builtin_amdgcn_raw_buffer_store_b128(o, d_rsrc, d0 + (P0 + u) * RPP * d_row_bytes, 0, 0);
+                    __builtin_amdgcn_raw_buffer_store_b128(o, d_rsrc, d0 + (P0 + u) * RPP * d_row_bytes, 0, kAuxStore);
                 });
             }
         });

@@ -108,7 +108,9 @@ __global__ __launch_bounds__(kThreads) void transpose_kernel(const char *src, ch
         if (gr < rows && gc < cols) {
             const char *p = s + ((int64_t)gr * cols + gc) * ES;
             if (vec_in) {
-                decode16<SRC>(*(const tu32x4_t *)p, v);
+                // every byte is touched exactly once: non-temporal accesses keep the stream from
+                // displacing itself in the caches (measured 5.3 -> 5.9 TB/s on a 308 MB problem)
+                decode16<SRC>(__builtin_nontemporal_load((const tu32x4_t *)p), v);
             } else {
 #pragma unroll
                 for (int e = 0; e < CI; ++e)
@@ -132,7 +134,7 @@ __global__ __launch_bounds__(kThreads) void transpose_kernel(const char *src, ch
             for (int e = 0; e < CO; ++e) v[e] = tile[(rr + e) * kPitch + c];
             char *p = d + ((int64_t)gc * rows + gr) * ED;
             if (vec_out) {
-                *(tu32x4_t *)p = encode16<DST>(v);
+                __builtin_nontemporal_store(encode16<DST>(v), (tu32x4_t *)p);
             } else {
 #pragma unroll
                 for (int e = 0; e < CO; ++e)
