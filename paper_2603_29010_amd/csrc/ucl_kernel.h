@@ -1142,6 +1142,12 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
     const int r_esz = r_dt == UCL_F32 ? 4 : 2;
     rsrc_t d_rsrc = buffer_rsrc(nullptr, 0), r_rsrc = buffer_rsrc(nullptr, 0);
     uint32_t d_lane = 0, r_lane = 0, d_row_bytes = 0, r_row_bytes = 0;
+    // fp32 output without a residual: a lane takes columns 4i..4i+3 and 4(i + LPR)..+3 of its row
+    // instead of 8i..8i+7, so that each of its two 128-bit stores is, across the lanes of a row, one
+    // contiguous run of whole lines (and can stream); with 8 consecutive columns per lane each store
+    // instruction writes every other 16 bytes.
+    const bool f_split = f.enabled && dtD == UCL_F32 && !f.has_res && LPR * 16 >= 128;
+    const int f_colA = f_split ? (lane % LPR) * 4 : e_col, f_colB = f_split ? f_colA + LPR * 4 : e_col + 4;
     auto fast_setup = [&]() __attribute__((always_inline)) {
         const int64_t col0 = n0 + wn * WTN;
         if (w_rows > 0) {
@@ -1153,7 +1159,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
         }
         d_row_bytes = (uint32_t)(p.ldd * d_esz);
         r_row_bytes = (uint32_t)(f.res_ld * r_esz);
-        d_lane = e_row * d_row_bytes + e_col * d_esz;
+        d_lane = e_row * d_row_bytes + f_colA * d_esz;
         r_lane = e_row * r_row_bytes + e_col * r_esz;
     };
     // passes whose operands are requested together (all of a block where registers allow)
@@ -1211,8 +1217,8 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
                 }
             }
             static_for<FGX>([&](auto u) {
-                const f32x4_t lo = *(const f32x4_t *)(stg + ((P0 + u) * RPP + e_row) * EPI_LD + e_col);
-                const f32x4_t hi = *(const f32x4_t *)(stg + ((P0 + u) * RPP + e_row) * EPI_LD + e_col + 4);
+                const f32x4_t lo = *(const f32x4_t *)(stg + ((P0 + u) * RPP + e_row) * EPI_LD + f_colA);
+                const f32x4_t hi = *(const f32x4_t *)(stg + ((P0 + u) * RPP + e_row) * EPI_LD + f_colB);
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     v[u][e] = lo[e] * alpha + bias8[e];
@@ -1272,11 +1278,19 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
             default: break;
             }
             if (dtD == UCL_F32) {
-                static_for<FGX>([&](auto u) {
-                    const uint32_t off = d0 + (P0 + u) * RPP * d_row_bytes;
-                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, f32x4_t{v[u][0], v[u][1], v[u][2], v[u][3]}), d_rsrc, off, 0, 0);
-                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, f32x4_t{v[u][4], v[u][5], v[u][6], v[u][7]}), d_rsrc, off + 16, 0, 0);
-                });
+                if (!HAS_RES && f_split) {
+                    static_for<FGX>([&](auto u) {
+                        const uint32_t off = d0 + (P0 + u) * RPP * d_row_bytes;
+                        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, f32x4_t{v[u][0], v[u][1], v[u][2], v[u][3]}), d_rsrc, off, 0, kAuxStore);
+                        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, f32x4_t{v[u][4], v[u][5], v[u][6], v[u][7]}), d_rsrc, off + LPR * 16, 0, kAuxStore);
+                    });
+                } else {
+                    static_for<FGX>([&](auto u) {
+                        const uint32_t off = d0 + (P0 + u) * RPP * d_row_bytes;
+                        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, f32x4_t{v[u][0], v[u][1], v[u][2], v[u][3]}), d_rsrc, off, 0, 0);
+                        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, f32x4_t{v[u][4], v[u][5], v[u][6], v[u][7]}), d_rsrc, off + 16, 0, 0);
+                    });
+                }
             } else if (dtD == UCL_BF16) {
                 static_for<FGX>([&](auto u) {
                     u32x4_t o;
@@ -1303,6 +1317,16 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
         if (f.has_bias) {
             const void *bp = group >= 0 ? ((const void *const *)f.bias)[group] : f.bias;
             decode8(load8(bp, f.bias_dt & 0xff, c.n, (f.bias_dt & 0x100) != 0, n_left), f.bias_dt & 0xff, bias8);
+            // (the split column mapping is only used where all of the wave's columns exist: see fast_ok)
+            if (f_split && dvec && (n0 + wn * WTN + WTN <= p.N) && (f.bias_dt & 0x100)) {
+                const int64_t nb = n0 + wn * WTN;
+                const int bdt = f.bias_dt & 0xff;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int64_t idx = nb + (e < 4 ? f_colA + e : f_colB + e - 4);
+                    bias8[e] = bdt == UCL_F32 ? ((const float *)bp)[idx] : bits_to_f32(((const uint16_t *)bp)[idx], bdt);
+                }
+            }
         }
         if (f.has_res) {
             const void *rp = group >= 0 ? ((const void *const *)f.res)[group] : f.res;
