@@ -151,6 +151,19 @@ def test_gemm_parity_every_tile(tile):
     parity.check(spec, T(*tile), label=f"tile{tile}")
 
 
+@pytest.mark.parametrize("tile", KK_TILES)
+def test_gemm_parity_every_tile_fp32_output(tile):
+    # fp32 output without a residual: wide wave tiles hand each lane two 4-column groups a row apart
+    # (bias index and store offsets follow); the same chain with a residual keeps 8 consecutive columns
+    spec = synth.gemm_spec(520, 392, 264, dt_out="f32", epilogue=(("scale", 0.5), "bias", "gelu_tanh"))
+    parity.check(spec, T(*tile), label=f"f32 out tile{tile}")
+    bias, dt = spec["tensors"]["bias11"]
+    spec["tensors"]["bias11"] = (synth.to_bits(synth.bits_to_f64(bias, dt), "bf16"), "bf16")     # 16-bit bias, fp32 output
+    parity.check(spec, T(*tile), label=f"f32 out, bf16 bias, tile{tile}")
+    spec = synth.gemm_spec(520, 392, 264, dt_out="f32", epilogue=("bias", "aux_load", "relu"))
+    parity.check(spec, T(*tile), label=f"f32 out with residual tile{tile}")
+
+
 ALL_CHAINS = [
     ("bias", "relu"),
     ("bias", "gelu_tanh"),
