@@ -259,7 +259,7 @@ def ucl_variant(i):
     _check(_load().ucl_variant(i, t.ref()))
     d = t.as_dict()
     d["mode"], lay = t.c.reserved[0], t.c.reserved[1]
-    d["f16"], d["la"], d["lb"] = lay // 16, lay // 4 % 4, lay % 4
+    d["f16"], d["la"], d["lb"] = lay // 64, lay // 8 % 8, lay % 8
     return d
 
 

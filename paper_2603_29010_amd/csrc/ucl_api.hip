@@ -29,7 +29,7 @@ ucl_status fail(ucl_status st, const char *fmt, ...) {
 const std::vector<VariantDesc> &all_variants() {
     static const std::vector<VariantDesc> v = [] {
         std::vector<VariantDesc> out;
-        for (VariantList l : {variants_gemm_kk_bf16_a(), variants_gemm_kk_bf16_b(), variants_gemm_kk_bf16_c(), variants_gemm_kk_bf16_d(), variants_gemm_kk_f16_a(), variants_gemm_kk_f16_b(), variants_gemm_mn_bf16(), variants_gemm_mn_f16(), variants_grouped_a(), variants_grouped_b(), variants_conv_a(), variants_conv_b(), variants_conv_f16(), variants_conv_halo()})
+        for (VariantList l : {variants_gemm_kk_bf16_a(), variants_gemm_kk_bf16_b(), variants_gemm_kk_bf16_c(), variants_gemm_kk_bf16_d(), variants_gemm_kk_f16_a(), variants_gemm_kk_f16_b(), variants_gemm_mn_bf16(), variants_gemm_mn_f16(), variants_grouped_a(), variants_grouped_b(), variants_conv_a(), variants_conv_b(), variants_conv_f16(), variants_conv_halo(), variants_gemm_kn_bf16(), variants_gemm_kn_f16()})
             for (int i = 0; i < l.n; ++i) out.push_back(l.v[i]);
         return out;
     }();
@@ -64,6 +64,7 @@ struct Launch {
     const int64_t *M_g = nullptr;
     int64_t max_Mg = 0, sum_Mg = 0;
     bool patch_ok = false;        // conv: the problem fits the resident-patch kernels
+    bool ndirect_ok = false;      // B contiguous along N and small enough for 32-bit byte offsets: direct-copy kernels apply
 };
 
 // The resident-patch conv kernels hold 64-channel pixels and address the taps of a 3x3 filter at unit
@@ -108,13 +109,14 @@ int workgroups_per_cu(const VariantDesc &v) {
 // Rate of a CU that is busy with variant v, relative to the best variant (measured, see above).
 double relative_rate(const VariantDesc &v) {
     const int64_t area = (int64_t)v.tile_m * v.tile_n;
-    const bool two_buf = v.stages == 2 && v.tile_k == 64 && v.lb == 0 && v.la != 1;
+    const bool two_buf = v.stages == 2 && v.tile_k == 64 && v.lb != 1 && v.la != 1;
     if (v.la == 1 || v.lb == 1) return area >= 128 * 128 ? 0.30 : 0.20;     // register-transposed operands
+    const double nd = v.lb == 4 ? 0.95 : 1.0;                               // two LDS reads per B fragment
     if (v.la == 3) return 0.85;                                             // conv from a resident patch: above the gather kernels
-    if (area >= 256 * 256) return two_buf ? 1.00 : v.stages >= 5 ? 0.92 : 0.90;
-    if (area >= 256 * 128) return two_buf ? 0.81 : v.stages == 3 ? 0.80 : 0.73;
-    if (area >= 128 * 128) return two_buf ? 0.86 : v.tile_k == 32 ? (v.stages >= 4 ? 0.67 : 0.65) : 0.58;
-    return v.tile_k == 64 ? 0.49 : v.stages == 3 ? 0.41 : 0.37;
+    if (area >= 256 * 256) return nd * (two_buf ? 1.00 : v.stages >= 5 ? 0.92 : 0.90);
+    if (area >= 256 * 128) return nd * (two_buf ? 0.81 : v.stages == 3 ? 0.80 : 0.73);
+    if (area >= 128 * 128) return nd * (two_buf ? 0.86 : v.tile_k == 32 ? (v.stages >= 4 ? 0.67 : 0.65) : 0.58);
+    return nd * (v.tile_k == 64 ? 0.49 : v.stages == 3 ? 0.41 : 0.37);
 }
 
 double estimate_seconds(const VariantDesc &v, const Launch &L) {
@@ -144,7 +146,8 @@ const VariantDesc *select_variant(const Launch &L, const ucl_tuning *tune) {
     const VariantDesc *best = nullptr;
     double best_t = 0;
     for (const auto &v : vs) {
-        if (v.mode != L.mode || v.f16 != L.f16 || v.lb != L.lb) continue;
+        if (v.mode != L.mode || v.f16 != L.f16) continue;
+        if (v.lb == 4 ? !(L.lb == 1 && L.ndirect_ok) : v.lb != L.lb) continue;
         if (L.mode == 2) {
             // conv: the iterator knob picks between the per-tap gather (la 2) and the resident patch (la 3)
             const int it = tune ? tune->iterator : 0;
@@ -359,6 +362,8 @@ ucl_status gemm_like(int64_t batch, int64_t M, int64_t N, int64_t K,
     memset(&kp, 0, sizeof(kp));
     if (ucl_status st = classify("A", A, a_cs, a_rs, M, K, &L.la, &kp.lda)) return st;
     if (ucl_status st = classify("B", B, b_rs, b_cs, N, K, &L.lb, &kp.ldb)) return st;
+    // direct copies of an N-contiguous B address it with 32-bit byte offsets from the start of a batch
+    L.ndirect_ok = L.lb == 1 && ((K - 1) * kp.ldb + N) * 2 < (1ll << 31);
     if (ucl_status st = check_epilogue(epi, L, kp)) return st;
     kp.A = A; kp.B = B; kp.D = D;
     kp.ldd = d_rs; kp.a_bs = a_bs; kp.b_bs = b_bs; kp.d_bs = d_bs;
@@ -616,7 +621,7 @@ ucl_status ucl_variant(int32_t i, ucl_tuning *out) {
     out->tile_m = vs[i].tile_m; out->tile_n = vs[i].tile_n; out->tile_k = vs[i].tile_k; out->stages = vs[i].stages;
     out->iterator = vs[i].la == 3 ? UCL_ITER_FIXED_STRIDE_DILATION : vs[i].la == 2 ? UCL_ITER_ANALYTIC : UCL_ITER_DEFAULT;
     // reserved[0..1]: which problems the variant serves (mode; 16-bit type and operand layouts)
-    out->reserved[0] = vs[i].mode; out->reserved[1] = vs[i].f16 * 16 + vs[i].la * 4 + vs[i].lb;
+    out->reserved[0] = vs[i].mode; out->reserved[1] = vs[i].f16 * 64 + vs[i].la * 8 + vs[i].lb;
     return UCL_OK;
 }
 

@@ -36,7 +36,10 @@ typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
 // kIm2col gathers every filter tap of the activations from global memory again; kHalo (3x3 filter,
 // unit stride and dilation, pad 1, 64 channels) copies the pixels a tile needs -- its rows plus one
 // image row and one pixel on either side -- into LDS once and reads every tap from there.
-enum OperandLayout { kKContig = 0, kMNContig = 1, kIm2col = 2, kHalo = 3 };
+// kNDirect (B only): B contiguous along N is copied row by row (k) straight into LDS like a
+// K-contiguous operand and the MFMA fragments -- 8 consecutive k per lane -- come out of the LDS
+// transpose read (ds_read_b64_tr_b16), so no register transpose and no 16-bit LDS writes are needed.
+enum OperandLayout { kKContig = 0, kMNContig = 1, kIm2col = 2, kHalo = 3, kNDirect = 4 };
 
 // Compile-time loop: register arrays (accumulators, fragments) must only ever be indexed by
 // constants, or the compiler moves them to scratch memory.
@@ -505,6 +508,22 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
         for (int i = 0; i < B_ITERS; ++i)
             b_off[i] = (uint32_t)(((int64_t)(i * RPI + l_row) * p.ldb + l_kc) * 2);
     }
+    // kNDirect: the stage holds TK rows (k) of TN elements (n); slot s = i*256 + tid is row s / CPRB,
+    // chunk position s % CPRB, filled from chunk position XOR nd_swz(row).  The resource starts at
+    // column n0 of row 0 and ends with the matrix, so rows past K read zeros; columns past N read
+    // elements of the following row, which only ever reach accumulators that are not stored.
+    constexpr int CPRB = TN / 8, RPIB = kThreads / CPRB;          // chunks per row, rows per 256-thread copy
+    auto nd_swz = [](int row) { return (((row & 3) << 1) | (((row >> 3) & 3) << 3)) & (CPRB - 1); };
+    const int nd_row = tid / CPRB;
+    if constexpr (LB == kNDirect) {
+        b_rsrc = buffer_rsrc(Bb + (int64_t)n0 * 2, (uint32_t)(((int64_t)(K - 1) * p.ldb + (p.N - n0)) * 2));
+#pragma unroll
+        for (int i = 0; i < B_ITERS; ++i) {
+            const int row = i * RPIB + nd_row;
+            const int chunk = (tid % CPRB) ^ nd_swz(row);
+            b_off[i] = (uint32_t)(((int64_t)row * p.ldb + chunk * 8) * 2);
+        }
+    }
 
     // Resident activation patch (kHalo).  Output pixel m of a 3x3 / stride 1 / pad 1 convolution reads
     // input pixels m + dy*W + dx of the flattened [N*H*W] pixel sequence, except where the tap leaves
@@ -633,6 +652,14 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
                 const uint32_t off = CHECK_K ? (kok ? b_off[i] : kOobOffset) : b_off[i];
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(b_rsrc, UCL_LDS_PTR(dst), 16, off, k0 * 2, 0, 0);
             }
+        } else if constexpr (LB == kNDirect) {
+            const uint32_t krow = (uint32_t)k0 * (uint32_t)p.ldb * 2u;       // validated: K * ldb * 2 < 2^31
+#pragma unroll
+            for (int i = 0; i < B_ITERS; ++i) {
+                char *dst = sB + (i * kThreads + wave * 64) * 16;
+                const uint32_t off = CHECK_K ? (k0 + i * RPIB + nd_row < K ? b_off[i] : kOobOffset) : b_off[i];
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(b_rsrc, UCL_LDS_PTR(dst), 16, off, krow, 0, 0);
+            }
         } else {   // B contiguous along N: element (k, n) at k*ldb + n
 #pragma unroll
             for (int i = 0; i < B_ITERS; ++i) {
@@ -678,8 +705,13 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
         } else {
             constexpr int i = IDX - A_ITERS;
             char *dst = sB + (i * kThreads + wave * 64) * 16;
-            const uint32_t off = CHECK_K ? (kok ? b_off[i] : kOobOffset) : b_off[i];
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(b_rsrc, UCL_LDS_PTR(dst), 16, off, k0 * 2, 0, 0);
+            if constexpr (LB == kNDirect) {
+                const uint32_t off = CHECK_K ? (k0 + i * RPIB + nd_row < K ? b_off[i] : kOobOffset) : b_off[i];
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(b_rsrc, UCL_LDS_PTR(dst), 16, off, (uint32_t)k0 * (uint32_t)p.ldb * 2u, 0, 0);
+            } else {
+                const uint32_t off = CHECK_K ? (kok ? b_off[i] : kOobOffset) : b_off[i];
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(b_rsrc, UCL_LDS_PTR(dst), 16, off, k0 * 2, 0, 0);
+            }
         }
     };
     auto issue_tile = [&](auto check_k_, int kt, int buf) {
@@ -740,6 +772,40 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
     auto frag = [&](const char *sbase, int base, int blk, int kk) __attribute__((always_inline)) {
         return *(const u32x4_t *)(sbase + base + blk * 16 * ROW_BYTES + (f_x ^ (kk << 6)));
     };
+    // B fragment of column block `blk`, k-step `kk`.  kNDirect: lanes 16g .. 16g+15 need k = 8g .. 8g+7
+    // of columns blk*16 + (lane % 16); one transpose read takes, per 16 lanes, 4 rows (k) x 16 columns
+    // -- lane l addresses 4 consecutive n at row l/4, column group l%4 -- and returns to lane l the 4
+    // consecutive k of column l, so two of them make the 8 k of a fragment.  Row & 3 = l / 4 and
+    // (row >> 3) & 3 = g for every row a lane addresses, so its swizzle term is a constant.
+    constexpr int NDB = LB == kNDirect ? NI : 1;
+    int nd_addr[NDB];
+    if constexpr (LB == kNDirect) {
+        const int l = lane & 15, g = lane >> 4;
+        const int xr = (((l >> 2) << 1) | (g << 3)) & (CPRB - 1);
+        static_for<NI>([&](auto ni_) {
+            constexpr int ni = decltype(ni_)::value;
+            const int chunk = (wn * Cfg::WTN + ni * 16) / 8 + ((l & 3) >> 1);
+            nd_addr[ni] = Cfg::A_BYTES + (8 * g + (l >> 2)) * (TN * 2) + ((chunk ^ xr) << 4) + (l & 1) * 8;
+        });
+    }
+    auto fragB = [&](const char *sbase, auto blk_, int kk) __attribute__((always_inline)) {
+        constexpr int blk = decltype(blk_)::value;
+        if constexpr (LB == kNDirect) {
+            // Written as asm: the compiler makes the builtin form of this read wait for every
+            // outstanding global -> LDS copy (it cannot tell that they go to other buffers), which
+            // drains the pipeline.  It therefore does not count these reads either: the code that
+            // consumes them runs behind an explicit lgkmcnt(0) (the barrier of the pipelined loop,
+            // the wait at the head of a k-tile in the two-buffer loop).
+            const uint32_t q = (uint32_t)(uintptr_t)(sbase - smem) + (uint32_t)nd_addr[blk] + (uint32_t)(kk * 32 * (TN * 2));
+            u32x2_t lo, hi;
+            asm volatile("ds_read_b64_tr_b16 %0, %2\n\tds_read_b64_tr_b16 %1, %2 offset:%3"
+                         : "=&v"(lo), "=&v"(hi)
+                         : "v"(q), "n"(4 * (TN * 2)));
+            return u32x4_t{lo[0], lo[1], hi[0], hi[1]};
+        } else {
+            return frag(sbase, b_frag_base, blk, kk);
+        }
+    };
     using I0 = std::integral_constant<int, 0>;
     using I1 = std::integral_constant<int, 1>;
 
@@ -787,6 +853,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
             });
         };
         auto first_step = [&](const char *sc) {
+            if constexpr (LB == kNDirect) __builtin_amdgcn_s_waitcnt((0xF) | (0x3 << 14) | (0x7 << 4) | (0x0 << 8));   // lgkmcnt(0)
             static_for<MI>([&](auto mi_) {
                 constexpr int mi = decltype(mi_)::value;
                 constexpr int ia = mi + RA - 1;
@@ -799,7 +866,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
                     constexpr int sx = decltype(s_)::value;
                     if constexpr (sx < na) ar[ia % RA] = frag(sc, a_frag_base, ia, 0);
                     else if constexpr (sx < na + nf) af[f0 + sx - na] = frag(sc, a_frag_base, f0 + sx - na, 1);
-                    else bq[1][b0 + sx - na - nf] = frag(sc, b_frag_base, b0 + sx - na - nf, 1);
+                    else bq[1][b0 + sx - na - nf] = fragB(sc, std::integral_constant<int, b0 + sx - na - nf>{}, 1);
                 };
                 row_block(mi_, ar[mi % RA], I0{}, std::integral_constant<int, na + nf + nb>{}, side);
             });
@@ -814,7 +881,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
                 auto side = [&](auto s_) __attribute__((always_inline)) {
                     constexpr int sx = decltype(s_)::value;
                     if constexpr (sx < na) ar[ih] = frag(sn, a_frag_base, ih, 0);
-                    else if constexpr (sx < na + nb) bq[0][b0 + sx - na] = frag(sn, b_frag_base, b0 + sx - na, 0);
+                    else if constexpr (sx < na + nb) bq[0][b0 + sx - na] = fragB(sn, std::integral_constant<int, b0 + sx - na>{}, 0);
                     else issue_one(check_, std::integral_constant<int, d0 + sx - na - nb>{}, kt_load, buf);
                 };
                 row_block(mi_, af[mi], I1{}, std::integral_constant<int, na + nb + nd>{}, side);
@@ -824,7 +891,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
         issue_tile(std::true_type{}, 1, 1);
         pipeline_barrier<DMA_PER_TILE>();
         static_for<RA - 1>([&](auto i) { ar[i] = frag(smem, a_frag_base, i, 0); });
-        static_for<NI>([&](auto ni) { bq[0][ni] = frag(smem, b_frag_base, ni, 0); });
+        static_for<NI>([&](auto ni) { bq[0][ni] = fragB(smem, ni, 0); });
         const int KT_full = k_tail ? KT - 1 : KT;
         int kt = 0;
         auto ktile2 = [&](auto check_, auto cur_) {
@@ -857,7 +924,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
         pipeline_barrier<(STAGES - 2) * DMA_PER_TILE>();
         int hb_c = halo_base(I0{}), hb_n = 0;
         static_for<RA - 1>([&](auto i) { ar[i] = halo_read(I0{}, i, hb_c, halo_test(I0{}, i)); });
-        static_for<NI>([&](auto ni) { bq[0][ni] = frag(smem, b_frag_base, ni, 0); });
+        static_for<NI>([&](auto ni) { bq[0][ni] = fragB(smem, ni, 0); });
         static_for<KT_ALL>([&](auto kt_) {
             constexpr int kt = decltype(kt_)::value, PB = kt & 1;
             constexpr bool more = kt + 1 < KT_ALL, load = kt + STAGES - 1 < KT_ALL;
@@ -941,7 +1008,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
                         if constexpr (ia < MI) ar[ia % RA] = frag(sc, a_frag_base, ia, KK);
                         else ar[ia % RA] = frag(sn, a_frag_base, ia - MI, KN);
                     } else if constexpr (sx <= nb) {
-                        bq[1 - PB][b0 + sx - 1] = frag(sn, b_frag_base, b0 + sx - 1, KN);
+                        bq[1 - PB][b0 + sx - 1] = fragB(sn, std::integral_constant<int, b0 + sx - 1>{}, KN);
                     } else {
                         issue_one(check_, std::integral_constant<int, d0 + sx - 1 - nb>{}, kt_load, fill_buf);
                     }
@@ -979,7 +1046,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
         static_for<STAGES - 1>([&](auto s_) { issue_tile(std::true_type{}, decltype(s_)::value, decltype(s_)::value); });
         pipeline_barrier<(STAGES - 2) * DMA_PER_TILE>();
         static_for<RA - 1>([&](auto i) { ar[i] = frag(smem, a_frag_base, i, 0); });
-        static_for<NI>([&](auto ni) { bq[0][ni] = frag(smem, b_frag_base, ni, 0); });
+        static_for<NI>([&](auto ni) { bq[0][ni] = fragB(smem, ni, 0); });
 
         const int KT_full = k_tail ? KT - 1 : KT;                  // complete k-tiles: loads skip the K-tail test
         const int KTP = (KT + TPU - 1) / TPU * TPU;

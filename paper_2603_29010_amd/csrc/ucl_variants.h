@@ -8,7 +8,8 @@ struct VariantDesc {
     int tile_m, tile_n, tile_k, stages;
     int f16;            // 1: fp16 inputs, 0: bf16 inputs
     int mode;           // 0 gemm / batched, 1 grouped, 2 conv2d fprop
-    int la, lb;         // 0: operand contiguous along K, 1: contiguous along M / N; A only: 2 im2col gather, 3 resident patch
+    int la, lb;         // 0: operand contiguous along K, 1: contiguous along M / N (register transpose); A only: 2 im2col gather,
+                        // 3 resident patch; B only: 4 contiguous along N, copied directly and read through the LDS transpose read
     int lds_bytes;
     hipError_t (*launch)(const KParams &p, const GroupTable *gt, int grid, hipStream_t stream);
 };
@@ -33,5 +34,7 @@ VariantList variants_conv_a();
 VariantList variants_conv_b();
 VariantList variants_conv_f16();
 VariantList variants_conv_halo();
+VariantList variants_gemm_kn_bf16();
+VariantList variants_gemm_kn_f16();
 
 }  // namespace ucl

@@ -65,6 +65,22 @@ def test_gemm_exact_transposed_layouts(a_layout, b_layout, dt):
         parity.check_exact(spec, T(*tile), label=f"{a_layout}/{b_layout}{tile}")
 
 
+# A row-major, B row-major (contiguous along N): B is copied row by row into LDS and read through the
+# LDS transpose read.  Every such variant, exact: several tiles in M and N, a K tail inside a k-tile,
+# K shorter than one k-tile, ragged N (multiple of 8 only), batches, a leading stride wider than N.
+@pytest.mark.parametrize("dt", ["bf16", "f16"])
+def test_gemm_exact_n_contiguous_b_direct(dt):
+    f16 = int(dt == "f16")
+    for tile in built(0, f16=f16, la=0, lb=4):
+        for (M, N, K) in ((328, 264, 200), (72, 520, 40), (260, 136, 8), (520, 392, 416)):
+            spec = synth.gemm_spec(M, N, K, dt_in=dt, dt_out="f32", a_layout="row", b_layout="row", epilogue=(), integer=True)
+            parity.check_exact(spec, T(*tile), label=f"row/row {tile} {M}x{N}x{K}")
+    spec = synth.gemm_spec(520, 392, 264, dt_in=dt, a_layout="row", b_layout="row", epilogue=("bias", "gelu_tanh"))
+    for tile in built(0, f16=f16, la=0, lb=4):
+        parity.check(spec, T(*tile), label=f"row/row fp {tile}")
+    parity.check(spec, None, label="row/row table choice")
+
+
 @pytest.mark.parametrize("shape", [(1, 8, 8), (8, 1, 8), (7, 5, 16), (64, 64, 64), (65, 63, 64), (1, 1, 8)])
 def test_gemm_exact_degenerate_shapes(shape):
     M, N, K = shape
