@@ -29,7 +29,7 @@ ucl_status fail(ucl_status st, const char *fmt, ...) {
 const std::vector<VariantDesc> &all_variants() {
     static const std::vector<VariantDesc> v = [] {
         std::vector<VariantDesc> out;
-        for (VariantList l : {variants_gemm_kk_bf16_a(), variants_gemm_kk_bf16_b(), variants_gemm_kk_bf16_c(), variants_gemm_kk_bf16_d(), variants_gemm_kk_f16_a(), variants_gemm_kk_f16_b(), variants_gemm_mn_bf16(), variants_gemm_mn_f16(), variants_grouped_a(), variants_grouped_b(), variants_conv_a(), variants_conv_b(), variants_conv_f16(), variants_conv_halo(), variants_gemm_kn_bf16(), variants_gemm_kn_f16()})
+        for (VariantList l : {variants_gemm_kk_bf16_a(), variants_gemm_kk_bf16_b(), variants_gemm_kk_bf16_c(), variants_gemm_kk_bf16_d(), variants_gemm_kk_f16_a(), variants_gemm_kk_f16_b(), variants_gemm_mn_bf16(), variants_gemm_mn_f16(), variants_grouped_a(), variants_grouped_b(), variants_conv_a(), variants_conv_b(), variants_conv_f16(), variants_conv_halo(), variants_gemm_kn_bf16(), variants_gemm_kn_f16(), variants_gemm_mx_bf16(), variants_gemm_mx_f16()})
             for (int i = 0; i < l.n; ++i) out.push_back(l.v[i]);
         return out;
     }();
@@ -65,6 +65,7 @@ struct Launch {
     int64_t max_Mg = 0, sum_Mg = 0;
     bool patch_ok = false;        // conv: the problem fits the resident-patch kernels
     bool ndirect_ok = false;      // B contiguous along N and small enough for 32-bit byte offsets: direct-copy kernels apply
+    bool mdirect_ok = false;      // the same for A contiguous along M
 };
 
 // The resident-patch conv kernels hold 64-channel pixels and address the taps of a 3x3 filter at unit
@@ -111,7 +112,7 @@ double relative_rate(const VariantDesc &v) {
     const int64_t area = (int64_t)v.tile_m * v.tile_n;
     const bool two_buf = v.stages == 2 && v.tile_k == 64 && v.lb != 1 && v.la != 1;
     if (v.la == 1 || v.lb == 1) return area >= 128 * 128 ? 0.30 : 0.20;     // register-transposed operands
-    const double nd = v.lb == 4 ? 0.95 : 1.0;                               // two LDS reads per B fragment
+    const double nd = (v.lb == 4 ? 0.95 : 1.0) * (v.la == 5 ? 0.9 : 1.0);   // two LDS reads per fragment of a directly copied operand
     if (v.la == 3) return 0.85;                                             // conv from a resident patch: above the gather kernels
     if (area >= 256 * 256) return nd * (two_buf ? 1.00 : v.stages >= 5 ? 0.92 : 0.90);
     if (area >= 256 * 128) return nd * (two_buf ? 0.81 : v.stages == 3 ? 0.80 : 0.73);
@@ -152,7 +153,7 @@ const VariantDesc *select_variant(const Launch &L, const ucl_tuning *tune) {
             // conv: the iterator knob picks between the per-tap gather (la 2) and the resident patch (la 3)
             const int it = tune ? tune->iterator : 0;
             if (v.la == 3 ? (!L.patch_ok || it == UCL_ITER_ANALYTIC) : (v.la != 2 || it == UCL_ITER_FIXED_STRIDE_DILATION)) continue;
-        } else if (v.la != L.la) {
+        } else if (v.la == 5 ? !(L.la == 1 && L.mdirect_ok) : v.la != L.la) {
             continue;
         }
         if (explicit_tune) {
@@ -364,6 +365,7 @@ ucl_status gemm_like(int64_t batch, int64_t M, int64_t N, int64_t K,
     if (ucl_status st = classify("B", B, b_rs, b_cs, N, K, &L.lb, &kp.ldb)) return st;
     // direct copies of an N-contiguous B address it with 32-bit byte offsets from the start of a batch
     L.ndirect_ok = L.lb == 1 && ((K - 1) * kp.ldb + N) * 2 < (1ll << 31);
+    L.mdirect_ok = L.la == 1 && ((K - 1) * kp.lda + M) * 2 < (1ll << 31);
     if (ucl_status st = check_epilogue(epi, L, kp)) return st;
     kp.A = A; kp.B = B; kp.D = D;
     kp.ldd = d_rs; kp.a_bs = a_bs; kp.b_bs = b_bs; kp.d_bs = d_bs;

@@ -39,7 +39,8 @@ typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
 // kNDirect (B only): B contiguous along N is copied row by row (k) straight into LDS like a
 // K-contiguous operand and the MFMA fragments -- 8 consecutive k per lane -- come out of the LDS
 // transpose read (ds_read_b64_tr_b16), so no register transpose and no 16-bit LDS writes are needed.
-enum OperandLayout { kKContig = 0, kMNContig = 1, kIm2col = 2, kHalo = 3, kNDirect = 4 };
+// kMDirect (A only) is the same for A contiguous along M.
+enum OperandLayout { kKContig = 0, kMNContig = 1, kIm2col = 2, kHalo = 3, kNDirect = 4, kMDirect = 5 };
 
 // Compile-time loop: register arrays (accumulators, fragments) must only ever be indexed by
 // constants, or the compiler moves them to scratch memory.
@@ -481,6 +482,16 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
 #pragma unroll
         for (int i = 0; i < A_ITERS; ++i)
             a_off[i] = (uint32_t)(((int64_t)(i * RPI + l_row) * p.lda + l_kc) * 2);   // rows past the edge: out of range
+    } else if constexpr (LA == kMDirect) {
+        // the stage holds TK rows (k) of TM elements (m), laid out and swizzled like the kNDirect B stage
+        constexpr int CPRA = TM / 8, RPIA = kThreads / CPRA;
+        a_rsrc = buffer_rsrc(Ab + (int64_t)m0 * 2, (uint32_t)(((int64_t)(K - 1) * p.lda + (Mloc - m0)) * 2));
+#pragma unroll
+        for (int i = 0; i < A_ITERS; ++i) {
+            const int row = i * RPIA + tid / CPRA;
+            const int chunk = (tid % CPRA) ^ ((((row & 3) << 1) | (((row >> 3) & 3) << 3)) & (CPRA - 1));
+            a_off[i] = (uint32_t)(((int64_t)row * p.lda + chunk * 8) * 2);
+        }
     } else if constexpr (LA == kIm2col) {
         a_rsrc = buffer_rsrc(Ab, (uint32_t)p.a_bytes);
 #pragma unroll
@@ -616,6 +627,15 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
                 const uint32_t off = CHECK_K ? (kok ? a_off[i] : kOobOffset) : a_off[i];
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, UCL_LDS_PTR(dst), 16, off, k0 * 2, 0, 0);
             }
+        } else if constexpr (LA == kMDirect) {
+            constexpr int RPIA = kThreads / (TM / 8);
+            const uint32_t krow = (uint32_t)k0 * (uint32_t)p.lda * 2u;       // validated: K * lda * 2 < 2^31
+#pragma unroll
+            for (int i = 0; i < A_ITERS; ++i) {
+                char *dst = sA + (i * kThreads + wave * 64) * 16;
+                const uint32_t off = CHECK_K ? (k0 + i * RPIA + tid / (TM / 8) < K ? a_off[i] : kOobOffset) : a_off[i];
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, UCL_LDS_PTR(dst), 16, off, krow, 0, 0);
+            }
         } else if constexpr (LA == kIm2col) {
             const int dh = a_r * p.dil_h, dw = a_s * p.dil_w;
             const uint32_t tap_off = (uint32_t)(((dh * p.cW + dw) * p.cC + a_ci) * 2);
@@ -687,6 +707,10 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
             if constexpr (LA == kKContig) {
                 const uint32_t off = CHECK_K ? (kok ? a_off[i] : kOobOffset) : a_off[i];
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, UCL_LDS_PTR(dst), 16, off, k0 * 2, 0, 0);
+            } else if constexpr (LA == kMDirect) {
+                constexpr int RPIA = kThreads / (TM / 8);
+                const uint32_t off = CHECK_K ? (k0 + i * RPIA + tid / (TM / 8) < K ? a_off[i] : kOobOffset) : a_off[i];
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, UCL_LDS_PTR(dst), 16, off, (uint32_t)k0 * (uint32_t)p.lda * 2u, 0, 0);
             } else {
                 const int dh = a_r * p.dil_h, dw = a_s * p.dil_w;
                 const uint32_t tap_off = (uint32_t)(((dh * p.cW + dw) * p.cC + a_ci) * 2);
@@ -806,6 +830,33 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
             return frag(sbase, b_frag_base, blk, kk);
         }
     };
+    // A fragment of row block `blk`, k-step `kk`; kMDirect mirrors kNDirect.  Consecutive row blocks
+    // are two chunks apart, i.e. bit 5 upward of the byte address, which the swizzle XORs but no
+    // other term touches: the address of block blk is that of block 0 XOR (blk << 5).
+    int md_addr = 0;
+    if constexpr (LA == kMDirect) {
+        const int l = lane & 15, g = lane >> 4;
+        const int xr = (((l >> 2) << 1) | (g << 3)) & (TM / 8 - 1);
+        const int chunk = (wm * Cfg::WTM) / 8 + ((l & 3) >> 1);
+        md_addr = (8 * g + (l >> 2)) * (TM * 2) + ((chunk ^ xr) << 4) + (l & 1) * 8;
+    }
+    auto fragA = [&](const char *sbase, int blk, int kk) __attribute__((always_inline)) {
+        if constexpr (LA == kMDirect) {
+            const uint32_t q = ((uint32_t)(uintptr_t)(sbase - smem) + (uint32_t)md_addr + (uint32_t)(kk * 32 * (TM * 2))) ^ (uint32_t)(blk << 5);
+            u32x2_t lo, hi;
+            asm volatile("ds_read_b64_tr_b16 %0, %2\n\tds_read_b64_tr_b16 %1, %2 offset:%3"
+                         : "=&v"(lo), "=&v"(hi)
+                         : "v"(q), "n"(4 * (TM * 2)));
+            return u32x4_t{lo[0], lo[1], hi[0], hi[1]};
+        } else {
+            return frag(sbase, a_frag_base, blk, kk);
+        }
+    };
+    // The compiler does not count asm LDS reads, so with kMDirect every row block first waits for all
+    // LDS reads issued so far (its own fragment was requested three row blocks earlier).
+    auto a_ready = [&]() __attribute__((always_inline)) {
+        if constexpr (LA == kMDirect) __builtin_amdgcn_s_waitcnt((0xF) | (0x3 << 14) | (0x7 << 4) | (0x0 << 8));   // lgkmcnt(0)
+    };
     using I0 = std::integral_constant<int, 0>;
     using I1 = std::integral_constant<int, 1>;
 
@@ -845,6 +896,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
         // the side instructions of a row block go out one (or their even share) behind each MFMA
         auto row_block = [&](auto mi_, const u32x4_t &a, auto pb_, auto ns_, auto &&side) __attribute__((always_inline)) {
             constexpr int mi = decltype(mi_)::value, PB = decltype(pb_)::value, NS = decltype(ns_)::value;
+            a_ready();
             static_for<NI>([&](auto ni_) {
                 constexpr int ni = decltype(ni_)::value;
                 mfma16<Cfg::F16>(acc[mi][ni], bq[PB][ni], a);
@@ -864,8 +916,8 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
                 constexpr int na = ia < MI ? 1 : 0;
                 auto side = [&](auto s_) __attribute__((always_inline)) {
                     constexpr int sx = decltype(s_)::value;
-                    if constexpr (sx < na) ar[ia % RA] = frag(sc, a_frag_base, ia, 0);
-                    else if constexpr (sx < na + nf) af[f0 + sx - na] = frag(sc, a_frag_base, f0 + sx - na, 1);
+                    if constexpr (sx < na) ar[ia % RA] = fragA(sc, ia, 0);
+                    else if constexpr (sx < na + nf) af[f0 + sx - na] = fragA(sc, f0 + sx - na, 1);
                     else bq[1][b0 + sx - na - nf] = fragB(sc, std::integral_constant<int, b0 + sx - na - nf>{}, 1);
                 };
                 row_block(mi_, ar[mi % RA], I0{}, std::integral_constant<int, na + nf + nb>{}, side);
@@ -880,7 +932,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
                 constexpr int d0 = mi * DMA_PER_TILE / MI, nd = (mi + 1) * DMA_PER_TILE / MI - d0;
                 auto side = [&](auto s_) __attribute__((always_inline)) {
                     constexpr int sx = decltype(s_)::value;
-                    if constexpr (sx < na) ar[ih] = frag(sn, a_frag_base, ih, 0);
+                    if constexpr (sx < na) ar[ih] = fragA(sn, ih, 0);
                     else if constexpr (sx < na + nb) bq[0][b0 + sx - na] = fragB(sn, std::integral_constant<int, b0 + sx - na>{}, 0);
                     else issue_one(check_, std::integral_constant<int, d0 + sx - na - nb>{}, kt_load, buf);
                 };
@@ -890,7 +942,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
         issue_tile(std::true_type{}, 0, 0);
         issue_tile(std::true_type{}, 1, 1);
         pipeline_barrier<DMA_PER_TILE>();
-        static_for<RA - 1>([&](auto i) { ar[i] = frag(smem, a_frag_base, i, 0); });
+        static_for<RA - 1>([&](auto i) { ar[i] = fragA(smem, i, 0); });
         static_for<NI>([&](auto ni) { bq[0][ni] = fragB(smem, ni, 0); });
         const int KT_full = k_tail ? KT - 1 : KT;
         int kt = 0;
@@ -1005,8 +1057,8 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
                 auto side = [&](auto s_) __attribute__((always_inline)) {
                     constexpr int sx = decltype(s_)::value;
                     if constexpr (sx == 0) {
-                        if constexpr (ia < MI) ar[ia % RA] = frag(sc, a_frag_base, ia, KK);
-                        else ar[ia % RA] = frag(sn, a_frag_base, ia - MI, KN);
+                        if constexpr (ia < MI) ar[ia % RA] = fragA(sc, ia, KK);
+                        else ar[ia % RA] = fragA(sn, ia - MI, KN);
                     } else if constexpr (sx <= nb) {
                         bq[1 - PB][b0 + sx - 1] = fragB(sn, std::integral_constant<int, b0 + sx - 1>{}, KN);
                     } else {
@@ -1017,6 +1069,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
                 // accumulator, which is what the row-major store wants.  The side instructions go
                 // out one (or their even share) behind each MFMA, so that none of the gaps between
                 // two MFMAs grows longer than the MFMA itself.
+                a_ready();
                 static_for<NI>([&](auto ni_) {
                     constexpr int ni = decltype(ni_)::value;
                     mfma16<Cfg::F16>(acc[mi][ni], bq[PB][ni], ar[mi % RA]);
@@ -1045,7 +1098,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
         // prologue: k-tiles 0 .. STAGES-2 on their way, k-tile 0 landed, first fragments in registers
         static_for<STAGES - 1>([&](auto s_) { issue_tile(std::true_type{}, decltype(s_)::value, decltype(s_)::value); });
         pipeline_barrier<(STAGES - 2) * DMA_PER_TILE>();
-        static_for<RA - 1>([&](auto i) { ar[i] = frag(smem, a_frag_base, i, 0); });
+        static_for<RA - 1>([&](auto i) { ar[i] = fragA(smem, i, 0); });
         static_for<NI>([&](auto ni) { bq[0][ni] = fragB(smem, ni, 0); });
 
         const int KT_full = k_tail ? KT - 1 : KT;                  // complete k-tiles: loads skip the K-tail test

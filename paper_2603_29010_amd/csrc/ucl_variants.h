@@ -9,7 +9,7 @@ struct VariantDesc {
     int f16;            // 1: fp16 inputs, 0: bf16 inputs
     int mode;           // 0 gemm / batched, 1 grouped, 2 conv2d fprop
     int la, lb;         // 0: operand contiguous along K, 1: contiguous along M / N (register transpose); A only: 2 im2col gather,
-                        // 3 resident patch; B only: 4 contiguous along N, copied directly and read through the LDS transpose read
+                        // 3 resident patch; 4 (B) / 5 (A): contiguous along N / M, copied directly and read through the LDS transpose read
     int lds_bytes;
     hipError_t (*launch)(const KParams &p, const GroupTable *gt, int grid, hipStream_t stream);
 };
@@ -36,5 +36,7 @@ VariantList variants_conv_f16();
 VariantList variants_conv_halo();
 VariantList variants_gemm_kn_bf16();
 VariantList variants_gemm_kn_f16();
+VariantList variants_gemm_mx_bf16();
+VariantList variants_gemm_mx_f16();
 
 }  // namespace ucl

@@ -81,6 +81,22 @@ def test_gemm_exact_n_contiguous_b_direct(dt):
     parity.check(spec, None, label="row/row table choice")
 
 
+# A column-major (contiguous along M) copied the same way, with B contiguous along K or along N.
+@pytest.mark.parametrize("b_layout", ["col", "row"])
+@pytest.mark.parametrize("dt", ["bf16", "f16"])
+def test_gemm_exact_m_contiguous_a_direct(dt, b_layout):
+    f16 = int(dt == "f16")
+    lb = 4 if b_layout == "row" else 0
+    for tile in built(0, f16=f16, la=5, lb=lb):
+        for (M, N, K) in ((328, 264, 200), (72, 520, 40), (264, 136, 8), (520, 392, 416)):
+            spec = synth.gemm_spec(M, N, K, dt_in=dt, dt_out="f32", a_layout="col", b_layout=b_layout, epilogue=(), integer=True)
+            parity.check_exact(spec, T(*tile), label=f"col/{b_layout} {tile} {M}x{N}x{K}")
+    spec = synth.gemm_spec(520, 392, 264, dt_in=dt, a_layout="col", b_layout=b_layout, epilogue=("bias", "gelu_tanh"))
+    for tile in built(0, f16=f16, la=5, lb=lb):
+        parity.check(spec, T(*tile), label=f"col/{b_layout} fp {tile}")
+    parity.check(spec, None, label=f"col/{b_layout} table choice")
+
+
 @pytest.mark.parametrize("shape", [(1, 8, 8), (8, 1, 8), (7, 5, 16), (64, 64, 64), (65, 63, 64), (1, 1, 8)])
 def test_gemm_exact_degenerate_shapes(shape):
     M, N, K = shape
