@@ -6,6 +6,7 @@ static const VariantDesc kTable[] = {
     describe<KernelCfg<256, 128, 32, 3, false, 0, kKContig, kNDirect>>(),
     describe<KernelCfg<128, 128, 32, 4, false, 0, kKContig, kNDirect>>(),
     describe<KernelCfg<64, 64, 32, 3, false, 0, kKContig, kNDirect>>(),
+    describe<KernelCfg<64, 64, 64, 4, false, 0, kKContig, kNDirect>>(),
 };
 VariantList variants_gemm_kn_bf16() { return {kTable, (int)(sizeof(kTable) / sizeof(kTable[0]))}; }
 }  // namespace ucl
