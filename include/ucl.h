@@ -158,7 +158,9 @@ ucl_status ucl_batched_gemm(int64_t batch, int64_t M, int64_t N, int64_t K,
  * (so the grid can be sized without a device round trip); M_g[g] == 0 is legal
  * and skips the group.  A_g, B_g, D_g are DEVICE arrays of `groups` device
  * pointers (the per-group pointer table); strides are shared by all groups.
- * groups <= UCL_MAX_GROUPS, M_g[g] < 2^31. */
+ * A is row-major (a_cs == 1); B is column-major (b_rs == 1, stored [N][K]) or
+ * row-major (b_cs == 1, stored [K][N], N a multiple of 8, each group's B below
+ * 2 GiB).  groups <= UCL_MAX_GROUPS, M_g[g] < 2^31. */
 ucl_status ucl_grouped_gemm(int32_t groups, const int64_t *M_g, int64_t N, int64_t K,
                             const void *const *A_g, int32_t dtA, int64_t a_rs, int64_t a_cs,
                             const void *const *B_g, int32_t dtB, int64_t b_rs, int64_t b_cs,

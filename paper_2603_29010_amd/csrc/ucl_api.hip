@@ -29,7 +29,7 @@ ucl_status fail(ucl_status st, const char *fmt, ...) {
 const std::vector<VariantDesc> &all_variants() {
     static const std::vector<VariantDesc> v = [] {
         std::vector<VariantDesc> out;
-        for (VariantList l : {variants_gemm_kk_bf16_a(), variants_gemm_kk_bf16_b(), variants_gemm_kk_bf16_c(), variants_gemm_kk_bf16_d(), variants_gemm_kk_f16_a(), variants_gemm_kk_f16_b(), variants_gemm_mn_bf16(), variants_gemm_mn_f16(), variants_grouped_a(), variants_grouped_b(), variants_conv_a(), variants_conv_b(), variants_conv_f16(), variants_conv_halo(), variants_gemm_kn_bf16(), variants_gemm_kn_f16(), variants_gemm_mx_bf16(), variants_gemm_mx_f16()})
+        for (VariantList l : {variants_gemm_kk_bf16_a(), variants_gemm_kk_bf16_b(), variants_gemm_kk_bf16_c(), variants_gemm_kk_bf16_d(), variants_gemm_kk_f16_a(), variants_gemm_kk_f16_b(), variants_gemm_mn_bf16(), variants_gemm_mn_f16(), variants_grouped_a(), variants_grouped_b(), variants_conv_a(), variants_conv_b(), variants_conv_f16(), variants_conv_halo(), variants_gemm_kn_bf16(), variants_gemm_kn_f16(), variants_gemm_mx_bf16(), variants_gemm_mx_f16(), variants_grouped_kn()})
             for (int i = 0; i < l.n; ++i) out.push_back(l.v[i]);
         return out;
     }();
@@ -479,16 +479,25 @@ ucl_status ucl_grouped_gemm(int32_t groups, const int64_t *M_g, int64_t N, int64
         if (M_g[g] > L.max_Mg) L.max_Mg = M_g[g];
     }
     if (ucl_status st = check_common(1, N, K, dtA, dtB, dtD, A_g, B_g, D_g)) return st;
-    if (a_cs != 1 || b_rs != 1)
-        return fail(UCL_ERR_UNSUPPORTED, "grouped_gemm is built for A row-major (a_cs == 1) and B column-major (b_rs == 1), i.e. both contiguous along K");
-    if (K % 8 || a_rs % 8 || b_cs % 8 || a_rs < K || b_cs < K)
-        return fail(UCL_ERR_UNSUPPORTED, "K=%lld and the leading strides (%lld, %lld) must be multiples of 8 and at least K", (long long)K, (long long)a_rs, (long long)b_cs);
+    if (a_cs != 1 || (b_rs != 1 && b_cs != 1))
+        return fail(UCL_ERR_UNSUPPORTED, "grouped_gemm is built for A row-major (a_cs == 1) and B column-major (b_rs == 1) or row-major (b_cs == 1)");
+    const bool b_row = b_rs != 1;             // B[k*b_rs + n]: contiguous along N
+    const int64_t ldb = b_row ? b_rs : b_cs;
+    if (K % 8 || a_rs % 8 || ldb % 8 || a_rs < K || ldb < (b_row ? N : K))
+        return fail(UCL_ERR_UNSUPPORTED, "K=%lld and the leading strides (%lld, %lld) must be multiples of 8 and at least the contiguous extent", (long long)K, (long long)a_rs, (long long)ldb);
+    if (b_row) {
+        if (N % 8) return fail(UCL_ERR_UNSUPPORTED, "B is contiguous along N=%lld, which is not a multiple of 8", (long long)N);
+        if (((K - 1) * ldb + N) * 2 >= (1ll << 31))
+            return fail(UCL_ERR_UNSUPPORTED, "a row-major B of a group must be smaller than 2 GiB (32-bit offsets)");
+        L.lb = 1;
+        L.ndirect_ok = true;
+    }
     if (d_cs != 1 || d_rs < N) return fail(UCL_ERR_UNSUPPORTED, "D must be row-major with d_rs >= N");
     KParams kp;
     memset(&kp, 0, sizeof(kp));
     if (ucl_status st = check_epilogue(epi, L, kp)) return st;
     kp.A_g = A_g; kp.B_g = B_g; kp.D_g = D_g;
-    kp.lda = a_rs; kp.ldb = b_cs; kp.ldd = d_rs;
+    kp.lda = a_rs; kp.ldb = ldb; kp.ldd = d_rs;
     kp.N = (int32_t)N; kp.K = (int32_t)K; kp.groups = groups; kp.dtD = dtD;
     kp.d_vec = d_rs % (16 / elem_size(dtD)) == 0;      // group base pointers are required to be 16-byte aligned
     return run(L, kp, nullptr, tune, stream);

@@ -38,5 +38,6 @@ VariantList variants_gemm_kn_bf16();
 VariantList variants_gemm_kn_f16();
 VariantList variants_gemm_mx_bf16();
 VariantList variants_gemm_mx_f16();
+VariantList variants_grouped_kn();
 
 }  // namespace ucl

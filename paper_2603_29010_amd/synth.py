@@ -184,8 +184,9 @@ def grouped_sizes(groups, seed, lo=128, step=64, count=31):
 
 
 def grouped_spec(M_g, N, K, dt_in="bf16", dt_out="bf16", scale=None, epilogue=("silu",),
-                 seed=BASE_SEED + 4, integer=False):
-    """Grouped GEMM: A packed [sum M_g, K] (row-major), one B per group stored [N,K], D packed."""
+                 seed=BASE_SEED + 4, integer=False, b_layout="col"):
+    """Grouped GEMM: A packed [sum M_g, K] (row-major), one B per group stored [N,K] (column-major B,
+    the default) or [K,N] (b_layout="row"), D packed."""
     if scale is None:
         scale = 1.0 / math.sqrt(K)
     G = len(M_g)
@@ -197,10 +198,11 @@ def grouped_spec(M_g, N, K, dt_in="bf16", dt_out="bf16", scale=None, epilogue=("
         return normal(seed, tid, n) * scale
 
     A = to_bits(draw(1, tot * K), dt_in).reshape(tot, K)
-    B = to_bits(draw(2, G * N * K), dt_in).reshape(G, N, K)
+    row = b_layout == "row"
+    B = to_bits(draw(2, G * N * K), dt_in).reshape((G, K, N) if row else (G, N, K))
     spec = {
         "op": "grouped_gemm", "M_g": list(M_g), "N": N, "K": K, "dt_in": dt_in, "dt_out": dt_out,
-        "A": A, "a_strides": (K, 1), "B": B, "b_strides": (1, K),
+        "A": A, "a_strides": (K, 1), "B": B, "b_strides": (N, 1) if row else (1, K),
         "tensors": {}, "epilogue": [tuple([s]) if isinstance(s, str) else tuple(s) for s in epilogue],
     }
     return spec

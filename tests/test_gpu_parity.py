@@ -130,6 +130,21 @@ def test_grouped_exact_ragged_offsets():
         parity.check_exact(spec, T(*tile), label=f"grouped{tile}")
 
 
+def test_grouped_row_major_b():
+    # expert weights stored [K, N]: ragged groups, empty groups, a K tail inside a k-tile
+    M_g = [64, 0, 200, 8, 321, 0, 128, 1]
+    spec = synth.grouped_spec(M_g, 136, 72, dt_out="f32", epilogue=(), integer=True, b_layout="row")
+    for tile in built(1, lb=4):
+        parity.check_exact(spec, T(*tile), label=f"grouped row-major B {tile}")
+    spec = synth.grouped_spec([200, 72, 0, 333], 264, 200, epilogue=("silu",), b_layout="row")
+    for tile in built(1, lb=4):
+        parity.check(spec, T(*tile), label=f"grouped row-major B fp {tile}")
+    parity.check(spec, None, label="grouped row-major B table choice")
+    spec16 = synth.grouped_spec([200, 72, 0, 333], 264, 200, dt_in="f16", dt_out="f16", epilogue=("silu",), b_layout="row")
+    for tile in built(1, f16=1, lb=4):
+        parity.check(spec16, T(*tile), label=f"grouped f16 row-major B {tile}")
+
+
 @pytest.mark.parametrize("geom", [
     dict(Nb=2, H=9, W=7, C=16, Ko=24, R=3, S=3, pad=(1, 1)),
     dict(Nb=1, H=12, W=10, C=8, Ko=8, R=5, S=3, pad=(2, 0), stride=(2, 1)),
