@@ -95,6 +95,12 @@ def test_gemm_exact_m_contiguous_a_direct(dt, b_layout):
     for tile in built(0, f16=f16, la=5, lb=lb):
         parity.check(spec, T(*tile), label=f"col/{b_layout} fp {tile}")
     parity.check(spec, None, label=f"col/{b_layout} table choice")
+    if b_layout == "row":
+        # neither operand is contiguous along K: K need not be a multiple of 8
+        for K in (3, 20, 45):
+            spec = synth.gemm_spec(136, 72, K, dt_in=dt, dt_out="f32", a_layout="col", b_layout="row", epilogue=(), integer=True)
+            for tile in built(0, f16=f16, la=5, lb=4):
+                parity.check_exact(spec, T(*tile), label=f"col/row K={K} {tile}")
 
 
 @pytest.mark.parametrize("shape", [(1, 8, 8), (8, 1, 8), (7, 5, 16), (64, 64, 64), (65, 63, 64), (1, 1, 8)])
