@@ -852,10 +852,13 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
             return frag(sbase, a_frag_base, blk, kk);
         }
     };
-    // The compiler does not count asm LDS reads, so with kMDirect every row block first waits for all
-    // LDS reads issued so far (its own fragment was requested three row blocks earlier).
-    auto a_ready = [&]() __attribute__((always_inline)) {
-        if constexpr (LA == kMDirect) __builtin_amdgcn_s_waitcnt((0xF) | (0x3 << 14) | (0x7 << 4) | (0x0 << 8));   // lgkmcnt(0)
+    // The compiler does not count asm LDS reads, so with kMDirect a row block waits for its A fragment
+    // itself: lgkmcnt(W).  The fragment was requested RA - 1 row blocks earlier and LDS reads return in
+    // order, so it has arrived once at most W reads are outstanding, W being a number of reads known
+    // to have been issued after it (2: the two transpose reads of the previous row block's request).
+    auto a_ready = [&](auto w_) __attribute__((always_inline)) {
+        constexpr int W = decltype(w_)::value;
+        if constexpr (LA == kMDirect && W >= 0) __builtin_amdgcn_s_waitcnt((0xF) | (0x3 << 14) | (0x7 << 4) | (W << 8));
     };
     using I0 = std::integral_constant<int, 0>;
     using I1 = std::integral_constant<int, 1>;
@@ -894,9 +897,9 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
         static_assert(MI % RA == 0, "ring slots must line up across k-tiles");
         u32x4_t ar[RA], af[MI], bq[2][NI];
         // the side instructions of a row block go out one (or their even share) behind each MFMA
-        auto row_block = [&](auto mi_, const u32x4_t &a, auto pb_, auto ns_, auto &&side) __attribute__((always_inline)) {
+        auto row_block = [&](auto mi_, const u32x4_t &a, auto pb_, auto ns_, auto w_, auto &&side) __attribute__((always_inline)) {
             constexpr int mi = decltype(mi_)::value, PB = decltype(pb_)::value, NS = decltype(ns_)::value;
-            a_ready();
+            a_ready(w_);
             static_for<NI>([&](auto ni_) {
                 constexpr int ni = decltype(ni_)::value;
                 mfma16<Cfg::F16>(acc[mi][ni], bq[PB][ni], a);
@@ -920,7 +923,9 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
                     else if constexpr (sx < na + nf) af[f0 + sx - na] = fragA(sc, f0 + sx - na, 1);
                     else bq[1][b0 + sx - na - nf] = fragB(sc, std::integral_constant<int, b0 + sx - na - nf>{}, 1);
                 };
-                row_block(mi_, ar[mi % RA], I0{}, std::integral_constant<int, na + nf + nb>{}, side);
+                // (the previous row block requested a ring fragment unless it was one of the last RA - 1 of this k-step)
+                constexpr int W = (mi == 0 || mi + RA - 2 < MI) ? 2 : 0;
+                row_block(mi_, ar[mi % RA], I0{}, std::integral_constant<int, na + nf + nb>{}, std::integral_constant<int, W>{}, side);
             });
         };
         auto last_step = [&](auto check_, const char *sn, int kt_load, int buf) {
@@ -936,7 +941,8 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
                     else if constexpr (sx < na + nb) bq[0][b0 + sx - na] = fragB(sn, std::integral_constant<int, b0 + sx - na>{}, 0);
                     else issue_one(check_, std::integral_constant<int, d0 + sx - na - nb>{}, kt_load, buf);
                 };
-                row_block(mi_, af[mi], I1{}, std::integral_constant<int, na + nb + nd>{}, side);
+                // (af[] and bq[1] were complete at the barrier: no wait)
+                row_block(mi_, af[mi], I1{}, std::integral_constant<int, na + nb + nd>{}, std::integral_constant<int, -1>{}, side);
             });
         };
         issue_tile(std::true_type{}, 0, 0);
@@ -1069,7 +1075,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
                 // accumulator, which is what the row-major store wants.  The side instructions go
                 // out one (or their even share) behind each MFMA, so that none of the gaps between
                 // two MFMAs grows longer than the MFMA itself.
-                a_ready();
+                a_ready(std::integral_constant<int, 2>{});
                 static_for<NI>([&](auto ni_) {
                     constexpr int ni = decltype(ni_)::value;
                     mfma16<Cfg::F16>(acc[mi][ni], bq[PB][ni], ar[mi % RA]);
