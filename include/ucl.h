@@ -121,8 +121,10 @@ typedef enum ucl_conv_iterator {
  * tile_k (K extent of one LDS stage) is 32 or 64; stages is the number of LDS stage
  * buffers: 3 or more for operands contiguous along K (stages - 1 k-tiles are in
  * flight while one is being multiplied), or 2 with tile_k = 64 (each half of a
- * buffer is refilled as soon as it has been read); 2 for the register-transposed
- * layouts.
+ * buffer is refilled as soon as it has been read).  Operands contiguous along M / N
+ * use the same loops (their rows of k are copied directly and read back through the
+ * LDS transpose read); a slower form with 2 buffers that transposes them in registers
+ * serves matrices beyond the 2 GiB reach of 32-bit offsets.
  * Only built combinations are accepted (ucl_variant()).  raster = width, in tile rows, of the
  * bands the tile order walks column by column (1, 2, 4, 8, 16; the swizzle
  * knob's Identity1..8), 0 = table default.  The order is also XCD-aware:
