@@ -1268,11 +1268,11 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
     const int r_esz = r_dt == UCL_F32 ? 4 : 2;
     rsrc_t d_rsrc = buffer_rsrc(nullptr, 0), r_rsrc = buffer_rsrc(nullptr, 0);
     uint32_t d_lane = 0, r_lane = 0, d_row_bytes = 0, r_row_bytes = 0;
-    // fp32 output without a residual: a lane takes columns 4i..4i+3 and 4(i + LPR)..+3 of its row
+    // fp32 output without a residual or with an fp32 one: a lane takes columns 4i..4i+3 and 4(i + LPR)..+3 of its row
     // instead of 8i..8i+7, so that each of its two 128-bit stores is, across the lanes of a row, one
     // contiguous run of whole lines (and can stream); with 8 consecutive columns per lane each store
     // instruction writes every other 16 bytes.
-    const bool f_split = f.enabled && dtD == UCL_F32 && !f.has_res && LPR * 16 >= 128;
+    const bool f_split = f.enabled && dtD == UCL_F32 && (!f.has_res || (f.res_dt & 0xff) == UCL_F32) && LPR * 16 >= 128;
     const int f_colA = f_split ? (lane % LPR) * 4 : e_col, f_colB = f_split ? f_colA + LPR * 4 : e_col + 4;
     auto fast_setup = [&]() __attribute__((always_inline)) {
         const int64_t col0 = n0 + wn * WTN;
@@ -1286,7 +1286,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
         d_row_bytes = (uint32_t)(p.ldd * d_esz);
         r_row_bytes = (uint32_t)(f.res_ld * r_esz);
         d_lane = e_row * d_row_bytes + f_colA * d_esz;
-        r_lane = e_row * r_row_bytes + e_col * r_esz;
+        r_lane = e_row * r_row_bytes + f_colA * r_esz;        // (f_colA != e_col only with an fp32 residual)
     };
     // passes whose operands are requested together (all of a block where registers allow)
     constexpr int FG = Cfg::MIN_WAVES >= 2 && PASSES > 2 ? 2 : PASSES;
@@ -1337,8 +1337,9 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
                     static_for<FGX>([&](auto u) { r_hi[u] = rr.hi[P0 + u]; });
                 } else if (r_dt == UCL_F32) {
                     const uint32_t r0 = r_lane + mi * 32 * r_row_bytes;
+                    const uint32_t hi_off = f_split ? LPR * 16 : 16;       // second column group of the lane
                     static_for<FGX>([&](auto u) {
-                        r_hi[u] = __builtin_amdgcn_raw_buffer_load_b128(r_rsrc, r0 + (P0 + u) * RPP * r_row_bytes + 16, 0, kAuxStream);
+                        r_hi[u] = __builtin_amdgcn_raw_buffer_load_b128(r_rsrc, r0 + (P0 + u) * RPP * r_row_bytes + hi_off, 0, kAuxStream);
                     });
                 }
             }
@@ -1404,7 +1405,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
             default: break;
             }
             if (dtD == UCL_F32) {
-                if (!HAS_RES && f_split) {
+                if (f_split) {
                     static_for<FGX>([&](auto u) {
                         const uint32_t off = d0 + (P0 + u) * RPP * d_row_bytes;
                         __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, f32x4_t{v[u][0], v[u][1], v[u][2], v[u][3]}), d_rsrc, off, 0, kAuxStore);
@@ -1438,13 +1439,16 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
     };
 
     if (f.enabled) {
+        // uniform per wave: all 8-column groups of the wave exist and every access may be 128-bit
+        const bool fast_ok = dvec && (n0 + wn * WTN + WTN <= p.N) && (!f.has_res || (f.res_dt & 0x100)) &&
+                             (!f.has_bias || (f.bias_dt & 0x100));
 #pragma unroll
         for (int e = 0; e < 8; ++e) bias8[e] = 0.f;
         if (f.has_bias) {
             const void *bp = group >= 0 ? ((const void *const *)f.bias)[group] : f.bias;
             decode8(load8(bp, f.bias_dt & 0xff, c.n, (f.bias_dt & 0x100) != 0, n_left), f.bias_dt & 0xff, bias8);
-            // (the split column mapping is only used where all of the wave's columns exist: see fast_ok)
-            if (f_split && dvec && (n0 + wn * WTN + WTN <= p.N) && (f.bias_dt & 0x100)) {
+            // (the split column mapping belongs to the fast form of the block)
+            if (f_split && fast_ok) {
                 const int64_t nb = n0 + wn * WTN;
                 const int bdt = f.bias_dt & 0xff;
 #pragma unroll
@@ -1460,9 +1464,6 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
             res_base = res_u + (int64_t)c.n * r_esz;
         }
         if (f.has_scale) alpha = f.alpha;
-        // uniform per wave: all 8-column groups of the wave exist and every access may be 128-bit
-        const bool fast_ok = dvec && (n0 + wn * WTN + WTN <= p.N) && (!f.has_res || (f.res_dt & 0x100)) &&
-                             (!f.has_bias || (f.bias_dt & 0x100));
         if (fast_ok) {
             fast_setup();
             // All block loops of the epilogue are REAL loops: their bodies are re-executed from the
