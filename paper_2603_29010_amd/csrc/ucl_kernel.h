@@ -1053,6 +1053,9 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
                          int fill_buf) {
             constexpr int PB = decltype(pb_)::value, KK = decltype(kk_)::value, KN = decltype(kn_)::value;
             constexpr int DN = decltype(dn_)::value;
+            // A k-step that issues no copies is not behind the k-tile's barrier: its directly copied B
+            // fragments were requested with asm reads during the previous k-step, so it waits itself.
+            if constexpr (LB == kNDirect && DN == 0) __builtin_amdgcn_s_waitcnt((0xF) | (0x3 << 14) | (0x7 << 4) | (0x0 << 8));   // lgkmcnt(0)
             static_for<MI>([&](auto mi_) {
                 constexpr int mi = decltype(mi_)::value;
                 constexpr int ia = mi + RA - 1;                    // A fragment requested in this row block
