@@ -410,6 +410,9 @@ __device__ __forceinline__ void mfma16(f32x4_t &c, const u32x4_t &a, const u32x4
 // Forces the accumulator to hold its value in an accumulation register at this point of the program.
 __device__ __forceinline__ void pin_acc(f32x4_t &c) { asm volatile("" : "+a"(c)); }
 
+// Keeps a fragment register allocated up to this point of the program (see drain_asm_reads).
+__device__ __forceinline__ void keep_alive(const u32x4_t &x) { asm volatile("" ::"v"(x)); }
+
 // First of the n items dealt to row block mi when they are spread over the first half of the
 // mblocks row blocks.
 constexpr int bshare(int mi, int mblocks, int n) {
@@ -964,6 +967,15 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
             ktile2(std::false_type{}, I1{});
         }
         while (kt < KT) ktile2(std::true_type{}, kt & 1);
+        // The last k-tile has requested fragments of a k-tile that does not exist.  Reads issued as asm
+        // are invisible to the compiler: it would hand their destination registers to the epilogue
+        // while the data is still on its way.  Wait for them, and keep the registers allocated until then.
+        if constexpr (LA == kMDirect || LB == kNDirect) {
+            __builtin_amdgcn_s_waitcnt((0xF) | (0x3 << 14) | (0x7 << 4) | (0x0 << 8));   // lgkmcnt(0)
+            static_for<RA>([&](auto i) { keep_alive(ar[i]); });
+            static_for<MI>([&](auto i) { keep_alive(af[i]); });
+            static_for<NI>([&](auto i) { keep_alive(bq[0][i]); keep_alive(bq[1][i]); });
+        }
     } else if constexpr (LA == kHalo) {
         // ---- resident patch: 18 k-tiles (9 taps x 2 channel halves), fully unrolled ------------------
         // The same ring of A fragments and two B sets as the pipelined loop below, with every buffer
@@ -1135,6 +1147,12 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
                 cur = nxt;
                 ++kt;
             });
+        }
+        // (as at the end of the two-buffer loop: asm reads of a k-tile that does not exist are still in flight)
+        if constexpr (LA == kMDirect || LB == kNDirect) {
+            __builtin_amdgcn_s_waitcnt((0xF) | (0x3 << 14) | (0x7 << 4) | (0x0 << 8));   // lgkmcnt(0)
+            static_for<RA>([&](auto i) { keep_alive(ar[i]); });
+            static_for<NI>([&](auto i) { keep_alive(bq[0][i]); keep_alive(bq[1][i]); });
         }
     }
 
