@@ -5,6 +5,7 @@ static const VariantDesc kTable[] = {
     describe<KernelCfg<256, 256, 64, 2, false, 0, kKContig, kNDirect>>(),
     describe<KernelCfg<256, 128, 32, 3, false, 0, kKContig, kNDirect>>(),
     describe<KernelCfg<128, 128, 32, 4, false, 0, kKContig, kNDirect>>(),
+    describe<KernelCfg<128, 128, 64, 2, false, 0, kKContig, kNDirect>>(),
     describe<KernelCfg<64, 64, 32, 3, false, 0, kKContig, kNDirect>>(),
     describe<KernelCfg<64, 64, 64, 4, false, 0, kKContig, kNDirect>>(),
 };

@@ -4,10 +4,12 @@ namespace ucl {
 static const VariantDesc kTable[] = {
     describe<KernelCfg<256, 256, 64, 2, false, 0, kMDirect, kKContig>>(),
     describe<KernelCfg<128, 128, 32, 4, false, 0, kMDirect, kKContig>>(),
+    describe<KernelCfg<128, 128, 64, 2, false, 0, kMDirect, kKContig>>(),
     describe<KernelCfg<64, 64, 32, 3, false, 0, kMDirect, kKContig>>(),
     describe<KernelCfg<64, 64, 64, 4, false, 0, kMDirect, kKContig>>(),
     describe<KernelCfg<256, 256, 64, 2, false, 0, kMDirect, kNDirect>>(),
     describe<KernelCfg<128, 128, 32, 4, false, 0, kMDirect, kNDirect>>(),
+    describe<KernelCfg<128, 128, 64, 2, false, 0, kMDirect, kNDirect>>(),
     describe<KernelCfg<64, 64, 32, 3, false, 0, kMDirect, kNDirect>>(),
     describe<KernelCfg<64, 64, 64, 4, false, 0, kMDirect, kNDirect>>(),
 };

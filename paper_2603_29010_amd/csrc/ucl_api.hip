@@ -116,7 +116,8 @@ double relative_rate(const VariantDesc &v) {
     if (v.la == 3) return 0.85;                                             // conv from a resident patch: above the gather kernels
     if (area >= 256 * 256) return nd * (two_buf ? 1.00 : v.stages >= 5 ? 0.92 : 0.90);
     if (area >= 256 * 128) return nd * (two_buf ? 0.81 : v.stages == 3 ? 0.80 : 0.73);
-    if (area >= 128 * 128) return nd * (two_buf ? 0.86 : v.tile_k == 32 ? (v.stages >= 4 ? 0.67 : 0.65) : 0.58);
+    // (with a directly copied operand the two-buffer loop of this size measured below the 4-stage one)
+    if (area >= 128 * 128) return nd * (two_buf ? (nd < 1.0 ? 0.62 : 0.86) : v.tile_k == 32 ? (v.stages >= 4 ? 0.67 : 0.65) : 0.58);
     return nd * (v.tile_k == 64 ? 0.49 : v.stages == 3 ? 0.41 : 0.37);
 }
 
@@ -138,7 +139,10 @@ double estimate_seconds(const VariantDesc &v, const Launch &L) {
     // co-resident workgroups hide about half of what perfect overlap of one's fixed cost with the
     // others' MFMA time would; a CU with a single tile has nothing to overlap with
     const double exposed = per_cu > 1.0 ? 0.5 * (1.0 + 1.0 / wg) : 1.0;
-    return per_cu * (tile_flops / (relative_rate(v) * kCuRate * boost) + fixed * exposed);
+    // a variant built to share its CU runs below its rate when it has the CU to itself (one wave per SIMD
+    // with the register budget of two: measured 0.7x for 256x128 tiles)
+    const double alone = (wg >= 2 && per_cu < 2.0) ? 0.7 : 1.0;
+    return per_cu * (tile_flops / (relative_rate(v) * alone * kCuRate * boost) + fixed * exposed);
 }
 
 const VariantDesc *select_variant(const Launch &L, const ucl_tuning *tune) {
@@ -159,7 +163,7 @@ const VariantDesc *select_variant(const Launch &L, const ucl_tuning *tune) {
         if (explicit_tune) {
             if (v.tile_m != tune->tile_m || v.tile_n != tune->tile_n || v.stages != tune->stages || v.tile_k != tune->tile_k)
                 continue;
-            if (v.la == 3) return &v;                       // of two kernels with the named shape the patch one
+            if (v.la == 3 || v.la == 5 || v.lb == 4) return &v;   // of two kernels with the named shape the patch / direct-copy one
             if (!best) best = &v;
             continue;
         }
