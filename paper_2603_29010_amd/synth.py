@@ -157,18 +157,20 @@ def _add_epilogue(spec, names, draw, M, N, aux_dt, tid0=10, aux_rows=None):
 
 
 def batched_spec(batch, M, N, K, dt_in="f16", dt_out="f32", scale=1.0, epilogue=None,
-                 seed=BASE_SEED + 3, integer=False):
-    """Strided batched GEMM, A stored [b,M,K], B stored [b,N,K] (Q.K^T-like), D [b,M,N]."""
+                 seed=BASE_SEED + 3, integer=False, a_layout="row", b_layout="col"):
+    """Strided batched GEMM, A stored [b,M,K], B stored [b,N,K] (Q.K^T-like), D [b,M,N];
+    a_layout="col" stores A as [b,K,M], b_layout="row" stores B as [b,K,N] (P.V-like)."""
     def draw(tid, n):
         if integer:
             return randint(seed, tid, n, -2, 2)
         return normal(seed, tid, n) * scale
 
-    A = to_bits(draw(1, batch * M * K), dt_in).reshape(batch, M, K)
-    B = to_bits(draw(2, batch * N * K), dt_in).reshape(batch, N, K)
+    A = to_bits(draw(1, batch * M * K), dt_in).reshape((batch, M, K) if a_layout == "row" else (batch, K, M))
+    B = to_bits(draw(2, batch * N * K), dt_in).reshape((batch, N, K) if b_layout == "col" else (batch, K, N))
     spec = {
         "op": "batched_gemm", "batch": batch, "M": M, "N": N, "K": K, "dt_in": dt_in, "dt_out": dt_out,
-        "A": A, "a_strides": (K, 1, M * K), "B": B, "b_strides": (1, K, N * K),
+        "A": A, "a_strides": (K, 1, M * K) if a_layout == "row" else (1, M, M * K),
+        "B": B, "b_strides": (1, K, N * K) if b_layout == "col" else (N, 1, N * K),
         "tensors": {}, "epilogue": [],
     }
     if epilogue is None:

@@ -129,6 +129,18 @@ def test_batched_exact():
         parity.check_exact(spec, T(*tile), label=f"batched{tile}")
 
 
+@pytest.mark.parametrize("a_layout,b_layout", [("row", "row"), ("col", "col"), ("col", "row")])
+def test_batched_exact_directly_copied_layouts(a_layout, b_layout):
+    # batches advance the directly copied operands too (P.V-like: B stored [b, K, N])
+    la, lb = (5 if a_layout == "col" else 0), (4 if b_layout == "row" else 0)
+    spec = synth.batched_spec(5, 136, 200, 72, dt_in="bf16", dt_out="f32", epilogue=(), integer=True,
+                              a_layout=a_layout, b_layout=b_layout)
+    for tile in built(0, la=la, lb=lb):
+        parity.check_exact(spec, T(*tile), label=f"batched {a_layout}/{b_layout} {tile}")
+    spec = synth.batched_spec(3, 264, 136, 200, dt_in="f16", dt_out="f16", a_layout=a_layout, b_layout=b_layout)
+    parity.check(spec, None, label=f"batched {a_layout}/{b_layout} fp")
+
+
 def test_grouped_exact_ragged_offsets():
     M_g = [64, 0, 200, 8, 321, 0, 128, 1]
     spec = synth.grouped_spec(M_g, 136, 72, dt_out="f32", epilogue=(), integer=True)
