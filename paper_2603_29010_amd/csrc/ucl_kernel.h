@@ -784,6 +784,21 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
         }
     };
 
+    // Small tiles serve short, latency-bound problems: their bias vector (and, grouped, the pointer to
+    // it) is requested here, ahead of the mainloop, instead of at the head of the epilogue where the
+    // wave would sit out a memory round trip.  (The large tiles have no registers to spare for it.)
+    constexpr bool kBiasAhead = Cfg::MIN_WAVES >= 4;
+    Raw8 bias_ahead;
+    bias_ahead.lo = bias_ahead.hi = u32x4_t{0u, 0u, 0u, 0u};
+    bias_ahead.packed = false;
+    if constexpr (kBiasAhead) {
+        if (p.fused.enabled && p.fused.has_bias) {
+            const int n_first = n0 + wn * Cfg::WTN + (lane % (Cfg::WTN / 8)) * 8;
+            const void *bp = MODE == 1 ? ((const void *const *)p.fused.bias)[group] : p.fused.bias;
+            bias_ahead = load8(bp, p.fused.bias_dt & 0xff, n_first, (p.fused.bias_dt & 0x100) != 0, p.N - n_first);
+        }
+    }
+
     // ---- accumulators and fragment addressing -----------------------------------------------
     f32x4_t acc[MI][NI];
     static_for<MI>([&](auto mi) {
@@ -1467,7 +1482,8 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
         for (int e = 0; e < 8; ++e) bias8[e] = 0.f;
         if (f.has_bias) {
             const void *bp = group >= 0 ? ((const void *const *)f.bias)[group] : f.bias;
-            decode8(load8(bp, f.bias_dt & 0xff, c.n, (f.bias_dt & 0x100) != 0, n_left), f.bias_dt & 0xff, bias8);
+            if constexpr (kBiasAhead) decode8(bias_ahead, f.bias_dt & 0xff, bias8);
+            else decode8(load8(bp, f.bias_dt & 0xff, c.n, (f.bias_dt & 0x100) != 0, n_left), f.bias_dt & 0xff, bias8);
             // (the split column mapping belongs to the fast form of the block)
             if (f_split && fast_ok) {
                 const int64_t nb = n0 + wn * WTN;
