@@ -1,20 +1,33 @@
 #!/usr/bin/env python3
 """Benchmark of the hot path on one MI355X.
 
-Default workload (config 2 of the baseline): single GEMM M=N=K=4096, A row-major / B column-major
+Headline workload (config 2 of the baseline): single GEMM M=N=K=4096, A row-major / B column-major
 bf16, fp32 accumulate, fused bias + tanh-GELU epilogue, bf16 output.  A "step" is one pass of the
 whole path: one ucl_gemm call (tile schedule, staged copies, MFMA mainloop, fused epilogue, store)
 on inputs already resident in HBM.  Prints ONE JSON line on stdout.
 
-  python bench.py [--steps K] [--warmup W] [--config {1..5}] [--all] [--no-cpu-baseline]
+  python bench.py [--steps K] [--warmup W] [--replays R] [--config {1..5}] [--headline-only]
+                  [--no-cpu-baseline] [--eager]
 
---all adds a "configs" object with the other four workloads (each timed the same way, HBM-cold by
-rotating over distinct buffer sets for the memory-bound ones).
+Timing protocol (the same for every workload):
+  1. spin-up: the workload is launched back to back for SPIN_UP_SECONDS regardless of --warmup, so
+     that the engine clock has left its idle state and settled under load (the first ~100 launches
+     after idle run 20-25 % slower); the engine clock is sampled from sysfs meanwhile;
+  2. W untimed warm-up steps;
+  3. K steps are recorded once into a HIP graph (kernel nodes only), replayed once untimed, then
+     replayed R times, each replay bracketed by its own pair of HIP events on the launch stream;
+     ms_per_step is the MEDIAN over the R replays of (replay time / K), with the minimum beside it.
+Memory-bound workloads rotate over enough distinct operand sets that no launch finds its inputs in
+the 256 MB last-level cache.  The line carries a "configs" object with all five workloads, each with
+its own roofline entry, unless --headline-only is given.
 """
 import argparse
+import glob
 import json
 import os
+import statistics
 import sys
+import threading
 import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
@@ -22,12 +35,14 @@ sys.path.insert(0, ROOT)
 
 PEAK_MFMA_TFLOPS = 2516.6      # dense bf16 / fp16, 256 CUs x 2.4 GHz x 4096 FLOP/clk
 PEAK_HBM_GBPS = 8000.0
+PEAK_SCLK_MHZ = 2400.0
+SPIN_UP_SECONDS = 0.5
 # HBM bytes moved per launch (read + written) as counted by rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
-# each scaled by what the same counter reads for a plain 256 MiB device copy (2.000 and 1.000); the
-# runs and their commands are recorded in profiles/ucl_tile_kernel_*.txt.  Counters cannot be read
-# from inside this process, so these are the recorded figures for the kernels the selection table
-# picks for each workload.
-MEASURED_TRAFFIC_BYTES = {1: 1117221, 2: 235344518, 3: 84282176, 4: 525390133, 5: 66129995}
+# each scaled by what the same counter reads for a plain 256 MiB device copy (2.000 and 1.000).
+# Counters cannot be read from inside this process: these are the figures RECORDED in
+# profiles/ucl_tile_kernel_*.txt (with the commands that produced them) for the kernels the selection
+# table picks, not measurements of the run that prints them.
+RECORDED_TRAFFIC_BYTES = {1: 1117221, 2: 235344518, 3: 84282176, 4: 525390133, 5: 66129995}
 WORKLOAD_NAMES = {
     1: "gemm_256x256x256_bf16_bias_relu",
     2: "gemm_4096x4096x4096_bf16_rowcol_bias_gelu_tanh",
@@ -37,9 +52,106 @@ WORKLOAD_NAMES = {
 }
 
 
-def time_workload(cfg, steps, warmup, copies=None, use_graph=True):
-    """Time `steps` back-to-back launches with HIP events on the launch stream."""
+class SclkSampler:
+    """Polls the engine clock the driver reports (pp_dpm_sclk, the level marked '*') while a
+    workload runs.  Best effort: where the file is missing or unreadable the result is None."""
+
+    def __init__(self):
+        self.paths = sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk"))
+        self.samples = []
+        self._stop = threading.Event()
+        self._thread = None
+
+    def _read(self):
+        for p in self.paths:
+            try:
+                for line in open(p):
+                    if "*" in line:
+                        return float(line.split(":")[1].lower().replace("mhz", "").replace("*", "").strip())
+            except (OSError, ValueError, IndexError):
+                continue
+        return None
+
+    def __enter__(self):
+        if self.paths:
+            def loop():
+                while not self._stop.is_set():
+                    v = self._read()
+                    if v:
+                        self.samples.append(v)
+                    time.sleep(0.02)
+            self._thread = threading.Thread(target=loop, daemon=True)
+            self._thread.start()
+        return self
+
+    def __exit__(self, *a):
+        self._stop.set()
+        if self._thread:
+            self._thread.join()
+
+    def median(self):
+        return statistics.median(self.samples) if self.samples else None
+
+
+def timed_replays(run_step, steps, warmup, replays, use_graph=True):
+    """Spin-up, warm-up, then `replays` timed passes of `steps` launches.  run_step(i) enqueues step
+    i on torch's current stream.  Returns (per-step ms of every replay, launch kind, sclk MHz)."""
     import torch
+    stream = torch.cuda.current_stream()
+    with SclkSampler() as sclk:
+        t0 = time.perf_counter()
+        i = 0
+        while time.perf_counter() - t0 < SPIN_UP_SECONDS:
+            for _ in range(50):
+                run_step(i)
+                i += 1
+            torch.cuda.synchronize()
+    for i in range(warmup):
+        run_step(i)
+    torch.cuda.synchronize()
+    launch, graph = "eager", None
+    if use_graph:
+        # the K launches recorded once into a HIP graph (kernel nodes only: the library issues no
+        # memset or copy), so that the host's per-call cost cannot limit back-to-back short kernels
+        try:
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                for i in range(steps):
+                    run_step(i)
+            graph.replay()                       # untimed first replay
+            torch.cuda.synchronize()
+            launch = "hipgraph"
+        except Exception as e:                   # capture unsupported: fall back to plain launches
+            print(f"bench.py: graph capture failed ({e}); timing eager launches", file=sys.stderr)
+            graph = None
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(replays)]
+    for a, b in pairs:
+        a.record(stream)
+        if graph is not None:
+            graph.replay()
+        else:
+            for i in range(steps):
+                run_step(i)
+        b.record(stream)
+    torch.cuda.synchronize()
+    return [a.elapsed_time(b) / steps for a, b in pairs], launch, sclk.median()
+
+
+def launch_floor_us(steps, replays):
+    """Per-launch time of the smallest launch the library can make (a one-element transform-stage
+    call: one workgroup, one load, one store), timed like the workloads: the floor under any kernel."""
+    import torch
+    import paper_2603_29010_amd as ucl
+    src = torch.zeros(4, dtype=torch.float32, device="cuda")
+    dst = torch.zeros(4, dtype=torch.float32, device="cuda")
+
+    def run(i):
+        ucl.ucl_transpose(1, 1, 1, src.data_ptr(), "f32", dst.data_ptr(), "f32", torch.cuda.current_stream().cuda_stream)
+    ms, _, _ = timed_replays(run, steps, 5, replays)
+    return statistics.median(ms) * 1e3
+
+
+def time_workload(cfg, steps, warmup, replays, copies=None, use_graph=True):
     from paper_2603_29010_amd import synth
     from paper_2603_29010_amd.workload import DeviceWorkload
     spec = synth.config(cfg)
@@ -50,64 +162,57 @@ def time_workload(cfg, steps, warmup, copies=None, use_graph=True):
         # served from the 256 MB last-level cache left warm by the previous one
         copies = 1 if sol["compute_bound"] else max(2, int(768e6 // sol["bytes"]) + 1)
     sets = [probe] + [DeviceWorkload(spec, poison=False) for _ in range(copies - 1)]
-    for i in range(warmup):
-        sets[i % copies].run()
-    torch.cuda.synchronize()
-    start = torch.cuda.Event(enable_timing=True)
-    stop = torch.cuda.Event(enable_timing=True)
-    launch = "eager"
-    graph = None
-    if use_graph:
-        # record the K launches once into a HIP graph (kernel nodes only: the library issues no memset
-        # or copy), so that the host's per-call cost cannot limit back-to-back short kernels
-        try:
-            graph = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(graph):
-                for i in range(steps):
-                    sets[i % copies].run()
-            graph.replay()                       # untimed first replay
-            torch.cuda.synchronize()
-            launch = "hipgraph"
-        except Exception as e:                   # capture unsupported: fall back to plain launches
-            print(f"bench.py: graph capture failed ({e}); timing eager launches", file=sys.stderr)
-            graph = None
-    stream = torch.cuda.current_stream()
-    start.record(stream)
-    if graph is not None:
-        graph.replay()
-    else:
-        for i in range(steps):
-            sets[i % copies].run()
-    stop.record(stream)
-    torch.cuda.synchronize()
-    ms = start.elapsed_time(stop) / steps
+    per_step, launch, sclk = timed_replays(lambda i: sets[i % copies].run(), steps, warmup, replays, use_graph)
+    ms = statistics.median(per_step)
     t = ms * 1e-3
+    mfma = bool(sol["compute_bound"])
+    tflops, gbps = sol["flops"] / t / 1e12, sol["bytes"] / t / 1e9
     res = {
-        "workload": WORKLOAD_NAMES[cfg], "ms_per_step": ms, "tflops": sol["flops"] / t / 1e12,
-        "gbps": sol["bytes"] / t / 1e9, "flops": sol["flops"], "bytes": sol["bytes"],
+        "workload": WORKLOAD_NAMES[cfg], "ms_per_step": ms, "ms_per_step_min": min(per_step),
+        "ms_per_step_max": max(per_step), "tflops": tflops, "gbps": gbps, "flops": sol["flops"], "bytes": sol["bytes"],
         "t_sol_us": sol["t_sol"] * 1e6, "frac_of_sol": sol["t_sol"] / t,
-        "bound": "mfma" if sol["compute_bound"] else "hbm", "buffer_sets": copies, "launch": launch,
+        "buffer_sets": copies, "launch": launch, "kernel": probe.selected(),
+        "roofline": {
+            "bound": "mfma" if mfma else "hbm", "achieved": tflops if mfma else gbps,
+            "peak": PEAK_MFMA_TFLOPS if mfma else PEAK_HBM_GBPS, "unit": "TFLOP/s" if mfma else "GB/s",
+            "frac": (tflops / PEAK_MFMA_TFLOPS) if mfma else (gbps / PEAK_HBM_GBPS),
+            "traffic": RECORDED_TRAFFIC_BYTES.get(cfg), "traffic_source": "recorded in profiles/ (rocprofv3 --pmc), not read in this run",
+        },
+        # integrity self-check (the paper's SOL-ceiling detector): nothing can beat the bound by > 10 %
+        "below_sol_flag": bool(min(per_step) * 1e-3 < 0.9 * sol["t_sol"]),
+        "sclk_mhz_under_load": sclk,
     }
+    if sclk:
+        # the paper's report scales the compute peak by current / maximum clock
+        scaled = probe.sol(hw={"peak_flops_16bit": PEAK_MFMA_TFLOPS * 1e12, "peak_flops_f32": 157.3e12,
+                               "peak_bw": PEAK_HBM_GBPS * 1e9, "compute_clock_ratio": min(1.0, sclk / PEAK_SCLK_MHZ)})
+        res["t_sol_clock_scaled_us"] = scaled["t_sol"] * 1e6
+        res["frac_of_clock_scaled_sol"] = scaled["t_sol"] / t
     if spec["op"] == "grouped_gemm":
         res["sum_M"] = int(sum(spec["M_g"]))
-    # integrity self-check (the paper's SOL-ceiling detector): nothing can beat the bound by > 10 %
-    res["below_sol_flag"] = bool(t < 0.9 * sol["t_sol"])
     return res, spec, probe
 
 
-def cpu_baseline(spec, cfg):
-    """The fp64 oracle, as it stands, on a bounded sample of the same workload."""
+def cpu_baseline(spec, cfg, probe):
+    """The fp64 oracle, as it stands, on a bounded sample of the same workload; what it computes is
+    compared with the GPU output of the same rows (the test suite's two tolerances)."""
     from oracle import run_spec
     import numpy as np
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    import parity
+    probe.run()
+    got_all = probe.result()
     if spec["op"] in ("gemm", "conv2d_fprop"):
         M = spec["M"]
         n = {1: M, 2: 4096, 5: 50176}.get(cfg, min(M, 1024))
         rows = list(range(0, M, max(1, M // n)))[:n]
         t0 = time.perf_counter()
-        run_spec.run(spec, rows=rows)
+        ref, absacc = run_spec.run(spec, rows=rows, want_abs=True)
         dt = time.perf_counter() - t0
         flops = 2.0 * len(rows) * spec["N"] * spec["K"]
         sample = f"{len(rows)} of {M} output rows (every {max(1, M // n)}th), all {spec['N']} columns"
+        got = got_all[np.asarray(rows)]
+        sub = spec
     else:
         import copy
         sub = copy.copy(spec)
@@ -116,18 +221,27 @@ def cpu_baseline(spec, cfg):
             sub["A"], sub["B"] = spec["A"][:16], spec["B"][:16]
             flops = 2.0 * 16 * spec["M"] * spec["N"] * spec["K"]
             sample = f"16 of {spec['batch']} batches"
+            got = got_all[:16]
         else:
             sub["M_g"] = [128] * len(spec["M_g"])
             offs = np.concatenate([[0], np.cumsum(spec["M_g"])])[:-1]
             sub["A"] = np.concatenate([spec["A"][o:o + 128] for o in offs])
             flops = 2.0 * 128 * len(spec["M_g"]) * spec["N"] * spec["K"]
             sample = "first 128 rows of each of the 16 groups"
+            got = np.concatenate([got_all[o:o + 128] for o in offs])
         t0 = time.perf_counter()
-        run_spec.run(sub)
+        ref, absacc = run_spec.run(sub, want_abs=True)
         dt = time.perf_counter() - t0
     cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
-    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
-            "sample": sample, "seconds": dt}
+    out = {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+           "sample": sample, "seconds": dt}
+    try:
+        out["gpu_vs_oracle_max_err"] = parity.compare(got.reshape(ref.shape), ref, absacc, sub, "bench")
+        out["gpu_matches_oracle"] = bool(np.all(np.isfinite(got_all)))
+    except AssertionError as e:
+        out["gpu_matches_oracle"] = False
+        out["gpu_vs_oracle_error"] = str(e)[:300]
+    return out
 
 
 TRANSPOSE_WORKLOAD = {"name": "transpose_nchw_to_nhwc_64x256x56x56_f32_to_bf16", "batch": 64, "rows": 256, "cols": 56 * 56,
@@ -153,39 +267,18 @@ def bench_transpose(args):
     def run(i):
         ucl.ucl_transpose(w["batch"], w["rows"], w["cols"], srcs[i % copies].data_ptr(), w["dt_src"],
                           dsts[i % copies].data_ptr(), w["dt_dst"], torch.cuda.current_stream().cuda_stream)
-    for i in range(args.warmup):
-        run(i)
-    torch.cuda.synchronize()
-    launch = "eager"
-    graph = None
-    if not args.eager:
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            for i in range(args.steps):
-                run(i)
-        graph.replay()
-        torch.cuda.synchronize()
-        launch = "hipgraph"
-    start = torch.cuda.Event(enable_timing=True)
-    stop = torch.cuda.Event(enable_timing=True)
-    stream = torch.cuda.current_stream()
-    start.record(stream)
-    if graph is not None:
-        graph.replay()
-    else:
-        for i in range(args.steps):
-            run(i)
-    stop.record(stream)
-    torch.cuda.synchronize()
-    ms = start.elapsed_time(stop) / args.steps
+    per_step, launch, sclk = timed_replays(run, args.steps, args.warmup, args.replays, not args.eager)
+    ms = statistics.median(per_step)
     gbps = nbytes / (ms * 1e-3) / 1e9
     out = {
         "metric": "GB/s of algorithmic bytes (elements x (source + destination size)), transpose with conversion, 1 MI355X",
-        "value": gbps, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+        "value": gbps, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "replays": args.replays,
+        "ms_per_step": ms, "ms_per_step_min": min(per_step),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": w["name"], "buffer_sets": copies, "launch": launch, "bytes": nbytes},
+        "config": {"workload": w["name"], "buffer_sets": copies, "launch": launch, "bytes": nbytes,
+                   "spin_up_seconds": SPIN_UP_SECONDS},
         "roofline": {"bound": "hbm", "achieved": gbps, "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": gbps / PEAK_HBM_GBPS,
-                     "traffic": TRANSPOSE_TRAFFIC_BYTES},
+                     "traffic": TRANSPOSE_TRAFFIC_BYTES, "traffic_source": "recorded in profiles/ (rocprofv3 --pmc), not read in this run"},
     }
     if not args.no_cpu_baseline:
         import oracle
@@ -202,10 +295,12 @@ def bench_transpose(args):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--replays", type=int, default=10, help="timed replays of the K-step graph (median reported)")
     ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5])
-    ap.add_argument("--all", action="store_true", help="also time the other four workloads")
+    ap.add_argument("--headline-only", action="store_true", help="skip the per-workload 'configs' object")
+    ap.add_argument("--all", action="store_true", help="(default behaviour, kept for older command lines)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--eager", action="store_true", help="plain launches instead of one captured HIP graph")
     ap.add_argument("--transpose", action="store_true",
@@ -217,6 +312,9 @@ def main():
     if args.gpus != 1:
         print("bench.py: this build is single-GPU (the hot path is one kernel on one GPU's share of the "
               "work); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    if args.replays < 1 or args.steps < 1:
+        print("bench.py: --steps and --replays must be positive", file=sys.stderr)
         sys.exit(2)
     import torch
     if not torch.cuda.is_available():
@@ -238,35 +336,36 @@ def main():
     if args.transpose:
         bench_transpose(args)
         return
-    res, spec, _ = time_workload(args.config, args.steps, args.warmup, use_graph=not args.eager)
-    mfma = res["bound"] == "mfma"
-    roofline = {
-        "bound": res["bound"],
-        "achieved": res["tflops"] if mfma else res["gbps"],
-        "peak": PEAK_MFMA_TFLOPS if mfma else PEAK_HBM_GBPS,
-        "unit": "TFLOP/s" if mfma else "GB/s",
-        "frac": (res["tflops"] / PEAK_MFMA_TFLOPS) if mfma else (res["gbps"] / PEAK_HBM_GBPS),
-        "traffic": MEASURED_TRAFFIC_BYTES.get(args.config),
-    }
+    res, spec, probe = time_workload(args.config, args.steps, args.warmup, args.replays, use_graph=not args.eager)
     out = {
         "metric": "TFLOP/s and % of SOL (MFMA/HBM roofline) per GEMM/conv config, 1 MI355X",
         "value": res["tflops"], "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "replays": args.replays, "ms_per_step": res["ms_per_step"], "ms_per_step_min": res["ms_per_step_min"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16" if spec["dt_in"] == "f16" else "bf16", "data": "synthetic",
         "config": {"workload": res["workload"], "frac_of_sol": res["frac_of_sol"], "t_sol_us": res["t_sol_us"],
-                   "buffer_sets": res["buffer_sets"], "launch": res["launch"]},
-        "roofline": roofline,
+                   "below_sol_flag": res["below_sol_flag"], "sclk_mhz_under_load": res["sclk_mhz_under_load"],
+                   "t_sol_clock_scaled_us": res.get("t_sol_clock_scaled_us"),
+                   "frac_of_clock_scaled_sol": res.get("frac_of_clock_scaled_sol"),
+                   "buffer_sets": res["buffer_sets"], "launch": res["launch"], "kernel": res["kernel"],
+                   "spin_up_seconds": SPIN_UP_SECONDS,
+                   "timing": "median over `replays` replays of a HIP graph of `steps` launches, one HIP event pair per replay"},
+        "roofline": res["roofline"],
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(spec, args.config)
-    if args.all:
+        out["cpu_baseline"] = cpu_baseline(spec, args.config, probe)
+    if not args.headline_only:
         out["configs"] = {}
         for c in (1, 2, 3, 4, 5):
             if c == args.config:
                 out["configs"][str(c)] = res
                 continue
-            r, _, _ = time_workload(c, args.steps, args.warmup, use_graph=not args.eager)
+            del probe, spec
+            torch.cuda.empty_cache()
+            r, spec, probe = time_workload(c, args.steps, args.warmup, args.replays, use_graph=not args.eager)
             out["configs"][str(c)] = r
+        # config 1 is bound by launch latency, not by either roofline: the floor it is measured against
+        out["launch_floor_us"] = launch_floor_us(args.steps, args.replays)
     print(json.dumps(out))
 
 

@@ -28,7 +28,10 @@
  *     any strides; they are accessed with 128-bit loads / stores when base and
  *     row starts are 16-byte aligned (leading and batch strides multiples of 8
  *     for 16-bit types, of 4 for fp32), element by element otherwise.  In
- *     ucl_grouped_gemm every per-group pointer must be 16-byte aligned.
+ *     ucl_grouped_gemm the per-group pointers live on the device, where the
+ *     host cannot inspect them: every one of them must be 16-byte aligned,
+ *     except those of vectors indexed by m (PER_ROW_SCALE, COL_BROADCAST),
+ *     which are read element by element.
  *   - Errors: a nonzero ucl_status is returned BEFORE anything is launched;
  *     ucl_last_error() gives a thread-local sentence saying what was wrong and
  *     why (the paper's compiler explains failed validation the same way,
@@ -129,7 +132,7 @@ typedef enum ucl_conv_iterator {
  * bands the tile order walks column by column (1, 2, 4, 8, 16; the swizzle
  * knob's Identity1..8), 0 = table default.  The order is also XCD-aware:
  * workgroup ids that land on the same XCD (id mod 8) get neighbouring tiles.
- * iterator is a ucl_conv_iterator and is ignored by the GEMM entry points. */
+ * iterator is a ucl_conv_iterator; the GEMM entry points accept any valid value and ignore it. */
 typedef struct ucl_tuning {
     int32_t tile_m, tile_n, tile_k, stages, raster;
     int32_t iterator;
@@ -184,11 +187,6 @@ ucl_status ucl_conv2d_fprop(int64_t N, int64_t H, int64_t W, int64_t C, int64_t 
                             void *y, int32_t dtY,
                             const ucl_epilogue *epi, const ucl_tuning *tune, void *stream);
 
-/* ---- Speed-of-Light analysis (paper Sec. 4.1, four steps) ------------------ */
-
-typedef enum ucl_op_kind { UCL_OP_GEMM = 0, UCL_OP_BATCHED_GEMM = 1, UCL_OP_GROUPED_GEMM = 2,
-                           UCL_OP_CONV2D_FPROP = 3 } ucl_op_kind;
-
 /* Transform stage of a `pipeline(...)` program (grammar `transpose_op`:
  * transpose(tensor, NCL, NLC [, dtype_in, dtype_out]); NCHW <-> NHWC is the same
  * with H*W flattened into L): src is `batch` packed row-major rows x cols matrices,
@@ -196,17 +194,30 @@ typedef enum ucl_op_kind { UCL_OP_GEMM = 0, UCL_OP_BATCHED_GEMM = 1, UCL_OP_GROU
  *   dst[b][c][r] = convert(src[b][r][c]),
  * the conversion between fp32 / fp16 / bf16 exact where the target holds the value
  * and round-to-nearest-even otherwise.  NCL -> NLC: rows = C, cols = L; NHWC -> NCHW:
- * rows = H*W, cols = C.  src and dst are DEVICE pointers owned by the caller and must
- * not overlap; any extents are accepted (zero extents do nothing), 16-byte aligned
+ * rows = H*W, cols = C.  src and dst are DEVICE pointers owned by the caller; their byte
+ * ranges must not overlap (an overlap is rejected with UCL_ERR_INVALID_ARG: a transpose in
+ * place is not supported); any extents are accepted (zero extents do nothing), 16-byte aligned
  * pointers with cols*size(dt_src) and rows*size(dt_dst) multiples of 16 take the
  * 128-bit path.  Errors as for the other entry points, nothing is launched then. */
 ucl_status ucl_transpose(int64_t batch, int64_t rows, int64_t cols, const void *src, int32_t dt_src,
                          void *dst, int32_t dt_dst, void *stream);
 
+/* ---- Speed-of-Light analysis (paper Sec. 4.1, four steps) ------------------ */
+
+typedef enum ucl_op_kind { UCL_OP_GEMM = 0, UCL_OP_BATCHED_GEMM = 1, UCL_OP_GROUPED_GEMM = 2,
+                           UCL_OP_CONV2D_FPROP = 3 } ucl_op_kind;
+
+/* Which extent of a GEMM operand is contiguous in memory (`.with_layout`): A RowMajor and
+ * B ColumnMajor are contiguous along K, A ColumnMajor and B RowMajor along M / N. */
+typedef enum ucl_operand_layout { UCL_LAYOUT_K_CONTIGUOUS = 0, UCL_LAYOUT_MN_CONTIGUOUS = 1 } ucl_operand_layout;
+
 /* Problem characterisation input.  GEMM family: batch (1 for gemm), M, N, K;
  * grouped: groups and M_g (HOST), N, K.  Conv: N,H,W,C,Kout,R,S and pads,
  * strides, dilations.  dt_in / dt_out are ucl_dtype.  The epilogue matters
- * only through the bytes of its tensor operands (each read or written once). */
+ * only through the bytes of its tensor operands (each read or written once).
+ * a_layout / b_layout (ucl_operand_layout, GEMM family only) do not change the
+ * SOL figures; ucl_select_tuning needs them because the kernels built for an
+ * operand depend on its layout. */
 typedef struct ucl_problem {
     int32_t op;                 /* ucl_op_kind */
     int32_t dt_in, dt_out;
@@ -216,6 +227,7 @@ typedef struct ucl_problem {
     int64_t cN, cH, cW, cC, cKout, cR, cS;
     int64_t pad_h, pad_w, stride_h, stride_w, dil_h, dil_w;
     const ucl_epilogue *epi;    /* may be NULL; pointers inside are not dereferenced */
+    int32_t a_layout, b_layout; /* ucl_operand_layout */
 } ucl_problem;
 
 /* Hardware limits: published peaks at maximum clocks, scaled linearly by the
@@ -245,8 +257,9 @@ ucl_status ucl_sol_bound(const ucl_problem *p, const ucl_hw *hw, ucl_sol_report 
 
 /* ---- Introspection (HOST only; used by tests and the benchmark) ------------ */
 
-/* The tuning the selection table would pick for a problem (same rules the
- * launch path applies when tune == NULL). */
+/* The tuning the selection table would pick for a problem: the launch path with
+ * tune == NULL applies the same function to the same description (packed
+ * operands assumed: leading strides equal to the contiguous extents). */
 ucl_status ucl_select_tuning(const ucl_problem *p, ucl_tuning *out);
 
 /* The tile schedule, evaluated on the host with the same code the kernels run:
@@ -257,10 +270,23 @@ ucl_status ucl_select_tuning(const ucl_problem *p, ucl_tuning *out);
 ucl_status ucl_tile_map(int32_t groups, const int32_t *tiles_m, int32_t tiles_n, int32_t raster,
                         int32_t wg, int32_t *group, int32_t *tile_m, int32_t *tile_n);
 
-/* Number of kernel variants built in, and the (tile_m, tile_n, tile_k, stages,
- * iterator) of variant i; explicit ucl_tuning must name one of these. */
+/* The kernel variants built in.  An explicit ucl_tuning must name the (tile_m,
+ * tile_n, tile_k, stages[, iterator]) of a variant built for the call's operation,
+ * input type and operand layouts. */
+typedef struct ucl_variant_info {
+    int32_t tile_m, tile_n, tile_k, stages;
+    int32_t iterator;           /* ucl_conv_iterator (conv variants), else 0 */
+    int32_t op_class;           /* 0 gemm + batched_gemm, 1 grouped_gemm, 2 conv2d_fprop */
+    int32_t dt_in;              /* ucl_dtype of both inputs */
+    int32_t a_layout, b_layout; /* ucl_operand_layout the variant serves (conv: 0) */
+    int32_t a_path, b_path;     /* how the operand reaches LDS: 0 direct 128-bit copies of K-contiguous rows,
+                                   1 through registers with a transposing write (fallback for matrices beyond the
+                                   reach of 32-bit offsets), 2 per-tap gather (conv), 3 resident patch (conv),
+                                   4 / 5 direct copies of rows contiguous along N / M, read back transposed */
+    int32_t lds_bytes;          /* LDS a workgroup of the variant occupies */
+} ucl_variant_info;
 int32_t ucl_num_variants(void);
-ucl_status ucl_variant(int32_t i, ucl_tuning *out);
+ucl_status ucl_variant(int32_t i, ucl_variant_info *out);
 
 const char *ucl_status_string(ucl_status s);
 const char *ucl_last_error(void);   /* thread-local; valid until the next call on this thread */

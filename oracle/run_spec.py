@@ -10,13 +10,16 @@ _TENSOR_OPS = {"bias", "per_col_scale", "row_broadcast", "per_row_scale", "colum
                "aux_load"}
 
 
-def _chain(spec, row_offset=0, n_rows=None, batch_index=None):
-    """Resolve tensor names; matrices are sliced to the rows a sub-problem (group) covers."""
+def _chain(spec, row_offset=0, n_rows=None, group=None):
+    """Resolve tensor names; matrices and m-indexed vectors are sliced to the rows a sub-problem
+    (group) covers, and of a [groups, N padded] array of n-indexed vectors group g takes row g."""
     out = []
     for st in spec["epilogue"]:
         name = st[0]
         if name in _TENSOR_OPS:
             arr, dt = spec["tensors"][st[1]]
+            if group is not None and name in ("bias", "per_col_scale", "row_broadcast"):
+                arr = np.ascontiguousarray(arr[group, :spec["N"]])
             if name == "aux_load" and n_rows is not None:
                 arr = np.ascontiguousarray(arr[row_offset:row_offset + n_rows])
             if name in ("per_row_scale", "column_broadcast") and n_rows is not None:
@@ -47,7 +50,7 @@ def run(spec, rows=None, want_abs=False):
         offs = np.concatenate([[0], np.cumsum(M_g)]).astype(int)
         A_list = [np.ascontiguousarray(spec["A"][offs[g]:offs[g + 1]]) for g in range(len(M_g))]
         B_list = [np.ascontiguousarray(spec["B"][g]) for g in range(len(M_g))]
-        chains = [_chain(spec, offs[g], M_g[g]) for g in range(len(M_g))]
+        chains = [_chain(spec, offs[g], M_g[g], group=g) for g in range(len(M_g))]
         return grouped_gemm(A_list, spec["dt_in"], spec["a_strides"], B_list, spec["dt_in"],
                             spec["b_strides"], M_g, spec["N"], spec["K"], chains=chains,
                             want_abs=want_abs)

@@ -49,7 +49,12 @@ class _Problem(C.Structure):
                 ("cKout", C.c_int64), ("cR", C.c_int64), ("cS", C.c_int64),
                 ("pad_h", C.c_int64), ("pad_w", C.c_int64), ("stride_h", C.c_int64),
                 ("stride_w", C.c_int64), ("dil_h", C.c_int64), ("dil_w", C.c_int64),
-                ("epi", C.POINTER(_Epilogue))]
+                ("epi", C.POINTER(_Epilogue)), ("a_layout", C.c_int32), ("b_layout", C.c_int32)]
+
+
+class _VariantInfo(C.Structure):
+    _fields_ = [(k, C.c_int32) for k in ("tile_m", "tile_n", "tile_k", "stages", "iterator", "op_class", "dt_in",
+                                         "a_layout", "b_layout", "a_path", "b_path", "lds_bytes")]
 
 
 class _Hw(C.Structure):
@@ -107,7 +112,7 @@ def _load():
                                      C.POINTER(i32)]
         lib.ucl_num_variants.restype = i32
         lib.ucl_variant.restype = C.c_int
-        lib.ucl_variant.argtypes = [i32, C.POINTER(_Tuning)]
+        lib.ucl_variant.argtypes = [i32, C.POINTER(_VariantInfo)]
         lib.ucl_status_string.restype = C.c_char_p
         lib.ucl_status_string.argtypes = [C.c_int]
         lib.ucl_last_error.restype = C.c_char_p
@@ -202,8 +207,13 @@ def ucl_transpose(batch, rows, cols, src, dt_src, dst, dt_dst, stream=0):
     _check(_load().ucl_transpose(batch, rows, cols, src, _dt(dt_src), dst, _dt(dt_dst), stream or None))
 
 
-def _problem(op, dt_in, dt_out, batch=1, M=0, N=0, K=0, M_g=None, conv=None, epi=None):
+LAYOUTS = {"k": 0, "mn": 1}
+
+
+def _problem(op, dt_in, dt_out, batch=1, M=0, N=0, K=0, M_g=None, conv=None, epi=None, a_layout="k", b_layout="k"):
+    """a_layout / b_layout: "k" (operand contiguous along K: A row-major, B column-major) or "mn"."""
     p = _Problem()
+    p.a_layout, p.b_layout = LAYOUTS[a_layout], LAYOUTS[b_layout]
     p.op = OP_KINDS[op]
     p.dt_in, p.dt_out = _dt(dt_in), _dt(dt_out)
     p.batch, p.M, p.N, p.K = batch, M, N, K
@@ -255,11 +265,12 @@ def ucl_num_variants():
 
 
 def ucl_variant(i):
-    t = Tuning()
-    _check(_load().ucl_variant(i, t.ref()))
-    d = t.as_dict()
-    d["mode"], lay = t.c.reserved[0], t.c.reserved[1]
-    d["f16"], d["la"], d["lb"] = lay // 64, lay // 8 % 8, lay % 8
+    """Variant i as a dict of the ucl_variant_info fields, plus the short keys the tests filter on:
+    mode = op_class, f16 = 1 for fp16 inputs, la / lb = a_path / b_path."""
+    v = _VariantInfo()
+    _check(_load().ucl_variant(i, C.byref(v)))
+    d = {k: getattr(v, k) for k, _ in _VariantInfo._fields_}
+    d["mode"], d["f16"], d["la"], d["lb"] = v.op_class, int(v.dt_in == DTYPES["f16"]), v.a_path, v.b_path
     return d
 
 

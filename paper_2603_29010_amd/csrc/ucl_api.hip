@@ -290,14 +290,15 @@ ucl_status check_common(int64_t M, int64_t N, int64_t K, int dtA, int dtB, int d
     return UCL_OK;
 }
 
-ucl_status run(const Launch &L, KParams &kp, const GroupTable *gt_in, const ucl_tuning *tune, void *stream) {
+ucl_status run(const Launch &L, KParams &kp, const ucl_tuning *tune, void *stream) {
     if (tune && (tune->iterator < 0 || tune->iterator > UCL_ITER_FIXED_STRIDE_DILATION))
         return fail(UCL_ERR_INVALID_ARG, "iterator=%d is not a ucl_conv_iterator", tune->iterator);
-    if (tune && tune->iterator == UCL_ITER_FIXED_STRIDE_DILATION && !(L.mode == 2 && L.patch_ok))
+    // (the GEMM entry points ignore the iterator)
+    if (tune && L.mode == 2 && tune->iterator == UCL_ITER_FIXED_STRIDE_DILATION && !L.patch_ok)
         return fail(UCL_ERR_UNSUPPORTED, "the fixed_stride_dilation iterator serves conv2d_fprop with a 3x3 filter, unit stride and dilation, pad 1, 64 channels and W <= 58");
     const VariantDesc *v = select_variant(L, tune);
     if (!v) {
-        if (tune && (tune->tile_m || tune->tile_n || tune->stages)) {
+        if (tune && (tune->tile_m || tune->tile_n || tune->tile_k || tune->stages)) {
             if (tune->tile_k != 32 && tune->tile_k != 64)
                 return fail(UCL_ERR_UNSUPPORTED, "tile_k=%d: the built kernels stage K in steps of 32 or 64", tune->tile_k);
             const int64_t lds = (int64_t)(tune->tile_m + tune->tile_n) * tune->tile_k * 2 * tune->stages;
@@ -342,7 +343,6 @@ ucl_status run(const Launch &L, KParams &kp, const GroupTable *gt_in, const ucl_
         return fail(UCL_ERR_UNSUPPORTED, "B leading stride %lld too large: a %d-row panel must span less than 2 GiB", (long long)kp.ldb, v->tile_n);
     kp.total_tiles = (int32_t)total;
     if (total == 0) return UCL_OK;     // grouped with every M_g == 0: nothing to do
-    (void)gt_in;
     hipError_t e = v->launch(kp, L.mode == 1 ? &gt : nullptr, (int)total, (hipStream_t)stream);
     if (e != hipSuccess) return fail(UCL_ERR_LAUNCH, "kernel launch failed: %s", hipGetErrorString(e));
     return UCL_OK;
@@ -376,7 +376,7 @@ ucl_status gemm_like(int64_t batch, int64_t M, int64_t N, int64_t K,
     kp.M = (int32_t)M; kp.N = (int32_t)N; kp.K = (int32_t)K;
     kp.dtD = dtD;
     kp.d_vec = aligned16(D) && (d_rs % (16 / elem_size(dtD)) == 0) && (d_bs % (16 / elem_size(dtD)) == 0);
-    return run(L, kp, nullptr, tune, stream);
+    return run(L, kp, tune, stream);
 }
 
 // ---- SOL ---------------------------------------------------------------------------------------
@@ -504,7 +504,7 @@ ucl_status ucl_grouped_gemm(int32_t groups, const int64_t *M_g, int64_t N, int64
     kp.lda = a_rs; kp.ldb = ldb; kp.ldd = d_rs;
     kp.N = (int32_t)N; kp.K = (int32_t)K; kp.groups = groups; kp.dtD = dtD;
     kp.d_vec = d_rs % (16 / elem_size(dtD)) == 0;      // group base pointers are required to be 16-byte aligned
-    return run(L, kp, nullptr, tune, stream);
+    return run(L, kp, tune, stream);
 }
 
 ucl_status ucl_conv2d_fprop(int64_t N, int64_t H, int64_t W, int64_t C, int64_t Kout, int64_t R, int64_t S,
@@ -539,7 +539,7 @@ ucl_status ucl_conv2d_fprop(int64_t N, int64_t H, int64_t W, int64_t C, int64_t 
     kp.pad_h = (int32_t)pad_h; kp.pad_w = (int32_t)pad_w; kp.str_h = (int32_t)stride_h; kp.str_w = (int32_t)stride_w;
     kp.dil_h = (int32_t)dil_h; kp.dil_w = (int32_t)dil_w;
     kp.d_vec = aligned16(y) && (Kout % (16 / elem_size(dtY)) == 0);
-    return run(L, kp, nullptr, tune, stream);
+    return run(L, kp, tune, stream);
 }
 
 ucl_status ucl_transpose(int64_t batch, int64_t rows, int64_t cols, const void *src, int32_t dt_src, void *dst,
@@ -590,7 +590,20 @@ ucl_status ucl_select_tuning(const ucl_problem *p, ucl_tuning *out) {
     L.M = M; L.N = N;
     L.K = p->op == UCL_OP_CONV2D_FPROP ? p->cR * p->cS * p->cC : p->K;
     L.groups = p->groups; L.M_g = p->M_g;
-    L.la = L.mode == 2 ? 2 : 0; L.lb = 0;
+    if (L.mode == 2) {
+        L.la = 2; L.lb = 0;
+    } else {
+        if ((p->a_layout != UCL_LAYOUT_K_CONTIGUOUS && p->a_layout != UCL_LAYOUT_MN_CONTIGUOUS) ||
+            (p->b_layout != UCL_LAYOUT_K_CONTIGUOUS && p->b_layout != UCL_LAYOUT_MN_CONTIGUOUS))
+            return fail(UCL_ERR_INVALID_ARG, "a_layout / b_layout must be ucl_operand_layout values");
+        if (L.mode == 1 && p->a_layout != UCL_LAYOUT_K_CONTIGUOUS)
+            return fail(UCL_ERR_UNSUPPORTED, "grouped_gemm is built for a row-major A");
+        L.la = p->a_layout; L.lb = p->b_layout;
+        // packed operands: the same reach test for directly copied rows as the launch path applies
+        const int64_t Mmax = L.mode == 1 ? 0 : M;
+        L.ndirect_ok = L.lb == 1 && ((L.K - 1) * N + N) * 2 < (1ll << 31);
+        L.mdirect_ok = L.la == 1 && ((L.K - 1) * Mmax + Mmax) * 2 < (1ll << 31);
+    }
     L.f16 = p->dt_in == UCL_F16;
     L.dtD = p->dt_out;
     if (L.mode == 2)
@@ -629,14 +642,19 @@ ucl_status ucl_tile_map(int32_t groups, const int32_t *tiles_m, int32_t tiles_n,
 
 int32_t ucl_num_variants(void) { return (int32_t)all_variants().size(); }
 
-ucl_status ucl_variant(int32_t i, ucl_tuning *out) {
+ucl_status ucl_variant(int32_t i, ucl_variant_info *out) {
     const auto &vs = all_variants();
     if (i < 0 || i >= (int)vs.size() || !out) return fail(UCL_ERR_INVALID_ARG, "variant index %d outside [0, %d)", i, (int)vs.size());
+    const VariantDesc &v = vs[i];
     memset(out, 0, sizeof(*out));
-    out->tile_m = vs[i].tile_m; out->tile_n = vs[i].tile_n; out->tile_k = vs[i].tile_k; out->stages = vs[i].stages;
-    out->iterator = vs[i].la == 3 ? UCL_ITER_FIXED_STRIDE_DILATION : vs[i].la == 2 ? UCL_ITER_ANALYTIC : UCL_ITER_DEFAULT;
-    // reserved[0..1]: which problems the variant serves (mode; 16-bit type and operand layouts)
-    out->reserved[0] = vs[i].mode; out->reserved[1] = vs[i].f16 * 64 + vs[i].la * 8 + vs[i].lb;
+    out->tile_m = v.tile_m; out->tile_n = v.tile_n; out->tile_k = v.tile_k; out->stages = v.stages;
+    out->iterator = v.la == 3 ? UCL_ITER_FIXED_STRIDE_DILATION : v.la == 2 ? UCL_ITER_ANALYTIC : UCL_ITER_DEFAULT;
+    out->op_class = v.mode;
+    out->dt_in = v.f16 ? UCL_F16 : UCL_BF16;
+    out->a_layout = (v.la == 1 || v.la == 5) ? UCL_LAYOUT_MN_CONTIGUOUS : UCL_LAYOUT_K_CONTIGUOUS;
+    out->b_layout = (v.lb == 1 || v.lb == 4) ? UCL_LAYOUT_MN_CONTIGUOUS : UCL_LAYOUT_K_CONTIGUOUS;
+    out->a_path = v.la; out->b_path = v.lb;
+    out->lds_bytes = v.lds_bytes;
     return UCL_OK;
 }
 

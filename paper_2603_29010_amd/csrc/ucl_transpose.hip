@@ -170,7 +170,14 @@ ucl_status transpose_run(int64_t batch, int64_t rows, int64_t cols, const void *
     if (!valid(dt_src) || !valid(dt_dst)) return fail(UCL_ERR_INVALID_ARG, "transpose: element types must be fp32, fp16 or bf16");
     if (batch == 0 || rows == 0 || cols == 0) return UCL_OK;         // nothing to move
     if (!src || !dst) return fail(UCL_ERR_INVALID_ARG, "transpose: src and dst must be non-NULL device pointers");
-    if (src == dst) return fail(UCL_ERR_UNSUPPORTED, "transpose works out of place: src and dst must differ");
+    {
+        // out of place only: a tile of the destination is written while other tiles of the source are still unread
+        const uintptr_t s0 = reinterpret_cast<uintptr_t>(src), d0 = reinterpret_cast<uintptr_t>(dst);
+        const uintptr_t sn = (uintptr_t)(batch * rows * cols) * (dt_src == UCL_F32 ? 4 : 2);
+        const uintptr_t dn = (uintptr_t)(batch * rows * cols) * (dt_dst == UCL_F32 ? 4 : 2);
+        if (s0 < d0 + dn && d0 < s0 + sn)
+            return fail(UCL_ERR_INVALID_ARG, "transpose works out of place: the byte ranges of src and dst overlap");
+    }
     if (rows >= (1ll << 31) - kTile || cols >= (1ll << 31) - kTile)
         return fail(UCL_ERR_UNSUPPORTED, "transpose: rows and cols must be below 2^31");
     const int64_t tiles_r = (rows + kTile - 1) / kTile, tiles_c = (cols + kTile - 1) / kTile;

@@ -130,9 +130,12 @@ def gemm_spec(M, N, K, dt_in="bf16", dt_out="bf16", a_layout="row", b_layout="co
     return spec
 
 
-def _add_epilogue(spec, names, draw, M, N, aux_dt, tid0=10, aux_rows=None):
+def _add_epilogue(spec, names, draw, M, N, aux_dt, tid0=10, aux_rows=None, groups=None):
     """Attach epilogue steps; tensor operands are drawn like the main operands.
-    aux_rows: row count of full-shape (aux_load) operands when it differs from M (batched)."""
+    aux_rows: row count of full-shape (aux_load) operands when it differs from M (batched).
+    groups: grouped GEMM -- every group gets its own n-indexed vector, stored as row g of a
+    [groups, N rounded up to 8] array (so that each row starts 16-byte aligned); m-indexed vectors
+    and matrices are packed like the output, M = sum of the group sizes."""
     tid = tid0
     aux_rows = M if aux_rows is None else aux_rows
     for st in names:
@@ -141,7 +144,11 @@ def _add_epilogue(spec, names, draw, M, N, aux_dt, tid0=10, aux_rows=None):
         name = st[0]
         if name in ("bias", "per_col_scale", "row_broadcast"):
             key = f"{name}{tid}"
-            spec["tensors"][key] = (to_bits(draw(tid, N), aux_dt), aux_dt)
+            if groups is None:
+                spec["tensors"][key] = (to_bits(draw(tid, N), aux_dt), aux_dt)
+            else:
+                npad = (N + 7) // 8 * 8
+                spec["tensors"][key] = (to_bits(draw(tid, groups * npad), aux_dt).reshape(groups, npad), aux_dt)
             spec["epilogue"].append((name, key))
         elif name in ("per_row_scale", "column_broadcast"):
             key = f"{name}{tid}"
@@ -188,7 +195,8 @@ def grouped_sizes(groups, seed, lo=128, step=64, count=31):
 def grouped_spec(M_g, N, K, dt_in="bf16", dt_out="bf16", scale=None, epilogue=("silu",),
                  seed=BASE_SEED + 4, integer=False, b_layout="col"):
     """Grouped GEMM: A packed [sum M_g, K] (row-major), one B per group stored [N,K] (column-major B,
-    the default) or [K,N] (b_layout="row"), D packed."""
+    the default) or [K,N] (b_layout="row"), D packed.  Epilogue tensors are per group: a [G, N]
+    array of n-indexed vectors, m-indexed vectors and matrices packed like D."""
     if scale is None:
         scale = 1.0 / math.sqrt(K)
     G = len(M_g)
@@ -205,8 +213,9 @@ def grouped_spec(M_g, N, K, dt_in="bf16", dt_out="bf16", scale=None, epilogue=("
     spec = {
         "op": "grouped_gemm", "M_g": list(M_g), "N": N, "K": K, "dt_in": dt_in, "dt_out": dt_out,
         "A": A, "a_strides": (K, 1), "B": B, "b_strides": (N, 1) if row else (1, K),
-        "tensors": {}, "epilogue": [tuple([s]) if isinstance(s, str) else tuple(s) for s in epilogue],
+        "tensors": {}, "epilogue": [],
     }
+    _add_epilogue(spec, epilogue, draw, tot, N, dt_out, groups=G)
     return spec
 
 

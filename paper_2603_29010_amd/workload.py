@@ -91,7 +91,8 @@ class DeviceWorkload:
         elif by_row:
             addr = [t.data_ptr() + int(o) * esz for o in offs]
         else:
-            addr = [t.data_ptr()] * len(M_g)
+            # n-indexed vectors: row g of a [groups, N rounded up to 8] array
+            addr = [t.data_ptr() + g * t.shape[-1] * esz for g in range(len(M_g))]
         tab = torch.tensor(addr, dtype=torch.int64, device=self.device)
         self.keep.append(tab)
         return tab.data_ptr()
@@ -149,6 +150,26 @@ class DeviceWorkload:
         return synth.bits_to_f64(a if dt == "f32" else a.view(np.uint16), dt)
 
     # -- bookkeeping for the benchmark ----------------------------------------------------------
+    def _problem_kwargs(self):
+        s = self.spec
+        if self.op == "conv2d_fprop":
+            return dict(conv=(s["Nb"], s["H"], s["W"], s["C"], s["Ko"], s["R"], s["S"], s["pad"][0], s["pad"][1],
+                              s["stride"][0], s["stride"][1], s["dil"][0], s["dil"][1]))
+        kw = dict(N=s["N"], K=s["K"], a_layout="k" if s["a_strides"][1] == 1 else "mn",
+                  b_layout="k" if s["b_strides"][0] == 1 else "mn")
+        if self.op == "grouped_gemm":
+            kw["M_g"] = s["M_g"]
+        else:
+            kw["M"] = s["M"]
+            if self.op == "batched_gemm":
+                kw["batch"] = s["batch"]
+        return kw
+
+    def selected(self):
+        """The kernel the selection table picks for this workload (what run(tune=None) launches)."""
+        s = self.spec
+        return ucl.ucl_select_tuning(self.op, s["dt_in"], s["dt_out"], **self._problem_kwargs())
+
     def sol(self, hw=None):
         s = self.spec
         if self.op == "gemm":

@@ -57,6 +57,9 @@ def gpu_result(spec, tune=None):
 
 def check(spec, tune=None, rows=None, label=""):
     got, w = gpu_result(spec, tune)
+    # every element of the output must have been written (the buffer starts as NaN patterns), also
+    # where the oracle is only asked for a sample of the rows
+    assert np.all(np.isfinite(got)), f"{label}: {np.count_nonzero(~np.isfinite(got))} output elements unwritten or non-finite"
     ref, absacc = oracle_result(spec, rows=rows)
     if rows is not None:
         got = got[np.asarray(rows)]

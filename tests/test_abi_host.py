@@ -107,8 +107,22 @@ def test_selection_table():
     t = ucl.ucl_select_tuning("conv2d_fprop", "bf16", "bf16", conv=(32, 56, 56, 32, 128, 3, 3, 1, 1, 1, 1, 1, 1))
     assert t["iterator"] == 1
     assert ucl.ucl_select_tuning("gemm", "bf16", "bf16", M=512, N=512, K=512)["iterator"] == 0
+    # operand layouts take part: a row-major B (contiguous along N, config 1) is served by the kernels
+    # that copy its rows directly, and only those; the pick must be one of the variants built for it
     variants = [ucl.ucl_variant(i) for i in range(ucl.ucl_num_variants())]
-    assert all((v["tile_m"] + v["tile_n"]) * v["tile_k"] * 2 * v["stages"] <= 160 * 1024 for v in variants)
+    for (al, bl) in itertools.product(("k", "mn"), repeat=2):
+        t = ucl.ucl_select_tuning("gemm", "bf16", "bf16", M=256, N=256, K=256, a_layout=al, b_layout=bl)
+        served = [v for v in variants if v["op_class"] == 0 and v["dt_in"] == 2
+                  and v["a_layout"] == (al == "mn") and v["b_layout"] == (bl == "mn")
+                  and v["a_path"] != 1 and v["b_path"] != 1]
+        assert served and any((v["tile_m"], v["tile_n"], v["tile_k"], v["stages"]) ==
+                              (t["tile_m"], t["tile_n"], t["tile_k"], t["stages"]) for v in served), (al, bl, t)
+    t = ucl.ucl_select_tuning("gemm", "bf16", "bf16", M=256, N=256, K=256, b_layout="mn")
+    assert (t["tile_m"], t["tile_n"], t["tile_k"], t["stages"]) == (64, 64, 64, 4)
+    with pytest.raises(UclError):
+        ucl.ucl_select_tuning("grouped_gemm", "bf16", "bf16", M_g=[64], N=64, K=64, a_layout="mn")
+    assert all(0 < v["lds_bytes"] <= 160 * 1024 for v in variants)
+    assert all(v["op_class"] in (0, 1, 2) and v["dt_in"] in (1, 2) for v in variants)
 
 
 def _err(fn, *a, **k):
@@ -150,5 +164,18 @@ def test_validation_rejects_before_any_launch():
     e = _err(ucl.ucl_conv2d_fprop, 1, 8, 8, 3, 8, 3, 3, 1, 1, 1, 1, 1, 1, P, "bf16", P, "bf16", P, "bf16")
     assert e.status == "UCL_ERR_UNSUPPORTED" and "multiple of 8" in e.message
     assert _err(ucl.ucl_conv2d_fprop, 1, 2, 2, 8, 8, 5, 5, 0, 0, 1, 1, 1, 1, P, "bf16", P, "bf16", P, "bf16").status == "UCL_ERR_INVALID_ARG"
+    # the GEMM entry points ignore a valid iterator value and still reject an invalid one
+    assert _err(gemm, M=0, tune=Tuning(0, 0, 0, 0, 0, 2)).status == "UCL_ERR_INVALID_ARG"     # (fails on M, not on the iterator)
+    assert _err(gemm, tune=Tuning(0, 0, 0, 0, 0, 7)).status == "UCL_ERR_INVALID_ARG"
+    # an explicit tuning that names only tile_k is still an explicit tuning
+    e = _err(gemm, tune=Tuning(0, 0, 48, 0))
+    assert e.status == "UCL_ERR_UNSUPPORTED" and "tile_k" in e.message
+    # transform stage: out of place only -- any overlap of the two byte ranges is rejected
+    T = ucl.ucl_transpose
+    assert _err(T, 1, 64, 64, P, "f32", P, "f32").status == "UCL_ERR_INVALID_ARG"
+    assert _err(T, 1, 64, 64, P, "f32", P + 64 * 64 * 4 - 4, "bf16").status == "UCL_ERR_INVALID_ARG"
+    assert _err(T, 2, 64, 64, P + 64 * 64 * 2 * 2 - 2, "f32", P, "bf16").status == "UCL_ERR_INVALID_ARG"
+    assert _err(T, 1, 64, 64, P, "f32", 0, "bf16").status == "UCL_ERR_INVALID_ARG"
+    T(0, 64, 64, P, "f32", P, "f32")             # zero extents: nothing to do, nothing launched
     # grouped with every group empty is a no-op, not an error (nothing is launched)
     ucl.ucl_grouped_gemm([0, 0], 64, 64, P, "bf16", 64, 1, P, "bf16", 1, 64, P, "bf16", 64, 1)

@@ -163,6 +163,51 @@ def test_grouped_row_major_b():
         parity.check(spec16, T(*tile), label=f"grouped f16 row-major B {tile}")
 
 
+# Per-group epilogue tensors through device pointer tables: every group has its own bias row, its
+# slice of the packed residual and of the packed per-row vector.  Exact on integers over every grouped
+# variant and both B layouts (fused fast form, fused element-predicated form via a ragged N, and
+# interpreted chains), then floating point through explicit variants and the table's choice.
+GROUPED_TENSOR_CHAINS = [
+    ("bias",),
+    ("bias", "aux_load"),
+    ("per_row_scale", "bias"),
+    ("column_broadcast", ("aux_load", 2.0), "row_broadcast"),
+]
+
+
+@pytest.mark.parametrize("b_layout", ["col", "row"])
+@pytest.mark.parametrize("chain", GROUPED_TENSOR_CHAINS, ids=lambda c: "-".join(s if isinstance(s, str) else s[0] for s in c))
+def test_grouped_exact_per_group_epilogue_tensors(chain, b_layout):
+    M_g = [64, 0, 200, 8, 321, 0, 128, 1]
+    spec = synth.grouped_spec(M_g, 136, 72, dt_out="f32", epilogue=chain, integer=True, b_layout=b_layout)
+    for tile in built(1, lb=4 if b_layout == "row" else 0):
+        parity.check_exact(spec, T(*tile), label=f"grouped {chain} {b_layout} {tile}")
+    parity.check_exact(spec, None, label=f"grouped {chain} {b_layout} table choice")
+
+
+def test_grouped_exact_per_group_tensors_ragged_n():
+    # N % 8 != 0: D rows and the residual are accessed element by element, bias rows stay 16-byte
+    # aligned; group sizes are multiples of 8 so that every per-group base pointer is aligned
+    M_g = [64, 0, 200, 8, 328, 128]
+    for chain in (("bias", "aux_load", "relu"), ("per_row_scale", "bias", "aux_load")):
+        for dt_out in ("f32", "bf16"):
+            spec = synth.grouped_spec(M_g, 77, 24, dt_out=dt_out, epilogue=chain, integer=True)
+            for tile in built(1):
+                parity.check_exact(spec, T(*tile), label=f"grouped N=77 {chain} {dt_out} {tile}")
+
+
+@pytest.mark.parametrize("dt", ["bf16", "f16"])
+def test_grouped_parity_per_group_epilogue_tensors(dt):
+    f16 = int(dt == "f16")
+    for chain in (("bias", "aux_load", "relu"), ("bias", "gelu_tanh"), ("per_row_scale", "per_col_scale", "silu"),
+                  (("scale", 0.5), "column_broadcast", ("aux_load", -0.5), "tanh")):
+        for b_layout, lb in (("col", 0), ("row", 4)):
+            spec = synth.grouped_spec([192, 64, 0, 448, 129], 264, 136, dt_in=dt, dt_out=dt, epilogue=chain, b_layout=b_layout)
+            for tile in built(1, f16=f16, lb=lb):
+                parity.check(spec, T(*tile), label=f"grouped {dt} {chain} {b_layout} {tile}")
+            parity.check(spec, None, label=f"grouped {dt} {chain} {b_layout} table choice")
+
+
 @pytest.mark.parametrize("geom", [
     dict(Nb=2, H=9, W=7, C=16, Ko=24, R=3, S=3, pad=(1, 1)),
     dict(Nb=1, H=12, W=10, C=8, Ko=8, R=5, S=3, pad=(2, 0), stride=(2, 1)),
@@ -328,51 +373,23 @@ def test_config5_shrunk():
     parity.check(synth.config(5, shrink=16), label="config5/16")
 
 
-def _sample_rows(M, n, seed):
-    rng = np.random.default_rng(seed)
-    rows = set(rng.integers(0, M, n).tolist()) | {0, M - 1}
-    return sorted(rows)
+# Full size, in the launch configuration bench.py times (selection table's choice), EVERY output
+# element against the oracle: a wrong or unwritten tile anywhere fails.
 
-
-def test_config2_full_size_sampled_rows():
-    spec = synth.config(2)
-    rows = _sample_rows(spec["M"], 24, 2)
-    parity.check(spec, rows=rows, label="config2 full")
+def test_config2_full_size_every_element():
+    parity.check(synth.config(2), label="config2 full")
 
 
 def test_config3_full_size():
     parity.check(synth.config(3), label="config3 full")
 
 
-def test_config4_full_size_sampled_rows():
-    import oracle
-    from paper_2603_29010_amd.workload import DeviceWorkload
-    spec = synth.config(4)
-    w = DeviceWorkload(spec)
-    w.run()
-    got = w.result()
-    offs = np.concatenate([[0], np.cumsum(spec["M_g"])])
-    # first, last and a few random rows of every group, each a GEMM row against that group's B
-    rng = np.random.default_rng(4)
-    for g, m in enumerate(spec["M_g"]):
-        rows = sorted({0, m - 1, *rng.integers(0, m, 2).tolist()})
-        A_g = np.ascontiguousarray(spec["A"][offs[g]:offs[g + 1]])
-        ref, s = oracle.gemm(A_g, "bf16", spec["a_strides"], np.ascontiguousarray(spec["B"][g]), "bf16",
-                             spec["b_strides"], m, spec["N"], spec["K"], chain=[("silu",)], rows=rows, want_abs=True)
-        parity.compare(got[offs[g] + np.asarray(rows)], ref, s, spec, f"config4 group {g}")
+def test_config4_full_size_every_element():
+    parity.check(synth.config(4), label="config4 full")
 
 
-def test_config5_full_size_sampled_rows():
-    spec = synth.config(5)
-    rows = _sample_rows(spec["M"], 400, 5)
-    # add every halo class of the first and last image
-    P, Q = spec["P"], spec["Q"]
-    for n in (0, spec["Nb"] - 1):
-        for p in (0, 1, P - 1):
-            for q in (0, 1, Q - 1):
-                rows.append((n * P + p) * Q + q)
-    rows = sorted(set(rows))
-    parity.check(spec, rows=rows, label="config5 full")
+def test_config5_full_size_every_element():
+    parity.check(synth.config(5), label="config5 full")
 
 
 def test_hip_graph_replays_match_eager_launch():

@@ -43,6 +43,19 @@ def test_fp16_round_trip_exhaustive():
         assert oracle.encode16(x, "f16") == b
 
 
+def test_bf16_encode_matches_torch_exhaustive():
+    allbits = np.arange(65536, dtype=np.uint16)
+    v = torch.from_numpy(allbits.view(np.int16)).view(torch.bfloat16).to(torch.float64).numpy()
+    for b, x in zip(allbits.tolist(), v.tolist()):
+        if math.isnan(x):
+            continue
+        assert oracle.encode16(x, "bf16") == b
+    # and values between two bf16 numbers land on the nearest (ties to even), as torch casts them
+    x = np.array([1 + 2 ** -8, 1 + 3 * 2 ** -8, -3.1415926, 1e-40, 3.0e38, 65504.0])
+    ref = torch.from_numpy(x.astype(np.float32)).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert [oracle.encode16(float(np.float32(t)), "bf16") for t in x] == ref.tolist()
+
+
 def test_bf16_decode_matches_torch_exhaustive():
     allbits = np.arange(65536, dtype=np.uint16)
     got = oracle.load(allbits, "bf16")

@@ -12,6 +12,30 @@ def test_counter_based_slices_are_reproducible():
     assert not np.array_equal(a, synth.uniform01(7, 4, 1000))
 
 
+def test_mixer_is_the_published_splitmix64():
+    # SplitMix64 seeded with 0 produces these three outputs (the generator's published test vector):
+    # output i is the finaliser applied to the state after i + 1 additions of the golden-ratio constant
+    g = 0x9E3779B97F4A7C15
+    z = np.array([0, g, (2 * g) & 0xFFFFFFFFFFFFFFFF], dtype=np.uint64)
+    assert [int(v) for v in synth._mix(z)] == [0xE220A8397B1DCDAF, 0x6E789E6AA1B965F4, 0x06C45D188009454F]
+
+
+def test_first_eight_draws_are_the_recorded_ones():
+    import os
+    import sys
+    gold = os.path.join(os.path.dirname(__file__), "golden")
+    sys.path.insert(0, gold)
+    import make_prng_first8 as mk
+    want = {}
+    for line in open(os.path.join(gold, "prng_first8.txt")):
+        if line.startswith("#"):
+            continue
+        name, *vals = line.split()
+        want[name] = [float.fromhex(v) for v in vals]
+    for name, v in mk.rows():
+        assert v.tolist() == want[name], name
+
+
 def test_distributions_within_5_sigma():
     n = 1 << 18
     u = synth.uniform_pm1(1, 1, n)
