@@ -160,7 +160,8 @@ def time_workload(cfg, steps, warmup, replays, copies=None, use_graph=True):
     if copies is None:
         # memory-bound workloads: rotate over enough distinct operand sets that a launch cannot be
         # served from the 256 MB last-level cache left warm by the previous one
-        copies = 1 if sol["compute_bound"] else max(2, int(768e6 // sol["bytes"]) + 1)
+        # (at most 64 sets: the 0.4 MB problem of config 1 is bound by launch latency, not by where its operands sit)
+        copies = 1 if sol["compute_bound"] else min(64, max(2, int(768e6 // sol["bytes"]) + 1))
     sets = [probe] + [DeviceWorkload(spec, poison=False) for _ in range(copies - 1)]
     per_step, launch, sclk = timed_replays(lambda i: sets[i % copies].run(), steps, warmup, replays, use_graph)
     ms = statistics.median(per_step)

@@ -82,7 +82,7 @@ def test_transpose_empty_and_rejected_arguments():
     ucl.ucl_transpose(0, 4, 4, 0, "f32", 0, "f32")                                   # not even pointers are needed
     with pytest.raises(ucl.UclError) as e:
         ucl.ucl_transpose(1, 4, 4, buf.data_ptr(), "f32", buf.data_ptr(), "f32")
-    assert e.value.status == "UCL_ERR_UNSUPPORTED"
+    assert e.value.status == "UCL_ERR_INVALID_ARG"
     with pytest.raises(ucl.UclError) as e:
         ucl.ucl_transpose(1, 4, 4, 0, "f32", out.data_ptr(), "f32")
     assert e.value.status == "UCL_ERR_INVALID_ARG"
