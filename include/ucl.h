@@ -53,7 +53,8 @@ typedef enum ucl_status {
     UCL_OK = 0,
     UCL_ERR_INVALID_ARG = 1,   /* null pointer, non-positive extent, bad enum            */
     UCL_ERR_UNSUPPORTED = 2,   /* legal request outside what the kernels implement       */
-    UCL_ERR_WORKSPACE = 3,     /* tile x stages exceeds the 160 KiB of LDS per CU        */
+    UCL_ERR_WORKSPACE = 3,     /* tile x stages exceeds the 160 KiB of LDS per CU, or the
+                                  split-K workspace is missing, misaligned or too small  */
     UCL_ERR_LAUNCH = 4         /* the HIP runtime refused the launch                     */
 } ucl_status;
 
@@ -120,7 +121,25 @@ typedef enum ucl_conv_iterator {
     UCL_ITER_FIXED_STRIDE_DILATION = 2
 } ucl_conv_iterator;
 
-/* Explicit kernel choice (`.with_tile`, `.with_stages`, `.with_swizzle`, `.with_iterator`).
+/* `.with_split_k(mode=..., slices=...)`: the K extent is cut into `slices` ranges (multiples of 64)
+ * that run as separate workgroups; their fp32 partial tiles pass through the caller's workspace and
+ * are added in slice order 0, 1, 2, ... (a fixed order: results do not depend on timing), after
+ * which the epilogue chain runs once.  SERIAL: one launch; the workgroup that finishes a tile last
+ * (a counter per tile in the workspace) adds the slices up and runs the epilogue.  PARALLEL: two
+ * launches, the second one adds up and runs the epilogue.  Both give bit-identical results. */
+typedef enum ucl_split_k_mode { UCL_SPLIT_K_NONE = 0, UCL_SPLIT_K_SERIAL = 1, UCL_SPLIT_K_PARALLEL = 2 } ucl_split_k_mode;
+
+/* `.with_scheduler(tile=...)`.  DEFAULT: one workgroup per output tile, dealt out by the hardware as
+ * CUs free up.  PERSISTENT: one workgroup per CU slot, each walking the tile order with a stride of
+ * the grid size.  (stream_k is not built and is rejected with UCL_ERR_UNSUPPORTED.) */
+typedef enum ucl_tile_scheduler { UCL_SCHED_DEFAULT = 0, UCL_SCHED_PERSISTENT = 1, UCL_SCHED_STREAM_K = 2 } ucl_tile_scheduler;
+
+/* The first UCL_WORKSPACE_COUNTER_BYTES of a split-K workspace hold the per-tile counters. */
+#define UCL_WORKSPACE_COUNTER_BYTES 65536
+#define UCL_SPLIT_K_MAX_TILES (UCL_WORKSPACE_COUNTER_BYTES / 4)
+
+/* Explicit kernel choice (`.with_tile`, `.with_stages`, `.with_swizzle`, `.with_iterator`,
+ * `.with_split_k`, `.with_scheduler`).
  * tile_k (K extent of one LDS stage) is 32 or 64; stages is the number of LDS stage
  * buffers: 3 or more for operands contiguous along K (stages - 1 k-tiles are in
  * flight while one is being multiplied), or 2 with tile_k = 64 (each half of a
@@ -128,15 +147,27 @@ typedef enum ucl_conv_iterator {
  * use the same loops (their rows of k are copied directly and read back through the
  * LDS transpose read); a slower form with 2 buffers that transposes them in registers
  * serves matrices beyond the 2 GiB reach of 32-bit offsets.
- * Only built combinations are accepted (ucl_variant()).  raster = width, in tile rows, of the
+ * Only built combinations are accepted (ucl_variant()); all four of tile_m, tile_n, tile_k,
+ * stages zero = the table's choice.  raster = width, in tile rows, of the
  * bands the tile order walks column by column (1, 2, 4, 8, 16; the swizzle
  * knob's Identity1..8), 0 = table default.  The order is also XCD-aware:
  * workgroup ids that land on the same XCD (id mod 8) get neighbouring tiles.
- * iterator is a ucl_conv_iterator; the GEMM entry points accept any valid value and ignore it. */
+ * iterator is a ucl_conv_iterator; the GEMM entry points accept any valid value and ignore it.
+ * split_k_mode / split_k_slices (ucl_gemm and ucl_batched_gemm only; slices = 0 lets the library
+ * choose, slices = 1 is no split): the library allocates nothing, so the caller passes
+ * `workspace`, DEVICE memory, 16-byte aligned, of at least ucl_workspace_size() bytes.  SERIAL needs
+ * the first UCL_WORKSPACE_COUNTER_BYTES to be zero when the call starts: clear them once with
+ * ucl_workspace_init(); every call leaves them zero again.  Calls that share a workspace must not
+ * overlap in time.  Without a split, workspace is ignored.
+ * scheduler is a ucl_tile_scheduler. */
 typedef struct ucl_tuning {
     int32_t tile_m, tile_n, tile_k, stages, raster;
     int32_t iterator;
-    int32_t reserved[2];
+    int32_t split_k_mode, split_k_slices;
+    int32_t scheduler;
+    int32_t reserved;
+    void *workspace;
+    int64_t workspace_bytes;
 } ucl_tuning;
 
 /* D[m,n] = E( sum_k A[m*a_rs + k*a_cs] * B[k*b_rs + n*b_cs] ), written to
@@ -261,6 +292,15 @@ ucl_status ucl_sol_bound(const ucl_problem *p, const ucl_hw *hw, ucl_sol_report 
  * tune == NULL applies the same function to the same description (packed
  * operands assumed: leading strides equal to the contiguous extents). */
 ucl_status ucl_select_tuning(const ucl_problem *p, ucl_tuning *out);
+
+/* Bytes of workspace a call on problem p with tuning `tune` needs (0 without a split):
+ * UCL_WORKSPACE_COUNTER_BYTES + slices x tiles x tile_m x tile_n x 4.  *slices_out (may be NULL)
+ * receives the number of K slices the call will use. */
+ucl_status ucl_workspace_size(const ucl_problem *p, const ucl_tuning *tune, int64_t *bytes, int32_t *slices_out);
+
+/* Zero the counter area at the start of a split-K workspace (one small kernel on `stream`; no
+ * memset node, so the call may be captured into a HIP graph).  Needed once per workspace. */
+ucl_status ucl_workspace_init(void *workspace, int64_t workspace_bytes, void *stream);
 
 /* The tile schedule, evaluated on the host with the same code the kernels run:
  * for workgroup id `wg` of a launch covering `groups` sub-problems with

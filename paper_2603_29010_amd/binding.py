@@ -38,7 +38,14 @@ class _Epilogue(C.Structure):
 
 class _Tuning(C.Structure):
     _fields_ = [("tile_m", C.c_int32), ("tile_n", C.c_int32), ("tile_k", C.c_int32),
-                ("stages", C.c_int32), ("raster", C.c_int32), ("iterator", C.c_int32), ("reserved", C.c_int32 * 2)]
+                ("stages", C.c_int32), ("raster", C.c_int32), ("iterator", C.c_int32),
+                ("split_k_mode", C.c_int32), ("split_k_slices", C.c_int32), ("scheduler", C.c_int32),
+                ("reserved", C.c_int32), ("workspace", C.c_void_p), ("workspace_bytes", C.c_int64)]
+
+
+SPLIT_K_MODES = {"none": 0, "serial": 1, "parallel": 2}
+SCHEDULERS = {"default": 0, "persistent": 1, "stream_k": 2}
+WORKSPACE_COUNTER_BYTES = 65536
 
 
 class _Problem(C.Structure):
@@ -107,6 +114,10 @@ def _load():
         lib.ucl_sol_bound.argtypes = [C.POINTER(_Problem), C.POINTER(_Hw), C.POINTER(_SolReport)]
         lib.ucl_select_tuning.restype = C.c_int
         lib.ucl_select_tuning.argtypes = [C.POINTER(_Problem), C.POINTER(_Tuning)]
+        lib.ucl_workspace_size.restype = C.c_int
+        lib.ucl_workspace_size.argtypes = [C.POINTER(_Problem), C.POINTER(_Tuning), C.POINTER(i64), C.POINTER(i32)]
+        lib.ucl_workspace_init.restype = C.c_int
+        lib.ucl_workspace_init.argtypes = [vp, i64, vp]
         lib.ucl_tile_map.restype = C.c_int
         lib.ucl_tile_map.argtypes = [i32, C.POINTER(i32), i32, i32, i32, C.POINTER(i32), C.POINTER(i32),
                                      C.POINTER(i32)]
@@ -162,8 +173,14 @@ class Epilogue:
 
 
 class Tuning:
-    def __init__(self, tile_m=0, tile_n=0, tile_k=0, stages=0, raster=0, iterator=0):
-        self.c = _Tuning(tile_m, tile_n, tile_k, stages, raster, iterator)
+    """split_k: "none" | "serial" | "parallel" (or the enum value); workspace: device address."""
+
+    def __init__(self, tile_m=0, tile_n=0, tile_k=0, stages=0, raster=0, iterator=0, split_k="none", slices=0,
+                 scheduler="default", workspace=0, workspace_bytes=0):
+        mode = SPLIT_K_MODES[split_k] if isinstance(split_k, str) else int(split_k)
+        sched = SCHEDULERS[scheduler] if isinstance(scheduler, str) else int(scheduler)
+        self.c = _Tuning(tile_m, tile_n, tile_k, stages, raster, iterator, mode, slices, sched, 0,
+                         workspace or None, workspace_bytes)
 
     def ref(self):
         return C.byref(self.c)
@@ -250,6 +267,18 @@ def ucl_select_tuning(op, dt_in, dt_out, **kw):
     t = Tuning()
     _check(_load().ucl_select_tuning(C.byref(p), t.ref()))
     return t.as_dict()
+
+
+def ucl_workspace_size(op, dt_in, dt_out, tune=None, **kw):
+    """(bytes, slices) a call on this problem with this tuning needs / uses."""
+    p, keep = _problem(op, dt_in, dt_out, **kw)
+    nbytes, slices = C.c_int64(), C.c_int32()
+    _check(_load().ucl_workspace_size(C.byref(p), _opt(tune), C.byref(nbytes), C.byref(slices)))
+    return nbytes.value, slices.value
+
+
+def ucl_workspace_init(workspace, workspace_bytes, stream=0):
+    _check(_load().ucl_workspace_init(workspace, workspace_bytes, stream or None))
 
 
 def ucl_tile_map(tiles_m, tiles_n, raster, wg):

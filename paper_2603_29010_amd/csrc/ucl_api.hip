@@ -9,6 +9,7 @@
 #include "ucl_variants.h"
 
 namespace ucl {
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 // the transform stage lives in its own unit
 ucl_status transpose_run(int64_t batch, int64_t rows, int64_t cols, const void *src, int32_t dt_src, void *dst, int32_t dt_dst,
                          void *stream);
@@ -150,8 +151,9 @@ const VariantDesc *select_variant(const Launch &L, const ucl_tuning *tune) {
     const bool explicit_tune = tune && (tune->tile_m || tune->tile_n || tune->tile_k || tune->stages);
     const VariantDesc *best = nullptr;
     double best_t = 0;
+    const int want_persistent = tune && tune->scheduler == UCL_SCHED_PERSISTENT ? 1 : 0;
     for (const auto &v : vs) {
-        if (v.mode != L.mode || v.f16 != L.f16) continue;
+        if (v.mode != L.mode || v.f16 != L.f16 || v.persistent != want_persistent) continue;
         if (v.lb == 4 ? !(L.lb == 1 && L.ndirect_ok) : v.lb != L.lb) continue;
         if (L.mode == 2) {
             // conv: the iterator knob picks between the per-tap gather (la 2) and the resident patch (la 3)
@@ -290,6 +292,53 @@ ucl_status check_common(int64_t M, int64_t N, int64_t K, int dtA, int dtB, int d
     return UCL_OK;
 }
 
+constexpr int kNumCUs = 256;
+
+// split-K plan of a launch: slices (1 = none), K extent per slice, workspace bytes.
+struct SplitPlan {
+    int slices = 1;
+    int k_per_slice = 0;
+    int64_t bytes = 0;
+};
+
+ucl_status plan_split(const Launch &L, const VariantDesc &v, const ucl_tuning *tune, int64_t total_tiles, SplitPlan &sp) {
+    sp = SplitPlan();
+    if (!tune) return UCL_OK;
+    if (tune->scheduler < UCL_SCHED_DEFAULT || tune->scheduler > UCL_SCHED_STREAM_K)
+        return fail(UCL_ERR_INVALID_ARG, "scheduler=%d is not a ucl_tile_scheduler", tune->scheduler);
+    if (tune->scheduler == UCL_SCHED_STREAM_K)
+        return fail(UCL_ERR_UNSUPPORTED, "the stream_k tile scheduler is not built; use split-K (fixed slices) or the persistent scheduler");
+    if (tune->split_k_mode < UCL_SPLIT_K_NONE || tune->split_k_mode > UCL_SPLIT_K_PARALLEL)
+        return fail(UCL_ERR_INVALID_ARG, "split_k_mode=%d is not a ucl_split_k_mode", tune->split_k_mode);
+    if (tune->split_k_slices < 0) return fail(UCL_ERR_INVALID_ARG, "split_k_slices=%d must be >= 0", tune->split_k_slices);
+    if (tune->split_k_mode == UCL_SPLIT_K_NONE) {
+        if (tune->split_k_slices > 1)
+            return fail(UCL_ERR_INVALID_ARG, "split_k_slices=%d with split_k_mode none: name serial or parallel", tune->split_k_slices);
+        return UCL_OK;
+    }
+    if (L.mode != 0) return fail(UCL_ERR_UNSUPPORTED, "split-K is built for gemm and batched_gemm");
+    if (tune->scheduler == UCL_SCHED_PERSISTENT)
+        return fail(UCL_ERR_UNSUPPORTED, "split-K and the persistent scheduler cannot be combined");
+    const int64_t kt = (L.K + 63) / 64;                     // slices are whole multiples of 64 along K
+    int64_t want = tune->split_k_slices;
+    if (want == 0) {
+        // enough slices to give every CU a workgroup, each keeping at least 4 x 64 of K
+        want = total_tiles >= kNumCUs ? 1 : (kNumCUs + total_tiles - 1) / total_tiles;
+        if (want > kt / 4) want = kt / 4;
+        if (want < 1) want = 1;
+    }
+    if (want > kt) want = kt;
+    const int64_t per = (kt + want - 1) / want;
+    sp.k_per_slice = (int)(per * 64);
+    sp.slices = (int)((kt + per - 1) / per);
+    if (sp.slices <= 1) { sp = SplitPlan(); return UCL_OK; }
+    if (total_tiles > UCL_SPLIT_K_MAX_TILES)
+        return fail(UCL_ERR_UNSUPPORTED, "split-K serves at most %d output tiles (this problem has %lld)", UCL_SPLIT_K_MAX_TILES, (long long)total_tiles);
+    if (total_tiles * sp.slices >= (1ll << 31)) return fail(UCL_ERR_UNSUPPORTED, "tiles x slices exceeds the grid limit");
+    sp.bytes = UCL_WORKSPACE_COUNTER_BYTES + (int64_t)sp.slices * total_tiles * v.tile_m * v.tile_n * 4;
+    return UCL_OK;
+}
+
 ucl_status run(const Launch &L, KParams &kp, const ucl_tuning *tune, void *stream) {
     if (tune && (tune->iterator < 0 || tune->iterator > UCL_ITER_FIXED_STRIDE_DILATION))
         return fail(UCL_ERR_INVALID_ARG, "iterator=%d is not a ucl_conv_iterator", tune->iterator);
@@ -308,6 +357,8 @@ ucl_status run(const Launch &L, KParams &kp, const ucl_tuning *tune, void *strea
             return fail(UCL_ERR_UNSUPPORTED, "no kernel built for tile %dx%dx%d, %d stages with these types/layouts; see ucl_variant()",
                         tune->tile_m, tune->tile_n, tune->tile_k, tune->stages);
         }
+        if (tune && tune->scheduler == UCL_SCHED_PERSISTENT)
+            return fail(UCL_ERR_UNSUPPORTED, "no kernel with the persistent tile scheduler is built for this combination of operation, input type and layouts");
         return fail(UCL_ERR_UNSUPPORTED, "no kernel built for this combination of operation, input type and layouts");
     }
     if (kp.ldd > kMaxWideLd) kp.d_vec = 0;
@@ -336,6 +387,20 @@ ucl_status run(const Launch &L, KParams &kp, const ucl_tuning *tune, void *strea
         total = (int64_t)kp.tiles_per_batch * L.batch;
     }
     if (total >= (1ll << 31)) return fail(UCL_ERR_UNSUPPORTED, "problem needs %lld tiles; the grid is limited to 2^31-1", (long long)total);
+    SplitPlan sp;
+    if (ucl_status st = plan_split(L, *v, tune, total, sp)) return st;
+    if (sp.slices > 1) {
+        if (!tune->workspace)
+            return fail(UCL_ERR_WORKSPACE, "split-K with %d slices needs a workspace of %lld bytes (ucl_workspace_size); tune->workspace is NULL", sp.slices, (long long)sp.bytes);
+        if (!aligned16(tune->workspace)) return fail(UCL_ERR_WORKSPACE, "the split-K workspace must be 16-byte aligned");
+        if (tune->workspace_bytes < sp.bytes)
+            return fail(UCL_ERR_WORKSPACE, "split-K with %d slices over %lld tiles of %dx%d needs %lld bytes of workspace, got %lld",
+                        sp.slices, (long long)total, v->tile_m, v->tile_n, (long long)sp.bytes, (long long)tune->workspace_bytes);
+        kp.split_k = sp.slices;
+        kp.k_per_slice = sp.k_per_slice;
+        kp.ws_counters = (uint32_t *)tune->workspace;
+        kp.ws_partials = (float *)((char *)tune->workspace + UCL_WORKSPACE_COUNTER_BYTES);
+    }
     // operand panels are addressed with 32-bit byte offsets inside range-checked buffer resources
     if (v->la == 0 && ((int64_t)v->tile_m * kp.lda + L.K) * 2 >= (1ll << 31))
         return fail(UCL_ERR_UNSUPPORTED, "A leading stride %lld too large: a %d-row panel must span less than 2 GiB", (long long)kp.lda, v->tile_m);
@@ -343,7 +408,24 @@ ucl_status run(const Launch &L, KParams &kp, const ucl_tuning *tune, void *strea
         return fail(UCL_ERR_UNSUPPORTED, "B leading stride %lld too large: a %d-row panel must span less than 2 GiB", (long long)kp.ldb, v->tile_n);
     kp.total_tiles = (int32_t)total;
     if (total == 0) return UCL_OK;     // grouped with every M_g == 0: nothing to do
-    hipError_t e = v->launch(kp, L.mode == 1 ? &gt : nullptr, (int)total, (hipStream_t)stream);
+    const GroupTable *gtp = L.mode == 1 ? &gt : nullptr;
+    hipError_t e;
+    if (sp.slices > 1 && tune->split_k_mode == UCL_SPLIT_K_PARALLEL) {
+        kp.split_phase = 1;
+        e = v->launch(kp, gtp, (int)(total * sp.slices), (hipStream_t)stream);
+        if (e == hipSuccess) {
+            kp.split_phase = 2;
+            e = v->launch(kp, gtp, (int)total, (hipStream_t)stream);
+        }
+    } else {
+        int64_t grid = total * sp.slices;
+        if (v->persistent) {
+            // one workgroup per CU slot; a multiple of 8 keeps each workgroup on the tile run of its XCD
+            const int64_t slots = (int64_t)kNumCUs * workgroups_per_cu(*v);
+            if (grid > slots) grid = slots;
+        }
+        e = v->launch(kp, gtp, (int)grid, (hipStream_t)stream);
+    }
     if (e != hipSuccess) return fail(UCL_ERR_LAUNCH, "kernel launch failed: %s", hipGetErrorString(e));
     return UCL_OK;
 }
@@ -444,6 +526,47 @@ ucl_status characterise(const ucl_problem *p, double *flops, double *bytes, int6
     if (M_out) *M_out = (int64_t)rows;
     if (N_out) *N_out = (int64_t)N;
     return UCL_OK;
+}
+
+
+// Launch description of a problem given as ucl_problem (packed operands), for the host-only queries.
+ucl_status launch_from_problem(const ucl_problem *p, Launch &L) {
+    double f, b;
+    int64_t M = 0, N = 0;
+    if (ucl_status st = characterise(p, &f, &b, &M, &N)) return st;
+    if (!is16(p->dt_in)) return fail(UCL_ERR_UNSUPPORTED, "kernels take bf16 or fp16 inputs");
+    L.mode = p->op == UCL_OP_GROUPED_GEMM ? 1 : p->op == UCL_OP_CONV2D_FPROP ? 2 : 0;
+    L.batch = p->op == UCL_OP_BATCHED_GEMM ? p->batch : 1;
+    L.M = M; L.N = N;
+    L.K = p->op == UCL_OP_CONV2D_FPROP ? p->cR * p->cS * p->cC : p->K;
+    L.groups = p->groups; L.M_g = p->M_g;
+    if (L.mode == 2) {
+        L.la = 2; L.lb = 0;
+    } else {
+        if ((p->a_layout != UCL_LAYOUT_K_CONTIGUOUS && p->a_layout != UCL_LAYOUT_MN_CONTIGUOUS) ||
+            (p->b_layout != UCL_LAYOUT_K_CONTIGUOUS && p->b_layout != UCL_LAYOUT_MN_CONTIGUOUS))
+            return fail(UCL_ERR_INVALID_ARG, "a_layout / b_layout must be ucl_operand_layout values");
+        if (L.mode == 1 && p->a_layout != UCL_LAYOUT_K_CONTIGUOUS)
+            return fail(UCL_ERR_UNSUPPORTED, "grouped_gemm is built for a row-major A");
+        L.la = p->a_layout; L.lb = p->b_layout;
+        // packed operands: the same reach test for directly copied rows as the launch path applies
+        const int64_t Mmax = L.mode == 1 ? 0 : M;
+        L.ndirect_ok = L.lb == 1 && ((L.K - 1) * N + N) * 2 < (1ll << 31);
+        L.mdirect_ok = L.la == 1 && ((L.K - 1) * Mmax + Mmax) * 2 < (1ll << 31);
+    }
+    L.f16 = p->dt_in == UCL_F16;
+    L.dtD = p->dt_out;
+    if (L.mode == 2)
+        L.patch_ok = conv_patch_ok(p->cW, p->cC, p->cR, p->cS, p->pad_h, p->pad_w, p->stride_h, p->stride_w, p->dil_h, p->dil_w);
+    if (L.mode == 1)
+        for (int g = 0; g < L.groups; ++g) L.sum_Mg += L.M_g[g];
+    return UCL_OK;
+}
+
+// Fill kernel for the counter area of a split-K workspace (a kernel, not a memset node: the call may
+// be captured into a HIP graph).  One 128-bit store per thread.
+__global__ void zero_words_kernel(uint32_t *w) {
+    ((u32x4 *)w)[blockIdx.x * blockDim.x + threadIdx.x] = u32x4{0u, 0u, 0u, 0u};
 }
 
 }  // namespace
@@ -580,42 +703,43 @@ ucl_status ucl_sol_bound(const ucl_problem *p, const ucl_hw *hw, ucl_sol_report 
 ucl_status ucl_select_tuning(const ucl_problem *p, ucl_tuning *out) {
     g_err[0] = 0;
     if (!out) return fail(UCL_ERR_INVALID_ARG, "output pointer is NULL");
-    double f, b;
-    int64_t M = 0, N = 0;
-    if (ucl_status st = characterise(p, &f, &b, &M, &N)) return st;
-    if (!is16(p->dt_in)) return fail(UCL_ERR_UNSUPPORTED, "kernels take bf16 or fp16 inputs");
     Launch L;
-    L.mode = p->op == UCL_OP_GROUPED_GEMM ? 1 : p->op == UCL_OP_CONV2D_FPROP ? 2 : 0;
-    L.batch = p->op == UCL_OP_BATCHED_GEMM ? p->batch : 1;
-    L.M = M; L.N = N;
-    L.K = p->op == UCL_OP_CONV2D_FPROP ? p->cR * p->cS * p->cC : p->K;
-    L.groups = p->groups; L.M_g = p->M_g;
-    if (L.mode == 2) {
-        L.la = 2; L.lb = 0;
-    } else {
-        if ((p->a_layout != UCL_LAYOUT_K_CONTIGUOUS && p->a_layout != UCL_LAYOUT_MN_CONTIGUOUS) ||
-            (p->b_layout != UCL_LAYOUT_K_CONTIGUOUS && p->b_layout != UCL_LAYOUT_MN_CONTIGUOUS))
-            return fail(UCL_ERR_INVALID_ARG, "a_layout / b_layout must be ucl_operand_layout values");
-        if (L.mode == 1 && p->a_layout != UCL_LAYOUT_K_CONTIGUOUS)
-            return fail(UCL_ERR_UNSUPPORTED, "grouped_gemm is built for a row-major A");
-        L.la = p->a_layout; L.lb = p->b_layout;
-        // packed operands: the same reach test for directly copied rows as the launch path applies
-        const int64_t Mmax = L.mode == 1 ? 0 : M;
-        L.ndirect_ok = L.lb == 1 && ((L.K - 1) * N + N) * 2 < (1ll << 31);
-        L.mdirect_ok = L.la == 1 && ((L.K - 1) * Mmax + Mmax) * 2 < (1ll << 31);
-    }
-    L.f16 = p->dt_in == UCL_F16;
-    L.dtD = p->dt_out;
-    if (L.mode == 2)
-        L.patch_ok = conv_patch_ok(p->cW, p->cC, p->cR, p->cS, p->pad_h, p->pad_w, p->stride_h, p->stride_w, p->dil_h, p->dil_w);
-    if (L.mode == 1)
-        for (int g = 0; g < L.groups; ++g) L.sum_Mg += L.M_g[g];
+    if (ucl_status st = launch_from_problem(p, L)) return st;
     const VariantDesc *v = select_variant(L, nullptr);
     if (!v) return fail(UCL_ERR_UNSUPPORTED, "no kernel built for this problem");
     memset(out, 0, sizeof(*out));
     out->tile_m = v->tile_m; out->tile_n = v->tile_n; out->tile_k = v->tile_k; out->stages = v->stages;
     out->raster = default_raster(*v, L);
     out->iterator = v->la == 3 ? UCL_ITER_FIXED_STRIDE_DILATION : v->la == 2 ? UCL_ITER_ANALYTIC : UCL_ITER_DEFAULT;
+    return UCL_OK;
+}
+
+ucl_status ucl_workspace_size(const ucl_problem *p, const ucl_tuning *tune, int64_t *bytes, int32_t *slices_out) {
+    g_err[0] = 0;
+    if (!bytes) return fail(UCL_ERR_INVALID_ARG, "output pointer is NULL");
+    *bytes = 0;
+    if (slices_out) *slices_out = 1;
+    Launch L;
+    if (ucl_status st = launch_from_problem(p, L)) return st;
+    if (tune && (tune->iterator < 0 || tune->iterator > UCL_ITER_FIXED_STRIDE_DILATION))
+        return fail(UCL_ERR_INVALID_ARG, "iterator=%d is not a ucl_conv_iterator", tune->iterator);
+    const VariantDesc *v = select_variant(L, tune);
+    if (!v) return fail(UCL_ERR_UNSUPPORTED, "no kernel built for this problem and tuning; see ucl_variant()");
+    SplitPlan sp;
+    if (ucl_status st = plan_split(L, *v, tune, count_tiles(L, v->tile_m, v->tile_n), sp)) return st;
+    *bytes = sp.bytes;
+    if (slices_out) *slices_out = sp.slices;
+    return UCL_OK;
+}
+
+ucl_status ucl_workspace_init(void *workspace, int64_t workspace_bytes, void *stream) {
+    g_err[0] = 0;
+    if (!workspace || !aligned16(workspace)) return fail(UCL_ERR_INVALID_ARG, "workspace must be a 16-byte aligned device pointer");
+    if (workspace_bytes < UCL_WORKSPACE_COUNTER_BYTES)
+        return fail(UCL_ERR_WORKSPACE, "a split-K workspace holds at least its %d bytes of counters, got %lld", UCL_WORKSPACE_COUNTER_BYTES, (long long)workspace_bytes);
+    hipLaunchKernelGGL(zero_words_kernel, dim3(UCL_WORKSPACE_COUNTER_BYTES / 16 / 256), dim3(256), 0, (hipStream_t)stream, (uint32_t *)workspace);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(UCL_ERR_LAUNCH, "kernel launch failed: %s", hipGetErrorString(e));
     return UCL_OK;
 }
 

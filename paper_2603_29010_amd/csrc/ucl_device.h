@@ -56,7 +56,12 @@ struct KParams {
     int32_t cH, cW, cC, cS, cP, cQ;
     int32_t pad_h, pad_w, str_h, str_w, dil_h, dil_w;
     int32_t n_steps;
-    int32_t pad_;
+    // split-K (gemm / batched): number of K slices (<= 1: none), K extent of a slice (multiple of 64),
+    // phase 0 = one launch, the last workgroup to arrive at a tile adds up; 1 = write partial tiles only;
+    // 2 = add up only
+    int32_t split_k, k_per_slice, split_phase;
+    float *ws_partials;
+    uint32_t *ws_counters;
     EpiStepDev steps[UCL_MAX_EPI_STEPS];   // must stay addressable as offsetof(KParams, steps)
     FusedEpi fused;
 };

@@ -336,9 +336,10 @@ __device__ __forceinline__ void apply_step(float (&v)[8], const EpiStepDev &s, c
 // ------------------------------------------------------------------------------------------------
 
 template <int TM_, int TN_, int TK_, int STAGES_, bool F16_, int MODE_ /*0 gemm+batched, 1 grouped, 2 conv*/,
-          int LA_ /*OperandLayout of A*/, int LB_ /*OperandLayout of B*/>
+          int LA_ /*OperandLayout of A*/, int LB_ /*OperandLayout of B*/, bool PERSIST_ = false /*persistent tile scheduler*/>
 struct KernelCfg {
     static constexpr int TM = TM_, TN = TN_, TK = TK_, STAGES = STAGES_, MODE = MODE_, LA = LA_, LB = LB_;
+    static constexpr bool PERSIST = PERSIST_;
     static constexpr int CPR = TK / 8;                            // 16-byte chunks per LDS row
     static constexpr int ROW_BYTES = TK * 2;
     static_assert(TK == 32 || TK == 64, "k-tile of 32 or 64 elements");
@@ -421,7 +422,7 @@ constexpr int bshare(int mi, int mblocks, int n) {
 }
 
 template <class Cfg>
-__global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(const KParams p, const typename Cfg::Groups gt) {
+__global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(const KParams p_arg, const typename Cfg::Groups gt) {
     constexpr int TM = Cfg::TM, TN = Cfg::TN, TK = Cfg::TK, STAGES = Cfg::STAGES;
     constexpr int MI = Cfg::MI, NI = Cfg::NI, MODE = Cfg::MODE, LA = Cfg::LA, LB = Cfg::LB;
     constexpr int A_ITERS = Cfg::A_ITERS, B_ITERS = Cfg::B_ITERS;
@@ -432,13 +433,37 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
 
     __shared__ __attribute__((aligned(1024))) char smem[Cfg::LDS_BYTES];
 
-    const int tid = threadIdx.x;
+    // ---- tile schedule ---------------------------------------------------------------------
+    // Default scheduler: the grid has one workgroup per tile (per tile and K slice with split-K) and
+    // the loop below runs once.  Persistent scheduler: the grid has one workgroup per CU slot (a
+    // multiple of 8, so a workgroup stays on the tile run of its XCD) and walks the tile order with
+    // a stride of the grid size.
+    for (int wg_id = blockIdx.x;;) {
+    // The kernel arguments are read through a pointer into the argument segment (p_arg is the first
+    // argument).  Persistent kernels make that pointer opaque once per tile: the compiler would
+    // otherwise load every argument ahead of the loop and keep all of them in registers across it.
+    typedef const __attribute__((address_space(4))) KParams ConstKParams;
+    ConstKParams *pp = (ConstKParams *)__builtin_amdgcn_kernarg_segment_ptr();
+    if constexpr (Cfg::PERSIST) asm volatile("" : "+s"(pp));
+    ConstKParams &p = *pp;
+    (void)p_arg;
+    int tid_ = threadIdx.x;
+    // (persistent kernels: everything derived from the thread index is worked out again for every tile,
+    // or the compiler keeps all of it in registers across the whole loop and runs out of them)
+    if constexpr (Cfg::PERSIST) asm volatile("" : "+v"(tid_));
+    const int tid = tid_;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / Cfg::WAVES_N, wn = wave % Cfg::WAVES_N;
-
-    // ---- tile schedule ---------------------------------------------------------------------
-    int t = xcd_remap(blockIdx.x, p.total_tiles);
+    // split-K (gemm / batched): workgroups [s * total_tiles, (s + 1) * total_tiles) work on K slice s
+    int slice = 0, wg_tile = wg_id;
+    if constexpr (MODE == 0 && !Cfg::PERSIST) {
+        if (p.split_k > 1 && p.split_phase != 2) {
+            slice = wg_id / p.total_tiles;
+            wg_tile = wg_id - slice * p.total_tiles;
+        }
+    }
+    int t = xcd_remap(wg_tile, p.total_tiles);
     int batch = 0, group = -1, tm, tn;
     int Mloc = p.M;
     const char *Ab = (const char *)p.A;
@@ -460,7 +485,21 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
         Bb += (int64_t)batch * p.b_bs * 2;
     }
     const int m0 = tm * TM, n0 = tn * TN;
-    const int K = p.K;
+    int k_len = p.K;
+    if constexpr (MODE == 0 && !Cfg::PERSIST) {
+        if (p.split_k > 1) {
+            // this slice's K range (a multiple of 64 long, so operand rows stay 16-byte aligned)
+            const int kb = slice * p.k_per_slice;
+            k_len = p.K - kb < p.k_per_slice ? p.K - kb : p.k_per_slice;
+            // the second launch of a parallel split-K only adds up the partial tiles: with K = 0 the
+            // loops below run no k-tile (their prologue copies land in LDS and are never read)
+            if (p.split_phase == 2) k_len = 0;
+            Ab += (int64_t)kb * (LA == kKContig ? 1 : p.lda) * 2;
+            Bb += (int64_t)kb * (LB == kKContig ? 1 : p.ldb) * 2;
+        }
+    }
+    const int K = k_len;
+    const int Kr = K > 0 ? K : 1;                      // rows of k a directly copied operand's resource covers (K = 0: see above)
     const int KT = (K + TK - 1) / TK;
     const bool k_tail = (K % TK) != 0;
 
@@ -488,7 +527,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
     } else if constexpr (LA == kMDirect) {
         // the stage holds TK rows (k) of TM elements (m), laid out and swizzled like the kNDirect B stage
         constexpr int CPRA = TM / 8, RPIA = kThreads / CPRA;
-        a_rsrc = buffer_rsrc(Ab + (int64_t)m0 * 2, (uint32_t)(((int64_t)(K - 1) * p.lda + (Mloc - m0)) * 2));
+        a_rsrc = buffer_rsrc(Ab + (int64_t)m0 * 2, (uint32_t)(((int64_t)(Kr - 1) * p.lda + (Mloc - m0)) * 2));
 #pragma unroll
         for (int i = 0; i < A_ITERS; ++i) {
             const int row = i * RPIA + tid / CPRA;
@@ -530,7 +569,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
     auto nd_swz = [](int row) { return (((row & 3) << 1) | (((row >> 3) & 3) << 3)) & (CPRB - 1); };
     const int nd_row = tid / CPRB;
     if constexpr (LB == kNDirect) {
-        b_rsrc = buffer_rsrc(Bb + (int64_t)n0 * 2, (uint32_t)(((int64_t)(K - 1) * p.ldb + (p.N - n0)) * 2));
+        b_rsrc = buffer_rsrc(Bb + (int64_t)n0 * 2, (uint32_t)(((int64_t)(Kr - 1) * p.ldb + (p.N - n0)) * 2));
 #pragma unroll
         for (int i = 0; i < B_ITERS; ++i) {
             const int row = i * RPIB + nd_row;
@@ -1176,6 +1215,59 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
     asm volatile("s_nop 15");
     asm volatile("s_nop 15");
 
+    // ---- split-K: partial tiles through the workspace ---------------------------------------------
+    // Slice s of tile t keeps its fp32 accumulators at partial[(s * tiles + t)][register][thread], one
+    // 128-bit store per accumulator and thread.  Whoever adds the slices up reads them back in the same
+    // layout, slice 0 first: the order of the additions is fixed, whichever workgroup does them.
+    if constexpr (MODE == 0 && !Cfg::PERSIST) {
+        if (p.split_k > 1) {
+            constexpr int64_t kTileElems = (int64_t)TM * TN;
+            // (slice and tile index are worked out again from the workgroup id rather than kept in
+            // registers across the mainloop; split-K never runs under the persistent scheduler)
+            int wg_again = blockIdx.x;
+            asm volatile("" : "+s"(wg_again));
+            const int slice2 = p.split_phase != 2 ? wg_again / p.total_tiles : 0;
+            const int t_lin = xcd_remap(wg_again - slice2 * p.total_tiles, p.total_tiles);
+            if (p.split_phase != 2) {
+                float *part = p.ws_partials + ((int64_t)slice2 * p.total_tiles + t_lin) * kTileElems + tid * 4;
+                static_for<MI>([&](auto mi) {
+                    static_for<NI>([&](auto ni) { *(f32x4_t *)(part + (mi * NI + ni) * (kThreads * 4)) = acc[mi][ni]; });
+                });
+                if (p.split_phase == 1) return;            // parallel mode, first launch: done
+                // serial mode: the workgroup that arrives last at the tile's counter does the rest.  Release
+                // this workgroup's partial tile to the device, count, and (if last) acquire the others'.
+                __threadfence();
+                __syncthreads();                           // (also: every wave is past its LDS reads and copies)
+                if (tid == 0) *(volatile int *)smem = (int)atomicAdd(&p.ws_counters[t_lin], 1u);
+                __syncthreads();
+                const int arrived = *(volatile int *)smem;
+                if (arrived != p.split_k - 1) return;
+                if (tid == 0) atomicExch(&p.ws_counters[t_lin], 0u);      // leave the counter as it was found
+                __threadfence();
+            }
+            static_for<MI>([&](auto mi) {
+                static_for<NI>([&](auto ni) {
+                    acc[mi][ni] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                    pin_acc(acc[mi][ni]);
+                });
+            });
+            for (int sl = 0; sl < p.split_k; ++sl) {
+                const float *part = p.ws_partials + ((int64_t)sl * p.total_tiles + t_lin) * kTileElems + tid * 4;
+                // (one row block at a time: the compiler would otherwise gather all of a slice's loads in
+                // front of the additions and need a second register file's worth of registers for them)
+                static_for<MI>([&](auto mi) {
+                    static_for<NI>([&](auto ni) {
+                        const f32x4_t v = __builtin_nontemporal_load((const f32x4_t *)(part + (mi * NI + ni) * (kThreads * 4)));
+                        acc[mi][ni] += v;
+                        pin_acc(acc[mi][ni]);          // back into its accumulation register: the sums must not
+                                                       // live in ordinary registers across the loop
+                    });
+                    asm volatile("" ::: "memory");
+                });
+            }
+        }
+    }
+
     // ---- epilogue ---------------------------------------------------------------------------------
     // The accumulators leave the MFMA layout (a lane holds 4 consecutive n of ONE row per quad)
     // through a wave-private LDS patch, one 32-row block at a time, and come back as 8 consecutive
@@ -1253,7 +1345,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
     // instruction cache instead of existing once per pass.
     // (one 32-row block; the caller stages the block and loops over blocks, so that the accumulator
     // registers are read at exactly one place in the code)
-    const FusedEpi &f = p.fused;
+    const __attribute__((address_space(4))) FusedEpi &f = p.fused;
     float bias8[8];
     const char *res_base = nullptr;       // residual, this lane's columns of row 0
     const char *res_u = nullptr;          // residual, element (0, 0) of this batch / group (wave-uniform)
@@ -1645,6 +1737,14 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
             }
         }
     }
+    if constexpr (!Cfg::PERSIST) {
+        break;
+    } else {
+        wg_id += gridDim.x;
+        if (wg_id >= p.total_tiles) break;
+        __syncthreads();                                  // the next tile's copies overwrite the staging patch
+    }
+    }   // tile loop
 #undef UCL_STAGE_BLOCK
 }
 

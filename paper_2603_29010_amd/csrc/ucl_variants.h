@@ -11,6 +11,8 @@ struct VariantDesc {
     int la, lb;         // 0: operand contiguous along K, 1: contiguous along M / N (register transpose); A only: 2 im2col gather,
                         // 3 resident patch; 4 (B) / 5 (A): contiguous along N / M, copied directly and read through the LDS transpose read
     int lds_bytes;
+    int persistent;     // 1: built for the persistent tile scheduler (grid = CU slots, workgroups loop over tiles)
+    int wgs_per_cu;     // workgroups of the kernel a CU is meant to hold (register budget it was built with)
     hipError_t (*launch)(const KParams &p, const GroupTable *gt, int grid, hipStream_t stream);
 };
 
