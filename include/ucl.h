@@ -15,8 +15,10 @@
  *   - Every tensor pointer is caller-owned DEVICE memory unless marked HOST.
  *     The library allocates nothing, frees nothing, keeps no pointer after a
  *     call returns, and never synchronises: each call validates its arguments
- *     on the host, then enqueues exactly one kernel on `stream`
- *     (a hipStream_t passed as void*; NULL = the null stream) and returns.
+ *     on the host, then enqueues its kernel on `stream` (a hipStream_t passed
+ *     as void*; NULL = the null stream) and returns: one kernel per call (two
+ *     for split-K in PARALLEL mode; ucl_gemm_static_workspace in SERIAL mode
+ *     puts a small fill kernel in front).
  *   - Strides are in ELEMENTS.  Inputs are UCL_BF16 or UCL_F16 (both operands
  *     the same type), accumulation is fp32, outputs are UCL_BF16, UCL_F16 or
  *     UCL_F32.
@@ -179,6 +181,24 @@ ucl_status ucl_gemm(int64_t M, int64_t N, int64_t K,
                     const void *B, int32_t dtB, int64_t b_rs, int64_t b_cs,
                     void *D, int32_t dtD, int64_t d_rs, int64_t d_cs,
                     const ucl_epilogue *epi, const ucl_tuning *tune, void *stream);
+
+/* ucl_gemm with split-K for callers that cannot allocate a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and results as
+ * ucl_gemm with the same tune (which must name split_k_mode SERIAL or PARALLEL; tune->workspace and
+ * tune->workspace_bytes are ignored), but the partial tiles and counters live in a workspace of
+ * UCL_STATIC_WORKSPACE_BYTES that is part of the library's device code: every GPU the library runs
+ * on holds one copy until the process ends.  The call allocates and frees nothing (the first call
+ * on a device looks the array's address up; make that call outside a graph capture).  A problem
+ * whose slices x tiles x tile_m x tile_n x 4 bytes of partial tiles (ucl_workspace_size) exceed the
+ * static workspace is rejected with UCL_ERR_WORKSPACE before anything is launched.  All calls on a
+ * GPU share that GPU's array: calls that overlap in time on one GPU race; the SERIAL form clears
+ * the counter area with a small fill kernel ahead of the GEMM kernel, on the same stream. */
+#define UCL_STATIC_WORKSPACE_BYTES (UCL_WORKSPACE_COUNTER_BYTES + (8 << 20))
+ucl_status ucl_gemm_static_workspace(int64_t M, int64_t N, int64_t K,
+                                     const void *A, int32_t dtA, int64_t a_rs, int64_t a_cs,
+                                     const void *B, int32_t dtB, int64_t b_rs, int64_t b_cs,
+                                     void *D, int32_t dtD, int64_t d_rs, int64_t d_cs,
+                                     const ucl_epilogue *epi, const ucl_tuning *tune, void *stream);
 
 /* Strided batched GEMM (grammar `batched_gemm_op`): the above for b in
  * [0, batch) with operands advanced by b * {a,b,d}_bs elements.  A batch

@@ -46,6 +46,7 @@ class _Tuning(C.Structure):
 SPLIT_K_MODES = {"none": 0, "serial": 1, "parallel": 2}
 SCHEDULERS = {"default": 0, "persistent": 1, "stream_k": 2}
 WORKSPACE_COUNTER_BYTES = 65536
+STATIC_WORKSPACE_BYTES = WORKSPACE_COUNTER_BYTES + (8 << 20)
 
 
 class _Problem(C.Structure):
@@ -99,6 +100,8 @@ def _load():
         lib.ucl_gemm.restype = C.c_int
         lib.ucl_gemm.argtypes = [i64, i64, i64, vp, i32, i64, i64, vp, i32, i64, i64, vp, i32, i64, i64,
                                  C.POINTER(_Epilogue), C.POINTER(_Tuning), vp]
+        lib.ucl_gemm_static_workspace.restype = C.c_int
+        lib.ucl_gemm_static_workspace.argtypes = lib.ucl_gemm.argtypes
         lib.ucl_batched_gemm.restype = C.c_int
         lib.ucl_batched_gemm.argtypes = [i64, i64, i64, i64, vp, i32, i64, i64, i64, vp, i32, i64, i64, i64,
                                          vp, i32, i64, i64, i64, C.POINTER(_Epilogue), C.POINTER(_Tuning), vp]
@@ -197,6 +200,12 @@ def ucl_gemm(M, N, K, A, dtA, a_rs, a_cs, B, dtB, b_rs, b_cs, D, dtD, d_rs, d_cs
              stream=0):
     _check(_load().ucl_gemm(M, N, K, A, _dt(dtA), a_rs, a_cs, B, _dt(dtB), b_rs, b_cs, D, _dt(dtD), d_rs, d_cs,
                             _opt(epi), _opt(tune), stream or None))
+
+
+def ucl_gemm_static_workspace(M, N, K, A, dtA, a_rs, a_cs, B, dtB, b_rs, b_cs, D, dtD, d_rs, d_cs, epi=None, tune=None,
+                              stream=0):
+    _check(_load().ucl_gemm_static_workspace(M, N, K, A, _dt(dtA), a_rs, a_cs, B, _dt(dtB), b_rs, b_cs, D, _dt(dtD),
+                                             d_rs, d_cs, _opt(epi), _opt(tune), stream or None))
 
 
 def ucl_batched_gemm(batch, M, N, K, A, dtA, a_rs, a_cs, a_bs, B, dtB, b_rs, b_cs, b_bs, D, dtD, d_rs, d_cs,

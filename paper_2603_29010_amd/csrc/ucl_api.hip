@@ -6,7 +6,14 @@
 #include <cstring>
 #include <vector>
 
+#include <mutex>
+
 #include "ucl_variants.h"
+
+// Split-K workspace of ucl_gemm_static_workspace: counters followed by partial tiles, held by every
+// GPU the library runs on until the process ends.  Host code never uses this name as an address: it
+// asks the runtime for the array's device address once per device (static_workspace() below).
+static __device__ __align__(256) unsigned char scratch[UCL_STATIC_WORKSPACE_BYTES];
 
 namespace ucl {
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
@@ -294,6 +301,12 @@ ucl_status check_common(int64_t M, int64_t N, int64_t K, int dtA, int dtB, int d
 
 constexpr int kNumCUs = 256;
 
+// Fill kernel for the counter area of a split-K workspace (a kernel, not a memset node: the call may
+// be captured into a HIP graph).  One 128-bit store per thread.
+__global__ void zero_words_kernel(uint32_t *w) {
+    ((u32x4 *)w)[blockIdx.x * blockDim.x + threadIdx.x] = u32x4{0u, 0u, 0u, 0u};
+}
+
 // split-K plan of a launch: slices (1 = none), K extent per slice, workspace bytes.
 struct SplitPlan {
     int slices = 1;
@@ -339,7 +352,7 @@ ucl_status plan_split(const Launch &L, const VariantDesc &v, const ucl_tuning *t
     return UCL_OK;
 }
 
-ucl_status run(const Launch &L, KParams &kp, const ucl_tuning *tune, void *stream) {
+ucl_status run(const Launch &L, KParams &kp, const ucl_tuning *tune, void *stream, bool clear_counters = false) {
     if (tune && (tune->iterator < 0 || tune->iterator > UCL_ITER_FIXED_STRIDE_DILATION))
         return fail(UCL_ERR_INVALID_ARG, "iterator=%d is not a ucl_conv_iterator", tune->iterator);
     // (the GEMM entry points ignore the iterator)
@@ -418,6 +431,14 @@ ucl_status run(const Launch &L, KParams &kp, const ucl_tuning *tune, void *strea
             e = v->launch(kp, gtp, (int)total, (hipStream_t)stream);
         }
     } else {
+        if (clear_counters && sp.slices > 1) {
+            // the static workspace is shared by every call on this GPU: start from zeroed counters whatever
+            // an earlier call left behind (a fill kernel, so that the call can be captured into a graph)
+            hipLaunchKernelGGL(zero_words_kernel, dim3(UCL_WORKSPACE_COUNTER_BYTES / 16 / 256), dim3(256), 0, (hipStream_t)stream,
+                               (uint32_t *)tune->workspace);
+            e = hipGetLastError();
+            if (e != hipSuccess) return fail(UCL_ERR_LAUNCH, "kernel launch failed: %s", hipGetErrorString(e));
+        }
         int64_t grid = total * sp.slices;
         if (v->persistent) {
             // one workgroup per CU slot; a multiple of 8 keeps each workgroup on the tile run of its XCD
@@ -434,7 +455,7 @@ ucl_status gemm_like(int64_t batch, int64_t M, int64_t N, int64_t K,
                      const void *A, int dtA, int64_t a_rs, int64_t a_cs, int64_t a_bs,
                      const void *B, int dtB, int64_t b_rs, int64_t b_cs, int64_t b_bs,
                      void *D, int dtD, int64_t d_rs, int64_t d_cs, int64_t d_bs,
-                     const ucl_epilogue *epi, const ucl_tuning *tune, void *stream) {
+                     const ucl_epilogue *epi, const ucl_tuning *tune, void *stream, bool clear_counters = false) {
     g_err[0] = 0;
     if (batch <= 0) return fail(UCL_ERR_INVALID_ARG, "batch=%lld must be positive", (long long)batch);
     if (ucl_status st = check_common(M, N, K, dtA, dtB, dtD, A, B, D)) return st;
@@ -458,7 +479,7 @@ ucl_status gemm_like(int64_t batch, int64_t M, int64_t N, int64_t K,
     kp.M = (int32_t)M; kp.N = (int32_t)N; kp.K = (int32_t)K;
     kp.dtD = dtD;
     kp.d_vec = aligned16(D) && (d_rs % (16 / elem_size(dtD)) == 0) && (d_bs % (16 / elem_size(dtD)) == 0);
-    return run(L, kp, tune, stream);
+    return run(L, kp, tune, stream, clear_counters);
 }
 
 // ---- SOL ---------------------------------------------------------------------------------------
@@ -529,6 +550,29 @@ ucl_status characterise(const ucl_problem *p, double *flops, double *bytes, int6
 }
 
 
+// Device address of this GPU's copy of the static workspace, looked up once per device with that
+// device current (each GPU holds its own copy at its own address).
+constexpr int kMaxDevices = 64;
+std::mutex g_static_mu;
+void *g_static_ptr[kMaxDevices] = {};
+
+ucl_status static_workspace(void **out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(UCL_ERR_LAUNCH, "hipGetDevice failed: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= kMaxDevices) return fail(UCL_ERR_UNSUPPORTED, "device index %d outside [0, %d)", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lock(g_static_mu);
+    if (!g_static_ptr[dev]) {
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr)
+            return fail(UCL_ERR_LAUNCH, "hipGetSymbolAddress of the static workspace failed: %s", hipGetErrorString(e));
+        g_static_ptr[dev] = ptr;
+    }
+    *out = g_static_ptr[dev];
+    return UCL_OK;
+}
+
 // Launch description of a problem given as ucl_problem (packed operands), for the host-only queries.
 ucl_status launch_from_problem(const ucl_problem *p, Launch &L) {
     double f, b;
@@ -563,11 +607,6 @@ ucl_status launch_from_problem(const ucl_problem *p, Launch &L) {
     return UCL_OK;
 }
 
-// Fill kernel for the counter area of a split-K workspace (a kernel, not a memset node: the call may
-// be captured into a HIP graph).  One 128-bit store per thread.
-__global__ void zero_words_kernel(uint32_t *w) {
-    ((u32x4 *)w)[blockIdx.x * blockDim.x + threadIdx.x] = u32x4{0u, 0u, 0u, 0u};
-}
 
 }  // namespace
 }  // namespace ucl
@@ -580,6 +619,29 @@ ucl_status ucl_gemm(int64_t M, int64_t N, int64_t K, const void *A, int32_t dtA,
                     const void *B, int32_t dtB, int64_t b_rs, int64_t b_cs, void *D, int32_t dtD, int64_t d_rs,
                     int64_t d_cs, const ucl_epilogue *epi, const ucl_tuning *tune, void *stream) {
     return gemm_like(1, M, N, K, A, dtA, a_rs, a_cs, 0, B, dtB, b_rs, b_cs, 0, D, dtD, d_rs, d_cs, 0, epi, tune, stream);
+}
+
+ucl_status ucl_gemm_static_workspace(int64_t M, int64_t N, int64_t K, const void *A, int32_t dtA, int64_t a_rs, int64_t a_cs,
+                                     const void *B, int32_t dtB, int64_t b_rs, int64_t b_cs, void *D, int32_t dtD, int64_t d_rs,
+                                     int64_t d_cs, const ucl_epilogue *epi, const ucl_tuning *tune, void *stream) {
+    g_err[0] = 0;
+    if (!tune || tune->split_k_mode == UCL_SPLIT_K_NONE)
+        return fail(UCL_ERR_INVALID_ARG, "ucl_gemm_static_workspace is the split-K form of ucl_gemm: tune must name split_k_mode serial or parallel");
+    void *ws = nullptr;
+    if (ucl_status st = static_workspace(&ws)) return st;
+    ucl_tuning t = *tune;
+    t.workspace = ws;                       // (the device address, never the array's name)
+    t.workspace_bytes = UCL_STATIC_WORKSPACE_BYTES;
+    const ucl_status st = gemm_like(1, M, N, K, A, dtA, a_rs, a_cs, 0, B, dtB, b_rs, b_cs, 0, D, dtD, d_rs, d_cs, 0, epi, &t, stream,
+                                    /*clear_counters=*/t.split_k_mode == UCL_SPLIT_K_SERIAL);
+    if (st == UCL_ERR_WORKSPACE) {
+        // say which limit was hit: the message of the general path speaks of the caller's workspace
+        char detail[384];
+        snprintf(detail, sizeof(detail), "%s", g_err);
+        return fail(UCL_ERR_WORKSPACE, "the static workspace holds %lld bytes: %s (use fewer slices, or ucl_gemm with a workspace of your own)",
+                    (long long)UCL_STATIC_WORKSPACE_BYTES, detail);
+    }
+    return st;
 }
 
 ucl_status ucl_batched_gemm(int64_t batch, int64_t M, int64_t N, int64_t K, const void *A, int32_t dtA, int64_t a_rs,
