@@ -225,6 +225,44 @@ def conv2d_fprop(x, dtX, w, dtW, Nb, H, W, Cin, Ko, R, S, pad=(0, 0), stride=(1,
     return (D, Sabs) if want_abs else D
 
 
+def conv2d_dgrad(dy, dtY, w, dtW, Nb, H, W, Cin, Ko, R, S, pad=(0, 0), stride=(1, 1), dil=(1, 1),
+                 chain=None, rows=None, want_abs=False):
+    """dy NPQK (P, Q as fprop gives them for this geometry), w KRSC -> dx as a [Nb*H*W (or len(rows)), Cin]
+    float64 matrix (grammar `conv2d_dgrad`)."""
+    keep = []
+    _check(dy, dtY); _check(w, dtW)
+    c = _chain(chain, keep)
+    rp, nr, rk = _rows(rows)
+    total = nr if rows is not None else Nb * H * W
+    D = np.empty((total, Cin), dtype=np.float64)
+    Sabs = np.empty((total, Cin), dtype=np.float64) if want_abs else None
+    lib().orc_conv2d_dgrad(*(C.c_int64(v) for v in (Nb, H, W, Cin, Ko, R, S, pad[0], pad[1],
+                                                    stride[0], stride[1], dil[0], dil[1])),
+                           _ptr(dy), DT[dtY], _ptr(w), DT[dtW],
+                           C.byref(c) if c is not None else None, rp, C.c_int64(nr),
+                           _ptr(D), _ptr(Sabs) if want_abs else None)
+    return (D, Sabs) if want_abs else D
+
+
+def conv2d_wgrad(dy, dtY, x, dtX, Nb, H, W, Cin, Ko, R, S, pad=(0, 0), stride=(1, 1), dil=(1, 1),
+                 chain=None, rows=None, want_abs=False):
+    """dy NPQK, x NHWC -> dw as a [Ko (or len(rows)), R*S*Cin] float64 matrix, i.e. KRSC
+    (grammar `conv2d_wgrad`)."""
+    keep = []
+    _check(dy, dtY); _check(x, dtX)
+    c = _chain(chain, keep)
+    rp, nr, rk = _rows(rows)
+    total = nr if rows is not None else Ko
+    D = np.empty((total, R * S * Cin), dtype=np.float64)
+    Sabs = np.empty((total, R * S * Cin), dtype=np.float64) if want_abs else None
+    lib().orc_conv2d_wgrad(*(C.c_int64(v) for v in (Nb, H, W, Cin, Ko, R, S, pad[0], pad[1],
+                                                    stride[0], stride[1], dil[0], dil[1])),
+                           _ptr(dy), DT[dtY], _ptr(x), DT[dtX],
+                           C.byref(c) if c is not None else None, rp, C.c_int64(nr),
+                           _ptr(D), _ptr(Sabs) if want_abs else None)
+    return (D, Sabs) if want_abs else D
+
+
 def transpose(src, dtype, batch, rows, cols):
     """dst[b][c][r] = src[b][r][c] as unrounded float64 (grammar `transpose_op`); round_to() gives
     what the target type stores."""

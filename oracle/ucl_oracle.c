@@ -337,6 +337,101 @@ void orc_conv2d_fprop(int64_t Nb, int64_t H, int64_t W, int64_t C, int64_t Ko,
     }
 }
 
+
+/* Data gradient of the convolution above (grammar `conv2d_dgrad`): the adjoint of fprop with
+ * respect to x.  dy [Nb,P,Q,Ko], w [Ko,R,S,C] -> dx [Nb,H,W,C],
+ *   dx[n,h,w,c] = E( sum over (p,r), (q,s), ko with p*stride_h - pad_h + r*dil_h == h and
+ *                    q*stride_w - pad_w + s*dil_w == w of dy[n,p,q,ko] * w[ko,r,s,c] ),
+ * i.e. every product of fprop in which x[n,h,w,c] takes part, with the other factor's partner dy.
+ * For a tap r the matching output row is p = (h + pad_h - r*dil_h) / stride_h when that division
+ * is exact and 0 <= p < P.  The epilogue sees row index (n*H+h)*W+w and column index c. */
+void orc_conv2d_dgrad(int64_t Nb, int64_t H, int64_t W, int64_t C, int64_t Ko,
+                      int64_t R, int64_t S,
+                      int64_t pad_h, int64_t pad_w, int64_t stride_h, int64_t stride_w,
+                      int64_t dil_h, int64_t dil_w,
+                      const void *dy, int dtY, const void *w, int dtW,
+                      const orc_chain *chain,
+                      const int64_t *rows, int64_t n_rows,
+                      double *Dout, double *absacc) {
+    int64_t P = orc_conv_out_dim(H, pad_h, dil_h, R, stride_h);
+    int64_t Q = orc_conv_out_dim(W, pad_w, dil_w, S, stride_w);
+    int64_t total = rows ? n_rows : Nb * H * W;
+#pragma omp parallel for schedule(static)
+    for (int64_t j = 0; j < total; ++j) {
+        int64_t row = rows ? rows[j] : j;
+        int64_t wi = row % W;
+        int64_t h = (row / W) % H;
+        int64_t n = row / (W * H);
+        for (int64_t c = 0; c < C; ++c) {
+            double acc = 0.0, aacc = 0.0;
+            for (int64_t r = 0; r < R; ++r) {
+                int64_t th = h + pad_h - r * dil_h;
+                if (th < 0 || th % stride_h != 0 || th / stride_h >= P) continue;
+                int64_t p = th / stride_h;
+                for (int64_t s2 = 0; s2 < S; ++s2) {
+                    int64_t tw = wi + pad_w - s2 * dil_w;
+                    if (tw < 0 || tw % stride_w != 0 || tw / stride_w >= Q) continue;
+                    int64_t q = tw / stride_w;
+                    for (int64_t ko = 0; ko < Ko; ++ko) {
+                        double gv = orc_load(dy, dtY, ((n * P + p) * Q + q) * Ko + ko);
+                        double wv = orc_load(w, dtW, ((ko * R + r) * S + s2) * C + c);
+                        acc += gv * wv;
+                        aacc += fabs(gv) * fabs(wv);
+                    }
+                }
+            }
+            Dout[j * C + c] = orc_epilogue(acc, row, c, chain);
+            if (absacc) absacc[j * C + c] = aacc;
+        }
+    }
+}
+
+/* Weight gradient (grammar `conv2d_wgrad`): the adjoint of fprop with respect to w.
+ * dy [Nb,P,Q,Ko], x [Nb,H,W,C] -> dw [Ko,R,S,C],
+ *   dw[ko,r,s,c] = E( sum_{n,p,q} dy[n,p,q,ko] * x[n, p*stride_h - pad_h + r*dil_h,
+ *                                                    q*stride_w - pad_w + s*dil_w, c] ),
+ * out-of-image x = 0.  The epilogue sees dw as a Ko x (R*S*C) matrix: row ko, column (r*S+s)*C+c.
+ * rows != NULL restricts the computation to the listed ko. */
+void orc_conv2d_wgrad(int64_t Nb, int64_t H, int64_t W, int64_t C, int64_t Ko,
+                      int64_t R, int64_t S,
+                      int64_t pad_h, int64_t pad_w, int64_t stride_h, int64_t stride_w,
+                      int64_t dil_h, int64_t dil_w,
+                      const void *dy, int dtY, const void *x, int dtX,
+                      const orc_chain *chain,
+                      const int64_t *rows, int64_t n_rows,
+                      double *Dout, double *absacc) {
+    int64_t P = orc_conv_out_dim(H, pad_h, dil_h, R, stride_h);
+    int64_t Q = orc_conv_out_dim(W, pad_w, dil_w, S, stride_w);
+    int64_t total = rows ? n_rows : Ko;
+    int64_t cols = R * S * C;
+#pragma omp parallel for schedule(static) collapse(2)
+    for (int64_t j = 0; j < total; ++j) {
+        for (int64_t col = 0; col < cols; ++col) {
+            int64_t ko = rows ? rows[j] : j;
+            int64_t c = col % C;
+            int64_t s2 = (col / C) % S;
+            int64_t r = col / (C * S);
+            double acc = 0.0, aacc = 0.0;
+            for (int64_t n = 0; n < Nb; ++n) {
+                for (int64_t p = 0; p < P; ++p) {
+                    int64_t h = p * stride_h - pad_h + r * dil_h;
+                    if (h < 0 || h >= H) continue;
+                    for (int64_t q = 0; q < Q; ++q) {
+                        int64_t ww = q * stride_w - pad_w + s2 * dil_w;
+                        if (ww < 0 || ww >= W) continue;
+                        double gv = orc_load(dy, dtY, ((n * P + p) * Q + q) * Ko + ko);
+                        double xv = orc_load(x, dtX, ((n * H + h) * W + ww) * C + c);
+                        acc += gv * xv;
+                        aacc += fabs(gv) * fabs(xv);
+                    }
+                }
+            }
+            Dout[j * cols + col] = orc_epilogue(acc, ko, col, chain);
+            if (absacc) absacc[j * cols + col] = aacc;
+        }
+    }
+}
+
 /* ---- SOL analysis (paper Sec. 4.1; Appendix "Example SOL Report") ---------- */
 
 typedef struct {
@@ -348,8 +443,6 @@ typedef struct {
     int32_t pad_;
 } orc_sol;
 
-/* The four steps of the analysis, given work (flops, bytes) and published peaks
- * (FLOP/s and B/s at max clocks) scaled linearly by clock ratios. */
 /* Transform stage of a `pipeline(...)` program (grammar `transpose_op`): per batch a rows x cols
  * matrix written transposed, dst[b][c][r] = src[b][r][c], as unrounded doubles (the caller rounds
  * to the target type with orc_round).  Three plain loops. */
@@ -360,6 +453,8 @@ void orc_transpose(int64_t batch, int64_t rows, int64_t cols, const void *src, i
                 dst[(b * cols + c) * rows + r] = orc_load(src, dtype, (b * rows + r) * cols + c);
 }
 
+/* The four steps of the analysis, given work (flops, bytes) and published peaks
+ * (FLOP/s and B/s at max clocks) scaled linearly by clock ratios. */
 void orc_sol_bound(double flops, double bytes,
                    double peak_flops_at_max, double compute_clock_ratio,
                    double peak_bw_at_max, double mem_clock_ratio, orc_sol *out) {
