@@ -155,7 +155,7 @@ typedef enum ucl_tile_scheduler { UCL_SCHED_DEFAULT = 0, UCL_SCHED_PERSISTENT = 
  * knob's Identity1..8), 0 = table default.  The order is also XCD-aware:
  * workgroup ids that land on the same XCD (id mod 8) get neighbouring tiles.
  * iterator is a ucl_conv_iterator; the GEMM entry points accept any valid value and ignore it.
- * split_k_mode / split_k_slices (ucl_gemm and ucl_batched_gemm only; slices = 0 lets the library
+ * split_k_mode / split_k_slices (ucl_gemm, ucl_batched_gemm and ucl_conv2d_wgrad only; slices = 0 lets the library
  * choose, slices = 1 is no split): the library allocates nothing, so the caller passes
  * `workspace`, DEVICE memory, 16-byte aligned, of at least ucl_workspace_size() bytes.  SERIAL needs
  * the first UCL_WORKSPACE_COUNTER_BYTES to be zero when the call starts: clear them once with
@@ -238,6 +238,34 @@ ucl_status ucl_conv2d_fprop(int64_t N, int64_t H, int64_t W, int64_t C, int64_t 
                             void *y, int32_t dtY,
                             const ucl_epilogue *epi, const ucl_tuning *tune, void *stream);
 
+/* Data gradient of the convolution above (grammar `conv2d_dgrad`), as an implicit GEMM of
+ * N*H*W rows, C columns and R*S*Kout deep: dy [N,P,Q,Kout], w [Kout,R,S,C] -> dx [N,H,W,C],
+ *   dx[n,h,w,c] = E( sum over (p,r), (q,s), k with p*stride_h - pad_h + r*dil_h == h and
+ *                    q*stride_w - pad_w + s*dil_w == w of dy[n,p,q,k] * w[k,r,s,c] ),
+ * P and Q as ucl_conv2d_fprop derives them from the same arguments (N, H, W, C describe the
+ * ACTIVATIONS, i.e. the output of this call).  The chain sees m = (n*H + h)*W + w and n = c.
+ * C and Kout must be multiples of 8, all three tensors packed, 16-byte aligned, below 2 GiB. */
+ucl_status ucl_conv2d_dgrad(int64_t N, int64_t H, int64_t W, int64_t C, int64_t Kout,
+                            int64_t R, int64_t S, int64_t pad_h, int64_t pad_w,
+                            int64_t stride_h, int64_t stride_w, int64_t dil_h, int64_t dil_w,
+                            const void *dy, int32_t dtDy, const void *w, int32_t dtW,
+                            void *dx, int32_t dtDx,
+                            const ucl_epilogue *epi, const ucl_tuning *tune, void *stream);
+
+/* Weight gradient (grammar `conv2d_wgrad`), as an implicit GEMM of Kout rows, R*S*C columns and
+ * N*P*Q deep: dy [N,P,Q,Kout], x [N,H,W,C] -> dw [Kout,R,S,C],
+ *   dw[k,r,s,c] = E( sum_{n,p,q} dy[n,p,q,k] * x[n, p*stride_h - pad_h + r*dil_h,
+ *                                                   q*stride_w - pad_w + s*dil_w, c] ),
+ * out-of-image x contributing zero.  The chain sees m = k and n = (r*S + s)*C + c.  The deep
+ * reduction over few output tiles is what split-K is for: tune->split_k_mode / workspace apply as
+ * for ucl_gemm (ucl_workspace_size with UCL_OP_CONV2D_WGRAD).  Same size and alignment rules. */
+ucl_status ucl_conv2d_wgrad(int64_t N, int64_t H, int64_t W, int64_t C, int64_t Kout,
+                            int64_t R, int64_t S, int64_t pad_h, int64_t pad_w,
+                            int64_t stride_h, int64_t stride_w, int64_t dil_h, int64_t dil_w,
+                            const void *dy, int32_t dtDy, const void *x, int32_t dtX,
+                            void *dw, int32_t dtDw,
+                            const ucl_epilogue *epi, const ucl_tuning *tune, void *stream);
+
 /* Transform stage of a `pipeline(...)` program (grammar `transpose_op`:
  * transpose(tensor, NCL, NLC [, dtype_in, dtype_out]); NCHW <-> NHWC is the same
  * with H*W flattened into L): src is `batch` packed row-major rows x cols matrices,
@@ -256,15 +284,15 @@ ucl_status ucl_transpose(int64_t batch, int64_t rows, int64_t cols, const void *
 /* ---- Speed-of-Light analysis (paper Sec. 4.1, four steps) ------------------ */
 
 typedef enum ucl_op_kind { UCL_OP_GEMM = 0, UCL_OP_BATCHED_GEMM = 1, UCL_OP_GROUPED_GEMM = 2,
-                           UCL_OP_CONV2D_FPROP = 3 } ucl_op_kind;
+                           UCL_OP_CONV2D_FPROP = 3, UCL_OP_CONV2D_DGRAD = 4, UCL_OP_CONV2D_WGRAD = 5 } ucl_op_kind;
 
 /* Which extent of a GEMM operand is contiguous in memory (`.with_layout`): A RowMajor and
  * B ColumnMajor are contiguous along K, A ColumnMajor and B RowMajor along M / N. */
 typedef enum ucl_operand_layout { UCL_LAYOUT_K_CONTIGUOUS = 0, UCL_LAYOUT_MN_CONTIGUOUS = 1 } ucl_operand_layout;
 
 /* Problem characterisation input.  GEMM family: batch (1 for gemm), M, N, K;
- * grouped: groups and M_g (HOST), N, K.  Conv: N,H,W,C,Kout,R,S and pads,
- * strides, dilations.  dt_in / dt_out are ucl_dtype.  The epilogue matters
+ * grouped: groups and M_g (HOST), N, K.  Conv (fprop, dgrad, wgrad alike): N,H,W,C,Kout,R,S
+ * and pads, strides, dilations of the forward convolution.  dt_in / dt_out are ucl_dtype.  The epilogue matters
  * only through the bytes of its tensor operands (each read or written once).
  * a_layout / b_layout (ucl_operand_layout, GEMM family only) do not change the
  * SOL figures; ucl_select_tuning needs them because the kernels built for an
@@ -336,7 +364,7 @@ ucl_status ucl_tile_map(int32_t groups, const int32_t *tiles_m, int32_t tiles_n,
 typedef struct ucl_variant_info {
     int32_t tile_m, tile_n, tile_k, stages;
     int32_t iterator;           /* ucl_conv_iterator (conv variants), else 0 */
-    int32_t op_class;           /* 0 gemm + batched_gemm, 1 grouped_gemm, 2 conv2d_fprop */
+    int32_t op_class;           /* 0 gemm + batched_gemm, 1 grouped_gemm, 2 conv2d_fprop, 3 conv2d_dgrad, 4 conv2d_wgrad */
     int32_t dt_in;              /* ucl_dtype of both inputs */
     int32_t a_layout, b_layout; /* ucl_operand_layout the variant serves (conv: 0) */
     int32_t a_path, b_path;     /* how the operand reaches LDS: 0 direct 128-bit copies of K-contiguous rows,

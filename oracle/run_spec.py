@@ -4,7 +4,7 @@ TEST INFRASTRUCTURE: imported by tests, the smoke check and the benchmark's CPU-
 """
 import numpy as np
 
-from . import batched_gemm, conv2d_fprop, gemm, grouped_gemm
+from . import batched_gemm, conv2d_dgrad, conv2d_fprop, conv2d_wgrad, gemm, grouped_gemm
 
 _TENSOR_OPS = {"bias", "per_col_scale", "row_broadcast", "per_row_scale", "column_broadcast",
                "aux_load"}
@@ -59,4 +59,9 @@ def run(spec, rows=None, want_abs=False):
                             spec["W"], spec["C"], spec["Ko"], spec["R"], spec["S"], pad=spec["pad"],
                             stride=spec["stride"], dil=spec["dil"], chain=_chain(spec), rows=rows,
                             want_abs=want_abs)
+    if op in ("conv2d_dgrad", "conv2d_wgrad"):
+        fn, other = (conv2d_dgrad, spec["w"]) if op == "conv2d_dgrad" else (conv2d_wgrad, spec["x"])
+        return fn(spec["dy"], spec["dt_in"], other, spec["dt_in"], spec["Nb"], spec["H"], spec["W"], spec["C"],
+                  spec["Ko"], spec["R"], spec["S"], pad=spec["pad"], stride=spec["stride"], dil=spec["dil"],
+                  chain=_chain(spec), rows=rows, want_abs=want_abs)
     raise ValueError(op)

@@ -16,7 +16,7 @@ EPI_OPS = {
     "per_row_scale": 15, "per_col_scale": 16, "row_broadcast": 17, "column_broadcast": 18,
     "aux_store": 19,
 }
-OP_KINDS = {"gemm": 0, "batched_gemm": 1, "grouped_gemm": 2, "conv2d_fprop": 3}
+OP_KINDS = {"gemm": 0, "batched_gemm": 1, "grouped_gemm": 2, "conv2d_fprop": 3, "conv2d_dgrad": 4, "conv2d_wgrad": 5}
 MAX_EPI_STEPS = 8
 
 
@@ -111,6 +111,9 @@ def _load():
         lib.ucl_conv2d_fprop.restype = C.c_int
         lib.ucl_conv2d_fprop.argtypes = [i64] * 13 + [vp, i32, vp, i32, vp, i32, C.POINTER(_Epilogue),
                                                       C.POINTER(_Tuning), vp]
+        for fn in (lib.ucl_conv2d_dgrad, lib.ucl_conv2d_wgrad):
+            fn.restype = C.c_int
+            fn.argtypes = lib.ucl_conv2d_fprop.argtypes
         lib.ucl_transpose.restype = C.c_int
         lib.ucl_transpose.argtypes = [i64, i64, i64, vp, i32, vp, i32, vp]
         lib.ucl_sol_bound.restype = C.c_int
@@ -227,6 +230,18 @@ def ucl_conv2d_fprop(N, H, W, Cin, Kout, R, S, pad_h, pad_w, stride_h, stride_w,
                      y, dtY, epi=None, tune=None, stream=0):
     _check(_load().ucl_conv2d_fprop(N, H, W, Cin, Kout, R, S, pad_h, pad_w, stride_h, stride_w, dil_h, dil_w,
                                     x, _dt(dtX), w, _dt(dtW), y, _dt(dtY), _opt(epi), _opt(tune), stream or None))
+
+
+def ucl_conv2d_dgrad(N, H, W, Cin, Kout, R, S, pad_h, pad_w, stride_h, stride_w, dil_h, dil_w, dy, dtDy, w, dtW,
+                     dx, dtDx, epi=None, tune=None, stream=0):
+    _check(_load().ucl_conv2d_dgrad(N, H, W, Cin, Kout, R, S, pad_h, pad_w, stride_h, stride_w, dil_h, dil_w,
+                                    dy, _dt(dtDy), w, _dt(dtW), dx, _dt(dtDx), _opt(epi), _opt(tune), stream or None))
+
+
+def ucl_conv2d_wgrad(N, H, W, Cin, Kout, R, S, pad_h, pad_w, stride_h, stride_w, dil_h, dil_w, dy, dtDy, x, dtX,
+                     dw, dtDw, epi=None, tune=None, stream=0):
+    _check(_load().ucl_conv2d_wgrad(N, H, W, Cin, Kout, R, S, pad_h, pad_w, stride_h, stride_w, dil_h, dil_w,
+                                    dy, _dt(dtDy), x, _dt(dtX), dw, _dt(dtDw), _opt(epi), _opt(tune), stream or None))
 
 
 def ucl_transpose(batch, rows, cols, src, dt_src, dst, dt_dst, stream=0):

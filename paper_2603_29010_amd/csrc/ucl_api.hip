@@ -37,7 +37,7 @@ ucl_status fail(ucl_status st, const char *fmt, ...) {
 const std::vector<VariantDesc> &all_variants() {
     static const std::vector<VariantDesc> v = [] {
         std::vector<VariantDesc> out;
-        for (VariantList l : {variants_gemm_kk_bf16_a(), variants_gemm_kk_bf16_b(), variants_gemm_kk_bf16_c(), variants_gemm_kk_bf16_d(), variants_gemm_kk_f16_a(), variants_gemm_kk_f16_b(), variants_gemm_mn_bf16(), variants_gemm_mn_f16(), variants_grouped_a(), variants_grouped_b(), variants_conv_a(), variants_conv_b(), variants_conv_f16(), variants_conv_halo(), variants_gemm_kn_bf16(), variants_gemm_kn_f16(), variants_gemm_mx_bf16(), variants_gemm_mx_f16(), variants_grouped_kn()})
+        for (VariantList l : {variants_gemm_kk_bf16_a(), variants_gemm_kk_bf16_b(), variants_gemm_kk_bf16_c(), variants_gemm_kk_bf16_d(), variants_gemm_kk_f16_a(), variants_gemm_kk_f16_b(), variants_gemm_mn_bf16(), variants_gemm_mn_f16(), variants_grouped_a(), variants_grouped_b(), variants_conv_a(), variants_conv_b(), variants_conv_f16(), variants_conv_halo(), variants_gemm_kn_bf16(), variants_gemm_kn_f16(), variants_gemm_mx_bf16(), variants_gemm_mx_f16(), variants_grouped_kn(), variants_conv_dgrad(), variants_conv_wgrad()})
             for (int i = 0; i < l.n; ++i) out.push_back(l.v[i]);
         return out;
     }();
@@ -63,7 +63,7 @@ bool op_is_matrix(int op) { return op == UCL_EPI_AUX_LOAD || op == UCL_EPI_AUX_S
 
 // ---- generic description of one launch, filled by the four entry points -------------------------
 struct Launch {
-    int mode = 0;                 // 0 gemm / batched, 1 grouped, 2 conv
+    int mode = 0;                 // 0 gemm / batched, 1 grouped, 2 conv fprop, 3 conv dgrad, 4 conv wgrad
     int64_t batch = 1, M = 0, N = 0, K = 0;
     int la = 0, lb = 0;           // operand layouts
     int f16 = 0;
@@ -329,7 +329,7 @@ ucl_status plan_split(const Launch &L, const VariantDesc &v, const ucl_tuning *t
             return fail(UCL_ERR_INVALID_ARG, "split_k_slices=%d with split_k_mode none: name serial or parallel", tune->split_k_slices);
         return UCL_OK;
     }
-    if (L.mode != 0) return fail(UCL_ERR_UNSUPPORTED, "split-K is built for gemm and batched_gemm");
+    if (L.mode != 0 && L.mode != 4) return fail(UCL_ERR_UNSUPPORTED, "split-K is built for gemm, batched_gemm and conv2d_wgrad");
     if (tune->scheduler == UCL_SCHED_PERSISTENT)
         return fail(UCL_ERR_UNSUPPORTED, "split-K and the persistent scheduler cannot be combined");
     const int64_t kt = (L.K + 63) / 64;                     // slices are whole multiples of 64 along K
@@ -516,17 +516,29 @@ ucl_status characterise(const ucl_problem *p, double *flops, double *bytes, int6
         *bytes = (sumM * p->K + (double)p->groups * p->K * p->N) * si + sumM * p->N * so;
         break;
     }
-    case UCL_OP_CONV2D_FPROP: {
+    case UCL_OP_CONV2D_FPROP:
+    case UCL_OP_CONV2D_DGRAD:
+    case UCL_OP_CONV2D_WGRAD: {
         if (p->cN <= 0 || p->cH <= 0 || p->cW <= 0 || p->cC <= 0 || p->cKout <= 0 || p->cR <= 0 || p->cS <= 0 ||
             p->stride_h <= 0 || p->stride_w <= 0 || p->dil_h <= 0 || p->dil_w <= 0 || p->pad_h < 0 || p->pad_w < 0)
             return fail(UCL_ERR_INVALID_ARG, "conv geometry must be positive (pads non-negative)");
         const int64_t P = conv_out(p->cH, p->pad_h, p->dil_h, p->cR, p->stride_h);
         const int64_t Q = conv_out(p->cW, p->pad_w, p->dil_w, p->cS, p->stride_w);
         if (P <= 0 || Q <= 0) return fail(UCL_ERR_INVALID_ARG, "conv output is empty");
-        rows = (double)p->cN * P * Q; N = (double)p->cKout;
-        // padded taps are counted, as a dense implicit GEMM executes them
-        *flops = 2.0 * rows * N * (double)(p->cR * p->cS * p->cC);
-        *bytes = ((double)p->cN * p->cH * p->cW * p->cC + (double)p->cKout * p->cR * p->cS * p->cC) * si + rows * N * so;
+        const double n_y = (double)p->cN * P * Q * (double)p->cKout, n_x = (double)p->cN * p->cH * p->cW * p->cC;
+        const double n_w = (double)p->cKout * p->cR * p->cS * p->cC;
+        // padded taps are counted, as a dense implicit GEMM executes them (the same count in all three directions)
+        *flops = 2.0 * n_y * (double)(p->cR * p->cS * p->cC);
+        if (p->op == UCL_OP_CONV2D_FPROP) {
+            rows = (double)p->cN * P * Q; N = (double)p->cKout;
+            *bytes = (n_x + n_w) * si + n_y * so;
+        } else if (p->op == UCL_OP_CONV2D_DGRAD) {
+            rows = (double)p->cN * p->cH * p->cW; N = (double)p->cC;
+            *bytes = (n_y + n_w) * si + n_x * so;
+        } else {
+            rows = (double)p->cKout; N = (double)(p->cR * p->cS * p->cC);
+            *bytes = (n_y + n_x) * si + n_w * so;
+        }
         break;
     }
     default:
@@ -579,13 +591,22 @@ ucl_status launch_from_problem(const ucl_problem *p, Launch &L) {
     int64_t M = 0, N = 0;
     if (ucl_status st = characterise(p, &f, &b, &M, &N)) return st;
     if (!is16(p->dt_in)) return fail(UCL_ERR_UNSUPPORTED, "kernels take bf16 or fp16 inputs");
-    L.mode = p->op == UCL_OP_GROUPED_GEMM ? 1 : p->op == UCL_OP_CONV2D_FPROP ? 2 : 0;
+    L.mode = p->op == UCL_OP_GROUPED_GEMM ? 1 : p->op == UCL_OP_CONV2D_FPROP ? 2 : p->op == UCL_OP_CONV2D_DGRAD ? 3
+             : p->op == UCL_OP_CONV2D_WGRAD ? 4 : 0;
     L.batch = p->op == UCL_OP_BATCHED_GEMM ? p->batch : 1;
     L.M = M; L.N = N;
-    L.K = p->op == UCL_OP_CONV2D_FPROP ? p->cR * p->cS * p->cC : p->K;
+    L.K = p->K;
+    if (L.mode >= 2) {
+        const int64_t P = conv_out(p->cH, p->pad_h, p->dil_h, p->cR, p->stride_h), Q = conv_out(p->cW, p->pad_w, p->dil_w, p->cS, p->stride_w);
+        L.K = L.mode == 2 ? p->cR * p->cS * p->cC : L.mode == 3 ? p->cR * p->cS * p->cKout : p->cN * P * Q;
+    }
     L.groups = p->groups; L.M_g = p->M_g;
     if (L.mode == 2) {
         L.la = 2; L.lb = 0;
+    } else if (L.mode == 3) {
+        L.la = 2; L.lb = 1; L.ndirect_ok = true;
+    } else if (L.mode == 4) {
+        L.la = 1; L.lb = 1; L.ndirect_ok = L.mdirect_ok = true;
     } else {
         if ((p->a_layout != UCL_LAYOUT_K_CONTIGUOUS && p->a_layout != UCL_LAYOUT_MN_CONTIGUOUS) ||
             (p->b_layout != UCL_LAYOUT_K_CONTIGUOUS && p->b_layout != UCL_LAYOUT_MN_CONTIGUOUS))
@@ -724,6 +745,81 @@ ucl_status ucl_conv2d_fprop(int64_t N, int64_t H, int64_t W, int64_t C, int64_t 
     kp.pad_h = (int32_t)pad_h; kp.pad_w = (int32_t)pad_w; kp.str_h = (int32_t)stride_h; kp.str_w = (int32_t)stride_w;
     kp.dil_h = (int32_t)dil_h; kp.dil_w = (int32_t)dil_w;
     kp.d_vec = aligned16(y) && (Kout % (16 / elem_size(dtY)) == 0);
+    return run(L, kp, tune, stream);
+}
+
+// Shared checks of the two gradient entry points; P, Q of the forward geometry.
+static ucl_status conv_grad_common(int64_t N, int64_t H, int64_t W, int64_t C, int64_t Kout, int64_t R, int64_t S,
+                                   int64_t pad_h, int64_t pad_w, int64_t stride_h, int64_t stride_w, int64_t dil_h,
+                                   int64_t dil_w, int64_t *P, int64_t *Q) {
+    if (N <= 0 || H <= 0 || W <= 0 || C <= 0 || Kout <= 0 || R <= 0 || S <= 0)
+        return fail(UCL_ERR_INVALID_ARG, "conv extents must be positive");
+    if (pad_h < 0 || pad_w < 0 || stride_h <= 0 || stride_w <= 0 || dil_h <= 0 || dil_w <= 0)
+        return fail(UCL_ERR_INVALID_ARG, "pads must be >= 0, strides and dilations > 0");
+    *P = conv_out(H, pad_h, dil_h, R, stride_h);
+    *Q = conv_out(W, pad_w, dil_w, S, stride_w);
+    if (*P <= 0 || *Q <= 0) return fail(UCL_ERR_INVALID_ARG, "conv output is empty (P=%lld, Q=%lld)", (long long)*P, (long long)*Q);
+    if (C % 8 || Kout % 8)
+        return fail(UCL_ERR_UNSUPPORTED, "C=%lld and Kout=%lld must be multiples of 8 so that a 128-bit load never straddles a filter tap or a pixel", (long long)C, (long long)Kout);
+    if (N * H * W * C * 2 >= (1ll << 31) || N * *P * *Q * Kout * 2 >= (1ll << 31) || Kout * R * S * C * 2 >= (1ll << 31))
+        return fail(UCL_ERR_UNSUPPORTED, "activations, output gradient and filter must each be smaller than 2 GiB (32-bit offsets)");
+    if (H >= (1 << 24) || W >= (1 << 24) || pad_h >= (1 << 24) || pad_w >= (1 << 24) || dil_h * R >= (1 << 24) || dil_w * S >= (1 << 24))
+        return fail(UCL_ERR_UNSUPPORTED, "image extents, pads and dilated filter extents must be below 2^24");
+    return UCL_OK;
+}
+
+ucl_status ucl_conv2d_dgrad(int64_t N, int64_t H, int64_t W, int64_t C, int64_t Kout, int64_t R, int64_t S,
+                            int64_t pad_h, int64_t pad_w, int64_t stride_h, int64_t stride_w, int64_t dil_h,
+                            int64_t dil_w, const void *dy, int32_t dtDy, const void *w, int32_t dtW, void *dx, int32_t dtDx,
+                            const ucl_epilogue *epi, const ucl_tuning *tune, void *stream) {
+    g_err[0] = 0;
+    int64_t P = 0, Q = 0;
+    if (ucl_status st = conv_grad_common(N, H, W, C, Kout, R, S, pad_h, pad_w, stride_h, stride_w, dil_h, dil_w, &P, &Q)) return st;
+    const int64_t M = N * H * W, Kg = R * S * Kout;
+    if (ucl_status st = check_common(M, C, Kg, dtDy, dtW, dtDx, dy, w, dx)) return st;
+    if (!aligned16(dy) || !aligned16(w)) return fail(UCL_ERR_UNSUPPORTED, "dy and w must be 16-byte aligned");
+    Launch L;
+    L.mode = 3; L.M = M; L.N = C; L.K = Kg; L.la = 2; L.lb = 1; L.ndirect_ok = true; L.f16 = dtDy == UCL_F16; L.dtD = dtDx;
+    KParams kp;
+    memset(&kp, 0, sizeof(kp));
+    if (ucl_status st = check_epilogue(epi, L, kp)) return st;
+    kp.A = dy; kp.B = w; kp.D = dx;
+    kp.a_bytes = N * P * Q * Kout * 2;
+    kp.b_bytes = Kout * R * S * C * 2;
+    kp.lda = 0; kp.ldb = R * S * C; kp.ldd = C;
+    kp.M = (int32_t)M; kp.N = (int32_t)C; kp.K = (int32_t)Kg; kp.dtD = dtDx;
+    // the gathered tensor is dy: its extents take the place of the image's, the rows are input pixels
+    kp.cH = (int32_t)P; kp.cW = (int32_t)Q; kp.cC = (int32_t)Kout; kp.cS = (int32_t)S; kp.cP = (int32_t)H; kp.cQ = (int32_t)W;
+    kp.pad_h = (int32_t)pad_h; kp.pad_w = (int32_t)pad_w; kp.str_h = (int32_t)stride_h; kp.str_w = (int32_t)stride_w;
+    kp.dil_h = (int32_t)dil_h; kp.dil_w = (int32_t)dil_w;
+    kp.d_vec = aligned16(dx) && (C % (16 / elem_size(dtDx)) == 0);
+    return run(L, kp, tune, stream);
+}
+
+ucl_status ucl_conv2d_wgrad(int64_t N, int64_t H, int64_t W, int64_t C, int64_t Kout, int64_t R, int64_t S,
+                            int64_t pad_h, int64_t pad_w, int64_t stride_h, int64_t stride_w, int64_t dil_h,
+                            int64_t dil_w, const void *dy, int32_t dtDy, const void *x, int32_t dtX, void *dw, int32_t dtDw,
+                            const ucl_epilogue *epi, const ucl_tuning *tune, void *stream) {
+    g_err[0] = 0;
+    int64_t P = 0, Q = 0;
+    if (ucl_status st = conv_grad_common(N, H, W, C, Kout, R, S, pad_h, pad_w, stride_h, stride_w, dil_h, dil_w, &P, &Q)) return st;
+    const int64_t Ng = R * S * C, Kg = N * P * Q;
+    if (ucl_status st = check_common(Kout, Ng, Kg, dtDy, dtX, dtDw, dy, x, dw)) return st;
+    if (!aligned16(dy) || !aligned16(x)) return fail(UCL_ERR_UNSUPPORTED, "dy and x must be 16-byte aligned");
+    Launch L;
+    L.mode = 4; L.M = Kout; L.N = Ng; L.K = Kg; L.la = 1; L.lb = 1; L.ndirect_ok = L.mdirect_ok = true;
+    L.f16 = dtDy == UCL_F16; L.dtD = dtDw;
+    KParams kp;
+    memset(&kp, 0, sizeof(kp));
+    if (ucl_status st = check_epilogue(epi, L, kp)) return st;
+    kp.A = dy; kp.B = x; kp.D = dw;
+    kp.b_bytes = N * H * W * C * 2;
+    kp.lda = Kout; kp.ldb = 0; kp.ldd = Ng;
+    kp.M = (int32_t)Kout; kp.N = (int32_t)Ng; kp.K = (int32_t)Kg; kp.dtD = dtDw;
+    kp.cH = (int32_t)H; kp.cW = (int32_t)W; kp.cC = (int32_t)C; kp.cS = (int32_t)S; kp.cP = (int32_t)P; kp.cQ = (int32_t)Q;
+    kp.pad_h = (int32_t)pad_h; kp.pad_w = (int32_t)pad_w; kp.str_h = (int32_t)stride_h; kp.str_w = (int32_t)stride_w;
+    kp.dil_h = (int32_t)dil_h; kp.dil_w = (int32_t)dil_w;
+    kp.d_vec = aligned16(dw) && (Ng % (16 / elem_size(dtDw)) == 0);
     return run(L, kp, tune, stream);
 }
 

@@ -44,7 +44,8 @@ struct KParams {
     void *const *D_g;
     int64_t lda, ldb, ldd;            // element stride of the non-contiguous dimension
     int64_t a_bs, b_bs, d_bs;         // batch strides (elements)
-    int64_t a_bytes;                  // conv: size of the activation tensor in bytes (< 2^31)
+    int64_t a_bytes;                  // conv fprop / dgrad: size in bytes (< 2^31) of the tensor A is gathered from
+    int64_t b_bytes;                  // conv dgrad: size of the filter in bytes; wgrad: of the activations B is gathered from
     int32_t M, N, K;                  // grouped: M unused (per-group table)
     int32_t tiles_m, tiles_n;         // per batch (non-grouped)
     int32_t tiles_per_batch, total_tiles;

@@ -335,7 +335,7 @@ __device__ __forceinline__ void apply_step(float (&v)[8], const EpiStepDev &s, c
 
 // ------------------------------------------------------------------------------------------------
 
-template <int TM_, int TN_, int TK_, int STAGES_, bool F16_, int MODE_ /*0 gemm+batched, 1 grouped, 2 conv*/,
+template <int TM_, int TN_, int TK_, int STAGES_, bool F16_, int MODE_ /*0 gemm+batched, 1 grouped, 2 conv fprop, 3 conv dgrad, 4 conv wgrad*/,
           int LA_ /*OperandLayout of A*/, int LB_ /*OperandLayout of B*/, bool PERSIST_ = false /*persistent tile scheduler*/>
 struct KernelCfg {
     static constexpr int TM = TM_, TN = TN_, TK = TK_, STAGES = STAGES_, MODE = MODE_, LA = LA_, LB = LB_;
@@ -457,7 +457,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
     const int wm = wave / Cfg::WAVES_N, wn = wave % Cfg::WAVES_N;
     // split-K (gemm / batched): workgroups [s * total_tiles, (s + 1) * total_tiles) work on K slice s
     int slice = 0, wg_tile = wg_id;
-    if constexpr (MODE == 0 && !Cfg::PERSIST) {
+    if constexpr ((MODE == 0 || MODE == 4) && !Cfg::PERSIST) {
         if (p.split_k > 1 && p.split_phase != 2) {
             slice = wg_id / p.total_tiles;
             wg_tile = wg_id - slice * p.total_tiles;
@@ -486,7 +486,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
     }
     const int m0 = tm * TM, n0 = tn * TN;
     int k_len = p.K;
-    if constexpr (MODE == 0 && !Cfg::PERSIST) {
+    if constexpr ((MODE == 0 || MODE == 4) && !Cfg::PERSIST) {
         if (p.split_k > 1) {
             // this slice's K range (a multiple of 64 long, so operand rows stay 16-byte aligned)
             const int kb = slice * p.k_per_slice;
@@ -544,10 +544,19 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
             const int pq = row / p.cQ;
             const int pp = pq % p.cP;
             const int nb = pq / p.cP;
-            a_h0[i] = pp * p.str_h - p.pad_h;
-            a_w0[i] = q * p.str_w - p.pad_w;
-            // byte offset of x[nb, h0, w0, 0] (may be negative); only used at taps inside the image
-            a_off[i] = (uint32_t)(((nb * p.cH + a_h0[i]) * p.cW + a_w0[i]) * p.cC * 2);
+            if constexpr (MODE == 3) {
+                // data gradient: the row is an INPUT pixel (h, w) = (pp, q); tap (r, s) pairs it with the
+                // gradient pixel ((h + pad - r*dil) / stride, ...) where that division is exact.  The
+                // gathered tensor is dy: "image" extents cH x cW = P x Q, cC = its channels.
+                a_h0[i] = pp + p.pad_h;
+                a_w0[i] = q + p.pad_w;
+                a_off[i] = (uint32_t)(nb * p.cH * p.cW * p.cC * 2);
+            } else {
+                a_h0[i] = pp * p.str_h - p.pad_h;
+                a_w0[i] = q * p.str_w - p.pad_w;
+                // byte offset of x[nb, h0, w0, 0] (may be negative); only used at taps inside the image
+                a_off[i] = (uint32_t)(((nb * p.cH + a_h0[i]) * p.cW + a_w0[i]) * p.cC * 2);
+            }
         }
         a_ci = l_kc % p.cC;
         const int tap = l_kc / p.cC;
@@ -568,7 +577,48 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
     constexpr int CPRB = TN / 8, RPIB = kThreads / CPRB;          // chunks per row, rows per 256-thread copy
     auto nd_swz = [](int row) { return (((row & 3) << 1) | (((row >> 3) & 3) << 3)) & (CPRB - 1); };
     const int nd_row = tid / CPRB;
-    if constexpr (LB == kNDirect) {
+    // Per-slot state of the two gathered forms of such a B stage.
+    // MODE 3 (data gradient): GEMM row k = (r*S + s)*Ko + ko of B is filter row w[ko, r, s, :]: the slot
+    // keeps (ko, tap) of its row and steps ko by TK per k-tile.
+    // MODE 4 (weight gradient): GEMM row k is output pixel (n, p, q), GEMM column (r, s, c): the slot's 8
+    // columns are 8 channels of ONE tap (C is a multiple of 8), fixed for the whole loop; its pixel
+    // steps by TK per k-tile.  Every slot reads x[n, p*stride - pad + r*dil, q*stride - pad + s*dil, c..c+7].
+    constexpr bool kBGather = LB == kNDirect && (MODE == 3 || MODE == 4);
+    int g_a[kBGather ? B_ITERS : 1], g_b[kBGather ? B_ITERS : 1];          // MODE 3: ko, tap   MODE 4: q, p
+    int g_dh[MODE == 4 && kBGather ? B_ITERS : 1], g_dw[MODE == 4 && kBGather ? B_ITERS : 1];
+    uint32_t g_img[MODE == 4 && kBGather ? B_ITERS : 1];                   // byte offset of the slot's image
+    if constexpr (LB == kNDirect && MODE == 3) {
+        b_rsrc = buffer_rsrc(Bb + (int64_t)n0 * 2, (uint32_t)(p.b_bytes - (int64_t)n0 * 2));
+#pragma unroll
+        for (int i = 0; i < B_ITERS; ++i) {
+            const int row = i * RPIB + nd_row;
+            const int chunk = (tid % CPRB) ^ nd_swz(row);
+            b_off[i] = (uint32_t)(chunk * 16);
+            g_b[i] = row / p.cC;
+            g_a[i] = row - g_b[i] * p.cC;
+        }
+    } else if constexpr (LB == kNDirect && MODE == 4) {
+        b_rsrc = buffer_rsrc(Bb, (uint32_t)p.b_bytes);
+        const int kb = p.split_k > 1 && p.split_phase != 2 ? slice * p.k_per_slice : 0;
+#pragma unroll
+        for (int i = 0; i < B_ITERS; ++i) {
+            const int row = i * RPIB + nd_row;
+            const int chunk = (tid % CPRB) ^ nd_swz(row);
+            const int n = n0 + chunk * 8;                       // first of the slot's 8 GEMM columns
+            const int tap = n / p.cC, c = n - tap * p.cC;
+            const int r = tap / p.cS, sx = tap - r * p.cS;
+            // a column past N never reaches a stored accumulator: give it a tap far outside every image
+            g_dh[i] = n < p.N ? r * p.dil_h - p.pad_h : -(1 << 28);
+            g_dw[i] = sx * p.dil_w - p.pad_w;
+            b_off[i] = (uint32_t)(c * 2);
+            const int pix = kb + row;                            // (n, p, q) of the slot's row in k-tile 0
+            const int pq = p.cP * p.cQ;
+            const int img = pix / pq, rem = pix - img * pq;
+            g_b[i] = rem / p.cQ;
+            g_a[i] = rem - g_b[i] * p.cQ;
+            g_img[i] = (uint32_t)img * (uint32_t)(p.cH * p.cW * p.cC * 2);
+        }
+    } else if constexpr (LB == kNDirect) {
         b_rsrc = buffer_rsrc(Bb + (int64_t)n0 * 2, (uint32_t)(((int64_t)(Kr - 1) * p.ldb + (p.N - n0)) * 2));
 #pragma unroll
         for (int i = 0; i < B_ITERS; ++i) {
@@ -577,6 +627,41 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
             b_off[i] = (uint32_t)(((int64_t)row * p.ldb + chunk * 8) * 2);
         }
     }
+    // Offset of gathered slot i for the k-tile it stands at, then the slot steps on by one k-tile.
+    auto b_gather_off = [&](auto i_, bool kok) __attribute__((always_inline)) -> uint32_t {
+        constexpr int i = decltype(i_)::value;
+        uint32_t off = kOobOffset;
+        if constexpr (kBGather && MODE == 3) {
+            if (kok) off = (uint32_t)((g_a[i] * (int)p.ldb + g_b[i] * p.N) * 2) + b_off[i];
+            g_a[i] += TK;
+            while (g_a[i] >= p.cC) { g_a[i] -= p.cC; ++g_b[i]; }
+        } else if constexpr (kBGather && MODE == 4) {
+            const int h = g_b[i] * p.str_h + g_dh[i], w = g_a[i] * p.str_w + g_dw[i];
+            if (kok && (unsigned)h < (unsigned)p.cH && (unsigned)w < (unsigned)p.cW)
+                off = g_img[i] + (uint32_t)((h * p.cW + w) * p.cC * 2) + b_off[i];
+            g_a[i] += TK;
+            while (g_a[i] >= p.cQ) {
+                g_a[i] -= p.cQ;
+                if (++g_b[i] == p.cP) { g_b[i] = 0; g_img[i] += (uint32_t)(p.cH * p.cW * p.cC * 2); }
+            }
+        }
+        return off;
+    };
+    // Data gradient: offset of gather slot i of A at the tap (a_r, a_s) and channel offset a_ci the loader stands at.
+    auto a_gather_off = [&](auto i_, bool kok) __attribute__((always_inline)) -> uint32_t {
+        constexpr int i = decltype(i_)::value;
+        if constexpr (LA == kIm2col && MODE == 3) {
+            const int th = a_h0[i] - a_r * p.dil_h, tw = a_w0[i] - a_s * p.dil_w;
+            int hh = th, ww = tw;
+            bool ok = kok && th >= 0 && tw >= 0;
+            if (p.str_h != 1) { hh = th / p.str_h; ok = ok && hh * p.str_h == th; }
+            if (p.str_w != 1) { ww = tw / p.str_w; ok = ok && ww * p.str_w == tw; }
+            ok = ok && hh < p.cH && ww < p.cW;
+            return ok ? a_off[i] + (uint32_t)(((hh * p.cW + ww) * p.cC + a_ci) * 2) : kOobOffset;
+        } else {
+            return kOobOffset;
+        }
+    };
 
     // Resident activation patch (kHalo).  Output pixel m of a 3x3 / stride 1 / pad 1 convolution reads
     // input pixels m + dy*W + dx of the flattened [N*H*W] pixel sequence, except where the tap leaves
@@ -679,15 +764,24 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, UCL_LDS_PTR(dst), 16, off, krow, 0, 0);
             }
         } else if constexpr (LA == kIm2col) {
-            const int dh = a_r * p.dil_h, dw = a_s * p.dil_w;
-            const uint32_t tap_off = (uint32_t)(((dh * p.cW + dw) * p.cC + a_ci) * 2);
+            if constexpr (MODE == 3) {
+                static_for<A_ITERS>([&](auto i_) {
+                    constexpr int i = decltype(i_)::value;
+                    char *dst = sA + (i * kThreads + wave * 64) * 16;
+                    const uint32_t off = a_gather_off(i_, kok);
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, UCL_LDS_PTR(dst), 16, off, 0, 0, 0);
+                });
+            } else {
+                const int dh = a_r * p.dil_h, dw = a_s * p.dil_w;
+                const uint32_t tap_off = (uint32_t)(((dh * p.cW + dw) * p.cC + a_ci) * 2);
 #pragma unroll
-            for (int i = 0; i < A_ITERS; ++i) {
-                char *dst = sA + (i * kThreads + wave * 64) * 16;
-                const int h = a_h0[i] + dh, w = a_w0[i] + dw;
-                const bool ok = kok && (unsigned)h < (unsigned)p.cH && (unsigned)w < (unsigned)p.cW;
-                const uint32_t off = ok ? a_off[i] + tap_off : kOobOffset;
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, UCL_LDS_PTR(dst), 16, off, 0, 0, 0);
+                for (int i = 0; i < A_ITERS; ++i) {
+                    char *dst = sA + (i * kThreads + wave * 64) * 16;
+                    const int h = a_h0[i] + dh, w = a_w0[i] + dw;
+                    const bool ok = kok && (unsigned)h < (unsigned)p.cH && (unsigned)w < (unsigned)p.cW;
+                    const uint32_t off = ok ? a_off[i] + tap_off : kOobOffset;
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, UCL_LDS_PTR(dst), 16, off, 0, 0, 0);
+                }
             }
             // advance k by one k-tile: (ci, s, r) += TK channels
             a_ci += TK;
@@ -714,6 +808,13 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
                 const uint32_t off = CHECK_K ? (kok ? b_off[i] : kOobOffset) : b_off[i];
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(b_rsrc, UCL_LDS_PTR(dst), 16, off, k0 * 2, 0, 0);
             }
+        } else if constexpr (kBGather) {
+            static_for<B_ITERS>([&](auto i_) {
+                constexpr int i = decltype(i_)::value;
+                char *dst = sB + (i * kThreads + wave * 64) * 16;
+                const uint32_t off = b_gather_off(i_, !CHECK_K || k0 + i * RPIB + nd_row < K);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(b_rsrc, UCL_LDS_PTR(dst), 16, off, 0, 0, 0);
+            });
         } else if constexpr (LB == kNDirect) {
             const uint32_t krow = (uint32_t)k0 * (uint32_t)p.ldb * 2u;       // validated: K * ldb * 2 < 2^31
 #pragma unroll
@@ -754,12 +855,17 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
                 const uint32_t off = CHECK_K ? (k0 + i * RPIA + tid / (TM / 8) < K ? a_off[i] : kOobOffset) : a_off[i];
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, UCL_LDS_PTR(dst), 16, off, (uint32_t)k0 * (uint32_t)p.lda * 2u, 0, 0);
             } else {
-                const int dh = a_r * p.dil_h, dw = a_s * p.dil_w;
-                const uint32_t tap_off = (uint32_t)(((dh * p.cW + dw) * p.cC + a_ci) * 2);
-                const int h = a_h0[i] + dh, w = a_w0[i] + dw;
-                const bool ok = kok && (unsigned)h < (unsigned)p.cH && (unsigned)w < (unsigned)p.cW;
-                const uint32_t off = ok ? a_off[i] + tap_off : kOobOffset;
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, UCL_LDS_PTR(dst), 16, off, 0, 0, 0);
+                if constexpr (MODE == 3) {
+                    const uint32_t off = a_gather_off(std::integral_constant<int, i>{}, kok);
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, UCL_LDS_PTR(dst), 16, off, 0, 0, 0);
+                } else {
+                    const int dh = a_r * p.dil_h, dw = a_s * p.dil_w;
+                    const uint32_t tap_off = (uint32_t)(((dh * p.cW + dw) * p.cC + a_ci) * 2);
+                    const int h = a_h0[i] + dh, w = a_w0[i] + dw;
+                    const bool ok = kok && (unsigned)h < (unsigned)p.cH && (unsigned)w < (unsigned)p.cW;
+                    const uint32_t off = ok ? a_off[i] + tap_off : kOobOffset;
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, UCL_LDS_PTR(dst), 16, off, 0, 0, 0);
+                }
                 if constexpr (i == A_ITERS - 1) {     // advance k by one k-tile: (ci, s, r) += TK channels
                     a_ci += TK;
                     while (a_ci >= p.cC) {
@@ -771,7 +877,10 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
         } else {
             constexpr int i = IDX - A_ITERS;
             char *dst = sB + (i * kThreads + wave * 64) * 16;
-            if constexpr (LB == kNDirect) {
+            if constexpr (kBGather) {
+                const uint32_t off = b_gather_off(std::integral_constant<int, i>{}, !CHECK_K || k0 + i * RPIB + nd_row < K);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(b_rsrc, UCL_LDS_PTR(dst), 16, off, 0, 0, 0);
+            } else if constexpr (LB == kNDirect) {
                 const uint32_t off = CHECK_K ? (k0 + i * RPIB + nd_row < K ? b_off[i] : kOobOffset) : b_off[i];
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(b_rsrc, UCL_LDS_PTR(dst), 16, off, (uint32_t)k0 * (uint32_t)p.ldb * 2u, 0, 0);
             } else {
@@ -1219,7 +1328,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
     // Slice s of tile t keeps its fp32 accumulators at partial[(s * tiles + t)][register][thread], one
     // 128-bit store per accumulator and thread.  Whoever adds the slices up reads them back in the same
     // layout, slice 0 first: the order of the additions is fixed, whichever workgroup does them.
-    if constexpr (MODE == 0 && !Cfg::PERSIST) {
+    if constexpr ((MODE == 0 || MODE == 4) && !Cfg::PERSIST) {
         if (p.split_k > 1) {
             constexpr int64_t kTileElems = (int64_t)TM * TN;
             // (slice and tile index are worked out again from the workgroup id rather than kept in

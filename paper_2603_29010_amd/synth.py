@@ -245,6 +245,38 @@ def conv_spec(Nb, H, W, C, Ko, R, S, pad=(1, 1), stride=(1, 1), dil=(1, 1), dt_i
     return spec
 
 
+def conv_grad_spec(kind, Nb, H, W, C, Ko, R, S, pad=(1, 1), stride=(1, 1), dil=(1, 1), dt_in="bf16",
+                   dt_out="bf16", scale=None, epilogue=(), seed=BASE_SEED + 7, integer=False):
+    """conv2d_dgrad (kind "dgrad": dy NPQK, w KRSC -> dx NHWC) or conv2d_wgrad (kind "wgrad": dy NPQK,
+    x NHWC -> dw KRSC) of the forward geometry given.  M, N, K are those of the implicit GEMM."""
+    P = (H + 2 * pad[0] - dil[0] * (R - 1) - 1) // stride[0] + 1
+    Q = (W + 2 * pad[1] - dil[1] * (S - 1) - 1) // stride[1] + 1
+    if kind == "dgrad":
+        M, N, K = Nb * H * W, C, R * S * Ko
+    else:
+        M, N, K = Ko, R * S * C, Nb * P * Q
+    if scale is None:
+        scale = 1.0 / math.sqrt(math.sqrt(K))      # both factors scaled: products of variance 1/K
+
+    def draw(tid, n):
+        if integer:
+            return randint(seed, tid, n, -2, 2)
+        return normal(seed, tid, n) * scale
+
+    spec = {
+        "op": "conv2d_" + kind, "Nb": Nb, "H": H, "W": W, "C": C, "Ko": Ko, "R": R, "S": S, "P": P, "Q": Q,
+        "pad": tuple(pad), "stride": tuple(stride), "dil": tuple(dil), "dt_in": dt_in, "dt_out": dt_out,
+        "dy": to_bits(draw(1, Nb * P * Q * Ko), dt_in).reshape(Nb, P, Q, Ko),
+        "tensors": {}, "epilogue": [], "M": M, "N": N, "K": K,
+    }
+    if kind == "dgrad":
+        spec["w"] = to_bits(draw(2, Ko * R * S * C), dt_in).reshape(Ko, R, S, C)
+    else:
+        spec["x"] = to_bits(draw(2, Nb * H * W * C), dt_in).reshape(Nb, H, W, C)
+    _add_epilogue(spec, epilogue, draw, M, N, dt_out)
+    return spec
+
+
 def config(i, shrink=1):
     """The five benchmark workloads (i = 1..5).  shrink > 1 divides the large extents so the
     CPU checker finishes quickly while the structure (layouts, epilogue, raggedness) is kept."""

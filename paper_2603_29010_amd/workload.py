@@ -31,6 +31,10 @@ class DeviceWorkload:
             self.A = _to_device(spec["x"], dt_in, self.device)
             self.B = _to_device(spec["w"], dt_in, self.device)
             self.out_shape = (spec["M"], spec["N"])
+        elif self.op in ("conv2d_dgrad", "conv2d_wgrad"):
+            self.A = _to_device(spec["dy"], dt_in, self.device)
+            self.B = _to_device(spec["w" if self.op == "conv2d_dgrad" else "x"], dt_in, self.device)
+            self.out_shape = (spec["M"], spec["N"])
         else:
             self.A = _to_device(spec["A"], dt_in, self.device)
             self.B = _to_device(spec["B"], dt_in, self.device)
@@ -127,6 +131,11 @@ class DeviceWorkload:
             ucl.ucl_grouped_gemm(s["M_g"], s["N"], s["K"], self.tabA.data_ptr(), s["dt_in"], *s["a_strides"],
                                  self.tabB.data_ptr(), s["dt_in"], *s["b_strides"], self.tabD.data_ptr(),
                                  s["dt_out"], s["N"], 1, self.epi, tune, st)
+        elif self.op in ("conv2d_dgrad", "conv2d_wgrad"):
+            fn = ucl.ucl_conv2d_dgrad if self.op == "conv2d_dgrad" else ucl.ucl_conv2d_wgrad
+            fn(s["Nb"], s["H"], s["W"], s["C"], s["Ko"], s["R"], s["S"], s["pad"][0], s["pad"][1], s["stride"][0],
+               s["stride"][1], s["dil"][0], s["dil"][1], self.A.data_ptr(), s["dt_in"], self.B.data_ptr(), s["dt_in"],
+               self.D.data_ptr(), s["dt_out"], self.epi, tune, st)
         else:
             ucl.ucl_conv2d_fprop(s["Nb"], s["H"], s["W"], s["C"], s["Ko"], s["R"], s["S"], s["pad"][0],
                                  s["pad"][1], s["stride"][0], s["stride"][1], s["dil"][0], s["dil"][1],
@@ -152,7 +161,7 @@ class DeviceWorkload:
     # -- bookkeeping for the benchmark ----------------------------------------------------------
     def _problem_kwargs(self):
         s = self.spec
-        if self.op == "conv2d_fprop":
+        if self.op.startswith("conv2d"):
             return dict(conv=(s["Nb"], s["H"], s["W"], s["C"], s["Ko"], s["R"], s["S"], s["pad"][0], s["pad"][1],
                               s["stride"][0], s["stride"][1], s["dil"][0], s["dil"][1]))
         kw = dict(N=s["N"], K=s["K"], a_layout="k" if s["a_strides"][1] == 1 else "mn",
@@ -180,6 +189,6 @@ class DeviceWorkload:
         if self.op == "grouped_gemm":
             return ucl.ucl_sol_bound("grouped_gemm", s["dt_in"], s["dt_out"], hw=hw, M_g=s["M_g"], N=s["N"],
                                      K=s["K"], epi=self.epi)
-        return ucl.ucl_sol_bound("conv2d_fprop", s["dt_in"], s["dt_out"], hw=hw, epi=self.epi,
+        return ucl.ucl_sol_bound(self.op, s["dt_in"], s["dt_out"], hw=hw, epi=self.epi,
                                  conv=(s["Nb"], s["H"], s["W"], s["C"], s["Ko"], s["R"], s["S"], s["pad"][0],
                                        s["pad"][1], s["stride"][0], s["stride"][1], s["dil"][0], s["dil"][1]))

@@ -70,6 +70,15 @@ def test_sol_bound_matches_oracle_arithmetic_on_the_five_configs():
         for k in ("t_compute", "t_mem", "t_sol", "ai", "ridge"):
             assert r[k] == pytest.approx(o[k], rel=1e-12)
         assert r["compute_bound"] == o["compute_bound"]
+    # the two gradients: the same multiply-accumulates as fprop, read dy + (w | x), write (dx | dw)
+    conv = (32, 56, 56, 64, 128, 3, 3, 1, 1, 1, 1, 1, 1)
+    n_x, n_w, n_y = 32 * 56 * 56 * 64, 128 * 9 * 64, 32 * 56 * 56 * 128
+    r = ucl.ucl_sol_bound("conv2d_dgrad", "bf16", "bf16", conv=conv)
+    assert r["flops"] == 14797504512 and r["bytes"] == 2 * (n_y + n_w) + 2 * n_x
+    r = ucl.ucl_sol_bound("conv2d_wgrad", "bf16", "f32", conv=conv)
+    assert r["flops"] == 14797504512 and r["bytes"] == 2 * (n_y + n_x) + 4 * n_w
+    t = ucl.ucl_select_tuning("conv2d_wgrad", "bf16", "f32", conv=conv)
+    assert t["tile_m"] in (64, 128) and t["iterator"] == 0
     M_g = [128, 2048, 640]
     r = ucl.ucl_sol_bound("grouped_gemm", "bf16", "bf16", M_g=M_g, N=4096, K=1024)
     assert r["flops"] == sum(M_g) * 8388608 and r["bytes"] == sum(M_g) * 10240 + 3 * 4096 * 1024 * 2
@@ -122,7 +131,7 @@ def test_selection_table():
     with pytest.raises(UclError):
         ucl.ucl_select_tuning("grouped_gemm", "bf16", "bf16", M_g=[64], N=64, K=64, a_layout="mn")
     assert all(0 < v["lds_bytes"] <= 160 * 1024 for v in variants)
-    assert all(v["op_class"] in (0, 1, 2) and v["dt_in"] in (1, 2) for v in variants)
+    assert all(v["op_class"] in (0, 1, 2, 3, 4) and v["dt_in"] in (1, 2) for v in variants)
 
 
 def _err(fn, *a, **k):
