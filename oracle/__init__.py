@@ -5,7 +5,8 @@ smoke check and the benchmark's CPU-baseline leg may import this package; the
 GPU library never does, and this package never imports the GPU library.
 
 Arrays go in as numpy arrays holding the *stored bit patterns*:
-``uint16`` for bf16 / fp16 (with ``dtype="bf16"`` or ``"f16"``), ``float32`` or
+``uint8`` for the 8-bit formats (``"e4m3"``, ``"e5m2"``), ``uint16`` for bf16 / fp16
+(with ``dtype="bf16"`` or ``"f16"``), ``float32`` or
 ``float64`` otherwise.  Results come back as unrounded ``float64``; use
 ``round_to`` for the value the output format would store.
 
@@ -28,7 +29,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "ucl_oracle.c")
 _LIB = os.path.join(_HERE, "libucl_oracle.so")
 
-DT = {"bf16": 16, "f16": 17, "f32": 32, "f64": 64}
+DT = {"e4m3": 8, "e5m2": 9, "bf16": 16, "f16": 17, "f32": 32, "f64": 64}
 _OPS = {
     "scale": 1, "bias": 2, "aux_load": 3, "relu": 4, "gelu_tanh": 5, "gelu_erf": 6,
     "silu": 7, "sigmoid": 8, "tanh": 9, "mish": 10, "hardswish": 11, "leaky_relu": 12,
@@ -94,7 +95,8 @@ def _ptr(a):
 
 
 def _check(a, dtype):
-    want = {"bf16": np.uint16, "f16": np.uint16, "f32": np.float32, "f64": np.float64}[dtype]
+    want = {"e4m3": np.uint8, "e5m2": np.uint8, "bf16": np.uint16, "f16": np.uint16, "f32": np.float32,
+            "f64": np.float64}[dtype]
     if a.dtype != want:
         raise TypeError(f"array for {dtype} must be {want}, got {a.dtype}")
     if not a.flags["C_CONTIGUOUS"]:

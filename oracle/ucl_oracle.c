@@ -14,7 +14,7 @@
  *             (cross-correlation, NHWC activations, KRSC filter, NPQK output,
  *              taps that fall outside the image contribute zero)
  * with E the epilogue chain applied left to right to the fp64 accumulator.
- * Inputs are the stored bit patterns (bf16 / fp16 / fp32 / fp64) converted
+ * Inputs are the stored bit patterns (fp8 e4m3 / e5m2, bf16 / fp16 / fp32 / fp64) converted
  * exactly to double.  No blocking, no reordering; OpenMP splits output rows only.
  *
  * Pins (tests/test_oracle_*.py): closed forms (identity, all-ones, K=1 outer
@@ -34,7 +34,7 @@
 #include <string.h>
 
 /* ---- storage formats (oracle's own codes) -------------------------------- */
-enum { ORC_BF16 = 16, ORC_F16 = 17, ORC_F32 = 32, ORC_F64 = 64 };
+enum { ORC_E4M3 = 8, ORC_E5M2 = 9, ORC_BF16 = 16, ORC_F16 = 17, ORC_F32 = 32, ORC_F64 = 64 };
 
 static double load_bf16(uint16_t h) {
     uint32_t u = (uint32_t)h << 16;
@@ -58,8 +58,38 @@ static double load_f16(uint16_t h) {
     return sign ? -v : v;
 }
 
+/* The two 8-bit floating-point formats of the DSL's DTYPE rule (fp8_e4m3, fp8_e5m2), in their
+ * open-standard encodings.  e4m3: 1 sign, 4 exponent (bias 7), 3 fraction bits, no infinities, the
+ * single NaN pattern S.1111.111, largest finite value 448.  e5m2: 1 sign, 5 exponent (bias 15),
+ * 2 fraction bits, IEEE-style infinities and NaNs (binary16 cut to its top byte). */
+static double load_e4m3(uint8_t b) {
+    int sign = (b >> 7) & 1, e = (b >> 3) & 0xf, f = b & 7;
+    double v;
+    if (e == 15 && f == 7)
+        v = NAN;
+    else if (e == 0)
+        v = ldexp((double)f, -9);                /* subnormal: f * 2^-3 * 2^-6 */
+    else
+        v = ldexp(1.0 + (double)f / 8.0, e - 7);
+    return sign ? -v : v;
+}
+
+static double load_e5m2(uint8_t b) {
+    int sign = (b >> 7) & 1, e = (b >> 2) & 0x1f, f = b & 3;
+    double v;
+    if (e == 31)
+        v = f ? NAN : INFINITY;
+    else if (e == 0)
+        v = ldexp((double)f, -16);               /* subnormal: f * 2^-2 * 2^-14 */
+    else
+        v = ldexp(1.0 + (double)f / 4.0, e - 15);
+    return sign ? -v : v;
+}
+
 double orc_load(const void *p, int dtype, int64_t i) {
     switch (dtype) {
+    case ORC_E4M3: return load_e4m3(((const uint8_t *)p)[i]);
+    case ORC_E5M2: return load_e5m2(((const uint8_t *)p)[i]);
     case ORC_BF16: return load_bf16(((const uint16_t *)p)[i]);
     case ORC_F16:  return load_f16(((const uint16_t *)p)[i]);
     case ORC_F32:  return (double)((const float *)p)[i];

@@ -75,6 +75,13 @@ def to_bits(x, dtype):
         return x.astype(np.float32)
     if dtype == "f16":
         return x.astype(np.float16).view(np.uint16)
+    if dtype in ("e4m3", "e5m2"):
+        # the library cast (ties to even, e4m3 saturating at +-448); values are kept inside the finite range
+        import torch
+        t = torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32))
+        lim = 448.0 if dtype == "e4m3" else 57344.0
+        t = t.clamp(-lim, lim).to(torch.float8_e4m3fn if dtype == "e4m3" else torch.float8_e5m2)
+        return t.view(torch.uint8).numpy().copy()
     if dtype == "bf16":
         # float64 -> float32 -> bf16, each step ties-to-even.  (Two roundings; harmless here:
         # the stored bits *are* the input, nobody compares them to the float64 draw.)
@@ -97,11 +104,15 @@ def bits_to_f64(a, dtype):
         return a.view(np.float16).astype(np.float64)
     if dtype == "bf16":
         return (a.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+    if dtype in ("e4m3", "e5m2"):
+        import torch
+        t = torch.from_numpy(np.ascontiguousarray(a)).view(torch.float8_e4m3fn if dtype == "e4m3" else torch.float8_e5m2)
+        return t.to(torch.float64).numpy()
     raise ValueError(dtype)
 
 
 def itemsize(dtype):
-    return {"bf16": 2, "f16": 2, "f32": 4}[dtype]
+    return {"e4m3": 1, "e5m2": 1, "bf16": 2, "f16": 2, "f32": 4}[dtype]
 
 
 # ---- workloads -------------------------------------------------------------------------------

@@ -63,6 +63,52 @@ def test_bf16_decode_matches_torch_exhaustive():
     assert np.array_equal(got, ref, equal_nan=True)
 
 
+def _fp8_hand_table(ebits, mbits, bias, ieee_specials):
+    """Value of every code of an 8-bit format from its definition, written out independently:
+    (-1)^s 2^(e-bias) (1 + m/2^mbits), subnormals 2^(1-bias) m/2^mbits; IEEE-style formats keep the
+    top exponent for inf / NaN, the other kind only gives up the all-ones code for NaN."""
+    out = []
+    for code in range(256):
+        sgn = -1.0 if code & 0x80 else 1.0
+        e = (code >> mbits) & ((1 << ebits) - 1)
+        m = code & ((1 << mbits) - 1)
+        top = (1 << ebits) - 1
+        if ieee_specials and e == top:
+            v = math.inf if m == 0 else math.nan
+        elif not ieee_specials and e == top and m == (1 << mbits) - 1:
+            v = math.nan
+        elif e == 0:
+            v = 2.0 ** (1 - bias) * (m / 2.0 ** mbits)
+        else:
+            v = 2.0 ** (e - bias) * (1 + m / 2.0 ** mbits)
+        out.append(sgn * v)
+    return np.array(out)
+
+
+def test_fp8_decode_every_code_against_hand_table_and_torch():
+    codes = np.arange(256, dtype=np.uint8)
+    for name, tdt, table in (("e4m3", torch.float8_e4m3fn, _fp8_hand_table(4, 3, 7, False)),
+                             ("e5m2", torch.float8_e5m2, _fp8_hand_table(5, 2, 15, True))):
+        got = oracle.load(codes, name)
+        assert np.array_equal(got, table, equal_nan=True), name
+        ref = torch.from_numpy(codes).view(tdt).to(torch.float64).numpy()
+        assert np.array_equal(got, ref, equal_nan=True), name
+    e4 = oracle.load(codes, "e4m3")
+    assert np.nanmax(e4) == 448.0 and e4[0x08] == 2.0 ** -6 and e4[0x01] == 2.0 ** -9 and e4[0x38] == 1.0
+    e5 = oracle.load(codes, "e5m2")
+    assert e5[0x7B] == 57344.0 and e5[0x7C] == math.inf and e5[0x3C] == 1.0 and e5[0x01] == 2.0 ** -16
+
+
+def test_gemm_with_fp8_inputs_matches_numpy():
+    rng = np.random.default_rng(5)
+    for dt in ("e4m3", "e5m2"):
+        A = synth.to_bits(rng.standard_normal((5, 16)), dt)
+        B = synth.to_bits(rng.standard_normal((4, 16)), dt)
+        assert A.dtype == np.uint8
+        D = oracle.gemm(A, dt, (16, 1), B, dt, (1, 16), 5, 4, 16)
+        np.testing.assert_allclose(D, val(A, dt) @ val(B, dt).T, atol=1e-12)
+
+
 def test_rounding_ties_and_double_rounding():
     r = oracle.round_to
     # bf16 has 8 significant bits: spacing 2^-7 in [1,2)
