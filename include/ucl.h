@@ -21,7 +21,9 @@
  *     puts a small fill kernel in front).
  *   - Strides are in ELEMENTS.  Inputs are UCL_BF16 or UCL_F16 (both operands
  *     the same type), accumulation is fp32, outputs are UCL_BF16, UCL_F16 or
- *     UCL_F32.
+ *     UCL_F32.  ucl_gemm and ucl_batched_gemm also take UCL_FP8_E4M3 or
+ *     UCL_FP8_E5M2 inputs (both operands the same type, both contiguous
+ *     along K; K, the leading strides and the batch strides multiples of 16).
  *   - Alignment (the paper's rule (alignment * element_size) % 16 == 0,
  *     grammar notes, constraint 3): A and B base pointers are 16-byte aligned,
  *     one of their two strides is 1 and the other a multiple of 8, and K (for
@@ -60,7 +62,9 @@ typedef enum ucl_status {
     UCL_ERR_LAUNCH = 4         /* the HIP runtime refused the launch                     */
 } ucl_status;
 
-typedef enum ucl_dtype { UCL_F32 = 0, UCL_F16 = 1, UCL_BF16 = 2 } ucl_dtype;
+/* UCL_FP8_E4M3 / UCL_FP8_E5M2 (the open-standard 8-bit formats: e4m3 without infinities, largest value
+ * 448; e5m2 with IEEE-style infinities) are input types only. */
+typedef enum ucl_dtype { UCL_F32 = 0, UCL_F16 = 1, UCL_BF16 = 2, UCL_FP8_E4M3 = 3, UCL_FP8_E5M2 = 4 } ucl_dtype;
 
 /* Epilogue vocabulary: grammar rule `epilogue_op`.  v is the running fp32
  * value of output element (m, n); m = output row (GEMM row / flattened n,p,q
@@ -319,6 +323,7 @@ typedef struct ucl_hw {
     double peak_bw;             /* B/s */
     double compute_clock_ratio; /* (0,1] */
     double memory_clock_ratio;  /* (0,1] */
+    double peak_flops_8bit;     /* FLOP/s, dense, fp8 inputs (MI355X: 5033.2 TFLOP/s) */
 } ucl_hw;
 
 typedef struct ucl_sol_report {

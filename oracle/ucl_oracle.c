@@ -86,6 +86,11 @@ static double load_e5m2(uint8_t b) {
     return sign ? -v : v;
 }
 
+/* Bytes one stored element of a format occupies (batch strides are counted in elements). */
+static int elem_bytes(int dtype) {
+    return dtype == ORC_F64 ? 8 : dtype == ORC_F32 ? 4 : (dtype == ORC_E4M3 || dtype == ORC_E5M2) ? 1 : 2;
+}
+
 double orc_load(const void *p, int dtype, int64_t i) {
     switch (dtype) {
     case ORC_E4M3: return load_e4m3(((const uint8_t *)p)[i]);
@@ -281,15 +286,15 @@ void orc_batched_gemm(int64_t batch, int64_t M, int64_t N, int64_t K,
             for (int i = 0; i < c.n_steps; ++i) {
                 orc_step *s = &c.steps[i];
                 if (s->op == ORC_E_AUX_LOAD) {
-                    int esz = (s->dtype == ORC_F64) ? 8 : (s->dtype == ORC_F32) ? 4 : 2;
+                    int esz = elem_bytes(s->dtype);
                     s->ptr = (char *)s->ptr + b * aux_bs * esz;
                 } else if (s->op == ORC_E_AUX_STORE) {
                     s->ptr = (double *)s->ptr + b * aux_bs;
                 }
             }
         }
-        int esA = (dtA == ORC_F64) ? 8 : (dtA == ORC_F32) ? 4 : 2;
-        int esB = (dtB == ORC_F64) ? 8 : (dtB == ORC_F32) ? 4 : 2;
+        int esA = elem_bytes(dtA);
+        int esB = elem_bytes(dtB);
         orc_gemm(M, N, K,
                  (const char *)A + b * a_bs * esA, dtA, a_rs, a_cs,
                  (const char *)B + b * b_bs * esB, dtB, b_rs, b_cs,

@@ -9,7 +9,7 @@ import os
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libucl.so")
 
-DTYPES = {"f32": 0, "f16": 1, "bf16": 2}
+DTYPES = {"f32": 0, "f16": 1, "bf16": 2, "e4m3": 3, "e5m2": 4}
 EPI_OPS = {
     "scale": 1, "bias": 2, "aux_load": 3, "relu": 4, "gelu_tanh": 5, "gelu_erf": 6, "silu": 7,
     "sigmoid": 8, "tanh": 9, "mish": 10, "hardswish": 11, "leaky_relu": 12, "elu": 13, "clamp": 14,
@@ -67,7 +67,7 @@ class _VariantInfo(C.Structure):
 
 class _Hw(C.Structure):
     _fields_ = [("peak_flops_16bit", C.c_double), ("peak_flops_f32", C.c_double), ("peak_bw", C.c_double),
-                ("compute_clock_ratio", C.c_double), ("memory_clock_ratio", C.c_double)]
+                ("compute_clock_ratio", C.c_double), ("memory_clock_ratio", C.c_double), ("peak_flops_8bit", C.c_double)]
 
 
 class _SolReport(C.Structure):
@@ -280,7 +280,7 @@ def ucl_sol_bound(op, dt_in, dt_out, hw=None, **kw):
     h = None
     if hw is not None:
         h = _Hw(hw.get("peak_flops_16bit", 0.0), hw.get("peak_flops_f32", 0.0), hw["peak_bw"],
-                hw.get("compute_clock_ratio", 1.0), hw.get("memory_clock_ratio", 1.0))
+                hw.get("compute_clock_ratio", 1.0), hw.get("memory_clock_ratio", 1.0), hw.get("peak_flops_8bit", 0.0))
     r = _SolReport()
     _check(_load().ucl_sol_bound(C.byref(p), C.byref(h) if h is not None else None, C.byref(r)))
     return {k: getattr(r, k) for k, _ in _SolReport._fields_ if k != "reserved"}
@@ -324,6 +324,7 @@ def ucl_variant(i):
     _check(_load().ucl_variant(i, C.byref(v)))
     d = {k: getattr(v, k) for k, _ in _VariantInfo._fields_}
     d["mode"], d["f16"], d["la"], d["lb"] = v.op_class, int(v.dt_in == DTYPES["f16"]), v.a_path, v.b_path
+    d["dt"] = {code: name for name, code in DTYPES.items()}[v.dt_in]
     return d
 
 

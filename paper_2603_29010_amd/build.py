@@ -41,9 +41,15 @@ def _check_asm(obj):
     stem = os.path.basename(obj)[:-len(".hip.o")]
     for asm in glob.glob(os.path.join(OBJ, stem + "-hip-amdgcn-amd-amdhsa-gfx950.s")):
         text = open(asm).read()
-        for name, scratch in re.findall(r"\.name:\s+(\S+)\n\s+\.private_segment_fixed_size:\s+(\d+)", text):
+        names = re.findall(r"\.amdhsa_kernel\s+(\S+)", text)
+        sizes = re.findall(r"\.amdhsa_private_segment_fixed_size\s+(\d+)", text)
+        if len(names) != len(sizes):
+            raise RuntimeError(f"{asm}: cannot match kernels to their scratch sizes")
+        for name, scratch in zip(names, sizes):
             if int(scratch) != 0:
                 raise RuntimeError(f"kernel {name} uses {scratch} bytes of scratch memory")
+        if re.search(r"s_swappc_b64", text):
+            raise RuntimeError(f"{asm}: a kernel calls a function (a loop body was not inlined)")
 
 
 def build(force=False, jobs=None, verbose=False):

@@ -37,17 +37,23 @@ ucl_status fail(ucl_status st, const char *fmt, ...) {
 const std::vector<VariantDesc> &all_variants() {
     static const std::vector<VariantDesc> v = [] {
         std::vector<VariantDesc> out;
-        for (VariantList l : {variants_gemm_kk_bf16_a(), variants_gemm_kk_bf16_b(), variants_gemm_kk_bf16_c(), variants_gemm_kk_bf16_d(), variants_gemm_kk_f16_a(), variants_gemm_kk_f16_b(), variants_gemm_mn_bf16(), variants_gemm_mn_f16(), variants_grouped_a(), variants_grouped_b(), variants_conv_a(), variants_conv_b(), variants_conv_f16(), variants_conv_halo(), variants_gemm_kn_bf16(), variants_gemm_kn_f16(), variants_gemm_mx_bf16(), variants_gemm_mx_f16(), variants_grouped_kn(), variants_conv_dgrad(), variants_conv_wgrad()})
+        for (VariantList l : {variants_gemm_kk_bf16_a(), variants_gemm_kk_bf16_b(), variants_gemm_kk_bf16_c(), variants_gemm_kk_bf16_d(), variants_gemm_kk_f16_a(), variants_gemm_kk_f16_b(), variants_gemm_mn_bf16(), variants_gemm_mn_f16(), variants_grouped_a(), variants_grouped_b(), variants_conv_a(), variants_conv_b(), variants_conv_f16(), variants_conv_halo(), variants_gemm_kn_bf16(), variants_gemm_kn_f16(), variants_gemm_mx_bf16(), variants_gemm_mx_f16(), variants_grouped_kn(), variants_conv_dgrad(), variants_conv_wgrad(), variants_gemm_kk_fp8()})
             for (int i = 0; i < l.n; ++i) out.push_back(l.v[i]);
         return out;
     }();
     return v;
 }
 
-int elem_size(int dt) { return dt == UCL_F32 ? 4 : 2; }
+bool is8(int dt) { return dt == UCL_FP8_E4M3 || dt == UCL_FP8_E5M2; }
+int elem_size(int dt) { return dt == UCL_F32 ? 4 : is8(dt) ? 1 : 2; }
 bool is16(int dt) { return dt == UCL_F16 || dt == UCL_BF16; }
-bool valid_dtype(int dt) { return dt == UCL_F32 || dt == UCL_F16 || dt == UCL_BF16; }
-const char *dtype_name(int dt) { return dt == UCL_F32 ? "fp32" : dt == UCL_F16 ? "fp16" : dt == UCL_BF16 ? "bf16" : "?"; }
+bool valid_dtype(int dt) { return dt == UCL_F32 || dt == UCL_F16 || dt == UCL_BF16; }     // outputs and epilogue tensors
+const char *dtype_name(int dt) {
+    return dt == UCL_F32 ? "fp32" : dt == UCL_F16 ? "fp16" : dt == UCL_BF16 ? "bf16" : dt == UCL_FP8_E4M3 ? "fp8_e4m3"
+           : dt == UCL_FP8_E5M2 ? "fp8_e5m2" : "?";
+}
+// input type code of the kernel variants
+int dt_code(int dt) { return dt == UCL_F16 ? 1 : dt == UCL_FP8_E4M3 ? 2 : dt == UCL_FP8_E5M2 ? 3 : 0; }
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
 bool op_has_tensor(int op) {
@@ -66,7 +72,7 @@ struct Launch {
     int mode = 0;                 // 0 gemm / batched, 1 grouped, 2 conv fprop, 3 conv dgrad, 4 conv wgrad
     int64_t batch = 1, M = 0, N = 0, K = 0;
     int la = 0, lb = 0;           // operand layouts
-    int f16 = 0;
+    int dt = 0;                   // input type code of the kernels: 0 bf16, 1 fp16, 2 fp8 e4m3, 3 fp8 e5m2
     int dtD = 0;
     int groups = 0;
     const int64_t *M_g = nullptr;
@@ -141,6 +147,7 @@ double estimate_seconds(const VariantDesc &v, const Launch &L) {
     const double active = tiles / per_cu < 256.0 ? tiles / per_cu : 256.0;
     double boost = pow(256.0 / (active < 1.0 ? 1.0 : active), 0.7);
     if (boost > 1.5) boost = 1.5;
+    // (8-bit inputs: K counts pairs, and the 8-bit MFMA used runs at the 16-bit rate per byte of operand)
     const double tile_flops = 2.0 * v.tile_m * v.tile_n * (double)L.K;
     const double out_bytes = (double)v.tile_m * v.tile_n * (L.dtD == UCL_F32 ? 4.0 : 2.0);
     const double fixed = 2.0e-6 + out_bytes / kCuStore;
@@ -160,7 +167,7 @@ const VariantDesc *select_variant(const Launch &L, const ucl_tuning *tune) {
     double best_t = 0;
     const int want_persistent = tune && tune->scheduler == UCL_SCHED_PERSISTENT ? 1 : 0;
     for (const auto &v : vs) {
-        if (v.mode != L.mode || v.f16 != L.f16 || v.persistent != want_persistent) continue;
+        if (v.mode != L.mode || v.dt != L.dt || v.persistent != want_persistent) continue;
         if (v.lb == 4 ? !(L.lb == 1 && L.ndirect_ok) : v.lb != L.lb) continue;
         if (L.mode == 2) {
             // conv: the iterator knob picks between the per-tap gather (la 2) and the resident patch (la 3)
@@ -287,14 +294,16 @@ ucl_status classify(const char *name, const void *ptr, int64_t k_stride, int64_t
 }
 
 ucl_status check_common(int64_t M, int64_t N, int64_t K, int dtA, int dtB, int dtD, const void *A, const void *B,
-                        const void *D) {
+                        const void *D, bool fp8_ok = false) {
     if (M <= 0 || N <= 0 || K <= 0)
         return fail(UCL_ERR_INVALID_ARG, "extents must be positive, got M=%lld N=%lld K=%lld", (long long)M, (long long)N, (long long)K);
     if (M >= (1ll << 31) || N >= (1ll << 31) || K >= (1ll << 31))
         return fail(UCL_ERR_UNSUPPORTED, "extents must be below 2^31");
     if (!A || !B || !D) return fail(UCL_ERR_INVALID_ARG, "A, B and D must be non-NULL device pointers");
-    if (!is16(dtA) || dtA != dtB)
-        return fail(UCL_ERR_UNSUPPORTED, "inputs must both be bf16 or both fp16 (got %s, %s); accumulation is fp32", dtype_name(dtA), dtype_name(dtB));
+    if (is8(dtA) && dtA == dtB && !fp8_ok)
+        return fail(UCL_ERR_UNSUPPORTED, "fp8 inputs are built for gemm and batched_gemm");
+    if (!(is16(dtA) || is8(dtA)) || dtA != dtB)
+        return fail(UCL_ERR_UNSUPPORTED, "inputs must both be bf16, both fp16 or both the same fp8 type (got %s, %s); accumulation is fp32", dtype_name(dtA), dtype_name(dtB));
     if (!valid_dtype(dtD)) return fail(UCL_ERR_INVALID_ARG, "bad output dtype %d", dtD);
     return UCL_OK;
 }
@@ -458,14 +467,24 @@ ucl_status gemm_like(int64_t batch, int64_t M, int64_t N, int64_t K,
                      const ucl_epilogue *epi, const ucl_tuning *tune, void *stream, bool clear_counters = false) {
     g_err[0] = 0;
     if (batch <= 0) return fail(UCL_ERR_INVALID_ARG, "batch=%lld must be positive", (long long)batch);
-    if (ucl_status st = check_common(M, N, K, dtA, dtB, dtD, A, B, D)) return st;
+    if (ucl_status st = check_common(M, N, K, dtA, dtB, dtD, A, B, D, /*fp8_ok=*/true)) return st;
+    if (is8(dtA)) {
+        // 8-bit inputs are handled as pairs of elements: from here on K and the strides of A and B count
+        // 16-bit units, which the checks below require to be 16-byte aligned like those of 16-bit inputs
+        if (a_cs != 1 || b_rs != 1)
+            return fail(UCL_ERR_UNSUPPORTED, "fp8 inputs must both be contiguous along K (A row-major, B column-major)");
+        if (K % 16 || (M > 1 && a_rs % 16) || (N > 1 && b_cs % 16) || (batch > 1 && (a_bs % 16 || b_bs % 16)))
+            return fail(UCL_ERR_UNSUPPORTED, "fp8 inputs: K=%lld, the leading strides (%lld, %lld) and the batch strides must be multiples of 16 (alignment 16 x 1 byte = 16)",
+                        (long long)K, (long long)a_rs, (long long)b_cs);
+        K /= 2; a_rs /= 2; b_cs /= 2; a_bs /= 2; b_bs /= 2;
+    }
     if (d_cs != 1)
         return fail(UCL_ERR_UNSUPPORTED, "D must be row-major (d_cs == 1, got %lld); for a column-major D swap the operands' roles: (A.B)^T = B^T.A^T", (long long)d_cs);
     if (d_rs < N && M > 1) return fail(UCL_ERR_INVALID_ARG, "d_rs=%lld is smaller than N=%lld", (long long)d_rs, (long long)N);
     if (batch > 1 && ((a_bs % 8) || (b_bs % 8)))
         return fail(UCL_ERR_UNSUPPORTED, "batch strides of A and B must be multiples of 8 elements (16-byte alignment of every batch)");
     Launch L;
-    L.mode = 0; L.batch = batch; L.M = M; L.N = N; L.K = K; L.f16 = dtA == UCL_F16; L.dtD = dtD;
+    L.mode = 0; L.batch = batch; L.M = M; L.N = N; L.K = K; L.dt = dt_code(dtA); L.dtD = dtD;
     KParams kp;
     memset(&kp, 0, sizeof(kp));
     if (ucl_status st = classify("A", A, a_cs, a_rs, M, K, &L.la, &kp.lda)) return st;
@@ -490,7 +509,7 @@ int64_t conv_out(int64_t in, int64_t pad, int64_t dil, int64_t ker, int64_t stri
 
 ucl_status characterise(const ucl_problem *p, double *flops, double *bytes, int64_t *M_out, int64_t *N_out) {
     if (!p) return fail(UCL_ERR_INVALID_ARG, "problem is NULL");
-    if (!valid_dtype(p->dt_in) || !valid_dtype(p->dt_out)) return fail(UCL_ERR_INVALID_ARG, "bad dtype in problem");
+    if (!(valid_dtype(p->dt_in) || is8(p->dt_in)) || !valid_dtype(p->dt_out)) return fail(UCL_ERR_INVALID_ARG, "bad dtype in problem");
     const double si = elem_size(p->dt_in), so = elem_size(p->dt_out);
     double rows = 0, N = 0, batch = 1;
     switch (p->op) {
@@ -590,12 +609,14 @@ ucl_status launch_from_problem(const ucl_problem *p, Launch &L) {
     double f, b;
     int64_t M = 0, N = 0;
     if (ucl_status st = characterise(p, &f, &b, &M, &N)) return st;
-    if (!is16(p->dt_in)) return fail(UCL_ERR_UNSUPPORTED, "kernels take bf16 or fp16 inputs");
+    if (!is16(p->dt_in) && !is8(p->dt_in)) return fail(UCL_ERR_UNSUPPORTED, "kernels take bf16, fp16 or fp8 inputs");
+    if (is8(p->dt_in) && (p->op > UCL_OP_BATCHED_GEMM || p->a_layout != UCL_LAYOUT_K_CONTIGUOUS || p->b_layout != UCL_LAYOUT_K_CONTIGUOUS || p->K % 16))
+        return fail(UCL_ERR_UNSUPPORTED, "fp8 inputs are built for gemm and batched_gemm with both operands contiguous along K, K a multiple of 16");
     L.mode = p->op == UCL_OP_GROUPED_GEMM ? 1 : p->op == UCL_OP_CONV2D_FPROP ? 2 : p->op == UCL_OP_CONV2D_DGRAD ? 3
              : p->op == UCL_OP_CONV2D_WGRAD ? 4 : 0;
     L.batch = p->op == UCL_OP_BATCHED_GEMM ? p->batch : 1;
     L.M = M; L.N = N;
-    L.K = p->K;
+    L.K = is8(p->dt_in) ? p->K / 2 : p->K;          // 8-bit inputs: the kernels count pairs
     if (L.mode >= 2) {
         const int64_t P = conv_out(p->cH, p->pad_h, p->dil_h, p->cR, p->stride_h), Q = conv_out(p->cW, p->pad_w, p->dil_w, p->cS, p->stride_w);
         L.K = L.mode == 2 ? p->cR * p->cS * p->cC : L.mode == 3 ? p->cR * p->cS * p->cKout : p->cN * P * Q;
@@ -619,7 +640,7 @@ ucl_status launch_from_problem(const ucl_problem *p, Launch &L) {
         L.ndirect_ok = L.lb == 1 && ((L.K - 1) * N + N) * 2 < (1ll << 31);
         L.mdirect_ok = L.la == 1 && ((L.K - 1) * Mmax + Mmax) * 2 < (1ll << 31);
     }
-    L.f16 = p->dt_in == UCL_F16;
+    L.dt = dt_code(p->dt_in);
     L.dtD = p->dt_out;
     if (L.mode == 2)
         L.patch_ok = conv_patch_ok(p->cW, p->cC, p->cR, p->cS, p->pad_h, p->pad_w, p->stride_h, p->stride_w, p->dil_h, p->dil_w);
@@ -682,7 +703,7 @@ ucl_status ucl_grouped_gemm(int32_t groups, const int64_t *M_g, int64_t N, int64
         return fail(UCL_ERR_INVALID_ARG, "groups=%d must be in 1..%d", groups, UCL_MAX_GROUPS);
     if (!M_g) return fail(UCL_ERR_INVALID_ARG, "M_g (host array of group sizes) is NULL");
     Launch L;
-    L.mode = 1; L.groups = groups; L.M_g = M_g; L.N = N; L.K = K; L.f16 = dtA == UCL_F16; L.dtD = dtD;
+    L.mode = 1; L.groups = groups; L.M_g = M_g; L.N = N; L.K = K; L.dt = dt_code(dtA); L.dtD = dtD;
     for (int g = 0; g < groups; ++g) {
         if (M_g[g] < 0 || M_g[g] >= (1ll << 31)) return fail(UCL_ERR_INVALID_ARG, "M_g[%d]=%lld must be in [0, 2^31)", g, (long long)M_g[g]);
         L.sum_Mg += M_g[g];
@@ -732,7 +753,7 @@ ucl_status ucl_conv2d_fprop(int64_t N, int64_t H, int64_t W, int64_t C, int64_t 
     if (H >= (1 << 24) || W >= (1 << 24) || pad_h >= (1 << 24) || pad_w >= (1 << 24))
         return fail(UCL_ERR_UNSUPPORTED, "image extents / pads must be below 2^24");
     Launch L;
-    L.mode = 2; L.M = M; L.N = Kout; L.K = Kg; L.la = 2; L.lb = 0; L.f16 = dtX == UCL_F16; L.dtD = dtY;
+    L.mode = 2; L.M = M; L.N = Kout; L.K = Kg; L.la = 2; L.lb = 0; L.dt = dt_code(dtX); L.dtD = dtY;
     L.patch_ok = conv_patch_ok(W, C, R, S, pad_h, pad_w, stride_h, stride_w, dil_h, dil_w);
     KParams kp;
     memset(&kp, 0, sizeof(kp));
@@ -779,7 +800,7 @@ ucl_status ucl_conv2d_dgrad(int64_t N, int64_t H, int64_t W, int64_t C, int64_t 
     if (ucl_status st = check_common(M, C, Kg, dtDy, dtW, dtDx, dy, w, dx)) return st;
     if (!aligned16(dy) || !aligned16(w)) return fail(UCL_ERR_UNSUPPORTED, "dy and w must be 16-byte aligned");
     Launch L;
-    L.mode = 3; L.M = M; L.N = C; L.K = Kg; L.la = 2; L.lb = 1; L.ndirect_ok = true; L.f16 = dtDy == UCL_F16; L.dtD = dtDx;
+    L.mode = 3; L.M = M; L.N = C; L.K = Kg; L.la = 2; L.lb = 1; L.ndirect_ok = true; L.dt = dt_code(dtDy); L.dtD = dtDx;
     KParams kp;
     memset(&kp, 0, sizeof(kp));
     if (ucl_status st = check_epilogue(epi, L, kp)) return st;
@@ -808,7 +829,7 @@ ucl_status ucl_conv2d_wgrad(int64_t N, int64_t H, int64_t W, int64_t C, int64_t 
     if (!aligned16(dy) || !aligned16(x)) return fail(UCL_ERR_UNSUPPORTED, "dy and x must be 16-byte aligned");
     Launch L;
     L.mode = 4; L.M = Kout; L.N = Ng; L.K = Kg; L.la = 1; L.lb = 1; L.ndirect_ok = L.mdirect_ok = true;
-    L.f16 = dtDy == UCL_F16; L.dtD = dtDw;
+    L.dt = dt_code(dtDy); L.dtD = dtDw;
     KParams kp;
     memset(&kp, 0, sizeof(kp));
     if (ucl_status st = check_epilogue(epi, L, kp)) return st;
@@ -837,11 +858,11 @@ ucl_status ucl_sol_bound(const ucl_problem *p, const ucl_hw *hw, ucl_sol_report 
     double flops = 0, bytes = 0;
     if (ucl_status st = characterise(p, &flops, &bytes, nullptr, nullptr)) return st;
     // Hardware limits: published peaks, scaled linearly by the clock ratios.
-    ucl_hw mi355x = {2516.6e12, 157.3e12, 8.0e12, 1.0, 1.0};
+    ucl_hw mi355x = {2516.6e12, 157.3e12, 8.0e12, 1.0, 1.0, 5033.2e12};
     const ucl_hw &h = hw ? *hw : mi355x;
     if (!(h.peak_bw > 0) || !(h.compute_clock_ratio > 0) || !(h.memory_clock_ratio > 0))
         return fail(UCL_ERR_INVALID_ARG, "hardware descriptor needs positive peaks and clock ratios");
-    const double peak = (p->dt_in == UCL_F32 ? h.peak_flops_f32 : h.peak_flops_16bit) * h.compute_clock_ratio;
+    const double peak = (p->dt_in == UCL_F32 ? h.peak_flops_f32 : is8(p->dt_in) ? h.peak_flops_8bit : h.peak_flops_16bit) * h.compute_clock_ratio;
     if (!(peak > 0)) return fail(UCL_ERR_INVALID_ARG, "hardware descriptor has no compute peak for %s inputs", dtype_name(p->dt_in));
     const double bw = h.peak_bw * h.memory_clock_ratio;
     out->flops = flops;
@@ -932,7 +953,7 @@ ucl_status ucl_variant(int32_t i, ucl_variant_info *out) {
     out->tile_m = v.tile_m; out->tile_n = v.tile_n; out->tile_k = v.tile_k; out->stages = v.stages;
     out->iterator = v.la == 3 ? UCL_ITER_FIXED_STRIDE_DILATION : v.la == 2 ? UCL_ITER_ANALYTIC : UCL_ITER_DEFAULT;
     out->op_class = v.mode;
-    out->dt_in = v.f16 ? UCL_F16 : UCL_BF16;
+    out->dt_in = v.dt == 1 ? UCL_F16 : v.dt == 2 ? UCL_FP8_E4M3 : v.dt == 3 ? UCL_FP8_E5M2 : UCL_BF16;
     out->a_layout = (v.la == 1 || v.la == 5) ? UCL_LAYOUT_MN_CONTIGUOUS : UCL_LAYOUT_K_CONTIGUOUS;
     out->b_layout = (v.lb == 1 || v.lb == 4) ? UCL_LAYOUT_MN_CONTIGUOUS : UCL_LAYOUT_K_CONTIGUOUS;
     out->a_path = v.la; out->b_path = v.lb;

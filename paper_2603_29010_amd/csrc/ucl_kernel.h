@@ -335,7 +335,7 @@ __device__ __forceinline__ void apply_step(float (&v)[8], const EpiStepDev &s, c
 
 // ------------------------------------------------------------------------------------------------
 
-template <int TM_, int TN_, int TK_, int STAGES_, bool F16_, int MODE_ /*0 gemm+batched, 1 grouped, 2 conv fprop, 3 conv dgrad, 4 conv wgrad*/,
+template <int TM_, int TN_, int TK_, int STAGES_, int DT_ /*inputs: 0 bf16, 1 fp16, 2 fp8 e4m3, 3 fp8 e5m2*/, int MODE_ /*0 gemm+batched, 1 grouped, 2 conv fprop, 3 conv dgrad, 4 conv wgrad*/,
           int LA_ /*OperandLayout of A*/, int LB_ /*OperandLayout of B*/, bool PERSIST_ = false /*persistent tile scheduler*/>
 struct KernelCfg {
     static constexpr int TM = TM_, TN = TN_, TK = TK_, STAGES = STAGES_, MODE = MODE_, LA = LA_, LB = LB_;
@@ -343,7 +343,9 @@ struct KernelCfg {
     static constexpr int CPR = TK / 8;                            // 16-byte chunks per LDS row
     static constexpr int ROW_BYTES = TK * 2;
     static_assert(TK == 32 || TK == 64, "k-tile of 32 or 64 elements");
-    static constexpr bool F16 = F16_;
+    static constexpr int DT = DT_;
+    static_assert(DT_ >= 0 && DT_ <= 3, "input type code");
+    static_assert(DT_ < 2 || (LA_ == kKContig && LB_ == kKContig), "8-bit inputs: both operands contiguous along K");
     static constexpr int WAVES_M = 2, WAVES_N = 2;
     static constexpr int WTM = TM / WAVES_M, WTN = TN / WAVES_N;  // wave tile
     static constexpr int MI = WTM / 16, NI = WTN / 16;            // 16x16 MFMA blocks per wave
@@ -402,10 +404,26 @@ __device__ __forceinline__ rsrc_t buffer_rsrc(const void *base, uint32_t bytes) 
 // register allocator otherwise shuffles the 64 four-register accumulators of a wave tile between the
 // two register files inside the loop.  The statements are volatile, so MFMAs, LDS reads and copy
 // instructions issue in source order, which is how the loop below spaces them.
-template <bool F16>
+template <int DT>
 __device__ __forceinline__ void mfma16(f32x4_t &c, const u32x4_t &a, const u32x4_t &b) {
-    if constexpr (F16) asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
-    else asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
+    if constexpr (DT == 1) asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
+    else if constexpr (DT == 0) asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
+    else {
+        // 8-bit inputs.  The kernel handles them as pairs: one 16-bit unit of every address computation
+        // is two fp8 values, so a 16-byte fragment is 16 consecutive k of a lane's row / column, and a
+        // "k-step" is 64 of them.  The 8-bit MFMA takes 8 k per lane: the low and the high half of the
+        // fragment go through one MFMA each.  Which k a lane's bytes stand for is the same for both
+        // operands, and every k of the k-step is held by exactly one lane and half: the two MFMAs add
+        // up the 64 products of the k-step.
+        const u32x2_t a0{a[0], a[1]}, a1{a[2], a[3]}, b0{b[0], b[1]}, b1{b[2], b[3]};
+        if constexpr (DT == 2) {
+            asm volatile("v_mfma_f32_16x16x32_fp8_fp8 %0, %1, %2, %0" : "+a"(c) : "v"(a0), "v"(b0));
+            asm volatile("v_mfma_f32_16x16x32_fp8_fp8 %0, %1, %2, %0" : "+a"(c) : "v"(a1), "v"(b1));
+        } else {
+            asm volatile("v_mfma_f32_16x16x32_bf8_bf8 %0, %1, %2, %0" : "+a"(c) : "v"(a0), "v"(b0));
+            asm volatile("v_mfma_f32_16x16x32_bf8_bf8 %0, %1, %2, %0" : "+a"(c) : "v"(a1), "v"(b1));
+        }
+    }
 }
 
 // Forces the accumulator to hold its value in an accumulation register at this point of the program.
@@ -739,7 +757,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
     // K-tail test; full k-tiles skip it.
     // PART: 0 = both operands, 1 = A only, 2 = B only (the deep pipelines spread the two halves of a
     // stage's loads over different k-steps).
-    auto issue_part = [&](auto check_k_, auto part_, int kt, int buf) {
+    auto issue_part = [&](auto check_k_, auto part_, int kt, int buf) __attribute__((always_inline)) {
         constexpr bool CHECK_K = decltype(check_k_)::value;
         constexpr int PART = decltype(part_)::value;
         char *sA = smem + buf * Cfg::STAGE_BYTES;
@@ -837,7 +855,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
     };
     // One copy instruction of k-tile `kt`: slot IDX counts the A slots first, then the B slots.  The
     // deep pipeline deals these out one at a time between the MFMAs (K-contiguous / im2col operands).
-    auto issue_one = [&](auto check_k_, auto idx_, int kt, int buf) {
+    auto issue_one = [&](auto check_k_, auto idx_, int kt, int buf) __attribute__((always_inline)) {
         constexpr bool CHECK_K = decltype(check_k_)::value;
         constexpr int IDX = decltype(idx_)::value;
         char *sA = smem + buf * Cfg::STAGE_BYTES;
@@ -889,7 +907,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
             }
         }
     };
-    auto issue_tile = [&](auto check_k_, int kt, int buf) {
+    auto issue_tile = [&](auto check_k_, int kt, int buf) __attribute__((always_inline)) {
         issue_part(check_k_, std::integral_constant<int, 0>{}, kt, buf);
     };
     // only the last k-tile can be partial
@@ -1045,7 +1063,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
                 // B fragment as the MFMA's first operand: the lane then holds 4 consecutive n per
                 // accumulator, which is what the row-major store wants.
                 static_for<MI>([&](auto mi) {
-                    static_for<NI>([&](auto ni) { mfma16<Cfg::F16>(acc[mi][ni], bf[ni], af[mi]); });
+                    static_for<NI>([&](auto ni) { mfma16<Cfg::DT>(acc[mi][ni], bf[ni], af[mi]); });
                 });
             });
             if (kt + 1 < KT) commit_regs((kt + 1) % STAGES);
@@ -1068,12 +1086,12 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
             a_ready(w_);
             static_for<NI>([&](auto ni_) {
                 constexpr int ni = decltype(ni_)::value;
-                mfma16<Cfg::F16>(acc[mi][ni], bq[PB][ni], a);
+                mfma16<Cfg::DT>(acc[mi][ni], bq[PB][ni], a);
                 constexpr int s0 = ni * NS / NI, s1 = (ni + 1) * NS / NI;
                 static_for<s1 - s0>([&](auto j) { side(std::integral_constant<int, s0 + decltype(j)::value>{}); });
             });
         };
-        auto first_step = [&](const char *sc) {
+        auto first_step = [&](const char *sc) __attribute__((always_inline)) {
             if constexpr (LB == kNDirect) __builtin_amdgcn_s_waitcnt((0xF) | (0x3 << 14) | (0x7 << 4) | (0x0 << 8));   // lgkmcnt(0)
             static_for<MI>([&](auto mi_) {
                 constexpr int mi = decltype(mi_)::value;
@@ -1094,7 +1112,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
                 row_block(mi_, ar[mi % RA], I0{}, std::integral_constant<int, na + nf + nb>{}, std::integral_constant<int, W>{}, side);
             });
         };
-        auto last_step = [&](auto check_, const char *sn, int kt_load, int buf) {
+        auto last_step = [&](auto check_, const char *sn, int kt_load, int buf) __attribute__((always_inline)) {
             static_for<MI>([&](auto mi_) {
                 constexpr int mi = decltype(mi_)::value;
                 constexpr int ih = mi - (MI - (RA - 1));           // ring head of the next k-tile
@@ -1118,7 +1136,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
         static_for<NI>([&](auto ni) { bq[0][ni] = fragB(smem, ni, 0); });
         const int KT_full = k_tail ? KT - 1 : KT;
         int kt = 0;
-        auto ktile2 = [&](auto check_, auto cur_) {
+        auto ktile2 = [&](auto check_, auto cur_) __attribute__((always_inline)) {
             const int cur = cur_;
             first_step(smem + cur * Cfg::STAGE_BYTES);
             pipeline_barrier<0>();
@@ -1192,7 +1210,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
                 };
                 static_for<NI>([&](auto ni_) {
                     constexpr int ni = decltype(ni_)::value;
-                    mfma16<Cfg::F16>(acc[mi][ni], bq[PB][ni], ar[mi % RA]);
+                    mfma16<Cfg::DT>(acc[mi][ni], bq[PB][ni], ar[mi % RA]);
                     constexpr int s0 = ni * NS / NI, s1 = (ni + 1) * NS / NI;
                     static_for<s1 - s0>([&](auto j) { side(std::integral_constant<int, s0 + decltype(j)::value>{}); });
                 });
@@ -1225,7 +1243,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
         // One k-step: fragment set PB of B, k-step KK of stage `sc`; the following k-step is KN of
         // stage `sn`.  DN > 0: also the copies of k-tile kt_load into buffer fill_buf.
         auto kstep = [&](auto pb_, auto kk_, auto kn_, const char *sc, const char *sn, auto check_, auto dn_, int kt_load,
-                         int fill_buf) {
+                         int fill_buf) __attribute__((always_inline)) {
             constexpr int PB = decltype(pb_)::value, KK = decltype(kk_)::value, KN = decltype(kn_)::value;
             constexpr int DN = decltype(dn_)::value;
             // A k-step that issues no copies is not behind the k-tile's barrier: its directly copied B
@@ -1256,7 +1274,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
                 a_ready(std::integral_constant<int, 2>{});
                 static_for<NI>([&](auto ni_) {
                     constexpr int ni = decltype(ni_)::value;
-                    mfma16<Cfg::F16>(acc[mi][ni], bq[PB][ni], ar[mi % RA]);
+                    mfma16<Cfg::DT>(acc[mi][ni], bq[PB][ni], ar[mi % RA]);
                     constexpr int s0 = ni * NS / NI, s1 = (ni + 1) * NS / NI;
                     static_for<s1 - s0>([&](auto j) { side(std::integral_constant<int, s0 + decltype(j)::value>{}); });
                 });
@@ -1265,7 +1283,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
         // One k-tile.  P0: B set of its first k-step.  cur / nxt / fill: buffers of k-tiles kt, kt+1 and
         // kt-1 (= kt+STAGES-1); constants in the unrolled steady loop, so that every LDS address
         // there is a loop-invariant register plus an immediate.
-        auto ktile = [&](auto p0_, auto check_, auto cur_, auto nxt_, auto fill_, int kt) {
+        auto ktile = [&](auto p0_, auto check_, auto cur_, auto nxt_, auto fill_, int kt) __attribute__((always_inline)) {
             constexpr int P0 = decltype(p0_)::value;
             const int cur = cur_, nxt = nxt_, fill = fill_;
             const char *sc = smem + cur * Cfg::STAGE_BYTES;

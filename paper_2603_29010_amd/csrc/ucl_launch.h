@@ -18,7 +18,7 @@ hipError_t launch_cfg(const KParams &p, const GroupTable *gt, int grid, hipStrea
 
 template <class Cfg>
 constexpr VariantDesc describe() {
-    return VariantDesc{Cfg::TM, Cfg::TN, Cfg::TK, Cfg::STAGES, Cfg::F16 ? 1 : 0, Cfg::MODE, Cfg::LA, Cfg::LB,
+    return VariantDesc{Cfg::TM, Cfg::TN, Cfg::TK, Cfg::STAGES, Cfg::DT, Cfg::MODE, Cfg::LA, Cfg::LB,
                        Cfg::LDS_BYTES, Cfg::PERSIST ? 1 : 0, Cfg::MIN_WAVES, &launch_cfg<Cfg>};
 }
 

@@ -6,7 +6,7 @@ namespace ucl {
 
 struct VariantDesc {
     int tile_m, tile_n, tile_k, stages;
-    int f16;            // 1: fp16 inputs, 0: bf16 inputs
+    int dt;             // inputs: 0 bf16, 1 fp16, 2 fp8 e4m3, 3 fp8 e5m2 (8-bit inputs are handled as pairs: K, strides in 16-bit units)
     int mode;           // 0 gemm / batched, 1 grouped, 2 conv2d fprop, 3 conv2d dgrad, 4 conv2d wgrad
     int la, lb;         // 0: operand contiguous along K, 1: contiguous along M / N (register transpose); A only: 2 im2col gather,
                         // 3 resident patch; 4 (B) / 5 (A): contiguous along N / M, copied directly and read through the LDS transpose read
@@ -41,6 +41,7 @@ VariantList variants_gemm_kn_f16();
 VariantList variants_gemm_mx_bf16();
 VariantList variants_gemm_mx_f16();
 VariantList variants_grouped_kn();
+VariantList variants_gemm_kk_fp8();
 VariantList variants_conv_dgrad();
 VariantList variants_conv_wgrad();
 

@@ -9,7 +9,7 @@ import torch
 from . import binding as ucl
 from . import synth
 
-_RAW = {"bf16": np.int16, "f16": np.int16, "f32": np.float32}
+_RAW = {"bf16": np.int16, "f16": np.int16, "f32": np.float32, "e4m3": np.uint8, "e5m2": np.uint8}
 _TENSOR_OPS = ucl.Epilogue.TENSOR
 
 

@@ -131,7 +131,7 @@ def test_selection_table():
     with pytest.raises(UclError):
         ucl.ucl_select_tuning("grouped_gemm", "bf16", "bf16", M_g=[64], N=64, K=64, a_layout="mn")
     assert all(0 < v["lds_bytes"] <= 160 * 1024 for v in variants)
-    assert all(v["op_class"] in (0, 1, 2, 3, 4) and v["dt_in"] in (1, 2) for v in variants)
+    assert all(v["op_class"] in (0, 1, 2, 3, 4) and v["dt_in"] in (1, 2, 3, 4) for v in variants)
 
 
 def _err(fn, *a, **k):

@@ -22,13 +22,14 @@ def T(tm, tn, tk, st, raster=0, iterator=0):
 ANALYTIC, PATCH = 1, 2      # ucl_conv_iterator
 
 
-def built(mode, f16=0, la=None, lb=0):
+def built(mode, f16=0, la=None, lb=0, dt=None):
     """(tile_m, tile_n, tile_k, stages) of every kernel variant built for a problem class."""
     la = (2 if mode == 2 else 0) if la is None else la
+    dt = ("f16" if f16 else "bf16") if dt is None else dt
     out = []
     for i in range(ucl.ucl_num_variants()):
         v = ucl.ucl_variant(i)
-        if (v["mode"], v["f16"], v["la"], v["lb"]) == (mode, f16, la, lb):
+        if (v["mode"], v["dt"], v["la"], v["lb"]) == (mode, dt, la, lb):
             out.append((v["tile_m"], v["tile_n"], v["tile_k"], v["stages"]))
     assert out
     return out

@@ -109,6 +109,14 @@ def test_gemm_with_fp8_inputs_matches_numpy():
         np.testing.assert_allclose(D, val(A, dt) @ val(B, dt).T, atol=1e-12)
 
 
+def test_batched_gemm_with_fp8_inputs_advances_by_one_byte_elements():
+    rng = np.random.default_rng(6)
+    A = synth.to_bits(rng.standard_normal((3, 5, 16)), "e5m2")
+    B = synth.to_bits(rng.standard_normal((3, 4, 16)), "e5m2")
+    D = oracle.batched_gemm(A, "e5m2", (16, 1, 80), B, "e5m2", (1, 16, 64), 3, 5, 4, 16)
+    np.testing.assert_allclose(D, np.einsum("bmk,bnk->bmn", val(A, "e5m2"), val(B, "e5m2")), atol=1e-12)
+
+
 def test_rounding_ties_and_double_rounding():
     r = oracle.round_to
     # bf16 has 8 significant bits: spacing 2^-7 in [1,2)
