@@ -30,6 +30,7 @@ typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
+typedef __attribute__((ext_vector_type(8))) uint32_t u32x8_t;
 
 #define UCL_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
 
@@ -424,6 +425,13 @@ __device__ __forceinline__ void mfma16(f32x4_t &c, const u32x4_t &a, const u32x4
             asm volatile("v_mfma_f32_16x16x32_bf8_bf8 %0, %1, %2, %0" : "+a"(c) : "v"(a1), "v"(b1));
         }
     }
+}
+
+// D(16x16, fp32) += A(16x128) * B(128x16), 8-bit operands: 32 bytes per lane and operand.
+template <int DT>
+__device__ __forceinline__ void mfma128(f32x4_t &c, const u32x8_t &a, const u32x8_t &b) {
+    if constexpr (DT == 2) asm volatile("v_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
+    else asm volatile("v_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, %0 cbsz:1 blgp:1" : "+a"(c) : "v"(a), "v"(b));
 }
 
 // Forces the accumulator to hold its value in an accumulation register at this point of the program.
@@ -1068,6 +1076,39 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
             });
             if (kt + 1 < KT) commit_regs((kt + 1) % STAGES);
         }
+    } else if constexpr (STAGES == 2 && Cfg::DT >= 2) {
+        // ---- 8-bit inputs, two stage buffers: one 128-deep MFMA per 16x16 block and k-tile -----------
+        // A k-tile row is 128 bytes = 128 fp8 values.  The wide 8-bit MFMA (16x16x128) takes 32 bytes per
+        // lane and operand: the lane's 16-byte fragments of both halves of the row side by side (which
+        // k a byte stands for is the same for A and B, and every k of the row is held exactly once).
+        // It does four times the work of the 32-deep form in twice the time, so the k-tile costs what a
+        // 16-bit k-tile of the same bytes costs and carries twice the FLOPs.
+        // Plain double buffering: k-tile kt is multiplied out of one buffer while k-tile kt+1 is in
+        // flight into the other; when every wave is done with the buffer it is refilled with kt+2.
+        static_assert(KSTEPS == 2 && LA == kKContig && LB == kKContig, "128-byte rows of K-contiguous operands");
+        u32x8_t b8[NI];
+        issue_tile(std::true_type{}, 0, 0);
+        issue_tile(std::true_type{}, 1, 1);
+        auto pair = [&](const char *sbase, int base, auto blk_) __attribute__((always_inline)) {
+            constexpr int blk = decltype(blk_)::value;
+            const u32x4_t lo = frag(sbase, base, blk, 0), hi = frag(sbase, base, blk, 1);
+            return u32x8_t{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        };
+        for (int kt = 0; kt < KT; ++kt) {
+            const int cur = kt & 1;
+            const char *sc = smem + cur * Cfg::STAGE_BYTES;
+            pipeline_barrier<DMA_PER_TILE>();                      // k-tile kt has landed (kt+1 may be in flight)
+            u32x8_t a_cur = pair(sc, a_frag_base, I0{}), a_nxt = a_cur;
+            static_for<NI>([&](auto ni) { b8[ni] = pair(sc, b_frag_base, ni); });
+            static_for<MI>([&](auto mi_) {
+                constexpr int mi = decltype(mi_)::value;
+                if constexpr (mi + 1 < MI) a_nxt = pair(sc, a_frag_base, std::integral_constant<int, mi + 1>{});
+                static_for<NI>([&](auto ni) { mfma128<Cfg::DT>(acc[mi][ni], b8[ni], a_cur); });
+                a_cur = a_nxt;
+            });
+            pipeline_barrier<DMA_PER_TILE>();                      // every wave has read the buffer: refill it
+            issue_tile(std::true_type{}, kt + 2, cur);
+        }
     } else if constexpr (STAGES == 2) {
         // ---- two stage buffers, k-tiles of two k-steps --------------------------------------------
         // For tiles whose stage is too large for three buffers.  One k-tile is multiplied while the
@@ -1378,7 +1419,35 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
                     pin_acc(acc[mi][ni]);
                 });
             });
-            for (int sl = 0; sl < p.split_k; ++sl) {
+            // Several slices' loads are in flight at once (a thread's share of one slice of a small tile is a
+            // few hundred bytes: one slice at a time would pay a memory round trip per slice); the additions
+            // still happen in slice order.
+            constexpr int kRegs = MI * NI;
+            // (as many slices as fit into half of what the kernel's register budget leaves beside the
+            // accumulators, at most 8; large tiles have a slice's worth of loads in flight anyway)
+            constexpr int kFit = (512 / Cfg::MIN_WAVES - kRegs * 4) / 2 / (kRegs * 4);
+            constexpr int U = kFit < 1 ? 1 : kFit > 8 ? 8 : kFit;
+            int sl = 0;
+            if constexpr (kFit >= 1) {
+                for (; sl + U <= p.split_k; sl += U) {
+                    f32x4_t v[U][kRegs];
+                    static_for<U>([&](auto u) {
+                        const float *part = p.ws_partials + ((int64_t)(sl + u) * p.total_tiles + t_lin) * kTileElems + tid * 4;
+                        static_for<kRegs>([&](auto r) { v[u][r] = __builtin_nontemporal_load((const f32x4_t *)(part + r * (kThreads * 4))); });
+                    });
+                    static_for<U>([&](auto u) {
+                        static_for<MI>([&](auto mi) {
+                            static_for<NI>([&](auto ni) {
+                                acc[mi][ni] += v[u][mi * NI + ni];
+                                pin_acc(acc[mi][ni]);  // back into its accumulation register: the sums must not
+                                                       // live in ordinary registers across the loop
+                            });
+                        });
+                    });
+                    asm volatile("" ::: "memory");
+                }
+            }
+            for (; sl < p.split_k; ++sl) {
                 const float *part = p.ws_partials + ((int64_t)sl * p.total_tiles + t_lin) * kTileElems + tid * 4;
                 // (one row block at a time: the compiler would otherwise gather all of a slice's loads in
                 // front of the additions and need a second register file's worth of registers for them)
@@ -1386,8 +1455,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
                     static_for<NI>([&](auto ni) {
                         const f32x4_t v = __builtin_nontemporal_load((const f32x4_t *)(part + (mi * NI + ni) * (kThreads * 4)));
                         acc[mi][ni] += v;
-                        pin_acc(acc[mi][ni]);          // back into its accumulation register: the sums must not
-                                                       // live in ordinary registers across the loop
+                        pin_acc(acc[mi][ni]);
                     });
                     asm volatile("" ::: "memory");
                 });
