@@ -311,6 +311,65 @@ def bench_transpose(args):
     print(json.dumps(out))
 
 
+PEAK_FP8_TFLOPS = 5033.2
+
+
+def bench_widening(args):
+    """The rows beyond the five headline workloads (not part of the headline metric): fp8 GEMM, the two
+    convolution gradients and a deep-K split-K GEMM, each timed like the workloads above and set against
+    its own roofline (ucl_sol_bound with the peak of its input type)."""
+    import torch
+    from paper_2603_29010_amd import synth
+    from paper_2603_29010_amd.binding import Tuning
+    from paper_2603_29010_amd.workload import DeviceWorkload
+    ws = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
+    import paper_2603_29010_amd as ucl
+    ucl.ucl_workspace_init(ws.data_ptr(), ws.numel(), torch.cuda.current_stream().cuda_stream)
+    split = lambda mode, slices=0: Tuning(split_k=mode, slices=slices, workspace=ws.data_ptr(), workspace_bytes=ws.numel())
+    conv = dict(Nb=32, H=56, W=56, C=64, Ko=128, R=3, S=3, pad=(1, 1))
+    cases = [
+        ("gemm_4096x4096x4096_fp8_e4m3_rowcol_bias_gelu_tanh_bf16out",
+         lambda: synth.gemm_spec(4096, 4096, 4096, dt_in="e4m3", dt_out="bf16", scale=1.0 / 64, epilogue=("bias", "gelu_tanh")), None),
+        ("gemm_4096x4096x4096_fp8_e5m2_rowcol_bias_gelu_tanh_bf16out",
+         lambda: synth.gemm_spec(4096, 4096, 4096, dt_in="e5m2", dt_out="bf16", scale=1.0 / 64, epilogue=("bias", "gelu_tanh")), None),
+        ("conv2d_dgrad_nhwc_32x56x56x64_from_128_3x3_bf16", lambda: synth.conv_grad_spec("dgrad", **conv), None),
+        ("conv2d_wgrad_nhwc_32x56x56x64_to_128_3x3_bf16_f32out_splitk_parallel",
+         lambda: synth.conv_grad_spec("wgrad", dt_out="f32", **conv), split("parallel")),
+        ("conv2d_wgrad_nhwc_32x56x56x64_to_128_3x3_bf16_f32out_splitk_serial",
+         lambda: synth.conv_grad_spec("wgrad", dt_out="f32", **conv), split("serial")),
+        ("gemm_256x256x16384_bf16_bias_relu_no_split",
+         lambda: synth.gemm_spec(256, 256, 16384, dist="uniform", scale=0.05, epilogue=("bias", "relu")), None),
+        ("gemm_256x256x16384_bf16_bias_relu_splitk_parallel",
+         lambda: synth.gemm_spec(256, 256, 16384, dist="uniform", scale=0.05, epilogue=("bias", "relu")), split("parallel")),
+        ("gemm_256x256x16384_bf16_bias_relu_splitk_serial",
+         lambda: synth.gemm_spec(256, 256, 16384, dist="uniform", scale=0.05, epilogue=("bias", "relu")), split("serial")),
+    ]
+    out = {}
+    for name, make, tune in cases:
+        spec = make()
+        w = DeviceWorkload(spec, poison=False)
+        sol = w.sol()
+        timing, launch, sclk = timed_replays(lambda i: w.run(tune=tune), args.steps, args.warmup, args.replays, not args.eager)
+        ms = statistics.median(timing["per_replay"])
+        t = ms * 1e-3
+        mfma = bool(sol["compute_bound"])
+        peak = (PEAK_FP8_TFLOPS if spec["dt_in"] in ("e4m3", "e5m2") else PEAK_MFMA_TFLOPS) if mfma else PEAK_HBM_GBPS
+        ach = sol["flops"] / t / 1e12 if mfma else sol["bytes"] / t / 1e9
+        out[name] = {"ms_per_step": ms, "ms_per_step_min": min(timing["per_replay"]), "tflops": sol["flops"] / t / 1e12,
+                     "gbps": sol["bytes"] / t / 1e9, "t_sol_us": sol["t_sol"] * 1e6, "frac_of_sol": sol["t_sol"] / t,
+                     "roofline": {"bound": "mfma" if mfma else "hbm", "achieved": ach, "peak": peak,
+                                  "unit": "TFLOP/s" if mfma else "GB/s", "frac": ach / peak, "traffic": None},
+                     "kernel": w.selected(), "launch": launch, "sclk_mhz_under_load": sclk}
+        if tune is not None:
+            kw = w._problem_kwargs()
+            out[name]["split_k"] = dict(zip(("workspace_bytes", "slices"),
+                                            ucl.ucl_workspace_size(w.op, spec["dt_in"], spec["dt_out"], tune, **kw)))
+        del w
+        torch.cuda.empty_cache()
+    print(json.dumps({"metric": "widening rows: TFLOP/s or GB/s and fraction of the roofline per workload, 1 MI355X", "n_gpus": 1,
+                      "steps": args.steps, "warmup": args.warmup, "replays": args.replays, "data": "synthetic", "workloads": out}))
+
+
 def main():
     global SPIN_UP_SECONDS
     ap = argparse.ArgumentParser()
@@ -327,6 +386,8 @@ def main():
     ap.add_argument("--eager", action="store_true", help="plain launches instead of one captured HIP graph")
     ap.add_argument("--transpose", action="store_true",
                     help="time the pipeline transform stage (NCHW fp32 -> NHWC bf16) instead of a GEMM / conv workload")
+    ap.add_argument("--widening", action="store_true",
+                    help="time the rows beyond the headline workloads (fp8 GEMM, conv gradients, split-K) instead")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run 10 plain device copies of 256 MiB and exit (reference reading for the "
                          "FETCH_SIZE / WRITE_SIZE counters)")
@@ -358,6 +419,9 @@ def main():
 
     if args.transpose:
         bench_transpose(args)
+        return
+    if args.widening:
+        bench_widening(args)
         return
     res, spec, probe = time_workload(args.config, args.steps, args.warmup, args.replays, use_graph=not args.eager)
     out = {

@@ -1,17 +1,20 @@
 // The one mainloop of the library: an MFMA tile kernel for gfx950 (CDNA4, wave64), shared by
-// gemm / batched_gemm / grouped_gemm / conv2d_fprop.  Included only by the instantiation units.
+// gemm / batched_gemm / grouped_gemm / conv2d_fprop / conv2d_dgrad / conv2d_wgrad.  Included only by
+// the instantiation units.
 //
 // Structure of a workgroup (256 threads = 4 waves, one per SIMD):
 //   tile schedule  : workgroup id -> (batch or group, tile row, tile column), XCD-aware
-//   staging        : global -> LDS, `STAGES` buffers deep.  Operands that are contiguous along K
-//                    (and the implicit-GEMM view of NHWC activations) go straight from HBM/L2 into
-//                    LDS with 128-bit `buffer_load ... lds` (no VGPR round trip); operands contiguous
-//                    along M / N are loaded 128-bit into VGPRs and transposed on the way into LDS.
+//   staging        : global -> LDS, `STAGES` buffers deep, 128-bit `buffer_load ... lds` (no VGPR round
+//                    trip) for every operand form: rows contiguous along K, the gathered views of the
+//                    three convolutions, and rows contiguous along M / N (copied as they are and read
+//                    back through the LDS transpose read).  A fallback that loads M / N-contiguous
+//                    operands into VGPRs and transposes them on the way into LDS serves matrices beyond
+//                    the reach of 32-bit offsets.
 //   LDS layout     : [rows][TK elements] (TK = 64 or 32: 128- or 64-byte rows of 16-byte chunks), chunk
 //                    index XORed with a function of the row so that the 16-byte-per-lane MFMA
 //                    fragment reads of 16 consecutive rows spread over all banks.
-//   mainloop       : v_mfma_f32_16x16x32_{bf16,f16}, fp32 accumulators held in registers,
-//                    wave tile (TM/2) x (TN/2).
+//   mainloop       : v_mfma_f32_16x16x32_{bf16,f16} (8-bit inputs: the 32-deep or the 128-deep fp8 MFMA on
+//                    pairs of elements), fp32 accumulators held in registers, wave tile (TM/2) x (TN/2).
 //   epilogue       : accumulators pass through a wave-private LDS patch to a row-contiguous layout;
 //                    the `>>` chain runs on them in fp32 registers, one rounding to the output type,
 //                    128-bit stores of whole row segments.
@@ -1266,9 +1269,9 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
         // mi + RA - 1 is requested -- past the last row block that is the first of the NEXT k-step,
         // so the ring runs across k-step and k-tile boundaries without a bubble.  The B fragments of
         // the next k-step and the copy instructions of the k-tile being fetched are dealt out over
-        // the row blocks in the same way, one side instruction per MFMA (sched_group_barrier; the
-        // source order is the issue order, since the compiler keeps LDS reads and LDS-writing loads
-        // in program order).
+        // the row blocks in the same way, one side instruction per MFMA (the MFMAs, reads and copies are
+        // volatile asm statements or loads the compiler keeps in program order: the source order is
+        // the issue order).
         // One barrier per k-tile, before its last k-step: then k-tile kt+1 has landed (explicit
         // vmcnt) and every wave is done with k-tile kt-1, whose buffer the last k-step refills with
         // k-tile kt+STAGES-1.  The k-steps before it read their own stage only and issue no copies.
