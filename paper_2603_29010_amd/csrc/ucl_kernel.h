@@ -1390,31 +1390,42 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
     // Slice s of tile t keeps its fp32 accumulators at partial[(s * tiles + t)][register][thread], one
     // 128-bit store per accumulator and thread.  Whoever adds the slices up reads them back in the same
     // layout, slice 0 first: the order of the additions is fixed, whichever workgroup does them.
+    // Partial tiles are written and read with device-coherent accesses (they bypass the L2 of the XCD
+    // the workgroup runs on: the eight L2s are not coherent with one another), so handing a tile from
+    // one workgroup to another needs no write-back or invalidation of a whole cache, only the wait for
+    // the stores' completion in front of the counter update.
     if constexpr ((MODE == 0 || MODE == 4) && !Cfg::PERSIST) {
         if (p.split_k > 1) {
             constexpr int64_t kTileElems = (int64_t)TM * TN;
+            constexpr int kCoherent = 17;                  // cache policy bits sc0 | sc1: device scope
             // (slice and tile index are worked out again from the workgroup id rather than kept in
             // registers across the mainloop; split-K never runs under the persistent scheduler)
             int wg_again = blockIdx.x;
             asm volatile("" : "+s"(wg_again));
             const int slice2 = p.split_phase != 2 ? wg_again / p.total_tiles : 0;
             const int t_lin = xcd_remap(wg_again - slice2 * p.total_tiles, p.total_tiles);
+            auto part_rsrc = [&](int sl) __attribute__((always_inline)) {
+                return buffer_rsrc(p.ws_partials + ((int64_t)sl * p.total_tiles + t_lin) * kTileElems, (uint32_t)(kTileElems * 4));
+            };
             if (p.split_phase != 2) {
-                float *part = p.ws_partials + ((int64_t)slice2 * p.total_tiles + t_lin) * kTileElems + tid * 4;
+                const rsrc_t mine = part_rsrc(slice2);
                 static_for<MI>([&](auto mi) {
-                    static_for<NI>([&](auto ni) { *(f32x4_t *)(part + (mi * NI + ni) * (kThreads * 4)) = acc[mi][ni]; });
+                    static_for<NI>([&](auto ni) {
+                        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, acc[mi][ni]), mine,
+                                                               ((mi * NI + ni) * kThreads + tid) * 16, 0, kCoherent);
+                    });
                 });
                 if (p.split_phase == 1) return;            // parallel mode, first launch: done
-                // serial mode: the workgroup that arrives last at the tile's counter does the rest.  Release
-                // this workgroup's partial tile to the device, count, and (if last) acquire the others'.
-                __threadfence();
+                // serial mode: the workgroup that arrives last at the tile's counter does the rest.  Its
+                // partial tile has reached memory once the stores have completed (vmcnt 0); then count.
+                __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
                 __syncthreads();                           // (also: every wave is past its LDS reads and copies)
                 if (tid == 0) *(volatile int *)smem = (int)atomicAdd(&p.ws_counters[t_lin], 1u);
                 __syncthreads();
                 const int arrived = *(volatile int *)smem;
                 if (arrived != p.split_k - 1) return;
                 if (tid == 0) atomicExch(&p.ws_counters[t_lin], 0u);      // leave the counter as it was found
-                __threadfence();
             }
             static_for<MI>([&](auto mi) {
                 static_for<NI>([&](auto ni) {
@@ -1433,15 +1444,15 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
             int sl = 0;
             if constexpr (kFit >= 1) {
                 for (; sl + U <= p.split_k; sl += U) {
-                    f32x4_t v[U][kRegs];
+                    u32x4_t v[U][kRegs];
                     static_for<U>([&](auto u) {
-                        const float *part = p.ws_partials + ((int64_t)(sl + u) * p.total_tiles + t_lin) * kTileElems + tid * 4;
-                        static_for<kRegs>([&](auto r) { v[u][r] = __builtin_nontemporal_load((const f32x4_t *)(part + r * (kThreads * 4))); });
+                        const rsrc_t rs = part_rsrc(sl + u);
+                        static_for<kRegs>([&](auto r) { v[u][r] = __builtin_amdgcn_raw_buffer_load_b128(rs, (r * kThreads + tid) * 16, 0, kCoherent); });
                     });
                     static_for<U>([&](auto u) {
                         static_for<MI>([&](auto mi) {
                             static_for<NI>([&](auto ni) {
-                                acc[mi][ni] += v[u][mi * NI + ni];
+                                acc[mi][ni] += __builtin_bit_cast(f32x4_t, v[u][mi * NI + ni]);
                                 pin_acc(acc[mi][ni]);  // back into its accumulation register: the sums must not
                                                        // live in ordinary registers across the loop
                             });
@@ -1451,13 +1462,13 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
                 }
             }
             for (; sl < p.split_k; ++sl) {
-                const float *part = p.ws_partials + ((int64_t)sl * p.total_tiles + t_lin) * kTileElems + tid * 4;
+                const rsrc_t rs = part_rsrc(sl);
                 // (one row block at a time: the compiler would otherwise gather all of a slice's loads in
                 // front of the additions and need a second register file's worth of registers for them)
                 static_for<MI>([&](auto mi) {
                     static_for<NI>([&](auto ni) {
-                        const f32x4_t v = __builtin_nontemporal_load((const f32x4_t *)(part + (mi * NI + ni) * (kThreads * 4)));
-                        acc[mi][ni] += v;
+                        const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(rs, ((mi * NI + ni) * kThreads + tid) * 16, 0, kCoherent);
+                        acc[mi][ni] += __builtin_bit_cast(f32x4_t, v);
                         pin_acc(acc[mi][ni]);
                     });
                     asm volatile("" ::: "memory");

@@ -136,6 +136,25 @@ def test_split_k_repeated_calls_and_graph_replay():
     assert counters_are_zero()
 
 
+def test_split_k_serial_partials_are_never_stale():
+    # Partial tiles pass between workgroups on different XCDs, each with its own L2.  The same workspace
+    # region is written again and again with different data (three problems of one shape, alternating,
+    # different slice counts): a reader that saw a line left in its L2 by an earlier call would give an
+    # earlier call's sums.  Integer data: every call must reproduce its problem's result bit for bit.
+    specs = [synth.gemm_spec(264, 200, 2048, dt_out="f32", epilogue=(), integer=True, seed=synth.BASE_SEED + 20 + i) for i in range(3)]
+    works = [DeviceWorkload(sp) for sp in specs]
+    refs = [parity.orc_run.run(sp) for sp in specs]
+    assert not np.array_equal(refs[0], refs[1])
+    for it in range(36):
+        i = it % 3
+        tile = ((64, 64, 64, 4), (128, 128, 64, 2), (256, 256, 64, 2))[(it // 3) % 3]
+        works[i].D.fill_(float("nan"))
+        works[i].run(tune=split_tune(tile, "serial", 2 + it % 7))
+        got = works[i].result()
+        assert np.array_equal(got, refs[i]), f"call {it}: problem {i}, tile {tile}: {np.count_nonzero(got != refs[i])} wrong elements"
+    assert counters_are_zero()
+
+
 def test_split_k_workspace_contract():
     spec = synth.gemm_spec(200, 136, 1000, dt_out="f32", epilogue=(), integer=True)
     w = DeviceWorkload(spec)
