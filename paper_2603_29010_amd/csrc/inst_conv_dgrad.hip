@@ -3,6 +3,8 @@
 namespace ucl {
 static const VariantDesc kTable[] = {
     describe<KernelCfg<256, 128, 32, 3, false, 3, kIm2col, kNDirect>>(),
+    describe<KernelCfg<256, 64, 32, 4, false, 3, kIm2col, kNDirect>>(),
+    describe<KernelCfg<128, 64, 32, 4, false, 3, kIm2col, kNDirect>>(),
     describe<KernelCfg<128, 128, 32, 4, false, 3, kIm2col, kNDirect>>(),
     describe<KernelCfg<64, 64, 32, 3, false, 3, kIm2col, kNDirect>>(),
     describe<KernelCfg<128, 128, 32, 4, true, 3, kIm2col, kNDirect>>(),
