@@ -136,8 +136,11 @@ typedef enum ucl_conv_iterator {
 typedef enum ucl_split_k_mode { UCL_SPLIT_K_NONE = 0, UCL_SPLIT_K_SERIAL = 1, UCL_SPLIT_K_PARALLEL = 2 } ucl_split_k_mode;
 
 /* `.with_scheduler(tile=...)`.  DEFAULT: one workgroup per output tile, dealt out by the hardware as
- * CUs free up.  PERSISTENT: one workgroup per CU slot, each walking the tile order with a stride of
- * the grid size.  (stream_k is not built and is rejected with UCL_ERR_UNSUPPORTED.) */
+ * CUs free up.  PERSISTENT: one workgroup per CU slot (a multiple of 8, so a workgroup stays on the
+ * tile run of its XCD), each walking the tile order with a stride of the grid size; built for gemm,
+ * batched_gemm and grouped_gemm with operands contiguous along K and tiles up to 128x128 (grouped:
+ * 64x64; the larger tiles' kernels have no registers to spare for the loop; see ucl_variant()); other requests are rejected with
+ * UCL_ERR_UNSUPPORTED.  STREAM_K is part of the knob's vocabulary but not built (rejected likewise). */
 typedef enum ucl_tile_scheduler { UCL_SCHED_DEFAULT = 0, UCL_SCHED_PERSISTENT = 1, UCL_SCHED_STREAM_K = 2 } ucl_tile_scheduler;
 
 /* The first UCL_WORKSPACE_COUNTER_BYTES of a split-K workspace hold the per-tile counters. */
@@ -377,6 +380,7 @@ typedef struct ucl_variant_info {
                                    reach of 32-bit offsets), 2 per-tap gather (conv), 3 resident patch (conv),
                                    4 / 5 direct copies of rows contiguous along N / M, read back transposed */
     int32_t lds_bytes;          /* LDS a workgroup of the variant occupies */
+    int32_t scheduler;          /* ucl_tile_scheduler the variant is built for */
 } ucl_variant_info;
 int32_t ucl_num_variants(void);
 ucl_status ucl_variant(int32_t i, ucl_variant_info *out);

@@ -37,7 +37,7 @@ ucl_status fail(ucl_status st, const char *fmt, ...) {
 const std::vector<VariantDesc> &all_variants() {
     static const std::vector<VariantDesc> v = [] {
         std::vector<VariantDesc> out;
-        for (VariantList l : {variants_gemm_kk_bf16_a(), variants_gemm_kk_bf16_b(), variants_gemm_kk_bf16_c(), variants_gemm_kk_bf16_d(), variants_gemm_kk_f16_a(), variants_gemm_kk_f16_b(), variants_gemm_mn_bf16(), variants_gemm_mn_f16(), variants_grouped_a(), variants_grouped_b(), variants_conv_a(), variants_conv_b(), variants_conv_f16(), variants_conv_halo(), variants_gemm_kn_bf16(), variants_gemm_kn_f16(), variants_gemm_mx_bf16(), variants_gemm_mx_f16(), variants_grouped_kn(), variants_conv_dgrad(), variants_conv_wgrad(), variants_gemm_kk_fp8()})
+        for (VariantList l : {variants_gemm_kk_bf16_a(), variants_gemm_kk_bf16_b(), variants_gemm_kk_bf16_c(), variants_gemm_kk_bf16_d(), variants_gemm_kk_f16_a(), variants_gemm_kk_f16_b(), variants_gemm_mn_bf16(), variants_gemm_mn_f16(), variants_grouped_a(), variants_grouped_b(), variants_conv_a(), variants_conv_b(), variants_conv_f16(), variants_conv_halo(), variants_gemm_kn_bf16(), variants_gemm_kn_f16(), variants_gemm_mx_bf16(), variants_gemm_mx_f16(), variants_grouped_kn(), variants_conv_dgrad(), variants_conv_wgrad(), variants_gemm_kk_fp8(), variants_persistent()})
             for (int i = 0; i < l.n; ++i) out.push_back(l.v[i]);
         return out;
     }();
@@ -329,7 +329,7 @@ ucl_status plan_split(const Launch &L, const VariantDesc &v, const ucl_tuning *t
     if (tune->scheduler < UCL_SCHED_DEFAULT || tune->scheduler > UCL_SCHED_STREAM_K)
         return fail(UCL_ERR_INVALID_ARG, "scheduler=%d is not a ucl_tile_scheduler", tune->scheduler);
     if (tune->scheduler == UCL_SCHED_STREAM_K)
-        return fail(UCL_ERR_UNSUPPORTED, "the stream_k tile scheduler is not built; use split-K (fixed slices) or the persistent scheduler");
+        return fail(UCL_ERR_UNSUPPORTED, "the stream_k tile scheduler is not built; split-K (fixed slices of K) is");
     if (tune->split_k_mode < UCL_SPLIT_K_NONE || tune->split_k_mode > UCL_SPLIT_K_PARALLEL)
         return fail(UCL_ERR_INVALID_ARG, "split_k_mode=%d is not a ucl_split_k_mode", tune->split_k_mode);
     if (tune->split_k_slices < 0) return fail(UCL_ERR_INVALID_ARG, "split_k_slices=%d must be >= 0", tune->split_k_slices);
@@ -451,7 +451,8 @@ ucl_status run(const Launch &L, KParams &kp, const ucl_tuning *tune, void *strea
         int64_t grid = total * sp.slices;
         if (v->persistent) {
             // one workgroup per CU slot; a multiple of 8 keeps each workgroup on the tile run of its XCD
-            const int64_t slots = (int64_t)kNumCUs * workgroups_per_cu(*v);
+            // (as many as the compiled kernel's registers and LDS let a CU hold, so that the whole grid is resident)
+            const int64_t slots = (int64_t)kNumCUs * v->resident();
             if (grid > slots) grid = slots;
         }
         e = v->launch(kp, gtp, (int)grid, (hipStream_t)stream);
@@ -958,6 +959,7 @@ ucl_status ucl_variant(int32_t i, ucl_variant_info *out) {
     out->b_layout = (v.lb == 1 || v.lb == 4) ? UCL_LAYOUT_MN_CONTIGUOUS : UCL_LAYOUT_K_CONTIGUOUS;
     out->a_path = v.la; out->b_path = v.lb;
     out->lds_bytes = v.lds_bytes;
+    out->scheduler = v.persistent ? UCL_SCHED_PERSISTENT : UCL_SCHED_DEFAULT;
     return UCL_OK;
 }
 

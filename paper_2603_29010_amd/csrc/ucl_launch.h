@@ -16,10 +16,22 @@ hipError_t launch_cfg(const KParams &p, const GroupTable *gt, int grid, hipStrea
     return hipGetLastError();
 }
 
+// Workgroups of the variant that one CU holds at a time, as the runtime computes it from the registers and
+// LDS the compiled kernel uses (a host-side query: no device work, no allocation).
+template <class Cfg>
+int resident_cfg() {
+    int n = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, ucl_tile_kernel<Cfg>, kThreads, 0) != hipSuccess || n < 1) {
+        (void)hipGetLastError();
+        n = 1;
+    }
+    return n;
+}
+
 template <class Cfg>
 constexpr VariantDesc describe() {
     return VariantDesc{Cfg::TM, Cfg::TN, Cfg::TK, Cfg::STAGES, Cfg::DT, Cfg::MODE, Cfg::LA, Cfg::LB,
-                       Cfg::LDS_BYTES, Cfg::PERSIST ? 1 : 0, Cfg::MIN_WAVES, &launch_cfg<Cfg>};
+                       Cfg::LDS_BYTES, Cfg::PERSIST ? 1 : 0, Cfg::MIN_WAVES, &launch_cfg<Cfg>, &resident_cfg<Cfg>};
 }
 
 }  // namespace ucl

@@ -14,6 +14,7 @@ struct VariantDesc {
     int persistent;     // 1: built for the persistent tile scheduler (grid = CU slots, workgroups loop over tiles)
     int wgs_per_cu;     // workgroups of the kernel a CU is meant to hold (register budget it was built with)
     hipError_t (*launch)(const KParams &p, const GroupTable *gt, int grid, hipStream_t stream);
+    int (*resident)();          // workgroups one CU holds at a time (queried from the runtime)
 };
 
 struct VariantList {
@@ -41,6 +42,7 @@ VariantList variants_gemm_kn_f16();
 VariantList variants_gemm_mx_bf16();
 VariantList variants_gemm_mx_f16();
 VariantList variants_grouped_kn();
+VariantList variants_persistent();
 VariantList variants_gemm_kk_fp8();
 VariantList variants_conv_dgrad();
 VariantList variants_conv_wgrad();

@@ -22,14 +22,15 @@ def T(tm, tn, tk, st, raster=0, iterator=0):
 ANALYTIC, PATCH = 1, 2      # ucl_conv_iterator
 
 
-def built(mode, f16=0, la=None, lb=0, dt=None):
-    """(tile_m, tile_n, tile_k, stages) of every kernel variant built for a problem class."""
+def built(mode, f16=0, la=None, lb=0, dt=None, scheduler=0):
+    """(tile_m, tile_n, tile_k, stages) of every kernel variant built for a problem class and
+    tile scheduler (0: one workgroup per tile, 1: persistent)."""
     la = (2 if mode == 2 else 0) if la is None else la
     dt = ("f16" if f16 else "bf16") if dt is None else dt
     out = []
     for i in range(ucl.ucl_num_variants()):
         v = ucl.ucl_variant(i)
-        if (v["mode"], v["dt"], v["la"], v["lb"]) == (mode, dt, la, lb):
+        if (v["mode"], v["dt"], v["la"], v["lb"], v["scheduler"]) == (mode, dt, la, lb, scheduler):
             out.append((v["tile_m"], v["tile_n"], v["tile_k"], v["stages"]))
     assert out
     return out
