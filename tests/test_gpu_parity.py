@@ -353,6 +353,17 @@ def test_conv_parity_bias_residual_relu():
         parity.check(spec16, T(*tile, iterator=PATCH), label=f"conv f16 patch {tile}")
 
 
+@pytest.mark.parametrize("geom", [dict(Nb=3, H=13, W=11, Ko=72), dict(Nb=2, H=20, W=58, Ko=136), dict(Nb=5, H=1, W=1, Ko=8),
+                                  dict(Nb=4, H=31, W=29, Ko=128)])
+@pytest.mark.parametrize("dt_out", ["bf16", "f32"])
+def test_conv_patch_residual_ragged(geom, dt_out):
+    # the patch kernels touch the tile's 16-bit residual lines during the mainloop (a prefetch into L2): tiles whose last
+    # rows and columns do not exist, a residual row shorter than one line, an fp32 residual (no prefetch)
+    spec = synth.conv_spec(C=64, R=3, S=3, dt_out=dt_out, **geom)
+    for tile in built(2, la=3):
+        parity.check(spec, T(*tile, iterator=PATCH), label=f"conv patch residual {tile}")
+
+
 # ---------------------------------------------------------------- the benchmark configurations
 
 def test_config1_full():
