@@ -316,7 +316,7 @@ PEAK_FP8_TFLOPS = 5033.2
 
 def bench_widening(args):
     """The rows beyond the five headline workloads (not part of the headline metric): fp8 GEMM, the two
-    convolution gradients and a deep-K split-K GEMM, each timed like the workloads above and set against
+    convolution gradients, a deep-K split-K GEMM and the persistent tile scheduler, each timed like the workloads above and set against
     its own roofline (ucl_sol_bound with the peak of its input type)."""
     import torch
     from paper_2603_29010_amd import synth
@@ -343,6 +343,11 @@ def bench_widening(args):
          lambda: synth.gemm_spec(256, 256, 16384, dist="uniform", scale=0.05, epilogue=("bias", "relu")), split("parallel")),
         ("gemm_256x256x16384_bf16_bias_relu_splitk_serial",
          lambda: synth.gemm_spec(256, 256, 16384, dist="uniform", scale=0.05, epilogue=("bias", "relu")), split("serial")),
+        # tile scheduler: the same 128x128x32x4 kernel, one workgroup per tile against one per CU slot
+        ("gemm_8192x8192x64_bf16_bias_relu_tile128_default_scheduler",
+         lambda: synth.gemm_spec(8192, 8192, 64, epilogue=("bias", "relu")), Tuning(128, 128, 32, 4)),
+        ("gemm_8192x8192x64_bf16_bias_relu_tile128_persistent_scheduler",
+         lambda: synth.gemm_spec(8192, 8192, 64, epilogue=("bias", "relu")), Tuning(128, 128, 32, 4, scheduler="persistent")),
     ]
     out = {}
     for name, make, tune in cases:
@@ -359,8 +364,10 @@ def bench_widening(args):
                      "gbps": sol["bytes"] / t / 1e9, "t_sol_us": sol["t_sol"] * 1e6, "frac_of_sol": sol["t_sol"] / t,
                      "roofline": {"bound": "mfma" if mfma else "hbm", "achieved": ach, "peak": peak,
                                   "unit": "TFLOP/s" if mfma else "GB/s", "frac": ach / peak, "traffic": None},
-                     "kernel": w.selected(), "launch": launch, "sclk_mhz_under_load": sclk}
-        if tune is not None:
+                     "kernel": w.selected() if tune is None or tune.c.split_k_mode else
+                     dict(tune.as_dict(), scheduler="persistent" if tune.c.scheduler else "default"),
+                     "launch": launch, "sclk_mhz_under_load": sclk}
+        if tune is not None and tune.c.split_k_mode:
             kw = w._problem_kwargs()
             out[name]["split_k"] = dict(zip(("workspace_bytes", "slices"),
                                             ucl.ucl_workspace_size(w.op, spec["dt_in"], spec["dt_out"], tune, **kw)))

@@ -131,8 +131,11 @@ typedef enum ucl_conv_iterator {
  * that run as separate workgroups; their fp32 partial tiles pass through the caller's workspace and
  * are added in slice order 0, 1, 2, ... (a fixed order: results do not depend on timing), after
  * which the epilogue chain runs once.  SERIAL: one launch; the workgroup that finishes a tile last
- * (a counter per tile in the workspace) adds the slices up and runs the epilogue.  PARALLEL: two
- * launches, the second one adds up and runs the epilogue.  Both give bit-identical results. */
+ * (a counter per tile in the workspace) adds the slices up and runs the epilogue.  PARALLEL: the
+ * slices are written by one launch and added up and finished by another; with more than two slices
+ * a small reduction kernel between them adds the slices up with the whole GPU (three launches in
+ * all, on the caller's stream).  Both give bit-identical results.  With no tile named in the same
+ * ucl_tuning, the tile is chosen for the split-K launch (not as for the unsplit problem). */
 typedef enum ucl_split_k_mode { UCL_SPLIT_K_NONE = 0, UCL_SPLIT_K_SERIAL = 1, UCL_SPLIT_K_PARALLEL = 2 } ucl_split_k_mode;
 
 /* `.with_scheduler(tile=...)`.  DEFAULT: one workgroup per output tile, dealt out by the hardware as

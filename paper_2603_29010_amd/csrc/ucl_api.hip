@@ -160,6 +160,52 @@ double estimate_seconds(const VariantDesc &v, const Launch &L) {
     return per_cu * (tile_flops / (relative_rate(v) * alone * kCuRate * boost) + fixed * exposed);
 }
 
+constexpr int kNumCUs = 256;
+
+// Slices a split-K launch of `total_tiles` tiles gets: as asked for, or (0) enough to give every CU a workgroup
+// while each keeps at least 4 x 64 of K; slices are whole multiples of 64 along K.
+void split_slices(const Launch &L, int64_t want, int64_t total_tiles, int &slices, int &k_per_slice) {
+    const int64_t kt = (L.K + 63) / 64;
+    if (want == 0) {
+        want = total_tiles >= kNumCUs ? 1 : (kNumCUs + total_tiles - 1) / total_tiles;
+        if (want > kt / 4) want = kt / 4;
+        if (want < 1) want = 1;
+    }
+    if (want > kt) want = kt;
+    const int64_t per = (kt + want - 1) / want;
+    k_per_slice = (int)(per * 64);
+    slices = (int)((kt + per - 1) / per);
+}
+
+// Launch time of variant v under split-K, for the choice among the variants when the caller names no tile.
+// What counts differs from the unsplit case.  Every CU has a workgroup, so the mainloop is bound by one of: the
+// operand bytes all workgroups together copy into LDS (measured ~10 TB/s over the chip when they stream from
+// HBM, ~16 TB/s when the operands stay in the L2s), the MFMA rate, or a workgroup's own chain of copies (stages-1
+// k-tiles in flight, a round trip of ~1.5 us from HBM, ~0.8 us from L2).  The partial tiles then cross memory:
+// in parallel mode through a streaming reduction kernel and two more launches (measured: 6 us plus 1 us per MB
+// of partial tiles), in serial mode through the last workgroup of each tile, which reads all slices alone
+// (measured 15-28 GB/s per workgroup).
+double estimate_split_seconds(const VariantDesc &v, const Launch &L, const ucl_tuning *tune) {
+    const int64_t tiles = count_tiles(L, v.tile_m, v.tile_n);
+    int slices = 1, kps = 0;
+    split_slices(L, tune->split_k_slices, tiles, slices, kps);
+    if (slices <= 1) return estimate_seconds(v, L);
+    const double wgs = (double)tiles * slices;
+    const double rounds = ceil(wgs / (256.0 * workgroups_per_cu(v)));
+    const double busy = wgs < 256.0 ? wgs / 256.0 : 1.0;
+    const bool resident = (double)L.batch * (L.M + L.N) * (double)L.K * 2.0 <= 32.0e6;
+    const double copy_bytes = wgs * kps * (double)(v.tile_m + v.tile_n) * 2.0;
+    const double flops = 2.0 * wgs * kps * (double)v.tile_m * v.tile_n;
+    double main = copy_bytes / ((resident ? 16.0e12 : 10.0e12) * busy);
+    const double mfma = flops / (relative_rate(v) * 1.38e15 * busy);
+    if (mfma > main) main = mfma;
+    const double chain = rounds * (kps / (double)v.tile_k) * (resident ? 0.8e-6 : 1.5e-6) / (v.stages > 1 ? v.stages - 1 : 1);
+    if (chain > main) main = chain;
+    const double tile_bytes = (double)v.tile_m * v.tile_n * 4.0;
+    if (tune->split_k_mode == UCL_SPLIT_K_PARALLEL) return main + 6.0e-6 + wgs * tile_bytes / 1.0e12;
+    return main + 3.0e-6 + slices * tile_bytes / (v.tile_m * v.tile_n >= 128 * 128 ? 15.0e9 : 28.0e9);
+}
+
 const VariantDesc *select_variant(const Launch &L, const ucl_tuning *tune) {
     const auto &vs = all_variants();
     const bool explicit_tune = tune && (tune->tile_m || tune->tile_n || tune->tile_k || tune->stages);
@@ -183,7 +229,8 @@ const VariantDesc *select_variant(const Launch &L, const ucl_tuning *tune) {
             if (!best) best = &v;
             continue;
         }
-        const double t = estimate_seconds(v, L);
+        const bool split = tune && tune->split_k_mode != UCL_SPLIT_K_NONE && tune->split_k_slices >= 0 && (L.mode == 0 || L.mode == 4);
+        const double t = split ? estimate_split_seconds(v, L, tune) : estimate_seconds(v, L);
         if (!best || t < best_t) { best_t = t; best = &v; }
     }
     return best;
@@ -308,12 +355,35 @@ ucl_status check_common(int64_t M, int64_t N, int64_t K, int dtA, int dtB, int d
     return UCL_OK;
 }
 
-constexpr int kNumCUs = 256;
 
 // Fill kernel for the counter area of a split-K workspace (a kernel, not a memset node: the call may
 // be captured into a HIP graph).  One 128-bit store per thread.
 __global__ void zero_words_kernel(uint32_t *w) {
     ((u32x4 *)w)[blockIdx.x * blockDim.x + threadIdx.x] = u32x4{0u, 0u, 0u, 0u};
+}
+
+// Parallel split-K, between the two launches of the tile kernel: adds the slices of every partial tile up into
+// slice 0, slice 0 first (the same order, starting from +0, as the tile kernel's own loop: the results are
+// bit-identical).  A tile kernel that did this itself would have one workgroup per tile read all slices of its
+// tile; here every 16 bytes of a tile are a thread's work, so that the whole chip streams the partial tiles.
+// `slice_stride` = floats per slice (tiles x tile elements), `n4` = 16-byte words per slice.
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(float *partials, int64_t slice_stride, int slices, int64_t n4) {
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n4) return;
+    const f32x4 *src = (const f32x4 *)partials + i;
+    const int64_t stride4 = slice_stride / 4;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    int s = 0;
+    for (; s + 8 <= slices; s += 8) {
+        f32x4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load(src + (s + u) * stride4);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc += v[u];
+    }
+    for (; s < slices; ++s) acc += __builtin_nontemporal_load(src + s * stride4);
+    ((f32x4 *)partials)[i] = acc;
 }
 
 // split-K plan of a launch: slices (1 = none), K extent per slice, workspace bytes.
@@ -341,18 +411,7 @@ ucl_status plan_split(const Launch &L, const VariantDesc &v, const ucl_tuning *t
     if (L.mode != 0 && L.mode != 4) return fail(UCL_ERR_UNSUPPORTED, "split-K is built for gemm, batched_gemm and conv2d_wgrad");
     if (tune->scheduler == UCL_SCHED_PERSISTENT)
         return fail(UCL_ERR_UNSUPPORTED, "split-K and the persistent scheduler cannot be combined");
-    const int64_t kt = (L.K + 63) / 64;                     // slices are whole multiples of 64 along K
-    int64_t want = tune->split_k_slices;
-    if (want == 0) {
-        // enough slices to give every CU a workgroup, each keeping at least 4 x 64 of K
-        want = total_tiles >= kNumCUs ? 1 : (kNumCUs + total_tiles - 1) / total_tiles;
-        if (want > kt / 4) want = kt / 4;
-        if (want < 1) want = 1;
-    }
-    if (want > kt) want = kt;
-    const int64_t per = (kt + want - 1) / want;
-    sp.k_per_slice = (int)(per * 64);
-    sp.slices = (int)((kt + per - 1) / per);
+    split_slices(L, tune->split_k_slices, total_tiles, sp.slices, sp.k_per_slice);
     if (sp.slices <= 1) { sp = SplitPlan(); return UCL_OK; }
     if (total_tiles > UCL_SPLIT_K_MAX_TILES)
         return fail(UCL_ERR_UNSUPPORTED, "split-K serves at most %d output tiles (this problem has %lld)", UCL_SPLIT_K_MAX_TILES, (long long)total_tiles);
@@ -360,6 +419,9 @@ ucl_status plan_split(const Launch &L, const VariantDesc &v, const ucl_tuning *t
     sp.bytes = UCL_WORKSPACE_COUNTER_BYTES + (int64_t)sp.slices * total_tiles * v.tile_m * v.tile_n * 4;
     return UCL_OK;
 }
+
+// Parallel split-K with up to this many slices lets the last launch of the tile kernel add them up itself.
+constexpr int kReduceInTileKernel = 2;
 
 ucl_status run(const Launch &L, KParams &kp, const ucl_tuning *tune, void *stream, bool clear_counters = false) {
     if (tune && (tune->iterator < 0 || tune->iterator > UCL_ITER_FIXED_STRIDE_DILATION))
@@ -435,6 +497,14 @@ ucl_status run(const Launch &L, KParams &kp, const ucl_tuning *tune, void *strea
     if (sp.slices > 1 && tune->split_k_mode == UCL_SPLIT_K_PARALLEL) {
         kp.split_phase = 1;
         e = v->launch(kp, gtp, (int)(total * sp.slices), (hipStream_t)stream);
+        if (e == hipSuccess && sp.slices > kReduceInTileKernel) {
+            // many slices: a launch of its own adds them up with the whole chip, the last launch then finds one slice
+            const int64_t slice_floats = total * v->tile_m * v->tile_n, n4 = slice_floats / 4;
+            hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
+                               kp.ws_partials, slice_floats, sp.slices, n4);
+            e = hipGetLastError();
+            kp.split_k = 1;
+        }
         if (e == hipSuccess) {
             kp.split_phase = 2;
             e = v->launch(kp, gtp, (int)total, (hipStream_t)stream);

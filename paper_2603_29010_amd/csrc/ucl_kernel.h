@@ -484,15 +484,22 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / Cfg::WAVES_N, wn = wave % Cfg::WAVES_N;
-    // split-K (gemm / batched): workgroups [s * total_tiles, (s + 1) * total_tiles) work on K slice s
-    int slice = 0, wg_tile = wg_id;
+    // split-K (gemm / batched / wgrad): the (slice, tile) pairs are numbered slice by slice and that numbering is
+    // dealt to the XCDs in runs, like tiles are: the tiles of one K slice, which read the same rows of A and B,
+    // run side by side on one XCD and share them in its L2
+    int slice = 0;
+    int t = 0;
     if constexpr ((MODE == 0 || MODE == 4) && !Cfg::PERSIST) {
         if (p.split_k > 1 && p.split_phase != 2) {
-            slice = wg_id / p.total_tiles;
-            wg_tile = wg_id - slice * p.total_tiles;
+            t = xcd_remap(wg_id, p.total_tiles * p.split_k);
+            slice = t / p.total_tiles;
+            t -= slice * p.total_tiles;
+        } else {
+            t = xcd_remap(wg_id, p.total_tiles);
         }
+    } else {
+        t = xcd_remap(wg_id, p.total_tiles);
     }
-    int t = xcd_remap(wg_tile, p.total_tiles);
     int batch = 0, group = -1, tm, tn;
     int Mloc = p.M;
     const char *Ab = (const char *)p.A;
@@ -516,7 +523,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
     const int m0 = tm * TM, n0 = tn * TN;
     int k_len = p.K;
     if constexpr ((MODE == 0 || MODE == 4) && !Cfg::PERSIST) {
-        if (p.split_k > 1) {
+        if (p.split_k > 1 || p.split_phase == 2) {
             // this slice's K range (a multiple of 64 long, so operand rows stay 16-byte aligned)
             const int kb = slice * p.k_per_slice;
             k_len = p.K - kb < p.k_per_slice ? p.K - kb : p.k_per_slice;
@@ -1395,15 +1402,17 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
     // one workgroup to another needs no write-back or invalidation of a whole cache, only the wait for
     // the stores' completion in front of the counter update.
     if constexpr ((MODE == 0 || MODE == 4) && !Cfg::PERSIST) {
-        if (p.split_k > 1) {
+        // (phase 2 with one slice: the slices were added up into slice 0 by the reduction kernel)
+        if (p.split_k > 1 || p.split_phase == 2) {
             constexpr int64_t kTileElems = (int64_t)TM * TN;
             constexpr int kCoherent = 17;                  // cache policy bits sc0 | sc1: device scope
             // (slice and tile index are worked out again from the workgroup id rather than kept in
             // registers across the mainloop; split-K never runs under the persistent scheduler)
             int wg_again = blockIdx.x;
             asm volatile("" : "+s"(wg_again));
-            const int slice2 = p.split_phase != 2 ? wg_again / p.total_tiles : 0;
-            const int t_lin = xcd_remap(wg_again - slice2 * p.total_tiles, p.total_tiles);
+            const int pair = xcd_remap(wg_again, p.split_phase != 2 ? p.total_tiles * p.split_k : p.total_tiles);
+            const int slice2 = p.split_phase != 2 ? pair / p.total_tiles : 0;
+            const int t_lin = pair - slice2 * p.total_tiles;
             auto part_rsrc = [&](int sl) __attribute__((always_inline)) {
                 return buffer_rsrc(p.ws_partials + ((int64_t)sl * p.total_tiles + t_lin) * kTileElems, (uint32_t)(kTileElems * 4));
             };
@@ -1427,52 +1436,70 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
                 if (arrived != p.split_k - 1) return;
                 if (tid == 0) atomicExch(&p.ws_counters[t_lin], 0u);      // leave the counter as it was found
             }
-            static_for<MI>([&](auto mi) {
-                static_for<NI>([&](auto ni) {
-                    acc[mi][ni] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-                    pin_acc(acc[mi][ni]);
-                });
-            });
-            // Several slices' loads are in flight at once (a thread's share of one slice of a small tile is a
-            // few hundred bytes: one slice at a time would pay a memory round trip per slice); the additions
-            // still happen in slice order.
             constexpr int kRegs = MI * NI;
-            // (as many slices as fit into half of what the kernel's register budget leaves beside the
-            // accumulators, at most 8; large tiles have a slice's worth of loads in flight anyway)
-            constexpr int kFit = (512 / Cfg::MIN_WAVES - kRegs * 4) / 2 / (kRegs * 4);
-            constexpr int U = kFit < 1 ? 1 : kFit > 8 ? 8 : kFit;
-            int sl = 0;
-            if constexpr (kFit >= 1) {
-                for (; sl + U <= p.split_k; sl += U) {
-                    u32x4_t v[U][kRegs];
-                    static_for<U>([&](auto u) {
-                        const rsrc_t rs = part_rsrc(sl + u);
-                        static_for<kRegs>([&](auto r) { v[u][r] = __builtin_amdgcn_raw_buffer_load_b128(rs, (r * kThreads + tid) * 16, 0, kCoherent); });
-                    });
-                    static_for<U>([&](auto u) {
-                        static_for<MI>([&](auto mi) {
-                            static_for<NI>([&](auto ni) {
-                                acc[mi][ni] += __builtin_bit_cast(f32x4_t, v[u][mi * NI + ni]);
-                                pin_acc(acc[mi][ni]);  // back into its accumulation register: the sums must not
-                                                       // live in ordinary registers across the loop
-                            });
-                        });
+            if (p.split_k == 1) {
+                // One slice: the sum the reduction kernel left in slice 0.  It is taken as it is (0 + x is x bit for
+                // bit: a sum that started from +0 is never -0), sixteen accumulators' loads in flight at a time.
+                const rsrc_t rs = part_rsrc(0);
+                constexpr int kBatch = kRegs < 16 ? kRegs : 16;
+                static_for<kRegs / kBatch>([&](auto b_) {
+                    constexpr int r0 = decltype(b_)::value * kBatch;
+                    u32x4_t v[kBatch];
+                    static_for<kBatch>([&](auto j) { v[j] = __builtin_amdgcn_raw_buffer_load_b128(rs, ((r0 + j) * kThreads + tid) * 16, 0, kCoherent); });
+                    static_for<kBatch>([&](auto j) {
+                        constexpr int r = r0 + decltype(j)::value;
+                        acc[r / NI][r % NI] = __builtin_bit_cast(f32x4_t, v[j]);
+                        pin_acc(acc[r / NI][r % NI]);
                     });
                     asm volatile("" ::: "memory");
-                }
-            }
-            for (; sl < p.split_k; ++sl) {
-                const rsrc_t rs = part_rsrc(sl);
-                // (one row block at a time: the compiler would otherwise gather all of a slice's loads in
-                // front of the additions and need a second register file's worth of registers for them)
+                });
+            } else {
                 static_for<MI>([&](auto mi) {
                     static_for<NI>([&](auto ni) {
-                        const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(rs, ((mi * NI + ni) * kThreads + tid) * 16, 0, kCoherent);
-                        acc[mi][ni] += __builtin_bit_cast(f32x4_t, v);
+                        acc[mi][ni] = f32x4_t{0.f, 0.f, 0.f, 0.f};
                         pin_acc(acc[mi][ni]);
                     });
-                    asm volatile("" ::: "memory");
                 });
+                // Several slices' loads are in flight at once (a thread's share of one slice of a small tile is a
+                // few hundred bytes: one slice at a time would pay a memory round trip per slice); the additions
+                // still happen in slice order.
+                // (as many slices as fit into half of what the kernel's register budget leaves beside the
+                // accumulators, at most 8; large tiles have a slice's worth of loads in flight anyway)
+                constexpr int kFit = (512 / Cfg::MIN_WAVES - kRegs * 4) / 2 / (kRegs * 4);
+                constexpr int U = kFit < 1 ? 1 : kFit > 8 ? 8 : kFit;
+                int sl = 0;
+                if constexpr (kFit >= 1) {
+                    for (; sl + U <= p.split_k; sl += U) {
+                        u32x4_t v[U][kRegs];
+                        static_for<U>([&](auto u) {
+                            const rsrc_t rs = part_rsrc(sl + u);
+                            static_for<kRegs>([&](auto r) { v[u][r] = __builtin_amdgcn_raw_buffer_load_b128(rs, (r * kThreads + tid) * 16, 0, kCoherent); });
+                        });
+                        static_for<U>([&](auto u) {
+                            static_for<MI>([&](auto mi) {
+                                static_for<NI>([&](auto ni) {
+                                    acc[mi][ni] += __builtin_bit_cast(f32x4_t, v[u][mi * NI + ni]);
+                                    pin_acc(acc[mi][ni]);  // back into its accumulation register: the sums must not
+                                                           // live in ordinary registers across the loop
+                                });
+                            });
+                        });
+                        asm volatile("" ::: "memory");
+                    }
+                }
+                for (; sl < p.split_k; ++sl) {
+                    const rsrc_t rs = part_rsrc(sl);
+                    // (one row block at a time: the compiler would otherwise gather all of a slice's loads in
+                    // front of the additions and need a second register file's worth of registers for them)
+                    static_for<MI>([&](auto mi) {
+                        static_for<NI>([&](auto ni) {
+                            const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(rs, ((mi * NI + ni) * kThreads + tid) * 16, 0, kCoherent);
+                            acc[mi][ni] += __builtin_bit_cast(f32x4_t, v);
+                            pin_acc(acc[mi][ni]);
+                        });
+                        asm volatile("" ::: "memory");
+                    });
+                }
             }
         }
     }

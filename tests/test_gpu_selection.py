@@ -69,3 +69,31 @@ def test_table_pick_is_near_the_fastest_built_variant(name):
     assert t_pick <= 1.10 * times[best], (f"{name}: the table picks {pick_key} at {t_pick:.1f} us, "
                                           f"{best} runs {times[best]:.1f} us; all: " +
                                           ", ".join(f"{k}: {v:.1f}" for k, v in sorted(times.items(), key=lambda kv: kv[1])))
+
+
+SPLIT_SHAPES = {
+    "gemm 256x256x16384": (lambda: synth.gemm_spec(256, 256, 16384, dist="uniform", scale=0.05, epilogue=("bias", "relu")), 0, None),
+    "gemm 512x512x8192 -> fp32": (lambda: synth.gemm_spec(512, 512, 8192, dt_out="f32", epilogue=()), 0, None),
+    "wgrad 32x56x56, 64 -> 128 channels, 3x3": (lambda: synth.conv_grad_spec("wgrad", dt_out="f32", Nb=32, H=56, W=56, C=64, Ko=128, R=3, S=3,
+                                                                               pad=(1, 1)), 4, 5),
+}
+
+
+@pytest.mark.parametrize("mode", ["parallel", "serial"])
+@pytest.mark.parametrize("name", list(SPLIT_SHAPES))
+def test_split_k_pick_is_near_the_fastest_built_variant(name, mode):
+    # with split-K asked for and no tile named, the choice follows a model of its own (operand copy traffic, the
+    # workgroups' copy chains, the partial tiles' trip through memory): within 15 % of the best tile, slices left to the library
+    make, op_mode, la = SPLIT_SHAPES[name]
+    w = DeviceWorkload(make(), poison=False)
+    ws = torch.empty(128 << 20, dtype=torch.uint8, device="cuda")
+    ucl.ucl_workspace_init(ws.data_ptr(), ws.numel(), torch.cuda.current_stream().cuda_stream)
+    tune = lambda *tile: Tuning(*tile, split_k=mode, workspace=ws.data_ptr(), workspace_bytes=ws.numel())
+    for _ in range(100):
+        w.run(tune=tune())
+    torch.cuda.synchronize()
+    times = {tile: time_us(w, tune(*tile)) for tile in (built(op_mode, la=la, lb=4) if op_mode == 4 else built(0))}
+    t_pick = time_us(w, tune())
+    best = min(times, key=times.get)
+    assert t_pick <= 1.15 * times[best], (f"{name} ({mode}): the library's choice runs {t_pick:.1f} us, {best} runs {times[best]:.1f} us; all: " +
+                                          ", ".join(f"{k}: {v:.1f}" for k, v in sorted(times.items(), key=lambda kv: kv[1])))
