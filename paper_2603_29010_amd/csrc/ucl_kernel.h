@@ -1093,8 +1093,6 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
         // k a byte stands for is the same for A and B, and every k of the row is held exactly once).
         // It does four times the work of the 32-deep form in twice the time, so the k-tile costs what a
         // 16-bit k-tile of the same bytes costs and carries twice the FLOPs.
-        // Plain double buffering: k-tile kt is multiplied out of one buffer while k-tile kt+1 is in
-        // flight into the other; when every wave is done with the buffer it is refilled with kt+2.
         static_assert(KSTEPS == 2 && LA == kKContig && LB == kKContig, "128-byte rows of K-contiguous operands");
         u32x8_t b8[NI];
         issue_tile(std::true_type{}, 0, 0);
@@ -1104,20 +1102,50 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
             const u32x4_t lo = frag(sbase, base, blk, 0), hi = frag(sbase, base, blk, 1);
             return u32x8_t{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
         };
+        // The k-tile's MFMAs run in two halves with the barrier between them, as the k-steps of the 16-bit loop
+        // below do.  First half: row blocks 0 .. MI/2-1 (their A fragments and all of B were read during the previous
+        // k-tile); beside its MFMAs the A fragments of the other row blocks are read.  Barrier: this wave has every
+        // fragment of the k-tile, k-tile kt+1 has landed (vmcnt 0), every wave is past its reads.  Second half, column
+        // block by column block: beside its MFMAs the k-tile's own buffer is refilled with k-tile kt+2 and the
+        // fragments of k-tile kt+1 are read -- B into the registers of the column block just finished, A of the
+        // first row blocks into the registers the first half has released.  One set of B fragments and two half
+        // sets of A (16 fragments of 32 bytes) are all the registers it takes, and LDS reads, copies and MFMAs are
+        // spread evenly.  (Reading a k-tile's fragments in one burst at its head and refilling the buffer behind
+        // its MFMAs took 1.7 us per k-tile for 0.85 us of MFMAs.)
+        static_assert(MI % 2 == 0 && NI >= 2, "two halves of row blocks");
+        constexpr int MH = MI / 2;
+        u32x8_t a_lo[MH], a_hi[MH];
+        pipeline_barrier<DMA_PER_TILE>();                          // k-tile 0 has landed
+        static_for<MH>([&](auto mi) { a_lo[mi] = pair(smem, a_frag_base, mi); });
+        static_for<NI>([&](auto ni) { b8[ni] = pair(smem, b_frag_base, ni); });
         for (int kt = 0; kt < KT; ++kt) {
             const int cur = kt & 1;
-            const char *sc = smem + cur * Cfg::STAGE_BYTES;
-            pipeline_barrier<DMA_PER_TILE>();                      // k-tile kt has landed (kt+1 may be in flight)
-            u32x8_t a_cur = pair(sc, a_frag_base, I0{}), a_nxt = a_cur;
-            static_for<NI>([&](auto ni) { b8[ni] = pair(sc, b_frag_base, ni); });
-            static_for<MI>([&](auto mi_) {
+            const char *sc = smem + cur * Cfg::STAGE_BYTES, *sn = smem + (cur ^ 1) * Cfg::STAGE_BYTES;
+            static_for<MH>([&](auto mi_) {
                 constexpr int mi = decltype(mi_)::value;
-                if constexpr (mi + 1 < MI) a_nxt = pair(sc, a_frag_base, std::integral_constant<int, mi + 1>{});
-                static_for<NI>([&](auto ni) { mfma128<Cfg::DT>(acc[mi][ni], b8[ni], a_cur); });
-                a_cur = a_nxt;
+                static_for<NI>([&](auto ni_) {
+                    constexpr int ni = decltype(ni_)::value;
+                    mfma128<Cfg::DT>(acc[mi][ni], b8[ni], a_lo[mi]);
+                    if constexpr (ni == NI / 2) a_hi[mi] = pair(sc, a_frag_base, std::integral_constant<int, MH + mi>{});
+                });
             });
-            pipeline_barrier<DMA_PER_TILE>();                      // every wave has read the buffer: refill it
-            issue_tile(std::true_type{}, kt + 2, cur);
+            pipeline_barrier<0>();
+            static_for<NI>([&](auto ni_) {
+                constexpr int ni = decltype(ni_)::value;
+                constexpr int d0 = ni * DMA_PER_TILE / NI, nd = (ni + 1) * DMA_PER_TILE / NI - d0;
+                static_for<MH>([&](auto mi_) {
+                    constexpr int mi = decltype(mi_)::value;
+                    mfma128<Cfg::DT>(acc[MH + mi][ni], b8[ni], a_hi[mi]);
+                    // copies of k-tile kt+2 into this k-tile's buffer, their even share per column block
+                    static_for<(mi + 1) * nd / MH - mi * nd / MH>([&](auto j) {
+                        issue_one(std::true_type{}, std::integral_constant<int, d0 + mi * nd / MH + decltype(j)::value>{}, kt + 2, cur);
+                    });
+                    // fragments of k-tile kt+1: B of the column block finished before this one, A of row block ni
+                    if constexpr (mi == 1 % MH && ni >= 1) b8[ni - 1] = pair(sn, b_frag_base, std::integral_constant<int, ni - 1>{});
+                    if constexpr (mi == MH - 1 && ni < MH) a_lo[ni] = pair(sn, a_frag_base, ni_);
+                });
+            });
+            b8[NI - 1] = pair(sn, b_frag_base, std::integral_constant<int, NI - 1>{});
         }
     } else if constexpr (STAGES == 2) {
         // ---- two stage buffers, k-tiles of two k-steps --------------------------------------------
