@@ -46,6 +46,16 @@ def test_fp8_gemm_parity_with_epilogue(dt, dt_out):
     parity.check(spec, None, label=f"fp8 {dt} every code", mandated=False)
 
 
+@pytest.mark.parametrize("dt", ["e4m3", "e5m2"])
+def test_fp8_benchmark_size_every_row_tile(dt):
+    # the 4096^3 row of the benchmark's widening table, in the launch configuration it times (the table's choice):
+    # every output element must have been written, and two rows of every 128-row wave tile are compared with the oracle
+    spec = synth.gemm_spec(4096, 4096, 4096, dt_in=dt, dt_out="bf16", scale=1.0 / 64, epilogue=("bias", "gelu_tanh"))
+    rng = np.random.default_rng(11)
+    rows = sorted(int(b * 128 + r) for b in range(32) for r in rng.choice(128, 2, replace=False))
+    parity.check(spec, None, rows=rows, label=f"fp8 {dt} 4096^3")
+
+
 def test_fp8_batched_and_split_k():
     ws = torch.empty(32 << 20, dtype=torch.uint8, device="cuda")
     ucl.ucl_workspace_init(ws.data_ptr(), ws.numel(), torch.cuda.current_stream().cuda_stream)
