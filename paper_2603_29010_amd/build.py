@@ -50,6 +50,15 @@ def _check_asm(obj):
                 raise RuntimeError(f"kernel {name} uses {scratch} bytes of scratch memory")
         if re.search(r"s_swappc_b64", text):
             raise RuntimeError(f"{asm}: a kernel calls a function (a loop body was not inlined)")
+        # A buffer resource that the register allocator moved into vector registers (the tile kernels sit at their
+        # scalar-register budget) makes every global -> LDS copy a readfirstlane loop: 14 % slower when it happened.
+        lines = text.split("\n")
+        for k, line in enumerate(lines):
+            if "buffer_load_dword" in line and line.rstrip().endswith(" lds") and \
+                    any("v_readfirstlane_b32" in x for x in lines[max(0, k - 10):k]) and \
+                    any("s_cbranch_execnz" in x for x in lines[k + 1:k + 6]):
+                raise RuntimeError(f"{asm}: line {k + 1}: a global -> LDS copy sits in a readfirstlane loop "
+                                   "(its buffer resource is held in vector registers)")
 
 
 def build(force=False, jobs=None, verbose=False):

@@ -437,6 +437,13 @@ __device__ __forceinline__ void mfma128(f32x4_t &c, const u32x8_t &a, const u32x
     else asm volatile("v_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, %0 cbsz:1 blgp:1" : "+a"(c) : "v"(a), "v"(b));
 }
 
+// A pointer that is the same in every lane, moved into scalar registers.
+__device__ __forceinline__ const char *uniform_ptr(const char *q) {
+    const uint64_t v = (uint64_t)(uintptr_t)q;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return (const char *)(uintptr_t)(((uint64_t)hi << 32) | lo);
+}
+
 // Forces the accumulator to hold its value in an accumulation register at this point of the program.
 __device__ __forceinline__ void pin_acc(f32x4_t &c) { asm volatile("" : "+a"(c)); }
 
@@ -510,9 +517,13 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
         t -= gt.tile_start[group];
         Mloc = gt.m[group];
         band_raster(t, (Mloc + TM - 1) / TM, p.tiles_n, p.raster, tm, tn);
-        Ab = (const char *)p.A_g[group];
-        Bb = (const char *)p.B_g[group];
-        Db = (char *)p.D_g[group];
+        // The per-group pointers come out of device memory.  Where the compiler may not use a scalar load for them
+        // (persistent kernels: the table is read again after the previous tile's stores) they arrive in vector
+        // registers, and a buffer resource built on such a pointer makes every global -> LDS copy a readfirstlane
+        // loop.  They are the same in every lane: say so.
+        Ab = uniform_ptr((const char *)p.A_g[group]);
+        Bb = uniform_ptr((const char *)p.B_g[group]);
+        Db = (char *)uniform_ptr((const char *)p.D_g[group]);
     } else {
         batch = t / p.tiles_per_batch;
         t -= batch * p.tiles_per_batch;
