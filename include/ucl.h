@@ -349,7 +349,9 @@ ucl_status ucl_sol_bound(const ucl_problem *p, const ucl_hw *hw, ucl_sol_report 
 
 /* The tuning the selection table would pick for a problem: the launch path with
  * tune == NULL applies the same function to the same description (packed
- * operands assumed: leading strides equal to the contiguous extents). */
+ * operands assumed: leading strides equal to the contiguous extents).  A launch
+ * that asks for split-K without naming a tile chooses its tile for the split
+ * launch instead; ucl_workspace_size() follows that choice. */
 ucl_status ucl_select_tuning(const ucl_problem *p, ucl_tuning *out);
 
 /* Bytes of workspace a call on problem p with tuning `tune` needs (0 without a split):
