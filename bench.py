@@ -315,7 +315,7 @@ PEAK_FP8_TFLOPS = 5033.2
 
 
 def bench_widening(args):
-    """The rows beyond the five headline workloads (not part of the headline metric): fp8 GEMM, the two
+    """The rows beyond the five headline workloads (not part of the headline metric): fp8 GEMM and grouped GEMM, the two
     convolution gradients, a deep-K split-K GEMM and the persistent tile scheduler, each timed like the workloads above and set against
     its own roofline (ucl_sol_bound with the peak of its input type)."""
     import torch
@@ -332,6 +332,9 @@ def bench_widening(args):
          lambda: synth.gemm_spec(4096, 4096, 4096, dt_in="e4m3", dt_out="bf16", scale=1.0 / 64, epilogue=("bias", "gelu_tanh")), None),
         ("gemm_4096x4096x4096_fp8_e5m2_rowcol_bias_gelu_tanh_bf16out",
          lambda: synth.gemm_spec(4096, 4096, 4096, dt_in="e5m2", dt_out="bf16", scale=1.0 / 64, epilogue=("bias", "gelu_tanh")), None),
+        ("grouped_gemm_16groups_n4096_k1024_fp8_e4m3_silu_bf16out",
+         lambda: synth.grouped_spec(synth.grouped_sizes(16, synth.BASE_SEED + 4), 4096, 1024, dt_in="e4m3", scale=1.0 / 32,
+                                    seed=synth.BASE_SEED + 4), None),
         ("conv2d_dgrad_nhwc_32x56x56x64_from_128_3x3_bf16", lambda: synth.conv_grad_spec("dgrad", **conv), None),
         ("conv2d_wgrad_nhwc_32x56x56x64_to_128_3x3_bf16_f32out_splitk_parallel",
          lambda: synth.conv_grad_spec("wgrad", dt_out="f32", **conv), split("parallel")),

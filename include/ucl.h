@@ -21,9 +21,10 @@
  *     puts a small fill kernel in front).
  *   - Strides are in ELEMENTS.  Inputs are UCL_BF16 or UCL_F16 (both operands
  *     the same type), accumulation is fp32, outputs are UCL_BF16, UCL_F16 or
- *     UCL_F32.  ucl_gemm and ucl_batched_gemm also take UCL_FP8_E4M3 or
- *     UCL_FP8_E5M2 inputs (both operands the same type, both contiguous
- *     along K; K, the leading strides and the batch strides multiples of 16).
+ *     UCL_F32.  ucl_gemm, ucl_batched_gemm and ucl_grouped_gemm also take
+ *     UCL_FP8_E4M3 or UCL_FP8_E5M2 inputs (both operands the same type, both
+ *     contiguous along K; K, the leading strides and the batch strides
+ *     multiples of 16).
  *   - Alignment (the paper's rule (alignment * element_size) % 16 == 0,
  *     grammar notes, constraint 3): A and B base pointers are 16-byte aligned,
  *     one of their two strides is 1 and the other a multiple of 8, and K (for

@@ -37,7 +37,7 @@ ucl_status fail(ucl_status st, const char *fmt, ...) {
 const std::vector<VariantDesc> &all_variants() {
     static const std::vector<VariantDesc> v = [] {
         std::vector<VariantDesc> out;
-        for (VariantList l : {variants_gemm_kk_bf16_a(), variants_gemm_kk_bf16_b(), variants_gemm_kk_bf16_c(), variants_gemm_kk_bf16_d(), variants_gemm_kk_f16_a(), variants_gemm_kk_f16_b(), variants_gemm_mn_bf16(), variants_gemm_mn_f16(), variants_grouped_a(), variants_grouped_b(), variants_conv_a(), variants_conv_b(), variants_conv_f16(), variants_conv_halo(), variants_gemm_kn_bf16(), variants_gemm_kn_f16(), variants_gemm_mx_bf16(), variants_gemm_mx_f16(), variants_grouped_kn(), variants_conv_dgrad(), variants_conv_wgrad(), variants_gemm_kk_fp8(), variants_persistent()})
+        for (VariantList l : {variants_gemm_kk_bf16_a(), variants_gemm_kk_bf16_b(), variants_gemm_kk_bf16_c(), variants_gemm_kk_bf16_d(), variants_gemm_kk_f16_a(), variants_gemm_kk_f16_b(), variants_gemm_mn_bf16(), variants_gemm_mn_f16(), variants_grouped_a(), variants_grouped_b(), variants_conv_a(), variants_conv_b(), variants_conv_f16(), variants_conv_halo(), variants_gemm_kn_bf16(), variants_gemm_kn_f16(), variants_gemm_mx_bf16(), variants_gemm_mx_f16(), variants_grouped_kn(), variants_conv_dgrad(), variants_conv_wgrad(), variants_gemm_kk_fp8(), variants_persistent(), variants_grouped_fp8_e4m3(), variants_grouped_fp8_e5m2()})
             for (int i = 0; i < l.n; ++i) out.push_back(l.v[i]);
         return out;
     }();
@@ -348,7 +348,7 @@ ucl_status check_common(int64_t M, int64_t N, int64_t K, int dtA, int dtB, int d
         return fail(UCL_ERR_UNSUPPORTED, "extents must be below 2^31");
     if (!A || !B || !D) return fail(UCL_ERR_INVALID_ARG, "A, B and D must be non-NULL device pointers");
     if (is8(dtA) && dtA == dtB && !fp8_ok)
-        return fail(UCL_ERR_UNSUPPORTED, "fp8 inputs are built for gemm and batched_gemm");
+        return fail(UCL_ERR_UNSUPPORTED, "fp8 inputs are built for gemm, batched_gemm and grouped_gemm");
     if (!(is16(dtA) || is8(dtA)) || dtA != dtB)
         return fail(UCL_ERR_UNSUPPORTED, "inputs must both be bf16, both fp16 or both the same fp8 type (got %s, %s); accumulation is fp32", dtype_name(dtA), dtype_name(dtB));
     if (!valid_dtype(dtD)) return fail(UCL_ERR_INVALID_ARG, "bad output dtype %d", dtD);
@@ -681,8 +681,8 @@ ucl_status launch_from_problem(const ucl_problem *p, Launch &L) {
     int64_t M = 0, N = 0;
     if (ucl_status st = characterise(p, &f, &b, &M, &N)) return st;
     if (!is16(p->dt_in) && !is8(p->dt_in)) return fail(UCL_ERR_UNSUPPORTED, "kernels take bf16, fp16 or fp8 inputs");
-    if (is8(p->dt_in) && (p->op > UCL_OP_BATCHED_GEMM || p->a_layout != UCL_LAYOUT_K_CONTIGUOUS || p->b_layout != UCL_LAYOUT_K_CONTIGUOUS || p->K % 16))
-        return fail(UCL_ERR_UNSUPPORTED, "fp8 inputs are built for gemm and batched_gemm with both operands contiguous along K, K a multiple of 16");
+    if (is8(p->dt_in) && (p->op > UCL_OP_GROUPED_GEMM || p->a_layout != UCL_LAYOUT_K_CONTIGUOUS || p->b_layout != UCL_LAYOUT_K_CONTIGUOUS || p->K % 16))
+        return fail(UCL_ERR_UNSUPPORTED, "fp8 inputs are built for gemm, batched_gemm and grouped_gemm with both operands contiguous along K, K a multiple of 16");
     L.mode = p->op == UCL_OP_GROUPED_GEMM ? 1 : p->op == UCL_OP_CONV2D_FPROP ? 2 : p->op == UCL_OP_CONV2D_DGRAD ? 3
              : p->op == UCL_OP_CONV2D_WGRAD ? 4 : 0;
     L.batch = p->op == UCL_OP_BATCHED_GEMM ? p->batch : 1;
@@ -780,11 +780,20 @@ ucl_status ucl_grouped_gemm(int32_t groups, const int64_t *M_g, int64_t N, int64
         L.sum_Mg += M_g[g];
         if (M_g[g] > L.max_Mg) L.max_Mg = M_g[g];
     }
-    if (ucl_status st = check_common(1, N, K, dtA, dtB, dtD, A_g, B_g, D_g)) return st;
+    if (ucl_status st = check_common(1, N, K, dtA, dtB, dtD, A_g, B_g, D_g, /*fp8_ok=*/true)) return st;
     if (a_cs != 1 || (b_rs != 1 && b_cs != 1))
         return fail(UCL_ERR_UNSUPPORTED, "grouped_gemm is built for A row-major (a_cs == 1) and B column-major (b_rs == 1) or row-major (b_cs == 1)");
     const bool b_row = b_rs != 1;             // B[k*b_rs + n]: contiguous along N
-    const int64_t ldb = b_row ? b_rs : b_cs;
+    int64_t ldb = b_row ? b_rs : b_cs;
+    if (is8(dtA)) {
+        // 8-bit inputs are handled as pairs of elements (see gemm_like): K and the leading strides count 16-bit units below
+        if (b_row) return fail(UCL_ERR_UNSUPPORTED, "fp8 inputs must both be contiguous along K (A row-major, B column-major)");
+        if (K % 16 || a_rs % 16 || ldb % 16)
+            return fail(UCL_ERR_UNSUPPORTED, "fp8 inputs: K=%lld and the leading strides (%lld, %lld) must be multiples of 16 (alignment 16 x 1 byte = 16)",
+                        (long long)K, (long long)a_rs, (long long)ldb);
+        K /= 2; a_rs /= 2; ldb /= 2;
+        L.K = K;
+    }
     if (K % 8 || a_rs % 8 || ldb % 8 || a_rs < K || ldb < (b_row ? N : K))
         return fail(UCL_ERR_UNSUPPORTED, "K=%lld and the leading strides (%lld, %lld) must be multiples of 8 and at least the contiguous extent", (long long)K, (long long)a_rs, (long long)ldb);
     if (b_row) {

@@ -43,6 +43,8 @@ VariantList variants_gemm_mx_bf16();
 VariantList variants_gemm_mx_f16();
 VariantList variants_grouped_kn();
 VariantList variants_persistent();
+VariantList variants_grouped_fp8_e4m3();
+VariantList variants_grouped_fp8_e5m2();
 VariantList variants_gemm_kk_fp8();
 VariantList variants_conv_dgrad();
 VariantList variants_conv_wgrad();

@@ -9,6 +9,7 @@ import torch
 import paper_2603_29010_amd as ucl
 from paper_2603_29010_amd import synth
 from paper_2603_29010_amd.binding import Tuning
+from paper_2603_29010_amd.workload import DeviceWorkload
 
 import parity
 from test_gpu_parity import T, built
@@ -54,6 +55,33 @@ def test_fp8_benchmark_size_every_row_tile(dt):
     rng = np.random.default_rng(11)
     rows = sorted(int(b * 128 + r) for b in range(32) for r in rng.choice(128, 2, replace=False))
     parity.check(spec, None, rows=rows, label=f"fp8 {dt} 4096^3")
+
+
+@pytest.mark.parametrize("dt", ["e4m3", "e5m2"])
+def test_fp8_grouped_exact_and_parity(dt):
+    # per-group pointer tables with one-byte elements: empty groups, ragged groups, K tail (K = 208 = 3 * 64 + 16)
+    M_g = [0, 264, 64, 1, 0, 712, 130]
+    spec = synth.grouped_spec(M_g, 264, 208, dt_in=dt, dt_out="f32", epilogue=(), integer=True)
+    tiles = built(1, dt=dt)
+    assert len(tiles) >= 3
+    for tile in tiles:
+        parity.check_exact(spec, T(*tile), label=f"fp8 grouped {dt} {tile}")
+    parity.check_exact(spec, None, label=f"fp8 grouped {dt} table choice")
+    # floating point, per-group bias and residual through the pointer tables, bf16 output
+    spec = synth.grouped_spec([300, 0, 520, 77], 392, 528, dt_in=dt, dt_out="bf16", epilogue=("bias", "aux_load", "silu"))
+    for tile in tiles:
+        parity.check(spec, T(*tile), label=f"fp8 grouped {dt} bias+residual+silu {tile}")
+
+
+def test_fp8_grouped_rejects_row_major_b_and_odd_k():
+    w = DeviceWorkload(synth.grouped_spec([64, 64], 64, 72, dt_in="e4m3", dt_out="f32", epilogue=(), integer=True))
+    with pytest.raises(ucl.UclError) as e:
+        w.run()                                               # K = 72 is not a multiple of 16
+    assert e.value.status == "UCL_ERR_UNSUPPORTED"
+    w = DeviceWorkload(synth.grouped_spec([64, 64], 64, 64, dt_in="e4m3", dt_out="f32", epilogue=(), integer=True, b_layout="row"))
+    with pytest.raises(ucl.UclError) as e:
+        w.run()
+    assert e.value.status == "UCL_ERR_UNSUPPORTED" and "contiguous along K" in e.value.message
 
 
 def test_fp8_batched_and_split_k():

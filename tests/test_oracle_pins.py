@@ -117,6 +117,17 @@ def test_batched_gemm_with_fp8_inputs_advances_by_one_byte_elements():
     np.testing.assert_allclose(D, np.einsum("bmk,bnk->bmn", val(A, "e5m2"), val(B, "e5m2")), atol=1e-12)
 
 
+def test_grouped_gemm_with_fp8_inputs_matches_numpy_per_group():
+    rng = np.random.default_rng(8)
+    M_g, N, K = [4, 0, 7], 5, 32
+    for dt in ("e4m3", "e5m2"):
+        A = [synth.to_bits(rng.standard_normal((m, K)), dt) for m in M_g]
+        B = [synth.to_bits(rng.standard_normal((N, K)), dt) for _ in M_g]
+        D = oracle.grouped_gemm(A, dt, (K, 1), B, dt, (1, K), M_g, N, K)
+        ref = np.concatenate([val(a, dt) @ val(b, dt).T for a, b in zip(A, B)])
+        np.testing.assert_allclose(D, ref, atol=1e-12)
+
+
 def test_rounding_ties_and_double_rounding():
     r = oracle.round_to
     # bf16 has 8 significant bits: spacing 2^-7 in [1,2)
