@@ -134,3 +134,36 @@ def test_paper_example_program_runs_and_matches_the_oracle():
     ref, absacc = parity.oracle_result(spec)
     parity.compare(w.result(), ref, absacc, spec, "paper example through the translator")
     assert w.result().max() <= 6.0 and w.result().min() >= 0.0
+
+
+@pytest.mark.gpu
+def test_scheduler_split_k_and_fp8_programs_run_through_the_translator():
+    import torch
+    import parity
+    import paper_2603_29010_amd as ucl
+    from paper_2603_29010_amd.workload import DeviceWorkload
+    st = torch.cuda.current_stream().cuda_stream
+    # the persistent tile scheduler, tile named in the program
+    k = dsl.parse("""gemm().with_dtype(input=bf16, acc=fp32, output=fp32).with_layout(A=RowMajor, B=ColumnMajor, C=RowMajor)
+        .with_tile(m=128, n=128, k=32).with_stages(4).with_scheduler(tile=persistent)""")
+    spec = synth.gemm_spec(1100, 1300, 136, dt_out="f32", epilogue=(), integer=True)
+    w = DeviceWorkload(spec)
+    k.launch(M=1100, N=1300, K=136, A=w.A.data_ptr(), B=w.B.data_ptr(), D=w.D.data_ptr(), stream=st)
+    assert np.array_equal(w.result(), parity.orc_run.run(spec))
+    # split-K in parallel mode with a caller workspace: more than two slices, i.e. the reduction kernel between the launches
+    k = dsl.parse("""gemm().with_dtype(input=bf16, acc=fp32, output=fp32).with_layout(A=RowMajor, B=ColumnMajor, C=RowMajor)
+        .with_split_k(mode=parallel, slices=6)""")
+    spec = synth.gemm_spec(200, 136, 1992, dt_out="f32", epilogue=(), integer=True)
+    w = DeviceWorkload(spec)
+    ws = torch.empty(16 << 20, dtype=torch.uint8, device="cuda")
+    ucl.ucl_workspace_init(ws.data_ptr(), ws.numel(), st)
+    k.launch(M=200, N=136, K=1992, A=w.A.data_ptr(), B=w.B.data_ptr(), D=w.D.data_ptr(), stream=st,
+             workspace=ws.data_ptr(), workspace_bytes=ws.numel())
+    assert np.array_equal(w.result(), parity.orc_run.run(spec))
+    # grouped GEMM on fp8 inputs
+    k = dsl.parse("""grouped_gemm(expert_count=4).with_dtype(input=fp8_e4m3, acc=fp32, output=fp32)
+        .with_layout(A=RowMajor, B=ColumnMajor, C=RowMajor)""")
+    spec = synth.grouped_spec([130, 0, 64, 300], 136, 208, dt_in="e4m3", dt_out="f32", epilogue=(), integer=True)
+    w = DeviceWorkload(spec)
+    k.launch(M_g=spec["M_g"], N=136, K=208, A=w.tabA.data_ptr(), B=w.tabB.data_ptr(), D=w.tabD.data_ptr(), stream=st)
+    assert np.array_equal(w.result(), parity.orc_run.run(spec))
