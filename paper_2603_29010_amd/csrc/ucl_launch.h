@@ -17,15 +17,18 @@ hipError_t launch_cfg(const KParams &p, const GroupTable *gt, int grid, hipStrea
 }
 
 // Workgroups of the variant that one CU holds at a time, as the runtime computes it from the registers and
-// LDS the compiled kernel uses (a host-side query: no device work, no allocation).
+// LDS the compiled kernel uses (a host-side query, asked once: no device work, no allocation).
 template <class Cfg>
 int resident_cfg() {
-    int n = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, ucl_tile_kernel<Cfg>, kThreads, 0) != hipSuccess || n < 1) {
-        (void)hipGetLastError();
-        n = 1;
-    }
-    return n;
+    static const int cached = [] {
+        int n = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, ucl_tile_kernel<Cfg>, kThreads, 0) != hipSuccess || n < 1) {
+            (void)hipGetLastError();
+            n = 1;
+        }
+        return n;
+    }();
+    return cached;
 }
 
 template <class Cfg>
