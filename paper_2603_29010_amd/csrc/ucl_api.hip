@@ -37,7 +37,7 @@ ucl_status fail(ucl_status st, const char *fmt, ...) {
 const std::vector<VariantDesc> &all_variants() {
     static const std::vector<VariantDesc> v = [] {
         std::vector<VariantDesc> out;
-        for (VariantList l : {variants_gemm_kk_bf16_a(), variants_gemm_kk_bf16_b(), variants_gemm_kk_bf16_c(), variants_gemm_kk_bf16_d(), variants_gemm_kk_f16_a(), variants_gemm_kk_f16_b(), variants_gemm_mn_bf16(), variants_gemm_mn_f16(), variants_grouped_a(), variants_grouped_b(), variants_conv_a(), variants_conv_b(), variants_conv_f16(), variants_conv_halo(), variants_gemm_kn_bf16(), variants_gemm_kn_f16(), variants_gemm_mx_bf16(), variants_gemm_mx_f16(), variants_grouped_kn(), variants_conv_dgrad(), variants_conv_wgrad(), variants_gemm_kk_fp8(), variants_persistent(), variants_grouped_fp8_e4m3(), variants_grouped_fp8_e5m2()})
+        for (VariantList l : {variants_gemm_kk_bf16_a(), variants_gemm_kk_bf16_b(), variants_gemm_kk_bf16_c(), variants_gemm_kk_bf16_d(), variants_gemm_kk_f16_a(), variants_gemm_kk_f16_b(), variants_gemm_mn_bf16(), variants_gemm_mn_f16(), variants_grouped_a(), variants_grouped_b(), variants_conv_a(), variants_conv_b(), variants_conv_f16(), variants_conv_halo(), variants_gemm_kn_bf16(), variants_gemm_kn_f16(), variants_gemm_mx_bf16(), variants_gemm_mx_f16(), variants_grouped_kn(), variants_conv_dgrad(), variants_conv_wgrad(), variants_gemm_kk_fp8(), variants_persistent(), variants_grouped_fp8_e4m3(), variants_grouped_fp8_e5m2(), variants_streamk()})
             for (int i = 0; i < l.n; ++i) out.push_back(l.v[i]);
         return out;
     }();
@@ -211,7 +211,7 @@ const VariantDesc *select_variant(const Launch &L, const ucl_tuning *tune) {
     const bool explicit_tune = tune && (tune->tile_m || tune->tile_n || tune->tile_k || tune->stages);
     const VariantDesc *best = nullptr;
     double best_t = 0;
-    const int want_persistent = tune && tune->scheduler == UCL_SCHED_PERSISTENT ? 1 : 0;
+    const int want_persistent = !tune ? 0 : tune->scheduler == UCL_SCHED_PERSISTENT ? 1 : tune->scheduler == UCL_SCHED_STREAM_K ? 2 : 0;
     for (const auto &v : vs) {
         if (v.mode != L.mode || v.dt != L.dt || v.persistent != want_persistent) continue;
         if (v.lb == 4 ? !(L.lb == 1 && L.ndirect_ok) : v.lb != L.lb) continue;
@@ -391,6 +391,8 @@ struct SplitPlan {
     int slices = 1;
     int k_per_slice = 0;
     int64_t bytes = 0;
+    // stream-K: 64-wide k steps per tile, iterations per workgroup, workgroups (0: not a stream-K launch)
+    int sk_ipt = 0, sk_q = 0, sk_grid = 0;
 };
 
 ucl_status plan_split(const Launch &L, const VariantDesc &v, const ucl_tuning *tune, int64_t total_tiles, SplitPlan &sp) {
@@ -398,8 +400,27 @@ ucl_status plan_split(const Launch &L, const VariantDesc &v, const ucl_tuning *t
     if (!tune) return UCL_OK;
     if (tune->scheduler < UCL_SCHED_DEFAULT || tune->scheduler > UCL_SCHED_STREAM_K)
         return fail(UCL_ERR_INVALID_ARG, "scheduler=%d is not a ucl_tile_scheduler", tune->scheduler);
-    if (tune->scheduler == UCL_SCHED_STREAM_K)
-        return fail(UCL_ERR_UNSUPPORTED, "the stream_k tile scheduler is not built; split-K (fixed slices of K) is");
+    if (tune->scheduler == UCL_SCHED_STREAM_K) {
+        // every workgroup of a resident grid takes an equal run of (tile, 64-wide k range) iterations; a workgroup
+        // leaves at most two parts of tiles in the workspace (two slots per workgroup behind the counters)
+        if (tune->split_k_mode != UCL_SPLIT_K_NONE)
+            return fail(UCL_ERR_UNSUPPORTED, "split-K and the stream_k scheduler cannot be combined");
+        if (total_tiles > UCL_SPLIT_K_MAX_TILES)
+            return fail(UCL_ERR_UNSUPPORTED, "the stream_k scheduler serves at most %d output tiles (this problem has %lld)", UCL_SPLIT_K_MAX_TILES, (long long)total_tiles);
+        const int64_t ipt = (L.K + 63) / 64, all = total_tiles * ipt;
+        if (all >= (1ll << 31)) return fail(UCL_ERR_UNSUPPORTED, "tiles x k steps exceeds 2^31");
+        if (all == 0) return UCL_OK;
+        int64_t grid = (int64_t)kNumCUs * v.resident();
+        if (grid > all) grid = all;
+        const int64_t q = (all + grid - 1) / grid;
+        sp.sk_ipt = (int)ipt;
+        sp.sk_q = (int)q;
+        sp.sk_grid = (int)((all + q - 1) / q);
+        sp.slices = (int)((ipt + q - 2) / q + 1);            // parts a tile can fall into, at most
+        if (sp.slices > ipt) sp.slices = (int)ipt;
+        sp.bytes = UCL_WORKSPACE_COUNTER_BYTES + (int64_t)sp.sk_grid * 2 * v.tile_m * v.tile_n * 4;
+        return UCL_OK;
+    }
     if (tune->split_k_mode < UCL_SPLIT_K_NONE || tune->split_k_mode > UCL_SPLIT_K_PARALLEL)
         return fail(UCL_ERR_INVALID_ARG, "split_k_mode=%d is not a ucl_split_k_mode", tune->split_k_mode);
     if (tune->split_k_slices < 0) return fail(UCL_ERR_INVALID_ARG, "split_k_slices=%d must be >= 0", tune->split_k_slices);
@@ -443,6 +464,8 @@ ucl_status run(const Launch &L, KParams &kp, const ucl_tuning *tune, void *strea
         }
         if (tune && tune->scheduler == UCL_SCHED_PERSISTENT)
             return fail(UCL_ERR_UNSUPPORTED, "no kernel with the persistent tile scheduler is built for this combination of operation, input type and layouts");
+        if (tune && tune->scheduler == UCL_SCHED_STREAM_K)
+            return fail(UCL_ERR_UNSUPPORTED, "no kernel with the stream_k tile scheduler is built for this combination of operation, input type and layouts (gemm / batched_gemm, 16-bit inputs contiguous along K)");
         return fail(UCL_ERR_UNSUPPORTED, "no kernel built for this combination of operation, input type and layouts");
     }
     if (kp.ldd > kMaxWideLd) kp.d_vec = 0;
@@ -473,7 +496,18 @@ ucl_status run(const Launch &L, KParams &kp, const ucl_tuning *tune, void *strea
     if (total >= (1ll << 31)) return fail(UCL_ERR_UNSUPPORTED, "problem needs %lld tiles; the grid is limited to 2^31-1", (long long)total);
     SplitPlan sp;
     if (ucl_status st = plan_split(L, *v, tune, total, sp)) return st;
-    if (sp.slices > 1) {
+    if (sp.sk_grid > 0) {
+        if (!tune->workspace)
+            return fail(UCL_ERR_WORKSPACE, "the stream_k scheduler needs a workspace of %lld bytes (ucl_workspace_size); tune->workspace is NULL", (long long)sp.bytes);
+        if (!aligned16(tune->workspace)) return fail(UCL_ERR_WORKSPACE, "the workspace must be 16-byte aligned");
+        if (tune->workspace_bytes < sp.bytes)
+            return fail(UCL_ERR_WORKSPACE, "the stream_k scheduler with %d workgroups and tiles of %dx%d needs %lld bytes of workspace, got %lld",
+                        sp.sk_grid, v->tile_m, v->tile_n, (long long)sp.bytes, (long long)tune->workspace_bytes);
+        kp.sk_ipt = sp.sk_ipt;
+        kp.sk_q = sp.sk_q;
+        kp.ws_counters = (uint32_t *)tune->workspace;
+        kp.ws_partials = (float *)((char *)tune->workspace + UCL_WORKSPACE_COUNTER_BYTES);
+    } else if (sp.slices > 1) {
         if (!tune->workspace)
             return fail(UCL_ERR_WORKSPACE, "split-K with %d slices needs a workspace of %lld bytes (ucl_workspace_size); tune->workspace is NULL", sp.slices, (long long)sp.bytes);
         if (!aligned16(tune->workspace)) return fail(UCL_ERR_WORKSPACE, "the split-K workspace must be 16-byte aligned");
@@ -494,7 +528,15 @@ ucl_status run(const Launch &L, KParams &kp, const ucl_tuning *tune, void *strea
     if (total == 0) return UCL_OK;     // grouped with every M_g == 0: nothing to do
     const GroupTable *gtp = L.mode == 1 ? &gt : nullptr;
     hipError_t e;
-    if (sp.slices > 1 && tune->split_k_mode == UCL_SPLIT_K_PARALLEL) {
+    if (sp.sk_grid > 0) {
+        if (clear_counters) {
+            hipLaunchKernelGGL(zero_words_kernel, dim3(UCL_WORKSPACE_COUNTER_BYTES / 16 / 256), dim3(256), 0, (hipStream_t)stream,
+                               (uint32_t *)tune->workspace);
+            e = hipGetLastError();
+            if (e != hipSuccess) return fail(UCL_ERR_LAUNCH, "kernel launch failed: %s", hipGetErrorString(e));
+        }
+        e = v->launch(kp, gtp, sp.sk_grid, (hipStream_t)stream);
+    } else if (sp.slices > 1 && tune->split_k_mode == UCL_SPLIT_K_PARALLEL) {
         kp.split_phase = 1;
         e = v->launch(kp, gtp, (int)(total * sp.slices), (hipStream_t)stream);
         if (e == hipSuccess && sp.slices > kReduceInTileKernel) {
@@ -1038,7 +1080,7 @@ ucl_status ucl_variant(int32_t i, ucl_variant_info *out) {
     out->b_layout = (v.lb == 1 || v.lb == 4) ? UCL_LAYOUT_MN_CONTIGUOUS : UCL_LAYOUT_K_CONTIGUOUS;
     out->a_path = v.la; out->b_path = v.lb;
     out->lds_bytes = v.lds_bytes;
-    out->scheduler = v.persistent ? UCL_SCHED_PERSISTENT : UCL_SCHED_DEFAULT;
+    out->scheduler = v.persistent == 2 ? UCL_SCHED_STREAM_K : v.persistent ? UCL_SCHED_PERSISTENT : UCL_SCHED_DEFAULT;
     return UCL_OK;
 }
 

@@ -61,6 +61,7 @@ struct KParams {
     // phase 0 = one launch, the last workgroup to arrive at a tile adds up; 1 = write partial tiles only;
     // 2 = add up only
     int32_t split_k, k_per_slice, split_phase;
+    int32_t sk_ipt, sk_q;             // stream-K: 64-wide k steps per tile, iterations per workgroup
     float *ws_partials;
     uint32_t *ws_counters;
     EpiStepDev steps[UCL_MAX_EPI_STEPS];   // must stay addressable as offsetof(KParams, steps)

@@ -340,10 +340,14 @@ __device__ __forceinline__ void apply_step(float (&v)[8], const EpiStepDev &s, c
 // ------------------------------------------------------------------------------------------------
 
 template <int TM_, int TN_, int TK_, int STAGES_, int DT_ /*inputs: 0 bf16, 1 fp16, 2 fp8 e4m3, 3 fp8 e5m2*/, int MODE_ /*0 gemm+batched, 1 grouped, 2 conv fprop, 3 conv dgrad, 4 conv wgrad*/,
-          int LA_ /*OperandLayout of A*/, int LB_ /*OperandLayout of B*/, bool PERSIST_ = false /*persistent tile scheduler*/>
+          int LA_ /*OperandLayout of A*/, int LB_ /*OperandLayout of B*/, int SCHED_ = 0 /*tile scheduler: 0 default, 1 persistent, 2 stream-K*/>
 struct KernelCfg {
     static constexpr int TM = TM_, TN = TN_, TK = TK_, STAGES = STAGES_, MODE = MODE_, LA = LA_, LB = LB_;
-    static constexpr bool PERSIST = PERSIST_;
+    static constexpr int SCHED = SCHED_;
+    static constexpr bool PERSIST = SCHED_ != 0;          // the workgroup walks several tiles (or pieces of tiles)
+    static constexpr bool STREAMK = SCHED_ == 2;          // ... an equal run of (tile, 64-wide k range) iterations
+    static_assert(SCHED_ >= 0 && SCHED_ <= 2, "tile scheduler code");
+    static_assert(SCHED_ != 2 || (MODE_ == 0 && DT_ < 2), "stream-K: gemm / batched_gemm with 16-bit inputs");
     static constexpr int CPR = TK / 8;                            // 16-byte chunks per LDS row
     static constexpr int ROW_BYTES = TK * 2;
     static_assert(TK == 32 || TK == 64, "k-tile of 32 or 64 elements");
@@ -474,11 +478,23 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
     // the loop below runs once.  Persistent scheduler: the grid has one workgroup per CU slot (a
     // multiple of 8, so a workgroup stays on the tile run of its XCD) and walks the tile order with
     // a stride of the grid size.
-    for (int wg_id = blockIdx.x;;) {
+    // Stream-K scheduler: the (tile, 64-wide k range) pairs of the whole problem are numbered tile by tile and
+    // workgroup g (in XCD-run order) takes the sk_q of them from g * sk_q on: the end of a tile, whole tiles, the
+    // start of a tile.  The loop variable is then the iteration the workgroup stands at, and one pass of the loop
+    // body is one piece: a whole tile ends in the epilogue as usual; a part of a tile goes to the workspace, and
+    // the workgroup that delivers the last part of a tile adds the parts up in k order and runs the epilogue.
+    typedef const __attribute__((address_space(4))) KParams ConstKParams;
+    int wg_first = blockIdx.x, sk_end = 0;
+    if constexpr (Cfg::STREAMK) {
+        ConstKParams *p0 = (ConstKParams *)__builtin_amdgcn_kernarg_segment_ptr();
+        const int all = p0->total_tiles * p0->sk_ipt;
+        wg_first = xcd_remap(blockIdx.x, gridDim.x) * p0->sk_q;
+        sk_end = wg_first + p0->sk_q < all ? wg_first + p0->sk_q : all;
+    }
+    for (int wg_id = wg_first;;) {
     // The kernel arguments are read through a pointer into the argument segment (p_arg is the first
     // argument).  Persistent kernels make that pointer opaque once per tile: the compiler would
     // otherwise load every argument ahead of the loop and keep all of them in registers across it.
-    typedef const __attribute__((address_space(4))) KParams ConstKParams;
     ConstKParams *pp = (ConstKParams *)__builtin_amdgcn_kernarg_segment_ptr();
     if constexpr (Cfg::PERSIST) asm volatile("" : "+s"(pp));
     ConstKParams &p = *pp;
@@ -504,9 +520,14 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
         } else {
             t = xcd_remap(wg_id, p.total_tiles);
         }
+    } else if constexpr (Cfg::STREAMK) {
+        t = wg_id / p.sk_ipt;
     } else {
         t = xcd_remap(wg_id, p.total_tiles);
     }
+    // stream-K: the piece's range of 64-wide k steps within its tile
+    const int sk_k0 = Cfg::STREAMK ? wg_id - t * p.sk_ipt : 0;
+    const int sk_k1 = Cfg::STREAMK ? (sk_k0 + (sk_end - wg_id) < p.sk_ipt ? sk_k0 + (sk_end - wg_id) : p.sk_ipt) : 0;
     int batch = 0, group = -1, tm, tn;
     int Mloc = p.M;
     const char *Ab = (const char *)p.A;
@@ -544,6 +565,12 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
             Ab += (int64_t)kb * (LA == kKContig ? 1 : p.lda) * 2;
             Bb += (int64_t)kb * (LB == kKContig ? 1 : p.ldb) * 2;
         }
+    }
+    if constexpr (Cfg::STREAMK) {
+        const int kb = sk_k0 * 64;
+        k_len = (sk_k1 * 64 < p.K ? sk_k1 * 64 : p.K) - kb;
+        Ab += (int64_t)kb * (LA == kKContig ? 1 : p.lda) * 2;
+        Bb += (int64_t)kb * (LB == kKContig ? 1 : p.ldb) * 2;
     }
     const int K = k_len;
     const int Kr = K > 0 ? K : 1;                      // rows of k a directly copied operand's resource covers (K = 0: see above)
@@ -1543,6 +1570,69 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
         }
     }
 
+    // ---- stream-K: parts of a tile through the workspace -------------------------------------------
+    // Workgroup g keeps at most two parts: the one that starts inside a tile (slot 2g) and the one that ends
+    // inside a tile (slot 2g + 1).  Part s of a tile belongs to workgroup g_first + s, g_first owning the tile's
+    // first iteration; part 0 is that workgroup's second kind, every later part its owner's first kind.  The
+    // same device-coherent accesses, counter and fixed order of additions as split-K above.
+    if constexpr (Cfg::STREAMK) {
+        // (the piece is worked out again from the iteration index rather than kept in registers across the mainloop)
+        int it_again = wg_id;
+        asm volatile("" : "+s"(it_again));
+        const int tile_again = it_again / p.sk_ipt;
+        const int it0 = tile_again * p.sk_ipt;
+        const int k0_again = it_again - it0;
+        const int k1_again = k0_again + (sk_end - it_again) < p.sk_ipt ? k0_again + (sk_end - it_again) : p.sk_ipt;
+        if (k0_again != 0 || k1_again != p.sk_ipt) {
+            constexpr int64_t kTileElems = (int64_t)TM * TN;
+            constexpr int kCoherent = 17;
+            const int g_first = it0 / p.sk_q, n_parts = (it0 + p.sk_ipt - 1) / p.sk_q - g_first + 1;
+            auto part_rsrc = [&](int slot) __attribute__((always_inline)) {
+                return buffer_rsrc(p.ws_partials + (int64_t)slot * kTileElems, (uint32_t)(kTileElems * 4));
+            };
+            const rsrc_t mine = part_rsrc(2 * (wg_id / p.sk_q) + (k0_again != 0 ? 0 : 1));
+            static_for<MI>([&](auto mi) {
+                static_for<NI>([&](auto ni) {
+                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, acc[mi][ni]), mine,
+                                                           ((mi * NI + ni) * kThreads + tid) * 16, 0, kCoherent);
+                });
+            });
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+            __syncthreads();                               // (also: every wave is past its LDS reads and copies)
+            if (tid == 0) *(volatile int *)smem = (int)atomicAdd(&p.ws_counters[tile_again], 1u);
+            __syncthreads();
+            // (the same in every lane, and said so: a branch the compiler took for divergent would make the loop
+            // variable, and with it every address and buffer resource of the next piece, a vector value)
+            const int arrived = __builtin_amdgcn_readfirstlane(*(volatile int *)smem);
+            if (arrived != n_parts - 1) {
+                // not the last part: on to the workgroup's next piece
+                wg_id = it0 + k1_again;
+                if (wg_id >= sk_end) break;
+                __syncthreads();
+                continue;
+            }
+            if (tid == 0) atomicExch(&p.ws_counters[tile_again], 0u);
+            static_for<MI>([&](auto mi) {
+                static_for<NI>([&](auto ni) {
+                    acc[mi][ni] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                    pin_acc(acc[mi][ni]);
+                });
+            });
+            for (int s_ = 0; s_ < n_parts; ++s_) {
+                const rsrc_t rs = part_rsrc(2 * (g_first + s_) + (s_ == 0 ? 1 : 0));
+                static_for<MI>([&](auto mi) {
+                    static_for<NI>([&](auto ni) {
+                        const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(rs, ((mi * NI + ni) * kThreads + tid) * 16, 0, kCoherent);
+                        acc[mi][ni] += __builtin_bit_cast(f32x4_t, v);
+                        pin_acc(acc[mi][ni]);
+                    });
+                    asm volatile("" ::: "memory");
+                });
+            }
+        }
+    }
+
     // ---- epilogue ---------------------------------------------------------------------------------
     // The accumulators leave the MFMA layout (a lane holds 4 consecutive n of ONE row per quad)
     // through a wave-private LDS patch, one 32-row block at a time, and come back as 8 consecutive
@@ -2014,6 +2104,12 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
     }
     if constexpr (!Cfg::PERSIST) {
         break;
+    } else if constexpr (Cfg::STREAMK) {
+        // the piece ended at its tile's end or at the end of the workgroup's run
+        const int tile_end = (wg_id / p.sk_ipt + 1) * p.sk_ipt;
+        wg_id = tile_end;
+        if (wg_id >= sk_end) break;
+        __syncthreads();
     } else {
         wg_id += gridDim.x;
         if (wg_id >= p.total_tiles) break;

@@ -11,7 +11,8 @@ struct VariantDesc {
     int la, lb;         // 0: operand contiguous along K, 1: contiguous along M / N (register transpose); A only: 2 im2col gather,
                         // 3 resident patch; 4 (B) / 5 (A): contiguous along N / M, copied directly and read through the LDS transpose read
     int lds_bytes;
-    int persistent;     // 1: built for the persistent tile scheduler (grid = CU slots, workgroups loop over tiles)
+    int persistent;     // tile scheduler the kernel is built for: 0 one workgroup per tile, 1 persistent (grid = CU slots, workgroups
+                        // walk the tile order), 2 stream-K (grid = CU slots, workgroups take equal runs of (tile, k range) iterations)
     int wgs_per_cu;     // workgroups of the kernel a CU is meant to hold (register budget it was built with)
     hipError_t (*launch)(const KParams &p, const GroupTable *gt, int grid, hipStream_t stream);
     int (*resident)();          // workgroups one CU holds at a time (queried from the runtime)
@@ -43,6 +44,7 @@ VariantList variants_gemm_mx_bf16();
 VariantList variants_gemm_mx_f16();
 VariantList variants_grouped_kn();
 VariantList variants_persistent();
+VariantList variants_streamk();
 VariantList variants_grouped_fp8_e4m3();
 VariantList variants_grouped_fp8_e5m2();
 VariantList variants_gemm_kk_fp8();

@@ -173,8 +173,8 @@ def test_split_k_workspace_contract():
         w.run(tune=Tuning(64, 64, 32, 3, split_k="none", slices=4))
     assert e.value.status == "UCL_ERR_INVALID_ARG"
     with pytest.raises(ucl.UclError) as e:
-        w.run(tune=Tuning(scheduler="stream_k"))
-    assert e.value.status == "UCL_ERR_UNSUPPORTED"
+        w.run(tune=Tuning(scheduler="stream_k"))                # the stream-K scheduler needs a workspace as well
+    assert e.value.status == "UCL_ERR_WORKSPACE"
     g = DeviceWorkload(synth.grouped_spec([64, 64], 64, 256, dt_out="f32", epilogue=(), integer=True))
     with pytest.raises(ucl.UclError) as e:
         g.run(tune=split_tune((0, 0, 0, 0), "serial", 2))
