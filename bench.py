@@ -349,6 +349,9 @@ def bench_widening(args):
         # tile scheduler: the same 128x128x32x4 kernel, one workgroup per tile against one per CU slot
         ("gemm_8192x8192x64_bf16_bias_relu_tile128_default_scheduler",
          lambda: synth.gemm_spec(8192, 8192, 64, epilogue=("bias", "relu")), Tuning(128, 128, 32, 4)),
+        ("gemm_256x256x16384_bf16_bias_relu_tile64_stream_k_scheduler",
+         lambda: synth.gemm_spec(256, 256, 16384, dist="uniform", scale=0.05, epilogue=("bias", "relu")),
+         Tuning(64, 64, 64, 4, scheduler="stream_k", workspace=ws.data_ptr(), workspace_bytes=ws.numel())),
         ("gemm_8192x8192x64_bf16_bias_relu_tile128_persistent_scheduler",
          lambda: synth.gemm_spec(8192, 8192, 64, epilogue=("bias", "relu")), Tuning(128, 128, 32, 4, scheduler="persistent")),
     ]
@@ -368,7 +371,7 @@ def bench_widening(args):
                      "roofline": {"bound": "mfma" if mfma else "hbm", "achieved": ach, "peak": peak,
                                   "unit": "TFLOP/s" if mfma else "GB/s", "frac": ach / peak, "traffic": None},
                      "kernel": w.selected() if tune is None or tune.c.split_k_mode else
-                     dict(tune.as_dict(), scheduler="persistent" if tune.c.scheduler else "default"),
+                     dict(tune.as_dict(), scheduler=("default", "persistent", "stream_k")[tune.c.scheduler]),
                      "launch": launch, "sclk_mhz_under_load": sclk}
         if tune is not None and tune.c.split_k_mode:
             kw = w._problem_kwargs()

@@ -143,8 +143,15 @@ typedef enum ucl_split_k_mode { UCL_SPLIT_K_NONE = 0, UCL_SPLIT_K_SERIAL = 1, UC
  * CUs free up.  PERSISTENT: one workgroup per CU slot (a multiple of 8, so a workgroup stays on the
  * tile run of its XCD), each walking the tile order with a stride of the grid size; built for gemm,
  * batched_gemm and grouped_gemm with operands contiguous along K and tiles up to 128x128 (grouped:
- * 64x64; the larger tiles' kernels have no registers to spare for the loop; see ucl_variant()); other requests are rejected with
- * UCL_ERR_UNSUPPORTED.  STREAM_K is part of the knob's vocabulary but not built (rejected likewise). */
+ * 64x64; the larger tiles' kernels have no registers to spare for the loop; see ucl_variant()).
+ * STREAM_K: one workgroup per CU slot; as many whole rounds of tiles as the grid divides are walked
+ * as under PERSISTENT, and the K extent of the remaining tiles is cut into 64-wide steps that are
+ * dealt out evenly, so that a workgroup may compute parts of tiles.  Parts pass through the
+ * caller's workspace (as for split-K: ucl_workspace_size, ucl_workspace_init; two tile-sized slots
+ * per workgroup behind the counters) and are added in k order by the workgroup that delivers a
+ * tile's last part: results do not depend on timing.  Built for gemm and batched_gemm with 16-bit
+ * inputs contiguous along K, tiles 128x128 and 64x64; cannot be combined with split-K.  Requests
+ * outside what is built are rejected with UCL_ERR_UNSUPPORTED. */
 typedef enum ucl_tile_scheduler { UCL_SCHED_DEFAULT = 0, UCL_SCHED_PERSISTENT = 1, UCL_SCHED_STREAM_K = 2 } ucl_tile_scheduler;
 
 /* The first UCL_WORKSPACE_COUNTER_BYTES of a split-K workspace hold the per-tile counters. */
@@ -172,7 +179,7 @@ typedef enum ucl_tile_scheduler { UCL_SCHED_DEFAULT = 0, UCL_SCHED_PERSISTENT = 
  * the first UCL_WORKSPACE_COUNTER_BYTES to be zero when the call starts: clear them once with
  * ucl_workspace_init(); every call leaves them zero again.  Calls that share a workspace must not
  * overlap in time.  Without a split, workspace is ignored.
- * scheduler is a ucl_tile_scheduler. */
+ * scheduler is a ucl_tile_scheduler; STREAM_K uses the workspace in the same way (zeroed counters, left zero). */
 typedef struct ucl_tuning {
     int32_t tile_m, tile_n, tile_k, stages, raster;
     int32_t iterator;
@@ -357,7 +364,10 @@ ucl_status ucl_select_tuning(const ucl_problem *p, ucl_tuning *out);
 
 /* Bytes of workspace a call on problem p with tuning `tune` needs (0 without a split):
  * UCL_WORKSPACE_COUNTER_BYTES + slices x tiles x tile_m x tile_n x 4.  *slices_out (may be NULL)
- * receives the number of K slices the call will use. */
+ * receives the number of K slices the call will use.  With the STREAM_K scheduler:
+ * UCL_WORKSPACE_COUNTER_BYTES + workgroups x 2 x tile_m x tile_n x 4, *slices_out = the largest
+ * number of parts a tile can fall into; the number of workgroups follows from how many of them a
+ * CU holds, which is asked of the HIP runtime (this one query needs a device to be present). */
 ucl_status ucl_workspace_size(const ucl_problem *p, const ucl_tuning *tune, int64_t *bytes, int32_t *slices_out);
 
 /* Zero the counter area at the start of a split-K workspace (one small kernel on `stream`; no

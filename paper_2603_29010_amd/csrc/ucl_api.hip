@@ -392,7 +392,7 @@ struct SplitPlan {
     int k_per_slice = 0;
     int64_t bytes = 0;
     // stream-K: 64-wide k steps per tile, iterations per workgroup, workgroups (0: not a stream-K launch)
-    int sk_ipt = 0, sk_q = 0, sk_grid = 0;
+    int sk_ipt = 0, sk_q = 0, sk_rounds = 0, sk_grid = 0;
 };
 
 ucl_status plan_split(const Launch &L, const VariantDesc &v, const ucl_tuning *tune, int64_t total_tiles, SplitPlan &sp) {
@@ -410,13 +410,21 @@ ucl_status plan_split(const Launch &L, const VariantDesc &v, const ucl_tuning *t
         const int64_t ipt = (L.K + 63) / 64, all = total_tiles * ipt;
         if (all >= (1ll << 31)) return fail(UCL_ERR_UNSUPPORTED, "tiles x k steps exceeds 2^31");
         if (all == 0) return UCL_OK;
-        int64_t grid = (int64_t)kNumCUs * v.resident();
-        if (grid > all) grid = all;
-        const int64_t q = (all + grid - 1) / grid;
+        // whole rounds of tiles go one tile per workgroup and round; the k steps of the tiles that are left are
+        // dealt out evenly.  Fewer tiles than CU slots: no whole round, and only as many workgroups as get k steps.
+        const int64_t slots = (int64_t)kNumCUs * v.resident();
+        int64_t grid = slots, rounds = total_tiles / slots;
+        int64_t rest = (total_tiles - rounds * grid) * ipt, q = (rest + grid - 1) / grid;
+        if (rounds == 0) {
+            if (grid > rest) grid = rest;
+            q = (rest + grid - 1) / grid;
+            grid = (rest + q - 1) / q;
+        }
         sp.sk_ipt = (int)ipt;
         sp.sk_q = (int)q;
-        sp.sk_grid = (int)((all + q - 1) / q);
-        sp.slices = (int)((ipt + q - 2) / q + 1);            // parts a tile can fall into, at most
+        sp.sk_rounds = (int)rounds;
+        sp.sk_grid = (int)grid;
+        sp.slices = q ? (int)((ipt + q - 2) / q + 1) : 1;    // parts a tile can fall into, at most
         if (sp.slices > ipt) sp.slices = (int)ipt;
         sp.bytes = UCL_WORKSPACE_COUNTER_BYTES + (int64_t)sp.sk_grid * 2 * v.tile_m * v.tile_n * 4;
         return UCL_OK;
@@ -505,6 +513,7 @@ ucl_status run(const Launch &L, KParams &kp, const ucl_tuning *tune, void *strea
                         sp.sk_grid, v->tile_m, v->tile_n, (long long)sp.bytes, (long long)tune->workspace_bytes);
         kp.sk_ipt = sp.sk_ipt;
         kp.sk_q = sp.sk_q;
+        kp.sk_rounds = sp.sk_rounds;
         kp.ws_counters = (uint32_t *)tune->workspace;
         kp.ws_partials = (float *)((char *)tune->workspace + UCL_WORKSPACE_COUNTER_BYTES);
     } else if (sp.slices > 1) {

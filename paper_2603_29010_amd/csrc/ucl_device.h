@@ -61,7 +61,7 @@ struct KParams {
     // phase 0 = one launch, the last workgroup to arrive at a tile adds up; 1 = write partial tiles only;
     // 2 = add up only
     int32_t split_k, k_per_slice, split_phase;
-    int32_t sk_ipt, sk_q;             // stream-K: 64-wide k steps per tile, iterations per workgroup
+    int32_t sk_ipt, sk_q, sk_rounds;  // stream-K: 64-wide k steps per tile, k steps of the remaining tiles per workgroup, whole rounds
     float *ws_partials;
     uint32_t *ws_counters;
     EpiStepDev steps[UCL_MAX_EPI_STEPS];   // must stay addressable as offsetof(KParams, steps)
@@ -84,6 +84,37 @@ __host__ __device__ inline int xcd_remap(int wg, int total) {
     const int x = wg & 7, loc = wg >> 3;
     return x * q + (x < r ? x : r) + loc;
 }
+
+// Stream-K: the piece a workgroup stands at after `done` k steps of its run of `end` (see the kernel's tile loop).
+// The first rounds * ipt k steps are whole tiles, tile number round * grid + workgroup; the rest is the workgroup's
+// run [g * q, ...) of the k steps of the remaining tiles, numbered tile by tile.
+struct StreamKPiece {
+    int tile;        // in the numbering that xcd_remap deals to the XCDs
+    int rest_tile;   // index among the remaining tiles (-1: a whole tile of the first rounds)
+    int g;           // the workgroup's place in XCD-run order
+    int k0, k1;      // 64-wide k steps [k0, k1) of the tile
+};
+#if defined(__HIPCC__)
+__device__ inline StreamKPiece streamk_piece(int done, int end, int rounds, int ipt, int q, int total) {
+    StreamKPiece pc;
+    const int grid = (int)gridDim.x;
+    pc.g = xcd_remap((int)blockIdx.x, grid);
+    if (done < rounds * ipt) {
+        pc.tile = (done / ipt) * grid + (int)blockIdx.x;
+        pc.rest_tile = -1;
+        pc.k0 = 0;
+        pc.k1 = ipt;
+    } else {
+        const int it = done - rounds * ipt + pc.g * q;
+        pc.rest_tile = it / ipt;
+        pc.tile = rounds * grid + pc.rest_tile;
+        pc.k0 = it - pc.rest_tile * ipt;
+        pc.k1 = pc.k0 + (end - done) < ipt ? pc.k0 + (end - done) : ipt;
+    }
+    (void)total;
+    return pc;
+}
+#endif
 
 // Walk a tiles_m x tiles_n grid in bands of `gm` tile rows, column by column inside a band.
 __host__ __device__ inline void band_raster(int t, int tiles_m, int tiles_n, int gm, int &tm, int &tn) {

@@ -478,18 +478,23 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
     // the loop below runs once.  Persistent scheduler: the grid has one workgroup per CU slot (a
     // multiple of 8, so a workgroup stays on the tile run of its XCD) and walks the tile order with
     // a stride of the grid size.
-    // Stream-K scheduler: the (tile, 64-wide k range) pairs of the whole problem are numbered tile by tile and
-    // workgroup g (in XCD-run order) takes the sk_q of them from g * sk_q on: the end of a tile, whole tiles, the
-    // start of a tile.  The loop variable is then the iteration the workgroup stands at, and one pass of the loop
-    // body is one piece: a whole tile ends in the epilogue as usual; a part of a tile goes to the workspace, and
-    // the workgroup that delivers the last part of a tile adds the parts up in k order and runs the epilogue.
+    // Stream-K scheduler: as many whole rounds of tiles as the grid divides are walked like the persistent
+    // scheduler walks them (sk_rounds tiles per workgroup: workgroups that run side by side work on neighbouring
+    // tiles and share their operands in L2).  The (tile, 64-wide k range) pairs of the remaining tiles are numbered
+    // tile by tile and workgroup g (in XCD-run order) takes the sk_q of them from g * sk_q on.  The loop variable
+    // counts the k steps the workgroup has behind it (sk_ipt per whole tile); one pass of the loop body is one piece:
+    // a whole tile ends in the epilogue as usual; a part of a tile goes to the workspace, and the workgroup that
+    // delivers the last part of a tile adds the parts up in k order and runs the epilogue.
     typedef const __attribute__((address_space(4))) KParams ConstKParams;
     int wg_first = blockIdx.x, sk_end = 0;
     if constexpr (Cfg::STREAMK) {
         ConstKParams *p0 = (ConstKParams *)__builtin_amdgcn_kernarg_segment_ptr();
-        const int all = p0->total_tiles * p0->sk_ipt;
-        wg_first = xcd_remap(blockIdx.x, gridDim.x) * p0->sk_q;
-        sk_end = wg_first + p0->sk_q < all ? wg_first + p0->sk_q : all;
+        const int rest = (p0->total_tiles - p0->sk_rounds * (int)gridDim.x) * p0->sk_ipt;     // k steps of the remaining tiles
+        const int mine0 = xcd_remap(blockIdx.x, gridDim.x) * p0->sk_q;
+        const int mine_n = rest - mine0 < p0->sk_q ? rest - mine0 : p0->sk_q;
+        wg_first = 0;
+        sk_end = p0->sk_rounds * p0->sk_ipt + (mine_n > 0 ? mine_n : 0);
+        if (sk_end == 0) return;
     }
     for (int wg_id = wg_first;;) {
     // The kernel arguments are read through a pointer into the argument segment (p_arg is the first
@@ -512,6 +517,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
     // run side by side on one XCD and share them in its L2
     int slice = 0;
     int t = 0;
+    int sk_k0 = 0, sk_k1 = 0;           // stream-K: the piece's range of 64-wide k steps within its tile
     if constexpr ((MODE == 0 || MODE == 4) && !Cfg::PERSIST) {
         if (p.split_k > 1 && p.split_phase != 2) {
             t = xcd_remap(wg_id, p.total_tiles * p.split_k);
@@ -521,13 +527,14 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
             t = xcd_remap(wg_id, p.total_tiles);
         }
     } else if constexpr (Cfg::STREAMK) {
-        t = wg_id / p.sk_ipt;
+        // (nothing of a piece is kept across the mainloop: streamk_piece works it out from the loop variable)
+        const StreamKPiece pc = streamk_piece(wg_id, sk_end, p.sk_rounds, p.sk_ipt, p.sk_q, p.total_tiles);
+        t = xcd_remap(pc.tile, p.total_tiles);
+        sk_k0 = pc.k0;
+        sk_k1 = pc.k1;
     } else {
         t = xcd_remap(wg_id, p.total_tiles);
     }
-    // stream-K: the piece's range of 64-wide k steps within its tile
-    const int sk_k0 = Cfg::STREAMK ? wg_id - t * p.sk_ipt : 0;
-    const int sk_k1 = Cfg::STREAMK ? (sk_k0 + (sk_end - wg_id) < p.sk_ipt ? sk_k0 + (sk_end - wg_id) : p.sk_ipt) : 0;
     int batch = 0, group = -1, tm, tn;
     int Mloc = p.M;
     const char *Ab = (const char *)p.A;
@@ -1576,21 +1583,22 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
     // first iteration; part 0 is that workgroup's second kind, every later part its owner's first kind.  The
     // same device-coherent accesses, counter and fixed order of additions as split-K above.
     if constexpr (Cfg::STREAMK) {
-        // (the piece is worked out again from the iteration index rather than kept in registers across the mainloop)
+        // (the piece is worked out again from the loop variable rather than kept in registers across the mainloop)
         int it_again = wg_id;
         asm volatile("" : "+s"(it_again));
-        const int tile_again = it_again / p.sk_ipt;
-        const int it0 = tile_again * p.sk_ipt;
-        const int k0_again = it_again - it0;
-        const int k1_again = k0_again + (sk_end - it_again) < p.sk_ipt ? k0_again + (sk_end - it_again) : p.sk_ipt;
+        const StreamKPiece pc = streamk_piece(it_again, sk_end, p.sk_rounds, p.sk_ipt, p.sk_q, p.total_tiles);
+        const int k0_again = pc.k0, k1_again = pc.k1;
         if (k0_again != 0 || k1_again != p.sk_ipt) {
             constexpr int64_t kTileElems = (int64_t)TM * TN;
             constexpr int kCoherent = 17;
+            // the parts of remaining tile r: those of the workgroups whose runs meet its k steps [r, r + 1) * sk_ipt
+            const int tile_again = pc.rest_tile;
+            const int it0 = tile_again * p.sk_ipt;
             const int g_first = it0 / p.sk_q, n_parts = (it0 + p.sk_ipt - 1) / p.sk_q - g_first + 1;
             auto part_rsrc = [&](int slot) __attribute__((always_inline)) {
                 return buffer_rsrc(p.ws_partials + (int64_t)slot * kTileElems, (uint32_t)(kTileElems * 4));
             };
-            const rsrc_t mine = part_rsrc(2 * (wg_id / p.sk_q) + (k0_again != 0 ? 0 : 1));
+            const rsrc_t mine = part_rsrc(2 * pc.g + (k0_again != 0 ? 0 : 1));
             static_for<MI>([&](auto mi) {
                 static_for<NI>([&](auto ni) {
                     __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, acc[mi][ni]), mine,
@@ -1607,7 +1615,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
             const int arrived = __builtin_amdgcn_readfirstlane(*(volatile int *)smem);
             if (arrived != n_parts - 1) {
                 // not the last part: on to the workgroup's next piece
-                wg_id = it0 + k1_again;
+                wg_id = it_again + (k1_again - k0_again);
                 if (wg_id >= sk_end) break;
                 __syncthreads();
                 continue;
@@ -1619,7 +1627,30 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
                     pin_acc(acc[mi][ni]);
                 });
             });
-            for (int s_ = 0; s_ < n_parts; ++s_) {
+            // as in the split-K loop above: several parts' loads in flight where the registers allow, additions in part order
+            constexpr int kRegs = MI * NI;
+            constexpr int kFit = (512 / Cfg::MIN_WAVES - kRegs * 4) / 2 / (kRegs * 4);
+            constexpr int U = kFit < 1 ? 1 : kFit > 8 ? 8 : kFit;
+            int s_ = 0;
+            if constexpr (kFit >= 1) {
+                for (; s_ + U <= n_parts; s_ += U) {
+                    u32x4_t v[U][kRegs];
+                    static_for<U>([&](auto u) {
+                        const rsrc_t rs = part_rsrc(2 * (g_first + s_ + u) + (s_ + u == 0 ? 1 : 0));
+                        static_for<kRegs>([&](auto r) { v[u][r] = __builtin_amdgcn_raw_buffer_load_b128(rs, (r * kThreads + tid) * 16, 0, kCoherent); });
+                    });
+                    static_for<U>([&](auto u) {
+                        static_for<MI>([&](auto mi) {
+                            static_for<NI>([&](auto ni) {
+                                acc[mi][ni] += __builtin_bit_cast(f32x4_t, v[u][mi * NI + ni]);
+                                pin_acc(acc[mi][ni]);
+                            });
+                        });
+                    });
+                    asm volatile("" ::: "memory");
+                }
+            }
+            for (; s_ < n_parts; ++s_) {
                 const rsrc_t rs = part_rsrc(2 * (g_first + s_) + (s_ == 0 ? 1 : 0));
                 static_for<MI>([&](auto mi) {
                     static_for<NI>([&](auto ni) {
@@ -2105,9 +2136,9 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
     if constexpr (!Cfg::PERSIST) {
         break;
     } else if constexpr (Cfg::STREAMK) {
-        // the piece ended at its tile's end or at the end of the workgroup's run
-        const int tile_end = (wg_id / p.sk_ipt + 1) * p.sk_ipt;
-        wg_id = tile_end;
+        // the k steps of the piece are behind the workgroup
+        const StreamKPiece pe = streamk_piece(wg_id, sk_end, p.sk_rounds, p.sk_ipt, p.sk_q, p.total_tiles);
+        wg_id += pe.k1 - pe.k0;
         if (wg_id >= sk_end) break;
         __syncthreads();
     } else {
