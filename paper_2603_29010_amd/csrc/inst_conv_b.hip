@@ -2,11 +2,11 @@
 #include "ucl_launch.h"
 namespace ucl {
 static const VariantDesc kTable[] = {
-    describe<KernelCfg<128, 128, 64, 3, false, 2, kIm2col, kKContig>>(),
-    describe<KernelCfg<128, 128, 32, 4, false, 2, kIm2col, kKContig>>(),
-    describe<KernelCfg<128, 128, 32, 3, false, 2, kIm2col, kKContig>>(),
-    describe<KernelCfg<128, 128, 64, 2, false, 2, kIm2col, kKContig>>(),
-    describe<KernelCfg<64, 64, 32, 3, false, 2, kIm2col, kKContig>>(),
+    describe<KernelCfg<128, 128, 64, 3, 0, 2, kIm2col, kKContig>>(),
+    describe<KernelCfg<128, 128, 32, 4, 0, 2, kIm2col, kKContig>>(),
+    describe<KernelCfg<128, 128, 32, 3, 0, 2, kIm2col, kKContig>>(),
+    describe<KernelCfg<128, 128, 64, 2, 0, 2, kIm2col, kKContig>>(),
+    describe<KernelCfg<64, 64, 32, 3, 0, 2, kIm2col, kKContig>>(),
 };
 VariantList variants_conv_b() { return {kTable, (int)(sizeof(kTable) / sizeof(kTable[0]))}; }
 }  // namespace ucl

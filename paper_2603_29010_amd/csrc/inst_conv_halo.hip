@@ -2,8 +2,8 @@
 #include "ucl_launch.h"
 namespace ucl {
 static const VariantDesc kTable[] = {
-    describe<KernelCfg<256, 128, 32, 4, false, 2, kHalo, kKContig>>(),
-    describe<KernelCfg<256, 128, 32, 4, true, 2, kHalo, kKContig>>(),
+    describe<KernelCfg<256, 128, 32, 4, 0, 2, kHalo, kKContig>>(),
+    describe<KernelCfg<256, 128, 32, 4, 1, 2, kHalo, kKContig>>(),
 };
 VariantList variants_conv_halo() { return {kTable, (int)(sizeof(kTable) / sizeof(kTable[0]))}; }
 }  // namespace ucl

@@ -2,9 +2,9 @@
 #include "ucl_launch.h"
 namespace ucl {
 static const VariantDesc kTable[] = {
-    describe<KernelCfg<256, 256, 32, 4, false, 0, kKContig, kKContig>>(),
-    describe<KernelCfg<256, 256, 32, 5, false, 0, kKContig, kKContig>>(),
-    describe<KernelCfg<256, 256, 64, 2, false, 0, kKContig, kKContig>>(),
+    describe<KernelCfg<256, 256, 32, 4, 0, 0, kKContig, kKContig>>(),
+    describe<KernelCfg<256, 256, 32, 5, 0, 0, kKContig, kKContig>>(),
+    describe<KernelCfg<256, 256, 64, 2, 0, 0, kKContig, kKContig>>(),
 };
 VariantList variants_gemm_kk_bf16_a() { return {kTable, (int)(sizeof(kTable) / sizeof(kTable[0]))}; }
 }  // namespace ucl

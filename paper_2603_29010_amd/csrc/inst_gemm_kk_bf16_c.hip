@@ -2,10 +2,10 @@
 #include "ucl_launch.h"
 namespace ucl {
 static const VariantDesc kTable[] = {
-    describe<KernelCfg<128, 128, 64, 3, false, 0, kKContig, kKContig>>(),
-    describe<KernelCfg<128, 128, 32, 4, false, 0, kKContig, kKContig>>(),
-    describe<KernelCfg<128, 128, 32, 3, false, 0, kKContig, kKContig>>(),
-    describe<KernelCfg<128, 128, 64, 2, false, 0, kKContig, kKContig>>(),
+    describe<KernelCfg<128, 128, 64, 3, 0, 0, kKContig, kKContig>>(),
+    describe<KernelCfg<128, 128, 32, 4, 0, 0, kKContig, kKContig>>(),
+    describe<KernelCfg<128, 128, 32, 3, 0, 0, kKContig, kKContig>>(),
+    describe<KernelCfg<128, 128, 64, 2, 0, 0, kKContig, kKContig>>(),
 };
 VariantList variants_gemm_kk_bf16_c() { return {kTable, (int)(sizeof(kTable) / sizeof(kTable[0]))}; }
 }  // namespace ucl

@@ -2,9 +2,9 @@
 #include "ucl_launch.h"
 namespace ucl {
 static const VariantDesc kTable[] = {
-    describe<KernelCfg<64, 64, 64, 4, false, 0, kKContig, kKContig>>(),
-    describe<KernelCfg<64, 64, 32, 4, false, 0, kKContig, kKContig>>(),
-    describe<KernelCfg<64, 64, 32, 3, false, 0, kKContig, kKContig>>(),
+    describe<KernelCfg<64, 64, 64, 4, 0, 0, kKContig, kKContig>>(),
+    describe<KernelCfg<64, 64, 32, 4, 0, 0, kKContig, kKContig>>(),
+    describe<KernelCfg<64, 64, 32, 3, 0, 0, kKContig, kKContig>>(),
 };
 VariantList variants_gemm_kk_bf16_d() { return {kTable, (int)(sizeof(kTable) / sizeof(kTable[0]))}; }
 }  // namespace ucl

@@ -2,10 +2,10 @@
 #include "ucl_launch.h"
 namespace ucl {
 static const VariantDesc kTable[] = {
-    describe<KernelCfg<256, 256, 32, 4, true, 0, kKContig, kKContig>>(),
-    describe<KernelCfg<256, 256, 64, 2, true, 0, kKContig, kKContig>>(),
-    describe<KernelCfg<256, 128, 32, 4, true, 0, kKContig, kKContig>>(),
-    describe<KernelCfg<256, 128, 32, 3, true, 0, kKContig, kKContig>>(),
+    describe<KernelCfg<256, 256, 32, 4, 1, 0, kKContig, kKContig>>(),
+    describe<KernelCfg<256, 256, 64, 2, 1, 0, kKContig, kKContig>>(),
+    describe<KernelCfg<256, 128, 32, 4, 1, 0, kKContig, kKContig>>(),
+    describe<KernelCfg<256, 128, 32, 3, 1, 0, kKContig, kKContig>>(),
 };
 VariantList variants_gemm_kk_f16_a() { return {kTable, (int)(sizeof(kTable) / sizeof(kTable[0]))}; }
 }  // namespace ucl

@@ -2,12 +2,12 @@
 #include "ucl_launch.h"
 namespace ucl {
 static const VariantDesc kTable[] = {
-    describe<KernelCfg<256, 256, 64, 2, false, 0, kKContig, kNDirect>>(),
-    describe<KernelCfg<256, 128, 32, 3, false, 0, kKContig, kNDirect>>(),
-    describe<KernelCfg<128, 128, 32, 4, false, 0, kKContig, kNDirect>>(),
-    describe<KernelCfg<128, 128, 64, 2, false, 0, kKContig, kNDirect>>(),
-    describe<KernelCfg<64, 64, 32, 3, false, 0, kKContig, kNDirect>>(),
-    describe<KernelCfg<64, 64, 64, 4, false, 0, kKContig, kNDirect>>(),
+    describe<KernelCfg<256, 256, 64, 2, 0, 0, kKContig, kNDirect>>(),
+    describe<KernelCfg<256, 128, 32, 3, 0, 0, kKContig, kNDirect>>(),
+    describe<KernelCfg<128, 128, 32, 4, 0, 0, kKContig, kNDirect>>(),
+    describe<KernelCfg<128, 128, 64, 2, 0, 0, kKContig, kNDirect>>(),
+    describe<KernelCfg<64, 64, 32, 3, 0, 0, kKContig, kNDirect>>(),
+    describe<KernelCfg<64, 64, 64, 4, 0, 0, kKContig, kNDirect>>(),
 };
 VariantList variants_gemm_kn_bf16() { return {kTable, (int)(sizeof(kTable) / sizeof(kTable[0]))}; }
 }  // namespace ucl

@@ -2,10 +2,10 @@
 #include "ucl_launch.h"
 namespace ucl {
 static const VariantDesc kTable[] = {
-    describe<KernelCfg<256, 256, 64, 2, true, 0, kMDirect, kKContig>>(),
-    describe<KernelCfg<64, 64, 32, 3, true, 0, kMDirect, kKContig>>(),
-    describe<KernelCfg<256, 256, 64, 2, true, 0, kMDirect, kNDirect>>(),
-    describe<KernelCfg<64, 64, 32, 3, true, 0, kMDirect, kNDirect>>(),
+    describe<KernelCfg<256, 256, 64, 2, 1, 0, kMDirect, kKContig>>(),
+    describe<KernelCfg<64, 64, 32, 3, 1, 0, kMDirect, kKContig>>(),
+    describe<KernelCfg<256, 256, 64, 2, 1, 0, kMDirect, kNDirect>>(),
+    describe<KernelCfg<64, 64, 32, 3, 1, 0, kMDirect, kNDirect>>(),
 };
 VariantList variants_gemm_mx_f16() { return {kTable, (int)(sizeof(kTable) / sizeof(kTable[0]))}; }
 }  // namespace ucl

@@ -4,12 +4,12 @@
 #include "ucl_launch.h"
 namespace ucl {
 static const VariantDesc kTable[] = {
-    describe<KernelCfg<128, 128, 64, 2, 0, 0, kKContig, kKContig, true>>(),
-    describe<KernelCfg<128, 128, 32, 4, 0, 0, kKContig, kKContig, true>>(),
-    describe<KernelCfg<64, 64, 64, 4, 0, 0, kKContig, kKContig, true>>(),
-    describe<KernelCfg<128, 128, 32, 4, 1, 0, kKContig, kKContig, true>>(),
-    describe<KernelCfg<64, 64, 64, 4, 1, 0, kKContig, kKContig, true>>(),
-    describe<KernelCfg<64, 64, 64, 4, 0, 1, kKContig, kKContig, true>>(),
+    describe<KernelCfg<128, 128, 64, 2, 0, 0, kKContig, kKContig, 1>>(),
+    describe<KernelCfg<128, 128, 32, 4, 0, 0, kKContig, kKContig, 1>>(),
+    describe<KernelCfg<64, 64, 64, 4, 0, 0, kKContig, kKContig, 1>>(),
+    describe<KernelCfg<128, 128, 32, 4, 1, 0, kKContig, kKContig, 1>>(),
+    describe<KernelCfg<64, 64, 64, 4, 1, 0, kKContig, kKContig, 1>>(),
+    describe<KernelCfg<64, 64, 64, 4, 0, 1, kKContig, kKContig, 1>>(),
 };
 VariantList variants_persistent() { return {kTable, (int)(sizeof(kTable) / sizeof(kTable[0]))}; }
 }  // namespace ucl

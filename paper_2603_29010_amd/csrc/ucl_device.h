@@ -95,7 +95,7 @@ struct StreamKPiece {
     int k0, k1;      // 64-wide k steps [k0, k1) of the tile
 };
 #if defined(__HIPCC__)
-__device__ inline StreamKPiece streamk_piece(int done, int end, int rounds, int ipt, int q, int total) {
+__device__ inline StreamKPiece streamk_piece(int done, int end, int rounds, int ipt, int q) {
     StreamKPiece pc;
     const int grid = (int)gridDim.x;
     pc.g = xcd_remap((int)blockIdx.x, grid);
@@ -111,7 +111,6 @@ __device__ inline StreamKPiece streamk_piece(int done, int end, int rounds, int 
         pc.k0 = it - pc.rest_tile * ipt;
         pc.k1 = pc.k0 + (end - done) < ipt ? pc.k0 + (end - done) : ipt;
     }
-    (void)total;
     return pc;
 }
 #endif

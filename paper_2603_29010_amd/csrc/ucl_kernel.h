@@ -528,7 +528,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
         }
     } else if constexpr (Cfg::STREAMK) {
         // (nothing of a piece is kept across the mainloop: streamk_piece works it out from the loop variable)
-        const StreamKPiece pc = streamk_piece(wg_id, sk_end, p.sk_rounds, p.sk_ipt, p.sk_q, p.total_tiles);
+        const StreamKPiece pc = streamk_piece(wg_id, sk_end, p.sk_rounds, p.sk_ipt, p.sk_q);
         t = xcd_remap(pc.tile, p.total_tiles);
         sk_k0 = pc.k0;
         sk_k1 = pc.k1;
@@ -1586,7 +1586,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
         // (the piece is worked out again from the loop variable rather than kept in registers across the mainloop)
         int it_again = wg_id;
         asm volatile("" : "+s"(it_again));
-        const StreamKPiece pc = streamk_piece(it_again, sk_end, p.sk_rounds, p.sk_ipt, p.sk_q, p.total_tiles);
+        const StreamKPiece pc = streamk_piece(it_again, sk_end, p.sk_rounds, p.sk_ipt, p.sk_q);
         const int k0_again = pc.k0, k1_again = pc.k1;
         if (k0_again != 0 || k1_again != p.sk_ipt) {
             constexpr int64_t kTileElems = (int64_t)TM * TN;
@@ -2137,7 +2137,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
         break;
     } else if constexpr (Cfg::STREAMK) {
         // the k steps of the piece are behind the workgroup
-        const StreamKPiece pe = streamk_piece(wg_id, sk_end, p.sk_rounds, p.sk_ipt, p.sk_q, p.total_tiles);
+        const StreamKPiece pe = streamk_piece(wg_id, sk_end, p.sk_rounds, p.sk_ipt, p.sk_q);
         wg_id += pe.k1 - pe.k0;
         if (wg_id >= sk_end) break;
         __syncthreads();
