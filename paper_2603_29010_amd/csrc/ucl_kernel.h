@@ -3,7 +3,9 @@
 // the instantiation units.
 //
 // Structure of a workgroup (256 threads = 4 waves, one per SIMD):
-//   tile schedule  : workgroup id -> (batch or group, tile row, tile column), XCD-aware
+//   tile schedule  : workgroup id -> (batch or group, tile row, tile column), XCD-aware; with split-K also a K slice;
+//                    under the persistent scheduler a walk over several tiles, under stream-K over tiles and
+//                    parts of tiles (partial sums meet in a workspace and are added in a fixed order)
 //   staging        : global -> LDS, `STAGES` buffers deep, 128-bit `buffer_load ... lds` (no VGPR round
 //                    trip) for every operand form: rows contiguous along K, the gathered views of the
 //                    three convolutions, and rows contiguous along M / N (copied as they are and read
