@@ -71,3 +71,59 @@ def test_random_problem(seed):
         parity.check_exact(spec, None, label=label)
     else:
         parity.check(spec, None, label=label)
+
+
+_WS = {}
+
+
+def _workspace():
+    import torch
+    import paper_2603_29010_amd as ucl
+    ws = _WS.get("buf")
+    if ws is None:
+        ws = torch.empty(192 << 20, dtype=torch.uint8, device="cuda")
+        ucl.ucl_workspace_init(ws.data_ptr(), ws.numel(), torch.cuda.current_stream().cuda_stream)
+        _WS["buf"] = ws
+    return ws
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_random_problem_under_a_random_schedule(seed):
+    """The scheduling knobs on random GEMM shapes (kernel left to the library): split-K serial / parallel with a random
+    slice count, the persistent and the stream-K scheduler, fp8 inputs; all on one workspace, whose counters every
+    call must leave zero."""
+    import torch
+    from paper_2603_29010_amd.binding import Tuning, WORKSPACE_COUNTER_BYTES
+    rng = np.random.default_rng(77001 + seed)
+    ws = _workspace()
+    knob = ["serial", "parallel", "persistent", "stream_k"][seed % 4]
+    exact = bool(rng.integers(0, 2))
+    fp8 = knob in ("serial", "parallel") and bool(rng.integers(0, 3) == 0)      # the schedulers are built for 16-bit inputs
+    dt_in = ["e4m3", "e5m2"][int(rng.integers(0, 2))] if fp8 else ["bf16", "f16"][int(rng.integers(0, 2))]
+    dt_out = "f32" if exact else ["bf16", "f32"][int(rng.integers(0, 2))]
+    chain = () if exact else CHAINS[int(rng.integers(0, len(CHAINS)))]
+    kmult = 16 if fp8 else 8
+    batched = bool(rng.integers(0, 4) == 0)
+    M, N = _dims(rng, 8, 900, 1), _dims(rng, 8, 900, 1)
+    K = _dims(rng, 64, 3000 if knob != "persistent" else 400, kmult)
+    if batched:
+        b = int(rng.integers(2, 5))
+        chain = chain if "per_row_scale" not in chain else ("bias", "relu")
+        spec = synth.batched_spec(b, M // 2 + 8, N // 2 + 8, K, dt_in=dt_in, dt_out=dt_out, epilogue=list(chain), integer=exact,
+                                  seed=synth.BASE_SEED + 500 + seed)
+    else:
+        spec = synth.gemm_spec(M, N, K, dt_in=dt_in, dt_out=dt_out, epilogue=chain, integer=exact, seed=synth.BASE_SEED + 500 + seed)
+    kw = dict(workspace=ws.data_ptr(), workspace_bytes=ws.numel())
+    if knob in ("serial", "parallel"):
+        tune = Tuning(split_k=knob, slices=int(rng.integers(0, 12)), **kw)
+    elif knob == "persistent":
+        tune = Tuning(scheduler="persistent")
+    else:
+        tune = Tuning(scheduler="stream_k", **kw)
+    label = f"{'batched' if batched else 'gemm'} {M}x{N}x{K} {dt_in}->{dt_out} {chain} under {knob}"
+    if exact:
+        parity.check_exact(spec, tune, label=label)
+    else:
+        parity.check(spec, tune, label=label)
+    torch.cuda.synchronize()
+    assert int(ws[:WORKSPACE_COUNTER_BYTES].count_nonzero().item()) == 0, label
