@@ -76,6 +76,15 @@ def test_stream_k_exact_one_step_per_tile_and_batches(tile, dt):
     assert counters_are_zero()
 
 
+def test_stream_k_exact_whole_rounds_only():
+    # 2048 x 2048 with 64x64 tiles: 1024 tiles, whole rounds of a grid of 256, 512 or 1024 workgroups and nothing left over
+    # (no part of a tile, the workspace stays untouched); with 128x128 tiles 256 tiles
+    spec = synth.gemm_spec(2048, 2048, 136, dt_out="f32", epilogue=(), integer=True)
+    for tile in built(0, scheduler=2):
+        parity.check_exact(spec, SK(*tile), label=f"stream-K whole rounds {tile}")
+    assert counters_are_zero()
+
+
 def test_stream_k_floating_point_with_epilogue_and_table_choice():
     spec = synth.gemm_spec(1100, 900, 1544, epilogue=("bias", "gelu_erf", "aux_load"))
     for tile in built(0, scheduler=2):
