@@ -386,6 +386,53 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(float *partials, int
     ((f32x4 *)partials)[i] = acc;
 }
 
+// The same reduction for launches whose chain is empty and whose output is fp32: the sums are the result, so they are
+// stored to D directly and the finishing launch of the tile kernel is not needed.  A 16-byte word of a partial tile
+// is accumulator (mi, ni) of one lane: four consecutive columns of one row (the layout the tile kernel stores:
+// word = (mi * NI + ni) * 256 + thread; thread = wave * 64 + lane, wave = (row half, column half) of the tile;
+// row = mi * 16 + lane % 16, column = ni * 16 + 4 * (lane / 16) inside the wave's quarter).
+struct ReduceStore {
+    float *partials;
+    float *D;
+    int64_t slice_stride, n4, ldd, d_bs;
+    int32_t slices, tile_m, tile_n, M, N, tiles_m, tiles_n, tiles_per_batch, raster;
+};
+__global__ __launch_bounds__(256) void splitk_reduce_store_kernel(const ReduceStore a) {
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= a.n4) return;
+    const f32x4 *src = (const f32x4 *)a.partials + i;
+    const int64_t stride4 = a.slice_stride / 4;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    int s = 0;
+    for (; s + 8 <= a.slices; s += 8) {
+        f32x4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load(src + (s + u) * stride4);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc += v[u];
+    }
+    for (; s < a.slices; ++s) acc += __builtin_nontemporal_load(src + s * stride4);
+    const int words_per_tile = a.tile_m * a.tile_n / 4, ni_count = a.tile_n / 32;
+    int t = (int)(i / words_per_tile);
+    const int w = (int)(i - (int64_t)t * words_per_tile);
+    const int reg = w >> 8, thread = w & 255, wave = thread >> 6, lane = thread & 63;
+    const int m_loc = (wave >> 1) * (a.tile_m / 2) + (reg / ni_count) * 16 + (lane & 15);
+    const int n_loc = (wave & 1) * (a.tile_n / 2) + (reg % ni_count) * 16 + 4 * (lane >> 4);
+    const int batch = t / a.tiles_per_batch;
+    t -= batch * a.tiles_per_batch;
+    int tm, tn;
+    band_raster(t, a.tiles_m, a.tiles_n, a.raster, tm, tn);
+    const int m = tm * a.tile_m + m_loc, n = tn * a.tile_n + n_loc;
+    if (m >= a.M || n >= a.N) return;
+    float *dst = a.D + (int64_t)batch * a.d_bs + (int64_t)m * a.ldd + n;
+    if (n + 4 <= a.N) {
+        *(f32x4 *)dst = acc;
+    } else {
+        for (int e = 0; e < a.N - n; ++e) dst[e] = acc[e];
+    }
+}
+
 // split-K plan of a launch: slices (1 = none), K extent per slice, workspace bytes.
 struct SplitPlan {
     int slices = 1;
@@ -548,15 +595,28 @@ ucl_status run(const Launch &L, KParams &kp, const ucl_tuning *tune, void *strea
     } else if (sp.slices > 1 && tune->split_k_mode == UCL_SPLIT_K_PARALLEL) {
         kp.split_phase = 1;
         e = v->launch(kp, gtp, (int)(total * sp.slices), (hipStream_t)stream);
+        bool finished = false;
         if (e == hipSuccess && sp.slices > kReduceInTileKernel) {
             // many slices: a launch of its own adds them up with the whole chip, the last launch then finds one slice
             const int64_t slice_floats = total * v->tile_m * v->tile_n, n4 = slice_floats / 4;
-            hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
-                               kp.ws_partials, slice_floats, sp.slices, n4);
+            const bool plain = kp.n_steps == 0 && kp.dtD == UCL_F32 && kp.d_vec && L.mode != 1;
+            if (plain) {
+                // ... or none: an empty chain and an fp32 output, the sums go to D as they are
+                ReduceStore rs;
+                rs.partials = kp.ws_partials; rs.D = (float *)kp.D;
+                rs.slice_stride = slice_floats; rs.n4 = n4; rs.ldd = kp.ldd; rs.d_bs = kp.d_bs;
+                rs.slices = sp.slices; rs.tile_m = v->tile_m; rs.tile_n = v->tile_n; rs.M = kp.M; rs.N = kp.N;
+                rs.tiles_m = kp.tiles_m; rs.tiles_n = kp.tiles_n; rs.tiles_per_batch = kp.tiles_per_batch; rs.raster = kp.raster;
+                hipLaunchKernelGGL(splitk_reduce_store_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, (hipStream_t)stream, rs);
+                finished = true;
+            } else {
+                hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
+                                   kp.ws_partials, slice_floats, sp.slices, n4);
+            }
             e = hipGetLastError();
             kp.split_k = 1;
         }
-        if (e == hipSuccess) {
+        if (e == hipSuccess && !finished) {
             kp.split_phase = 2;
             e = v->launch(kp, gtp, (int)total, (hipStream_t)stream);
         }

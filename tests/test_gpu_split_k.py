@@ -12,6 +12,7 @@ from paper_2603_29010_amd.binding import Tuning, WORKSPACE_COUNTER_BYTES
 from paper_2603_29010_amd.workload import DeviceWorkload
 
 import parity
+from oracle import run_spec as orc_run
 from test_gpu_parity import built
 
 pytestmark = pytest.mark.gpu
@@ -69,6 +70,26 @@ def test_split_k_exact_batched_and_f16():
     for tile in built(0, f16=1):
         for mode in ("serial", "parallel"):
             parity.check_exact(spec, split_tune(tile, mode, 5), label=f"split-K batched {mode} {tile}")
+    assert counters_are_zero()
+
+
+def test_split_k_parallel_plain_f32_padded_rows():
+    # An empty chain with fp32 output and more than two slices: the sums are the result, written without a
+    # finishing pass over the tiles.  N = 134 is no multiple of 4 and the rows of D are 136 apart: the last
+    # vector of a row is cut short, and the padding, the rows past M and the space behind D stay untouched.
+    M, N, K, ldd = 200, 134, 1000, 136
+    spec = synth.gemm_spec(M, N, K, dt_out="f32", epilogue=(), integer=True)
+    ref = orc_run.run(spec).reshape(M, N)
+    w = DeviceWorkload(spec)
+    for tile in built(0):
+        for mode in ("parallel", "serial"):
+            D = torch.full((M + 1, ldd), -777.0, dtype=torch.float32, device="cuda")
+            ucl.ucl_gemm(M, N, K, w.A.data_ptr(), "bf16", *spec["a_strides"], w.B.data_ptr(), "bf16", *spec["b_strides"],
+                         D.data_ptr(), "f32", ldd, 1, None, split_tune(tile, mode, 6), torch.cuda.current_stream().cuda_stream)
+            torch.cuda.synchronize()
+            got = D.cpu().numpy().astype(np.float64)
+            assert np.array_equal(got[:M, :N], ref), f"{mode} {tile}"
+            assert (got[:M, N:] == -777.0).all() and (got[M] == -777.0).all(), f"{mode} {tile}: wrote outside D"
     assert counters_are_zero()
 
 
