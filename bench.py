@@ -46,6 +46,21 @@ SPIN_UP_SECONDS = 0.5
 # profiles/ucl_tile_kernel_*.txt (with the commands that produced them) for the kernels the selection
 # table picks, not measurements of the run that prints them.
 RECORDED_TRAFFIC_BYTES = {1: 1161222, 2: 235355210, 3: 84257767, 4: 525480784, 5: 66157948}
+# The same for the rows of --widening (profiles/ucl_tile_kernel_widening_rows.txt; all launches of a step added up).
+WIDENING_TRAFFIC_BYTES = {
+    "gemm_4096x4096x4096_fp8_e4m3_rowcol_bias_gelu_tanh_bf16out": 134654126,
+    "gemm_4096x4096x4096_fp8_e5m2_rowcol_bias_gelu_tanh_bf16out": 134633431,
+    "grouped_gemm_16groups_n4096_k1024_fp8_e4m3_silu_bf16out": 321418944,
+    "conv2d_dgrad_nhwc_32x56x56x64_from_128_3x3_bf16": 40420568,
+    "conv2d_wgrad_nhwc_32x56x56x64_to_128_3x3_bf16_f32out_splitk_parallel": 77827573,
+    "conv2d_wgrad_nhwc_32x56x56x64_to_128_3x3_bf16_f32out_splitk_serial": 66153438,
+    "gemm_256x256x16384_bf16_bias_relu_no_split": 50682106,
+    "gemm_256x256x16384_bf16_bias_relu_splitk_parallel": 26219893,
+    "gemm_256x256x16384_bf16_bias_relu_splitk_serial": 25507331,
+    "gemm_8192x8192x64_bf16_bias_relu_tile128_default_scheduler": 144121094,
+    "gemm_256x256x16384_bf16_bias_relu_tile64_stream_k_scheduler": 25561483,
+    "gemm_8192x8192x64_bf16_bias_relu_tile128_persistent_scheduler": 144121309,
+}
 WORKLOAD_NAMES = {
     1: "gemm_256x256x256_bf16_bias_relu",
     2: "gemm_4096x4096x4096_bf16_rowcol_bias_gelu_tanh",
@@ -357,6 +372,8 @@ def bench_widening(args):
     ]
     out = {}
     for name, make, tune in cases:
+        if args.only and args.only not in name:
+            continue
         spec = make()
         w = DeviceWorkload(spec, poison=False)
         sol = w.sol()
@@ -369,7 +386,9 @@ def bench_widening(args):
         out[name] = {"ms_per_step": ms, "ms_per_step_min": min(timing["per_replay"]), "tflops": sol["flops"] / t / 1e12,
                      "gbps": sol["bytes"] / t / 1e9, "t_sol_us": sol["t_sol"] * 1e6, "frac_of_sol": sol["t_sol"] / t,
                      "roofline": {"bound": "mfma" if mfma else "hbm", "achieved": ach, "peak": peak,
-                                  "unit": "TFLOP/s" if mfma else "GB/s", "frac": ach / peak, "traffic": None},
+                                  "unit": "TFLOP/s" if mfma else "GB/s", "frac": ach / peak,
+                                  "traffic": WIDENING_TRAFFIC_BYTES.get(name), "algorithmic_bytes": sol["bytes"],
+                                  "traffic_source": "recorded in profiles/ (rocprofv3 --pmc), not read in this run"},
                      "kernel": w.selected() if tune is None or tune.c.split_k_mode else
                      dict(tune.as_dict(), scheduler=("default", "persistent", "stream_k")[tune.c.scheduler]),
                      "launch": launch, "sclk_mhz_under_load": sclk}
@@ -401,6 +420,7 @@ def main():
                     help="time the pipeline transform stage (NCHW fp32 -> NHWC bf16) instead of a GEMM / conv workload")
     ap.add_argument("--widening", action="store_true",
                     help="time the rows beyond the headline workloads (fp8 GEMM, conv gradients, split-K) instead")
+    ap.add_argument("--only", default="", help="with --widening: only the workloads whose name contains this text")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run 10 plain device copies of 256 MiB and exit (reference reading for the "
                          "FETCH_SIZE / WRITE_SIZE counters)")

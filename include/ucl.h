@@ -147,7 +147,9 @@ typedef enum ucl_split_k_mode { UCL_SPLIT_K_NONE = 0, UCL_SPLIT_K_SERIAL = 1, UC
  * 64x64; the larger tiles' kernels have no registers to spare for the loop; see ucl_variant()).
  * STREAM_K: one workgroup per CU slot; as many whole rounds of tiles as the grid divides are walked
  * as under PERSISTENT, and the K extent of the remaining tiles is cut into 64-wide steps that are
- * dealt out evenly, so that a workgroup may compute parts of tiles.  Parts pass through the
+ * dealt out evenly, so that a workgroup may compute parts of tiles (fewer tiles than CU slots: no
+ * whole round, at most one workgroup per CU, and runs long enough that adding a tile's parts up
+ * does not take longer than computing them).  Parts pass through the
  * caller's workspace (as for split-K: ucl_workspace_size, ucl_workspace_init; two tile-sized slots
  * per workgroup behind the counters) and are added in k order by the workgroup that delivers a
  * tile's last part: results do not depend on timing.  Built for gemm and batched_gemm with 16-bit

@@ -439,7 +439,7 @@ struct SplitPlan {
     int k_per_slice = 0;
     int64_t bytes = 0;
     // stream-K: 64-wide k steps per tile, iterations per workgroup, workgroups (0: not a stream-K launch)
-    int sk_ipt = 0, sk_q = 0, sk_rounds = 0, sk_grid = 0;
+    int sk_ipt = 0, sk_q = 0, sk_rounds = 0, sk_grid = 0, sk_deal = 0;
 };
 
 ucl_status plan_split(const Launch &L, const VariantDesc &v, const ucl_tuning *tune, int64_t total_tiles, SplitPlan &sp) {
@@ -458,15 +458,30 @@ ucl_status plan_split(const Launch &L, const VariantDesc &v, const ucl_tuning *t
         if (all >= (1ll << 31)) return fail(UCL_ERR_UNSUPPORTED, "tiles x k steps exceeds 2^31");
         if (all == 0) return UCL_OK;
         // whole rounds of tiles go one tile per workgroup and round; the k steps of the tiles that are left are
-        // dealt out evenly.  Fewer tiles than CU slots: no whole round, and only as many workgroups as get k steps.
+        // dealt out evenly.  Fewer tiles than CU slots: no whole round, and only as many workgroups as it takes.
         const int64_t slots = (int64_t)kNumCUs * v.resident();
         int64_t grid = slots, rounds = total_tiles / slots;
         int64_t rest = (total_tiles - rounds * grid) * ipt, q = (rest + grid - 1) / grid;
         if (rounds == 0) {
+            // (one workgroup per CU at most, or per tile if there are more tiles than CUs)
+            if (grid > kNumCUs) grid = total_tiles > kNumCUs ? total_tiles : kNumCUs;
             if (grid > rest) grid = rest;
             q = (rest + grid - 1) / grid;
+            // The workgroup that ends a tile reads the tile's other parts back one after the other, which costs it
+            // about r k steps' time per part (measured: 1 for 64x64 tiles, whose parts are loaded several at a time,
+            // 9 for 128x128); a run of q steps and ipt / q parts to add make q = sqrt(r ipt) the shortest path
+            // through a tile.
+            const double r = (int64_t)v.tile_m * v.tile_n >= 128 * 128 ? 9.0 : 1.0;
+            const int64_t q_path = (int64_t)(sqrt(r * (double)ipt) + 0.5);
+            if (q < q_path) q = q_path;
+            if (q < 4) q = 4;
+            if (q > ipt) q = ipt;
+            // (a slightly longer run that divides the k steps of a tile: the runs can then be dealt k range by k range)
+            for (int64_t d = q; d <= q + q / 4; ++d)
+                if (ipt % d == 0) { q = d; break; }
             grid = (rest + q - 1) / q;
         }
+        if (q > 0 && ipt % q == 0 && (total_tiles - rounds * grid) * (ipt / q) <= grid) sp.sk_deal = (int)(total_tiles - rounds * grid);
         sp.sk_ipt = (int)ipt;
         sp.sk_q = (int)q;
         sp.sk_rounds = (int)rounds;
@@ -560,6 +575,7 @@ ucl_status run(const Launch &L, KParams &kp, const ucl_tuning *tune, void *strea
                         sp.sk_grid, v->tile_m, v->tile_n, (long long)sp.bytes, (long long)tune->workspace_bytes);
         kp.sk_ipt = sp.sk_ipt;
         kp.sk_q = sp.sk_q;
+        kp.sk_deal = sp.sk_deal;
         kp.sk_rounds = sp.sk_rounds;
         kp.ws_counters = (uint32_t *)tune->workspace;
         kp.ws_partials = (float *)((char *)tune->workspace + UCL_WORKSPACE_COUNTER_BYTES);

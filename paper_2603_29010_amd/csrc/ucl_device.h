@@ -62,6 +62,7 @@ struct KParams {
     // 2 = add up only
     int32_t split_k, k_per_slice, split_phase;
     int32_t sk_ipt, sk_q, sk_rounds;  // stream-K: 64-wide k steps per tile, k steps of the remaining tiles per workgroup, whole rounds
+    int32_t sk_deal;                  // stream-K: remaining tiles if sk_q divides sk_ipt (runs are dealt k range by k range), else 0
     float *ws_partials;
     uint32_t *ws_counters;
     EpiStepDev steps[UCL_MAX_EPI_STEPS];   // must stay addressable as offsetof(KParams, steps)
@@ -91,14 +92,26 @@ __host__ __device__ inline int xcd_remap(int wg, int total) {
 struct StreamKPiece {
     int tile;        // in the numbering that xcd_remap deals to the XCDs
     int rest_tile;   // index among the remaining tiles (-1: a whole tile of the first rounds)
-    int g;           // the workgroup's place in XCD-run order
+    int g;           // the workgroup's run (streamk_run)
     int k0, k1;      // 64-wide k steps [k0, k1) of the tile
 };
+// The run a workgroup takes: run g covers k steps [g * q, (g + 1) * q) of the remaining tiles.  Workgroups are
+// taken in XCD-run order (u).  Where q divides ipt every tile falls into the same ipt / q k ranges, and the runs are
+// dealt k range by k range: the workgroups of an XCD work on one k range of many tiles, which read the same
+// columns of A and B rows and share them in its L2 (tile by tile they would share nothing).  Bijective on [0, grid).
+__host__ __device__ inline int streamk_run(int wg, int grid, int deal_tiles, int ipt, int q) {
+    const int u = xcd_remap(wg, grid);
+    if (deal_tiles > 0) {
+        const int parts = ipt / q;
+        if (u < deal_tiles * parts) return (u % deal_tiles) * parts + u / deal_tiles;
+    }
+    return u;
+}
 #if defined(__HIPCC__)
-__device__ inline StreamKPiece streamk_piece(int done, int end, int rounds, int ipt, int q) {
+__device__ inline StreamKPiece streamk_piece(int done, int end, int rounds, int ipt, int q, int deal_tiles) {
     StreamKPiece pc;
     const int grid = (int)gridDim.x;
-    pc.g = xcd_remap((int)blockIdx.x, grid);
+    pc.g = streamk_run((int)blockIdx.x, grid, deal_tiles, ipt, q);
     if (done < rounds * ipt) {
         pc.tile = (done / ipt) * grid + (int)blockIdx.x;
         pc.rest_tile = -1;

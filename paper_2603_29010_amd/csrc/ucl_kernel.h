@@ -483,7 +483,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
     // Stream-K scheduler: as many whole rounds of tiles as the grid divides are walked like the persistent
     // scheduler walks them (sk_rounds tiles per workgroup: workgroups that run side by side work on neighbouring
     // tiles and share their operands in L2).  The (tile, 64-wide k range) pairs of the remaining tiles are numbered
-    // tile by tile and workgroup g (in XCD-run order) takes the sk_q of them from g * sk_q on.  The loop variable
+    // tile by tile and the workgroup with run g (streamk_run) takes the sk_q of them from g * sk_q on.  The loop variable
     // counts the k steps the workgroup has behind it (sk_ipt per whole tile); one pass of the loop body is one piece:
     // a whole tile ends in the epilogue as usual; a part of a tile goes to the workspace, and the workgroup that
     // delivers the last part of a tile adds the parts up in k order and runs the epilogue.
@@ -492,7 +492,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
     if constexpr (Cfg::STREAMK) {
         ConstKParams *p0 = (ConstKParams *)__builtin_amdgcn_kernarg_segment_ptr();
         const int rest = (p0->total_tiles - p0->sk_rounds * (int)gridDim.x) * p0->sk_ipt;     // k steps of the remaining tiles
-        const int mine0 = xcd_remap(blockIdx.x, gridDim.x) * p0->sk_q;
+        const int mine0 = streamk_run(blockIdx.x, gridDim.x, p0->sk_deal, p0->sk_ipt, p0->sk_q) * p0->sk_q;
         const int mine_n = rest - mine0 < p0->sk_q ? rest - mine0 : p0->sk_q;
         wg_first = 0;
         sk_end = p0->sk_rounds * p0->sk_ipt + (mine_n > 0 ? mine_n : 0);
@@ -530,7 +530,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
         }
     } else if constexpr (Cfg::STREAMK) {
         // (nothing of a piece is kept across the mainloop: streamk_piece works it out from the loop variable)
-        const StreamKPiece pc = streamk_piece(wg_id, sk_end, p.sk_rounds, p.sk_ipt, p.sk_q);
+        const StreamKPiece pc = streamk_piece(wg_id, sk_end, p.sk_rounds, p.sk_ipt, p.sk_q, p.sk_deal);
         t = xcd_remap(pc.tile, p.total_tiles);
         sk_k0 = pc.k0;
         sk_k1 = pc.k1;
@@ -1588,7 +1588,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
         // (the piece is worked out again from the loop variable rather than kept in registers across the mainloop)
         int it_again = wg_id;
         asm volatile("" : "+s"(it_again));
-        const StreamKPiece pc = streamk_piece(it_again, sk_end, p.sk_rounds, p.sk_ipt, p.sk_q);
+        const StreamKPiece pc = streamk_piece(it_again, sk_end, p.sk_rounds, p.sk_ipt, p.sk_q, p.sk_deal);
         const int k0_again = pc.k0, k1_again = pc.k1;
         if (k0_again != 0 || k1_again != p.sk_ipt) {
             constexpr int64_t kTileElems = (int64_t)TM * TN;
@@ -2139,7 +2139,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
         break;
     } else if constexpr (Cfg::STREAMK) {
         // the k steps of the piece are behind the workgroup
-        const StreamKPiece pe = streamk_piece(wg_id, sk_end, p.sk_rounds, p.sk_ipt, p.sk_q);
+        const StreamKPiece pe = streamk_piece(wg_id, sk_end, p.sk_rounds, p.sk_ipt, p.sk_q, p.sk_deal);
         wg_id += pe.k1 - pe.k0;
         if (wg_id >= sk_end) break;
         __syncthreads();

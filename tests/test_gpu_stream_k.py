@@ -85,6 +85,17 @@ def test_stream_k_exact_whole_rounds_only():
     assert counters_are_zero()
 
 
+@pytest.mark.parametrize("K", [1024, 960])
+def test_stream_k_exact_whole_rounds_and_a_few_tiles_left(K):
+    # 66 x 16 tiles of 64x64 (33 x 8 of 128x128): whole rounds of any grid of 256, 512 or 1024 workgroups and 32 (8)
+    # tiles left over, whose k steps are cut into short runs.  K = 1024: the runs divide a tile's 16 k steps and are
+    # dealt k range by k range; K = 960: 15 k steps, runs of two straddle tiles and are dealt tile by tile.
+    spec = synth.gemm_spec(4224, 1024, K, dt_out="f32", epilogue=(), integer=True)
+    for tile in built(0, scheduler=2):
+        parity.check_exact(spec, SK(*tile), label=f"stream-K rounds + rest, K={K} {tile}")
+    assert counters_are_zero()
+
+
 def test_stream_k_floating_point_with_epilogue_and_table_choice():
     spec = synth.gemm_spec(1100, 900, 1544, epilogue=("bias", "gelu_erf", "aux_load"))
     for tile in built(0, scheduler=2):
