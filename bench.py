@@ -51,7 +51,7 @@ WIDENING_TRAFFIC_BYTES = {
     "gemm_4096x4096x4096_fp8_e4m3_rowcol_bias_gelu_tanh_bf16out": 134654126,
     "gemm_4096x4096x4096_fp8_e5m2_rowcol_bias_gelu_tanh_bf16out": 134633431,
     "grouped_gemm_16groups_n4096_k1024_fp8_e4m3_silu_bf16out": 321418944,
-    "conv2d_dgrad_nhwc_32x56x56x64_from_128_3x3_bf16": 40420568,
+    "conv2d_dgrad_nhwc_32x56x56x64_from_128_3x3_bf16": 40370228,
     "conv2d_wgrad_nhwc_32x56x56x64_to_128_3x3_bf16_f32out_splitk_parallel": 77827573,
     "conv2d_wgrad_nhwc_32x56x56x64_to_128_3x3_bf16_f32out_splitk_serial": 66153438,
     "gemm_256x256x16384_bf16_bias_relu_no_split": 50682106,

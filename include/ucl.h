@@ -117,11 +117,12 @@ typedef struct ucl_epilogue {
     ucl_epi_step steps[UCL_MAX_EPI_STEPS];
 } ucl_epilogue;
 
-/* How conv2d_fprop reads the activations (`.with_iterator`).  ANALYTIC gathers every
- * filter tap from global memory and serves every geometry.  FIXED_STRIDE_DILATION
- * (3x3 filter, unit stride and dilation, pad 1, C = 64, W <= 58) copies the pixels a
- * tile needs into LDS once and reads all nine taps from there.  DEFAULT: the table
- * takes the second where it applies. */
+/* How conv2d_fprop reads the activations, and conv2d_dgrad the output gradient
+ * (`.with_iterator`).  ANALYTIC gathers every filter tap from global memory and serves
+ * every geometry.  FIXED_STRIDE_DILATION (3x3 filter, unit stride and dilation, pad 1,
+ * W <= 58; fprop: C = 64, dgrad: Kout = 128) copies the pixels a tile needs into LDS
+ * once and reads all nine taps from there.  DEFAULT: the table takes the second where it
+ * applies.  conv2d_wgrad accepts any valid value and ignores it. */
 typedef enum ucl_conv_iterator {
     UCL_ITER_DEFAULT = 0,
     UCL_ITER_ANALYTIC = 1,

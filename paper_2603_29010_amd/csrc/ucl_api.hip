@@ -37,7 +37,7 @@ ucl_status fail(ucl_status st, const char *fmt, ...) {
 const std::vector<VariantDesc> &all_variants() {
     static const std::vector<VariantDesc> v = [] {
         std::vector<VariantDesc> out;
-        for (VariantList l : {variants_gemm_kk_bf16_a(), variants_gemm_kk_bf16_b(), variants_gemm_kk_bf16_c(), variants_gemm_kk_bf16_d(), variants_gemm_kk_f16_a(), variants_gemm_kk_f16_b(), variants_gemm_mn_bf16(), variants_gemm_mn_f16(), variants_grouped_a(), variants_grouped_b(), variants_conv_a(), variants_conv_b(), variants_conv_f16(), variants_conv_halo(), variants_gemm_kn_bf16(), variants_gemm_kn_f16(), variants_gemm_mx_bf16(), variants_gemm_mx_f16(), variants_grouped_kn(), variants_conv_dgrad(), variants_conv_wgrad(), variants_gemm_kk_fp8(), variants_persistent(), variants_grouped_fp8_e4m3(), variants_grouped_fp8_e5m2(), variants_streamk()})
+        for (VariantList l : {variants_gemm_kk_bf16_a(), variants_gemm_kk_bf16_b(), variants_gemm_kk_bf16_c(), variants_gemm_kk_bf16_d(), variants_gemm_kk_f16_a(), variants_gemm_kk_f16_b(), variants_gemm_mn_bf16(), variants_gemm_mn_f16(), variants_grouped_a(), variants_grouped_b(), variants_conv_a(), variants_conv_b(), variants_conv_f16(), variants_conv_halo(), variants_gemm_kn_bf16(), variants_gemm_kn_f16(), variants_gemm_mx_bf16(), variants_gemm_mx_f16(), variants_grouped_kn(), variants_conv_dgrad(), variants_conv_dgrad_halo(), variants_conv_wgrad(), variants_gemm_kk_fp8(), variants_persistent(), variants_grouped_fp8_e4m3(), variants_grouped_fp8_e5m2(), variants_streamk()})
             for (int i = 0; i < l.n; ++i) out.push_back(l.v[i]);
         return out;
     }();
@@ -90,6 +90,14 @@ bool conv_patch_ok(int64_t W, int64_t C, int64_t R, int64_t S, int64_t pad_h, in
            dil_w == 1 && W + 1 <= 59;
 }
 
+// The data gradient of the same filter geometry reads a patch of the output gradient with mirrored taps; its
+// pixels hold Kout = 128 channels (P = H and Q = W follow from the geometry).
+bool dgrad_patch_ok(int64_t W, int64_t Kout, int64_t R, int64_t S, int64_t pad_h, int64_t pad_w, int64_t str_h,
+                    int64_t str_w, int64_t dil_h, int64_t dil_w) {
+    return Kout == 128 && R == 3 && S == 3 && pad_h == 1 && pad_w == 1 && str_h == 1 && str_w == 1 && dil_h == 1 &&
+           dil_w == 1 && W + 1 <= 59;
+}
+
 // Per-problem selection table: of the variants built for this (mode, input type, operand layouts)
 // take the one with the smallest estimated time
 //     ceil(tiles / 256) * ( tile FLOPs / (rate of a busy CU with this variant)
@@ -127,7 +135,9 @@ double relative_rate(const VariantDesc &v) {
     const bool two_buf = v.stages == 2 && v.tile_k == 64 && v.lb != 1 && v.la != 1;
     if (v.la == 1 || v.lb == 1) return area >= 128 * 128 ? 0.30 : 0.20;     // register-transposed operands
     const double nd = (v.lb == 4 ? 0.95 : 1.0) * (v.la == 5 ? 0.9 : 1.0);   // two LDS reads per fragment of a directly copied operand
-    if (v.la == 3) return 0.85;                                             // conv from a resident patch: above the gather kernels
+    // conv from a resident patch: above the gather kernels.  (The data gradient's 256-row tile is alone on its CU,
+    // with nothing to run while its 96 KB patch loads: measured 32 us against 27 us for the 128-row tile.)
+    if (v.la == 3) return v.mode == 3 && v.tile_m >= 256 ? 0.6 : 0.85;
     if (area >= 256 * 256) return nd * (two_buf ? 1.00 : v.stages >= 5 ? 0.92 : 0.90);
     if (area >= 256 * 128) return nd * (two_buf ? 0.81 : v.stages == 3 ? 0.80 : 0.73);
     // (with a directly copied operand the two-buffer loop of this size measured below the 4-stage one)
@@ -215,7 +225,7 @@ const VariantDesc *select_variant(const Launch &L, const ucl_tuning *tune) {
     for (const auto &v : vs) {
         if (v.mode != L.mode || v.dt != L.dt || v.persistent != want_persistent) continue;
         if (v.lb == 4 ? !(L.lb == 1 && L.ndirect_ok) : v.lb != L.lb) continue;
-        if (L.mode == 2) {
+        if (L.mode == 2 || L.mode == 3) {
             // conv: the iterator knob picks between the per-tap gather (la 2) and the resident patch (la 3)
             const int it = tune ? tune->iterator : 0;
             if (v.la == 3 ? (!L.patch_ok || it == UCL_ITER_ANALYTIC) : (v.la != 2 || it == UCL_ITER_FIXED_STRIDE_DILATION)) continue;
@@ -518,8 +528,8 @@ ucl_status run(const Launch &L, KParams &kp, const ucl_tuning *tune, void *strea
     if (tune && (tune->iterator < 0 || tune->iterator > UCL_ITER_FIXED_STRIDE_DILATION))
         return fail(UCL_ERR_INVALID_ARG, "iterator=%d is not a ucl_conv_iterator", tune->iterator);
     // (the GEMM entry points ignore the iterator)
-    if (tune && L.mode == 2 && tune->iterator == UCL_ITER_FIXED_STRIDE_DILATION && !L.patch_ok)
-        return fail(UCL_ERR_UNSUPPORTED, "the fixed_stride_dilation iterator serves conv2d_fprop with a 3x3 filter, unit stride and dilation, pad 1, 64 channels and W <= 58");
+    if (tune && (L.mode == 2 || L.mode == 3) && tune->iterator == UCL_ITER_FIXED_STRIDE_DILATION && !L.patch_ok)
+        return fail(UCL_ERR_UNSUPPORTED, "the fixed_stride_dilation iterator serves a 3x3 filter with unit stride and dilation, pad 1 and W <= 58: conv2d_fprop with 64 input channels, conv2d_dgrad with 128 output channels");
     const VariantDesc *v = select_variant(L, tune);
     if (!v) {
         if (tune && (tune->tile_m || tune->tile_n || tune->tile_k || tune->stages)) {
@@ -842,6 +852,8 @@ ucl_status launch_from_problem(const ucl_problem *p, Launch &L) {
     L.dtD = p->dt_out;
     if (L.mode == 2)
         L.patch_ok = conv_patch_ok(p->cW, p->cC, p->cR, p->cS, p->pad_h, p->pad_w, p->stride_h, p->stride_w, p->dil_h, p->dil_w);
+    if (L.mode == 3)
+        L.patch_ok = dgrad_patch_ok(p->cW, p->cKout, p->cR, p->cS, p->pad_h, p->pad_w, p->stride_h, p->stride_w, p->dil_h, p->dil_w);
     if (L.mode == 1)
         for (int g = 0; g < L.groups; ++g) L.sum_Mg += L.M_g[g];
     return UCL_OK;
@@ -1008,6 +1020,7 @@ ucl_status ucl_conv2d_dgrad(int64_t N, int64_t H, int64_t W, int64_t C, int64_t 
     if (!aligned16(dy) || !aligned16(w)) return fail(UCL_ERR_UNSUPPORTED, "dy and w must be 16-byte aligned");
     Launch L;
     L.mode = 3; L.M = M; L.N = C; L.K = Kg; L.la = 2; L.lb = 1; L.ndirect_ok = true; L.dt = dt_code(dtDy); L.dtD = dtDx;
+    L.patch_ok = dgrad_patch_ok(W, Kout, R, S, pad_h, pad_w, stride_h, stride_w, dil_h, dil_w);
     KParams kp;
     memset(&kp, 0, sizeof(kp));
     if (ucl_status st = check_epilogue(epi, L, kp)) return st;

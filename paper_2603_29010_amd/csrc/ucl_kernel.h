@@ -362,15 +362,18 @@ struct KernelCfg {
     static constexpr int KSTEPS = TK / 32;                        // MFMA k-steps (32 elements) per k-tile
     static constexpr bool HALO = LA_ == kHalo;
     // kHalo: the stage buffers hold B only; A is a resident patch of PATCH_ROWS pixels (rows of 64
-    // channels = 128 bytes) behind them, whose last row stays zero for padded taps to read.
+    // channels = 128 bytes; data gradient: rows of 128 channels of the output gradient = 256 bytes)
+    // behind them, whose last row stays zero for padded taps to read.
     static constexpr int A_BYTES = HALO ? 0 : TM * TK * 2, B_BYTES = TN * TK * 2;
     static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
     static constexpr int PIPE_BYTES = STAGES * STAGE_BYTES;
     static constexpr int HALO_MAX = 59;                           // pixels kept before and behind the tile's own
     static constexpr int PATCH_ROWS = TM + 2 * HALO_MAX + 2;      // a whole number of 8-row wave copies
-    static constexpr int PATCH_BYTES = HALO ? PATCH_ROWS * 128 : 0;
-    static_assert(PATCH_ROWS % 8 == 0, "one copy instruction of a wave fills 8 patch rows");
-    static_assert(!HALO || (TK == 32 && STAGES >= 3 && MODE_ == 2 && LB_ == kKContig), "patch kernels: pipelined loop, k-tiles of half a tap");
+    static constexpr int PATCH_ROW_BYTES = MODE_ == 3 ? 256 : 128;
+    static constexpr int PATCH_BYTES = HALO ? PATCH_ROWS * PATCH_ROW_BYTES : 0;
+    static_assert(PATCH_ROWS % 8 == 0, "one copy instruction of a wave fills a whole number of patch rows");
+    static_assert(!HALO || (TK == 32 && STAGES >= 3 && ((MODE_ == 2 && LB_ == kKContig) || (MODE_ == 3 && LB_ == kNDirect))),
+                  "patch kernels: pipelined loop, k-tiles of 32 channels of a tap");
     // epilogue staging: per wave 32 rows x (WTN + 4) fp32 (16 bytes of padding per row)
     static constexpr int EPI_LD = TN / 2 + 4;
     static constexpr int EPI_BYTES = 4 * 32 * EPI_LD * 4;
@@ -753,7 +756,16 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
     // stage row.  Per 16-row MFMA block and lane, one byte says for each of the eight outer taps
     // whether it leaves the image at the lane's pixel (first / last column, first / last row, and the
     // four corner combinations); such a tap reads the zero row.
-    constexpr int kPatchOff = Cfg::PIPE_BYTES, kZeroRow = Cfg::PIPE_BYTES + (Cfg::PATCH_ROWS - 1) * 128;
+    // Data gradient (same filter geometry): input pixel m reads gradient pixels m - dy*W - dx, the taps mirrored,
+    // from a patch of the output gradient whose pixels have 128 channels: rows of 256 bytes, sixteen chunks XORed
+    // with the row number (16 consecutive rows at one logical chunk then hit 16 different 16-byte slots), four
+    // k-tiles per tap.
+    constexpr int PRB = Cfg::PATCH_ROW_BYTES, PCPR = PRB / 16, KPT = PRB / 64, kTapSign = MODE == 3 ? -1 : 1;
+    auto patch_swz = [&](int r) __attribute__((always_inline)) -> int {
+        if constexpr (PCPR == 8) return lds_swz<8>(r);
+        else return r & 15;
+    };
+    constexpr int kPatchOff = Cfg::PIPE_BYTES, kZeroRow = Cfg::PIPE_BYTES + (Cfg::PATCH_ROWS - 1) * PRB;
     uint32_t h_flags[2] = {0u, 0u};                              // row blocks 0-3, 4-7
     int h_r0 = 0;
     if constexpr (LA == kHalo) {
@@ -771,7 +783,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
                                (wl || h0 ? 32u : 0u) | (w0 || hl ? 64u : 0u) | (wl || hl ? 128u : 0u);
             h_flags[blk >> 2] |= f << (8 * (blk & 3));
         }
-        constexpr int CHUNKS = Cfg::PATCH_ROWS * 8, SLOTS = (CHUNKS + kThreads - 1) / kThreads;
+        constexpr int CHUNKS = Cfg::PATCH_ROWS * PCPR, SLOTS = (CHUNKS + kThreads - 1) / kThreads;
         static_assert(MI <= 8, "one flag byte per row block");
         // rows the tile does not need (the last one among them: TM + 2 halo < PATCH_ROWS) are copied
         // from an out-of-range offset, i.e. zero-filled
@@ -779,29 +791,29 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
         for (int i = 0; i < SLOTS; ++i) {
             if (i * kThreads + wave * 64 < CHUNKS) {             // wave-uniform: the last slot may be partial
                 const int q = i * kThreads + tid;                // 16-byte slot of the patch
-                const int r = q >> 3;
-                const int chunk = (q & 7) ^ lds_swz<8>(r);
+                const int r = q / PCPR;
+                const int chunk = (q % PCPR) ^ patch_swz(r);
                 const int pix = m0 - halo + r;
                 const bool ok = pix >= 0 && pix < Mloc && r < TM + 2 * halo;
-                const uint32_t off = ok ? (uint32_t)(pix * 8 + chunk) * 16u : kOobOffset;
+                const uint32_t off = ok ? (uint32_t)(pix * PCPR + chunk) * 16u : kOobOffset;
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, UCL_LDS_PTR(smem + kPatchOff + (i * kThreads + wave * 64) * 16), 16, off, 0, 0, 0);
             }
         }
     }
-    // Patch addressing of k-tile KT (half a tap: 32 of the 64 channels; dy, dx and the half are
+    // Patch addressing of k-tile KT (32 of a tap's channels; dy, dx and the channel range are
     // compile-time): byte address of this lane's fragment chunk for row block 0.
     auto halo_base = [&](auto kt_) __attribute__((always_inline)) {
-        constexpr int KT_ = decltype(kt_)::value, tap = KT_ >> 1, dy = tap / 3 - 1, dx = tap % 3 - 1;
+        constexpr int KT_ = decltype(kt_)::value, tap = KT_ / KPT, dy = kTapSign * (tap / 3 - 1), dx = kTapSign * (tap % 3 - 1);
         const int r = h_r0 + dy * p.cW + dx;
-        const int chunk = ((KT_ & 1) << 2) | (lane >> 4);
-        return kPatchOff + r * 128 + ((chunk ^ lds_swz<8>(r)) << 4);
+        const int chunk = ((KT_ % KPT) << 2) | (lane >> 4);
+        return kPatchOff + r * PRB + ((chunk ^ patch_swz(r)) << 4);
     };
     // Fragment of row block BLK: one vector ALU instruction spreads the tap's flag bit over a register
     // (-1: the tap leaves the image at this lane's pixel), one merges the zero row's address in under
     // that mask, then the 128-bit LDS read.  Written as asm so that they stay where they are placed
     // between the MFMAs.
     auto halo_test = [&](auto kt_, auto blk_) __attribute__((always_inline)) -> int {
-        constexpr int KT_ = decltype(kt_)::value, BLK = decltype(blk_)::value, tap = KT_ >> 1, dy = tap / 3 - 1, dx = tap % 3 - 1;
+        constexpr int KT_ = decltype(kt_)::value, BLK = decltype(blk_)::value, tap = KT_ / KPT, dy = kTapSign * (tap / 3 - 1), dx = kTapSign * (tap % 3 - 1);
         constexpr int bit = dy == 0 ? (dx < 0 ? 0 : 1) : dx == 0 ? (dy < 0 ? 2 : 3) : 4 + (dx > 0 ? 1 : 0) + (dy > 0 ? 2 : 0);
         int dead = 0;
         if constexpr (dx != 0 || dy != 0)
@@ -809,11 +821,11 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
         return dead;
     };
     auto halo_read = [&](auto kt_, auto blk_, int base, int dead) __attribute__((always_inline)) {
-        constexpr int KT_ = decltype(kt_)::value, BLK = decltype(blk_)::value, tap = KT_ >> 1, dy = tap / 3 - 1, dx = tap % 3 - 1;
+        constexpr int KT_ = decltype(kt_)::value, BLK = decltype(blk_)::value, tap = KT_ / KPT, dy = kTapSign * (tap / 3 - 1), dx = kTapSign * (tap % 3 - 1);
         int addr = base;
-        if constexpr (dx != 0 || dy != 0)                        // the read adds BLK * 2048 as its immediate offset
-            asm volatile("v_bfi_b32 %0, %1, %2, %3" : "=v"(addr) : "v"(dead), "s"(kZeroRow - BLK * 2048), "v"(base));
-        return *(const u32x4_t *)(smem + addr + BLK * 2048);
+        if constexpr (dx != 0 || dy != 0)                        // the read adds BLK * 16 rows as its immediate offset
+            asm volatile("v_bfi_b32 %0, %1, %2, %3" : "=v"(addr) : "v"(dead), "s"(kZeroRow - BLK * 16 * PRB), "v"(base));
+        return *(const u32x4_t *)(smem + addr + BLK * 16 * PRB);
     };
 
     // Issue the copies of k-tile `kt` into stage buffer `buf`.  K-contiguous and im2col operands:
@@ -1284,11 +1296,11 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
             static_for<NI>([&](auto i) { keep_alive(bq[0][i]); keep_alive(bq[1][i]); });
         }
     } else if constexpr (LA == kHalo) {
-        // ---- resident patch: 18 k-tiles (9 taps x 2 channel halves), fully unrolled ------------------
+        // ---- resident patch: 18 k-tiles (9 taps x 2 channel halves; data gradient: 36), fully unrolled
         // The same ring of A fragments and two B sets as the pipelined loop below, with every buffer
         // index, tap offset and border test a compile-time constant; only B is copied (k-tile
         // kt + STAGES - 1 into the buffer released by the barrier of k-tile kt).
-        constexpr int KT_ALL = 18, RA = 4;
+        constexpr int KT_ALL = 9 * KPT, RA = 4;
         static_assert(MI % RA == 0 && KSTEPS == 1, "ring slots line up across k-tiles");
         u32x4_t ar[RA], bq[2][NI];
         static_for<STAGES - 1>([&](auto s_) { issue_tile(std::false_type{}, decltype(s_)::value, decltype(s_)::value); });
@@ -1328,7 +1340,7 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
                     } else if constexpr (sx == 1) {
                         if constexpr (a_any) ar[ia % RA] = halo_read(KA{}, BA{}, a_cur ? hb_c : hb_n, dead);
                     } else if constexpr (sx < 2 + nb) {
-                        bq[1 - PB][b0 + sx - 2] = frag(sn, b_frag_base, b0 + sx - 2, 0);
+                        bq[1 - PB][b0 + sx - 2] = fragB(sn, std::integral_constant<int, b0 + sx - 2>{}, 0);
                     } else {
                         issue_one(std::false_type{}, std::integral_constant<int, d0 + sx - 2 - nb>{}, kt + STAGES - 1,
                                   (kt + STAGES - 1) % STAGES);

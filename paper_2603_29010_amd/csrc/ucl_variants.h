@@ -49,6 +49,7 @@ VariantList variants_grouped_fp8_e4m3();
 VariantList variants_grouped_fp8_e5m2();
 VariantList variants_gemm_kk_fp8();
 VariantList variants_conv_dgrad();
+VariantList variants_conv_dgrad_halo();
 VariantList variants_conv_wgrad();
 
 }  // namespace ucl

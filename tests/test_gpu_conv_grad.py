@@ -35,6 +35,48 @@ def test_dgrad_exact_every_variant(geom):
     parity.check_exact(spec, None, label="dgrad table choice")
 
 
+# 3x3 / stride 1 / pad 1 / 128 output channels: geometries the resident-patch data-gradient kernels accept (the
+# output gradient of a tile held in LDS, taps mirrored).  Tiles that start and end mid-row and cross image
+# boundaries, one-pixel-wide and one-row-high images, the widest row the patch holds, ragged M and C tails;
+# the per-tap gather runs beside it.
+ANALYTIC, PATCH = 1, 2      # ucl_conv_iterator
+
+
+@pytest.mark.parametrize("geom", [
+    dict(Nb=3, H=13, W=11, C=72),
+    dict(Nb=2, H=20, W=58, C=64),
+    dict(Nb=5, H=1, W=1, C=8),
+    dict(Nb=2, H=9, W=1, C=24),
+    dict(Nb=2, H=1, W=37, C=136),
+    dict(Nb=7, H=6, W=6, C=16),
+    dict(Nb=1, H=56, W=56, C=64),
+])
+def test_dgrad_patch_iterator_exact(geom):
+    spec = synth.conv_grad_spec("dgrad", Ko=128, R=3, S=3, pad=(1, 1), dt_out="f32", integer=True, **geom)
+    for tile in built(3, la=3, lb=4):
+        parity.check_exact(spec, T(*tile, iterator=PATCH), label=f"dgrad patch {tile}")
+    parity.check_exact(spec, T(256, 64, 32, 4, iterator=ANALYTIC), label="dgrad gather")
+    parity.check_exact(spec, None, label="dgrad table choice")
+
+
+def test_dgrad_patch_iterator_parity_and_refusals():
+    g = dict(Nb=2, H=20, W=17, C=72, Ko=128, R=3, S=3, pad=(1, 1))
+    spec = synth.conv_grad_spec("dgrad", epilogue=("bias", "aux_load", "relu"), **g)
+    for tile in built(3, la=3, lb=4):
+        parity.check(spec, T(*tile, iterator=PATCH), label=f"dgrad patch epilogue {tile}")
+    spec16 = synth.conv_grad_spec("dgrad", dt_in="f16", dt_out="f16", epilogue=("gelu_tanh",), **g)
+    for tile in built(3, f16=1, la=3, lb=4):
+        parity.check(spec16, T(*tile, iterator=PATCH), label=f"dgrad f16 patch {tile}")
+    for kw in (dict(Ko=64), dict(R=1, S=1, pad=(0, 0)), dict(stride=(2, 2)), dict(dil=(2, 2), pad=(2, 2)), dict(W=59), dict(pad=(0, 0))):
+        gg = dict(Nb=1, H=8, W=8, C=16, Ko=128, R=3, S=3, pad=(1, 1))
+        gg.update(kw)
+        bad = synth.conv_grad_spec("dgrad", dt_out="f32", integer=True, **gg)
+        with pytest.raises(ucl.UclError) as e:
+            parity.gpu_result(bad, T(0, 0, 0, 0, iterator=PATCH))
+        assert e.value.status == "UCL_ERR_UNSUPPORTED" and "fixed_stride_dilation" in str(e.value)
+        parity.check_exact(bad, None, label=f"dgrad {kw}")
+
+
 @pytest.mark.parametrize("geom", GEOMS, ids=IDS)
 def test_wgrad_exact_every_variant(geom):
     spec = synth.conv_grad_spec("wgrad", dt_out="f32", integer=True, **geom)
