@@ -120,7 +120,7 @@ typedef struct ucl_epilogue {
 /* How conv2d_fprop reads the activations, and conv2d_dgrad the output gradient
  * (`.with_iterator`).  ANALYTIC gathers every filter tap from global memory and serves
  * every geometry.  FIXED_STRIDE_DILATION (3x3 filter, unit stride and dilation, pad 1,
- * W <= 58; fprop: C = 64, dgrad: Kout = 128) copies the pixels a tile needs into LDS
+ * W <= 58; fprop: C = 64 or 128, dgrad: Kout = 64 or 128) copies the pixels a tile needs into LDS
  * once and reads all nine taps from there.  DEFAULT: the table takes the second where it
  * applies.  conv2d_wgrad accepts any valid value and ignores it. */
 typedef enum ucl_conv_iterator {
@@ -401,6 +401,7 @@ typedef struct ucl_variant_info {
                                    4 / 5 direct copies of rows contiguous along N / M, read back transposed */
     int32_t lds_bytes;          /* LDS a workgroup of the variant occupies */
     int32_t scheduler;          /* ucl_tile_scheduler the variant is built for */
+    int32_t patch_channels;     /* resident-patch variants: channels per pixel they are built for (fprop: C, dgrad: Kout), else 0 */
 } ucl_variant_info;
 int32_t ucl_num_variants(void);
 ucl_status ucl_variant(int32_t i, ucl_variant_info *out);

@@ -62,7 +62,7 @@ class _Problem(C.Structure):
 
 class _VariantInfo(C.Structure):
     _fields_ = [(k, C.c_int32) for k in ("tile_m", "tile_n", "tile_k", "stages", "iterator", "op_class", "dt_in",
-                                         "a_layout", "b_layout", "a_path", "b_path", "lds_bytes", "scheduler")]
+                                         "a_layout", "b_layout", "a_path", "b_path", "lds_bytes", "scheduler", "patch_channels")]
 
 
 class _Hw(C.Structure):

@@ -77,25 +77,20 @@ struct Launch {
     int groups = 0;
     const int64_t *M_g = nullptr;
     int64_t max_Mg = 0, sum_Mg = 0;
-    bool patch_ok = false;        // conv: the problem fits the resident-patch kernels
+    int patch_c = 0;              // conv: the problem fits the resident-patch kernels built for pixels of this many channels (0: none)
     bool ndirect_ok = false;      // B contiguous along N and small enough for 32-bit byte offsets: direct-copy kernels apply
     bool mdirect_ok = false;      // the same for A contiguous along M
 };
 
-// The resident-patch conv kernels hold 64-channel pixels and address the taps of a 3x3 filter at unit
-// stride / dilation with one pad pixel, the image row (plus one pixel) on either side of a tile in LDS.
-bool conv_patch_ok(int64_t W, int64_t C, int64_t R, int64_t S, int64_t pad_h, int64_t pad_w, int64_t str_h,
-                   int64_t str_w, int64_t dil_h, int64_t dil_w) {
-    return C == 64 && R == 3 && S == 3 && pad_h == 1 && pad_w == 1 && str_h == 1 && str_w == 1 && dil_h == 1 &&
-           dil_w == 1 && W + 1 <= 59;
-}
-
-// The data gradient of the same filter geometry reads a patch of the output gradient with mirrored taps; its
-// pixels hold Kout = 128 channels (P = H and Q = W follow from the geometry).
-bool dgrad_patch_ok(int64_t W, int64_t Kout, int64_t R, int64_t S, int64_t pad_h, int64_t pad_w, int64_t str_h,
-                    int64_t str_w, int64_t dil_h, int64_t dil_w) {
-    return Kout == 128 && R == 3 && S == 3 && pad_h == 1 && pad_w == 1 && str_h == 1 && str_w == 1 && dil_h == 1 &&
-           dil_w == 1 && W + 1 <= 59;
+// The resident-patch conv kernels hold pixels of 64 or 128 channels and address the taps of a 3x3 filter at unit
+// stride / dilation with one pad pixel, the image row (plus one pixel) on either side of a tile in LDS.  fprop: the
+// pixels are those of the activations (C channels); data gradient: those of the output gradient (Kout channels;
+// P = H and Q = W follow from the geometry), taps mirrored.  Returns the channel count, 0 if the kernels do not apply.
+int conv_patch_channels(int64_t W, int64_t channels, int64_t R, int64_t S, int64_t pad_h, int64_t pad_w, int64_t str_h,
+                        int64_t str_w, int64_t dil_h, int64_t dil_w) {
+    const bool ok = (channels == 64 || channels == 128) && R == 3 && S == 3 && pad_h == 1 && pad_w == 1 && str_h == 1 &&
+                    str_w == 1 && dil_h == 1 && dil_w == 1 && W + 1 <= 59;
+    return ok ? (int)channels : 0;
 }
 
 // Per-problem selection table: of the variants built for this (mode, input type, operand layouts)
@@ -135,9 +130,9 @@ double relative_rate(const VariantDesc &v) {
     const bool two_buf = v.stages == 2 && v.tile_k == 64 && v.lb != 1 && v.la != 1;
     if (v.la == 1 || v.lb == 1) return area >= 128 * 128 ? 0.30 : 0.20;     // register-transposed operands
     const double nd = (v.lb == 4 ? 0.95 : 1.0) * (v.la == 5 ? 0.9 : 1.0);   // two LDS reads per fragment of a directly copied operand
-    // conv from a resident patch: above the gather kernels.  (The data gradient's 256-row tile is alone on its CU,
-    // with nothing to run while its 96 KB patch loads: measured 32 us against 27 us for the 128-row tile.)
-    if (v.la == 3) return v.mode == 3 && v.tile_m >= 256 ? 0.6 : 0.85;
+    // conv from a resident patch: above the gather kernels.  (A 256-row tile with 128-channel pixels is alone on its
+    // CU, with nothing to run while its 96 KB patch loads: measured 32 us against 27 us for the 128-row tile.)
+    if (v.la == 3) return 2 * v.lds_bytes > kLdsBytesPerCU ? 0.65 : 0.85;
     if (area >= 256 * 256) return nd * (two_buf ? 1.00 : v.stages >= 5 ? 0.92 : 0.90);
     if (area >= 256 * 128) return nd * (two_buf ? 0.81 : v.stages == 3 ? 0.80 : 0.73);
     // (with a directly copied operand the two-buffer loop of this size measured below the 4-stage one)
@@ -228,15 +223,17 @@ const VariantDesc *select_variant(const Launch &L, const ucl_tuning *tune) {
         if (L.mode == 2 || L.mode == 3) {
             // conv: the iterator knob picks between the per-tap gather (la 2) and the resident patch (la 3)
             const int it = tune ? tune->iterator : 0;
-            if (v.la == 3 ? (!L.patch_ok || it == UCL_ITER_ANALYTIC) : (v.la != 2 || it == UCL_ITER_FIXED_STRIDE_DILATION)) continue;
+            if (v.la == 3 ? (L.patch_c != v.patch_c || it == UCL_ITER_ANALYTIC) : (v.la != 2 || it == UCL_ITER_FIXED_STRIDE_DILATION)) continue;
         } else if (v.la == 5 ? !(L.la == 1 && L.mdirect_ok) : v.la != L.la) {
             continue;
         }
         if (explicit_tune) {
             if (v.tile_m != tune->tile_m || v.tile_n != tune->tile_n || v.stages != tune->stages || v.tile_k != tune->tile_k)
                 continue;
-            if (v.la == 3 || v.la == 5 || v.lb == 4) return &v;   // of two kernels with the named shape the patch / direct-copy one
-            if (!best) best = &v;
+            // of several kernels with the named shape: the resident-patch one, else a direct-copy one, else the first
+            if (v.la == 3) return &v;
+            const bool direct = v.la == 5 || v.lb == 4;
+            if (!best || (direct && !(best->la == 5 || best->lb == 4))) best = &v;
             continue;
         }
         const bool split = tune && tune->split_k_mode != UCL_SPLIT_K_NONE && tune->split_k_slices >= 0 && (L.mode == 0 || L.mode == 4);
@@ -528,8 +525,8 @@ ucl_status run(const Launch &L, KParams &kp, const ucl_tuning *tune, void *strea
     if (tune && (tune->iterator < 0 || tune->iterator > UCL_ITER_FIXED_STRIDE_DILATION))
         return fail(UCL_ERR_INVALID_ARG, "iterator=%d is not a ucl_conv_iterator", tune->iterator);
     // (the GEMM entry points ignore the iterator)
-    if (tune && (L.mode == 2 || L.mode == 3) && tune->iterator == UCL_ITER_FIXED_STRIDE_DILATION && !L.patch_ok)
-        return fail(UCL_ERR_UNSUPPORTED, "the fixed_stride_dilation iterator serves a 3x3 filter with unit stride and dilation, pad 1 and W <= 58: conv2d_fprop with 64 input channels, conv2d_dgrad with 128 output channels");
+    if (tune && (L.mode == 2 || L.mode == 3) && tune->iterator == UCL_ITER_FIXED_STRIDE_DILATION && !L.patch_c)
+        return fail(UCL_ERR_UNSUPPORTED, "the fixed_stride_dilation iterator serves a 3x3 filter with unit stride and dilation, pad 1 and W <= 58: conv2d_fprop with 64 or 128 input channels, conv2d_dgrad with 64 or 128 output channels");
     const VariantDesc *v = select_variant(L, tune);
     if (!v) {
         if (tune && (tune->tile_m || tune->tile_n || tune->tile_k || tune->stages)) {
@@ -851,9 +848,9 @@ ucl_status launch_from_problem(const ucl_problem *p, Launch &L) {
     L.dt = dt_code(p->dt_in);
     L.dtD = p->dt_out;
     if (L.mode == 2)
-        L.patch_ok = conv_patch_ok(p->cW, p->cC, p->cR, p->cS, p->pad_h, p->pad_w, p->stride_h, p->stride_w, p->dil_h, p->dil_w);
+        L.patch_c = conv_patch_channels(p->cW, p->cC, p->cR, p->cS, p->pad_h, p->pad_w, p->stride_h, p->stride_w, p->dil_h, p->dil_w);
     if (L.mode == 3)
-        L.patch_ok = dgrad_patch_ok(p->cW, p->cKout, p->cR, p->cS, p->pad_h, p->pad_w, p->stride_h, p->stride_w, p->dil_h, p->dil_w);
+        L.patch_c = conv_patch_channels(p->cW, p->cKout, p->cR, p->cS, p->pad_h, p->pad_w, p->stride_h, p->stride_w, p->dil_h, p->dil_w);
     if (L.mode == 1)
         for (int g = 0; g < L.groups; ++g) L.sum_Mg += L.M_g[g];
     return UCL_OK;
@@ -973,7 +970,7 @@ ucl_status ucl_conv2d_fprop(int64_t N, int64_t H, int64_t W, int64_t C, int64_t 
         return fail(UCL_ERR_UNSUPPORTED, "image extents / pads must be below 2^24");
     Launch L;
     L.mode = 2; L.M = M; L.N = Kout; L.K = Kg; L.la = 2; L.lb = 0; L.dt = dt_code(dtX); L.dtD = dtY;
-    L.patch_ok = conv_patch_ok(W, C, R, S, pad_h, pad_w, stride_h, stride_w, dil_h, dil_w);
+    L.patch_c = conv_patch_channels(W, C, R, S, pad_h, pad_w, stride_h, stride_w, dil_h, dil_w);
     KParams kp;
     memset(&kp, 0, sizeof(kp));
     if (ucl_status st = check_epilogue(epi, L, kp)) return st;
@@ -1020,7 +1017,7 @@ ucl_status ucl_conv2d_dgrad(int64_t N, int64_t H, int64_t W, int64_t C, int64_t 
     if (!aligned16(dy) || !aligned16(w)) return fail(UCL_ERR_UNSUPPORTED, "dy and w must be 16-byte aligned");
     Launch L;
     L.mode = 3; L.M = M; L.N = C; L.K = Kg; L.la = 2; L.lb = 1; L.ndirect_ok = true; L.dt = dt_code(dtDy); L.dtD = dtDx;
-    L.patch_ok = dgrad_patch_ok(W, Kout, R, S, pad_h, pad_w, stride_h, stride_w, dil_h, dil_w);
+    L.patch_c = conv_patch_channels(W, Kout, R, S, pad_h, pad_w, stride_h, stride_w, dil_h, dil_w);
     KParams kp;
     memset(&kp, 0, sizeof(kp));
     if (ucl_status st = check_epilogue(epi, L, kp)) return st;
@@ -1178,6 +1175,7 @@ ucl_status ucl_variant(int32_t i, ucl_variant_info *out) {
     out->b_layout = (v.lb == 1 || v.lb == 4) ? UCL_LAYOUT_MN_CONTIGUOUS : UCL_LAYOUT_K_CONTIGUOUS;
     out->a_path = v.la; out->b_path = v.lb;
     out->lds_bytes = v.lds_bytes;
+    out->patch_channels = v.patch_c;
     out->scheduler = v.persistent == 2 ? UCL_SCHED_STREAM_K : v.persistent ? UCL_SCHED_PERSISTENT : UCL_SCHED_DEFAULT;
     return UCL_OK;
 }

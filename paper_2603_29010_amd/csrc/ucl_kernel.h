@@ -40,8 +40,9 @@ typedef __attribute__((ext_vector_type(8))) uint32_t u32x8_t;
 #define UCL_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
 
 // kIm2col gathers every filter tap of the activations from global memory again; kHalo (3x3 filter,
-// unit stride and dilation, pad 1, 64 channels) copies the pixels a tile needs -- its rows plus one
-// image row and one pixel on either side -- into LDS once and reads every tap from there.
+// unit stride and dilation, pad 1, 64 or 128 channels) copies the pixels a tile needs -- its rows plus one
+// image row and one pixel on either side -- into LDS once and reads every tap from there (fprop: pixels
+// of the activations; dgrad: pixels of the output gradient, taps mirrored).
 // kNDirect (B only): B contiguous along N is copied row by row (k) straight into LDS like a
 // K-contiguous operand and the MFMA fragments -- 8 consecutive k per lane -- come out of the LDS
 // transpose read (ds_read_b64_tr_b16), so no register transpose and no 16-bit LDS writes are needed.
@@ -342,7 +343,8 @@ __device__ __forceinline__ void apply_step(float (&v)[8], const EpiStepDev &s, c
 // ------------------------------------------------------------------------------------------------
 
 template <int TM_, int TN_, int TK_, int STAGES_, int DT_ /*inputs: 0 bf16, 1 fp16, 2 fp8 e4m3, 3 fp8 e5m2*/, int MODE_ /*0 gemm+batched, 1 grouped, 2 conv fprop, 3 conv dgrad, 4 conv wgrad*/,
-          int LA_ /*OperandLayout of A*/, int LB_ /*OperandLayout of B*/, int SCHED_ = 0 /*tile scheduler: 0 default, 1 persistent, 2 stream-K*/>
+          int LA_ /*OperandLayout of A*/, int LB_ /*OperandLayout of B*/, int SCHED_ = 0 /*tile scheduler: 0 default, 1 persistent, 2 stream-K*/,
+          int PATCH_C_ = 0 /*kHalo: channels per pixel of the tensor the patch holds, 64 or 128 (0: 64 for fprop, 128 for dgrad)*/>
 struct KernelCfg {
     static constexpr int TM = TM_, TN = TN_, TK = TK_, STAGES = STAGES_, MODE = MODE_, LA = LA_, LB = LB_;
     static constexpr int SCHED = SCHED_;
@@ -361,15 +363,17 @@ struct KernelCfg {
     static constexpr int MI = WTM / 16, NI = WTN / 16;            // 16x16 MFMA blocks per wave
     static constexpr int KSTEPS = TK / 32;                        // MFMA k-steps (32 elements) per k-tile
     static constexpr bool HALO = LA_ == kHalo;
-    // kHalo: the stage buffers hold B only; A is a resident patch of PATCH_ROWS pixels (rows of 64
-    // channels = 128 bytes; data gradient: rows of 128 channels of the output gradient = 256 bytes)
-    // behind them, whose last row stays zero for padded taps to read.
+    // kHalo: the stage buffers hold B only; A is a resident patch of PATCH_ROWS pixels (rows of 64 or
+    // 128 channels = 128 or 256 bytes; fprop: activations, data gradient: the output gradient) behind
+    // them, whose last row stays zero for padded taps to read.
     static constexpr int A_BYTES = HALO ? 0 : TM * TK * 2, B_BYTES = TN * TK * 2;
     static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
     static constexpr int PIPE_BYTES = STAGES * STAGE_BYTES;
     static constexpr int HALO_MAX = 59;                           // pixels kept before and behind the tile's own
     static constexpr int PATCH_ROWS = TM + 2 * HALO_MAX + 2;      // a whole number of 8-row wave copies
-    static constexpr int PATCH_ROW_BYTES = MODE_ == 3 ? 256 : 128;
+    static constexpr int PATCH_C = PATCH_C_ ? PATCH_C_ : MODE_ == 3 ? 128 : 64;
+    static_assert(PATCH_C == 64 || PATCH_C == 128, "patch pixels of 64 or 128 channels");
+    static constexpr int PATCH_ROW_BYTES = PATCH_C * 2;
     static constexpr int PATCH_BYTES = HALO ? PATCH_ROWS * PATCH_ROW_BYTES : 0;
     static_assert(PATCH_ROWS % 8 == 0, "one copy instruction of a wave fills a whole number of patch rows");
     static_assert(!HALO || (TK == 32 && STAGES >= 3 && ((MODE_ == 2 && LB_ == kKContig) || (MODE_ == 3 && LB_ == kNDirect))),
@@ -756,10 +760,10 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
     // stage row.  Per 16-row MFMA block and lane, one byte says for each of the eight outer taps
     // whether it leaves the image at the lane's pixel (first / last column, first / last row, and the
     // four corner combinations); such a tap reads the zero row.
+    // Pixels of 128 channels: rows of 256 bytes, sixteen chunks XORed with the row number (16 consecutive rows at
+    // one logical chunk then hit 16 different 16-byte slots), four k-tiles per tap instead of two.
     // Data gradient (same filter geometry): input pixel m reads gradient pixels m - dy*W - dx, the taps mirrored,
-    // from a patch of the output gradient whose pixels have 128 channels: rows of 256 bytes, sixteen chunks XORed
-    // with the row number (16 consecutive rows at one logical chunk then hit 16 different 16-byte slots), four
-    // k-tiles per tap.
+    // from a patch of the output gradient.
     constexpr int PRB = Cfg::PATCH_ROW_BYTES, PCPR = PRB / 16, KPT = PRB / 64, kTapSign = MODE == 3 ? -1 : 1;
     auto patch_swz = [&](int r) __attribute__((always_inline)) -> int {
         if constexpr (PCPR == 8) return lds_swz<8>(r);

@@ -34,7 +34,7 @@ int resident_cfg() {
 template <class Cfg>
 constexpr VariantDesc describe() {
     return VariantDesc{Cfg::TM, Cfg::TN, Cfg::TK, Cfg::STAGES, Cfg::DT, Cfg::MODE, Cfg::LA, Cfg::LB,
-                       Cfg::LDS_BYTES, Cfg::SCHED, Cfg::MIN_WAVES, &launch_cfg<Cfg>, &resident_cfg<Cfg>};
+                       Cfg::LDS_BYTES, Cfg::SCHED, Cfg::MIN_WAVES, Cfg::HALO ? Cfg::PATCH_C : 0, &launch_cfg<Cfg>, &resident_cfg<Cfg>};
 }
 
 }  // namespace ucl

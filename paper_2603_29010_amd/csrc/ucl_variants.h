@@ -14,6 +14,7 @@ struct VariantDesc {
     int persistent;     // tile scheduler the kernel is built for: 0 one workgroup per tile, 1 persistent (grid = CU slots, workgroups
                         // walk the tile order), 2 stream-K (grid = CU slots, workgroups take equal runs of (tile, k range) iterations)
     int wgs_per_cu;     // workgroups of the kernel a CU is meant to hold (register budget it was built with)
+    int patch_c;        // resident-patch kernels: channels per pixel of the tensor the patch holds (64 or 128), else 0
     hipError_t (*launch)(const KParams &p, const GroupTable *gt, int grid, hipStream_t stream);
     int (*resident)();          // workgroups one CU holds at a time (queried from the runtime)
 };

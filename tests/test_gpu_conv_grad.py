@@ -59,6 +59,25 @@ def test_dgrad_patch_iterator_exact(geom):
     parity.check_exact(spec, None, label="dgrad table choice")
 
 
+@pytest.mark.parametrize("geom", [
+    dict(Nb=3, H=13, W=11, C=72),
+    dict(Nb=2, H=20, W=58, C=128),
+    dict(Nb=2, H=9, W=1, C=24),
+    dict(Nb=2, H=1, W=37, C=136),
+    dict(Nb=2, H=56, W=56, C=64),
+])
+def test_dgrad_patch_iterator_exact_64_channels(geom):
+    # an output gradient of 64 channels: patch rows of 128 bytes, two k-tiles per tap
+    spec = synth.conv_grad_spec("dgrad", Ko=64, R=3, S=3, pad=(1, 1), dt_out="f32", integer=True, **geom)
+    for tile in built(3, la=3, lb=4, patch_c=64):
+        parity.check_exact(spec, T(*tile, iterator=PATCH), label=f"dgrad patch, 64 channels {tile}")
+    parity.check_exact(spec, T(256, 64, 32, 4, iterator=ANALYTIC), label="dgrad gather")
+    parity.check_exact(spec, None, label="dgrad table choice")
+    spec16 = synth.conv_grad_spec("dgrad", Ko=64, R=3, S=3, pad=(1, 1), dt_in="f16", dt_out="f16", epilogue=("bias", "relu"), **geom)
+    for tile in built(3, f16=1, la=3, lb=4, patch_c=64):
+        parity.check(spec16, T(*tile, iterator=PATCH), label=f"dgrad f16 patch, 64 channels {tile}")
+
+
 def test_dgrad_patch_iterator_parity_and_refusals():
     g = dict(Nb=2, H=20, W=17, C=72, Ko=128, R=3, S=3, pad=(1, 1))
     spec = synth.conv_grad_spec("dgrad", epilogue=("bias", "aux_load", "relu"), **g)
@@ -67,7 +86,7 @@ def test_dgrad_patch_iterator_parity_and_refusals():
     spec16 = synth.conv_grad_spec("dgrad", dt_in="f16", dt_out="f16", epilogue=("gelu_tanh",), **g)
     for tile in built(3, f16=1, la=3, lb=4):
         parity.check(spec16, T(*tile, iterator=PATCH), label=f"dgrad f16 patch {tile}")
-    for kw in (dict(Ko=64), dict(R=1, S=1, pad=(0, 0)), dict(stride=(2, 2)), dict(dil=(2, 2), pad=(2, 2)), dict(W=59), dict(pad=(0, 0))):
+    for kw in (dict(Ko=32), dict(R=1, S=1, pad=(0, 0)), dict(stride=(2, 2)), dict(dil=(2, 2), pad=(2, 2)), dict(W=59), dict(pad=(0, 0))):
         gg = dict(Nb=1, H=8, W=8, C=16, Ko=128, R=3, S=3, pad=(1, 1))
         gg.update(kw)
         bad = synth.conv_grad_spec("dgrad", dt_out="f32", integer=True, **gg)

@@ -22,15 +22,17 @@ def T(tm, tn, tk, st, raster=0, iterator=0):
 ANALYTIC, PATCH = 1, 2      # ucl_conv_iterator
 
 
-def built(mode, f16=0, la=None, lb=0, dt=None, scheduler=0):
+def built(mode, f16=0, la=None, lb=0, dt=None, scheduler=0, patch_c=None):
     """(tile_m, tile_n, tile_k, stages) of every kernel variant built for a problem class and
-    tile scheduler (0: one workgroup per tile, 1: persistent)."""
+    tile scheduler (0: one workgroup per tile, 1: persistent); resident-patch variants (la 3): those for
+    pixels of `patch_c` channels (default: 64 for fprop, 128 for dgrad)."""
     la = (2 if mode == 2 else 0) if la is None else la
     dt = ("f16" if f16 else "bf16") if dt is None else dt
+    pc = 0 if la != 3 else patch_c if patch_c is not None else (64 if mode == 2 else 128)
     out = []
     for i in range(ucl.ucl_num_variants()):
         v = ucl.ucl_variant(i)
-        if (v["mode"], v["dt"], v["la"], v["lb"], v["scheduler"]) == (mode, dt, la, lb, scheduler):
+        if (v["mode"], v["dt"], v["la"], v["lb"], v["scheduler"], v["patch_channels"]) == (mode, dt, la, lb, scheduler, pc):
             out.append((v["tile_m"], v["tile_n"], v["tile_k"], v["stages"]))
     assert out
     return out
@@ -242,6 +244,25 @@ def test_conv_patch_iterator_exact(geom):
         parity.check_exact(spec, T(*tile, iterator=PATCH), label=f"conv patch {tile}")
     parity.check_exact(spec, T(256, 128, 32, 3, iterator=ANALYTIC), label="conv gather")
     parity.check_exact(spec, None, label="conv table choice")
+
+
+@pytest.mark.parametrize("geom", [
+    dict(Nb=3, H=13, W=11, Ko=72),
+    dict(Nb=2, H=20, W=58, Ko=64),
+    dict(Nb=2, H=9, W=1, Ko=24),
+    dict(Nb=2, H=1, W=37, Ko=136),
+    dict(Nb=4, H=28, W=28, Ko=128),
+])
+def test_conv_patch_iterator_exact_128_channels(geom):
+    # pixels of 128 channels: patch rows of 256 bytes, four k-tiles per tap
+    spec = synth.conv_spec(C=128, R=3, S=3, dt_out="f32", epilogue=(), integer=True, **geom)
+    for tile in built(2, la=3, patch_c=128):
+        parity.check_exact(spec, T(*tile, iterator=PATCH), label=f"conv patch, 128 channels {tile}")
+    parity.check_exact(spec, T(256, 128, 32, 3, iterator=ANALYTIC), label="conv gather")
+    parity.check_exact(spec, None, label="conv table choice")
+    spec16 = synth.conv_spec(C=128, R=3, S=3, dt_in="f16", dt_out="f16", epilogue=("bias", "relu"), **geom)
+    for tile in built(2, f16=1, la=3, patch_c=128):
+        parity.check(spec16, T(*tile, iterator=PATCH), label=f"conv f16 patch, 128 channels {tile}")
 
 
 def test_conv_patch_iterator_refuses_other_geometries():
