@@ -162,6 +162,16 @@ def test_resnet_stage_gradients_full_size():
     ws = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
     ucl.ucl_workspace_init(ws.data_ptr(), ws.numel(), torch.cuda.current_stream().cuda_stream)
     parity.check(spec, Tuning(split_k="serial", workspace=ws.data_ptr(), workspace_bytes=ws.numel()), label="wgrad 32x56x56 split-K")
+    # parallel mode (many slices, the reduction kernel stores dw itself) against serial mode with the same tile and
+    # slices: the same additions in the same order, so the same bits
+    from paper_2603_29010_amd.workload import DeviceWorkload
+    w = DeviceWorkload(spec)
+    out = {}
+    for mode in ("serial", "parallel"):
+        w.D.fill_(float("nan"))
+        w.run(tune=Tuning(128, 128, 32, 4, split_k=mode, slices=51, workspace=ws.data_ptr(), workspace_bytes=ws.numel()))
+        out[mode] = w.result_bits().copy()
+    assert np.isfinite(out["parallel"]).all() and np.array_equal(out["serial"], out["parallel"])
 
 
 def test_grad_validation():
