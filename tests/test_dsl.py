@@ -160,6 +160,13 @@ def test_scheduler_split_k_and_fp8_programs_run_through_the_translator():
     k.launch(M=200, N=136, K=1992, A=w.A.data_ptr(), B=w.B.data_ptr(), D=w.D.data_ptr(), stream=st,
              workspace=ws.data_ptr(), workspace_bytes=ws.numel())
     assert np.array_equal(w.result(), parity.orc_run.run(spec))
+    # the data gradient of a 3x3 convolution through the resident-patch iterator (128 output channels)
+    k = dsl.parse("""conv2d_dgrad(kernel_h=3, kernel_w=3).with_dtype(input=bf16, acc=fp32, output=fp32)
+        .with_iterator(fixed_stride_dilation)""")
+    spec = synth.conv_grad_spec("dgrad", Nb=2, H=13, W=11, C=24, Ko=128, R=3, S=3, pad=(1, 1), dt_out="f32", integer=True)
+    w = DeviceWorkload(spec)
+    k.launch(N=2, H=13, W=11, C=24, Kout=128, pad=(1, 1), A=w.A.data_ptr(), B=w.B.data_ptr(), D=w.D.data_ptr(), stream=st)
+    assert np.array_equal(w.result(), parity.orc_run.run(spec))
     # grouped GEMM on fp8 inputs
     k = dsl.parse("""grouped_gemm(expert_count=4).with_dtype(input=fp8_e4m3, acc=fp32, output=fp32)
         .with_layout(A=RowMajor, B=ColumnMajor, C=RowMajor)""")
