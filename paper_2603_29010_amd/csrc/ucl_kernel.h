@@ -1304,7 +1304,9 @@ __global__ __launch_bounds__(kThreads, Cfg::MIN_WAVES) void ucl_tile_kernel(cons
         // The same ring of A fragments and two B sets as the pipelined loop below, with every buffer
         // index, tap offset and border test a compile-time constant; only B is copied (k-tile
         // kt + STAGES - 1 into the buffer released by the barrier of k-tile kt).
-        constexpr int KT_ALL = 9 * KPT, RA = 4;
+        // (narrow wave tiles have two MFMAs per row block: a ring of four would request a fragment only 96 clocks
+        // ahead of its use, less than an LDS read takes under load)
+        constexpr int KT_ALL = 9 * KPT, RA = NI <= 2 && MI % 8 == 0 ? 8 : 4;
         static_assert(MI % RA == 0 && KSTEPS == 1, "ring slots line up across k-tiles");
         u32x4_t ar[RA], bq[2][NI];
         static_for<STAGES - 1>([&](auto s_) { issue_tile(std::false_type{}, decltype(s_)::value, decltype(s_)::value); });
