@@ -104,3 +104,34 @@ def test_split_k_pick_is_near_the_fastest_built_variant(name, mode):
         times[best] = max(times[best], time_us(w, tune(*best)))
     assert t_pick <= 1.15 * times[best], (f"{name} ({mode}): the library's choice runs {t_pick:.1f} us, {best} runs {times[best]:.1f} us; all: " +
                                           ", ".join(f"{k}: {v:.1f}" for k, v in sorted(times.items(), key=lambda kv: kv[1])))
+
+
+CONV_SHAPES = {
+    "fprop 32x56x56, 64 -> 128": (lambda: synth.config(5), 2),
+    "fprop 32x28x28, 128 -> 128": (lambda: synth.conv_spec(Nb=32, H=28, W=28, C=128, Ko=128, R=3, S=3), 2),
+    "dgrad 32x56x56, 64 <- 128": (lambda: synth.conv_grad_spec("dgrad", Nb=32, H=56, W=56, C=64, Ko=128, R=3, S=3, pad=(1, 1)), 3),
+    "dgrad 32x56x56, 64 <- 64": (lambda: synth.conv_grad_spec("dgrad", Nb=32, H=56, W=56, C=64, Ko=64, R=3, S=3, pad=(1, 1)), 3),
+}
+
+
+@pytest.mark.parametrize("name", list(CONV_SHAPES))
+def test_conv_pick_is_near_the_fastest_built_variant(name):
+    # 3x3 convolutions that the resident-patch kernels serve: the table chooses between them and the per-tap gather kernels
+    make, mode = CONV_SHAPES[name]
+    spec = make()
+    w = DeviceWorkload(spec, poison=False)
+    spin_up(w)
+    channels = spec["C"] if mode == 2 else spec["Ko"]
+    lb = 0 if mode == 2 else 4
+    times = {}
+    for tile in built(mode, la=2, lb=lb):
+        times[tile + ("gather",)] = time_us(w, Tuning(*tile, iterator=1))
+    for tile in built(mode, la=3, lb=lb, patch_c=channels):
+        times[tile + ("patch",)] = time_us(w, Tuning(*tile, iterator=2))
+    t_pick = time_us(w, None)
+    best = min(times, key=times.get)
+    if t_pick > 1.15 * times[best]:
+        t_pick = min(t_pick, time_us(w, None))
+        times[best] = max(times[best], time_us(w, Tuning(*best[:4], iterator=1 if best[4] == "gather" else 2)))
+    assert t_pick <= 1.15 * times[best], (f"{name}: the table's choice {w.selected()} runs {t_pick:.1f} us, {best} runs {times[best]:.1f} us; all: " +
+                                          ", ".join(f"{k}: {v:.1f}" for k, v in sorted(times.items(), key=lambda kv: kv[1])))
