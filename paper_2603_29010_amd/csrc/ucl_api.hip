@@ -169,10 +169,17 @@ constexpr int kNumCUs = 256;
 
 // Slices a split-K launch of `total_tiles` tiles gets: as asked for, or (0) enough to give every CU a workgroup
 // while each keeps at least 4 x 64 of K; slices are whole multiples of 64 along K.
-void split_slices(const Launch &L, int64_t want, int64_t total_tiles, int &slices, int &k_per_slice) {
+// The weight gradient in parallel mode gets two workgroups per CU where the variant fits twice: its gathered operand
+// leaves a lone workgroup waiting (measured 36.7 -> 32.6 us on 32x56x56x64 -> 128), and the streaming reduction
+// kernel takes the extra partial tiles in its stride; the GEMMs measured best with one (256x256x16384: 15.0 us with
+// 16 slices, 16.9 with 32).
+int split_fill(const Launch &L, const VariantDesc &v, const ucl_tuning *tune) {
+    return L.mode == 4 && tune->split_k_mode == UCL_SPLIT_K_PARALLEL && workgroups_per_cu(v) >= 2 ? 2 * kNumCUs : kNumCUs;
+}
+void split_slices(const Launch &L, int64_t want, int64_t total_tiles, int fill, int &slices, int &k_per_slice) {
     const int64_t kt = (L.K + 63) / 64;
     if (want == 0) {
-        want = total_tiles >= kNumCUs ? 1 : (kNumCUs + total_tiles - 1) / total_tiles;
+        want = total_tiles >= fill ? 1 : (fill + total_tiles - 1) / total_tiles;
         if (want > kt / 4) want = kt / 4;
         if (want < 1) want = 1;
     }
@@ -193,7 +200,7 @@ void split_slices(const Launch &L, int64_t want, int64_t total_tiles, int &slice
 double estimate_split_seconds(const VariantDesc &v, const Launch &L, const ucl_tuning *tune) {
     const int64_t tiles = count_tiles(L, v.tile_m, v.tile_n);
     int slices = 1, kps = 0;
-    split_slices(L, tune->split_k_slices, tiles, slices, kps);
+    split_slices(L, tune->split_k_slices, tiles, split_fill(L, v, tune), slices, kps);
     if (slices <= 1) return estimate_seconds(v, L);
     const double wgs = (double)tiles * slices;
     const double rounds = ceil(wgs / (256.0 * workgroups_per_cu(v)));
@@ -509,7 +516,7 @@ ucl_status plan_split(const Launch &L, const VariantDesc &v, const ucl_tuning *t
     if (L.mode != 0 && L.mode != 4) return fail(UCL_ERR_UNSUPPORTED, "split-K is built for gemm, batched_gemm and conv2d_wgrad");
     if (tune->scheduler == UCL_SCHED_PERSISTENT)
         return fail(UCL_ERR_UNSUPPORTED, "split-K and the persistent scheduler cannot be combined");
-    split_slices(L, tune->split_k_slices, total_tiles, sp.slices, sp.k_per_slice);
+    split_slices(L, tune->split_k_slices, total_tiles, split_fill(L, v, tune), sp.slices, sp.k_per_slice);
     if (sp.slices <= 1) { sp = SplitPlan(); return UCL_OK; }
     if (total_tiles > UCL_SPLIT_K_MAX_TILES)
         return fail(UCL_ERR_UNSUPPORTED, "split-K serves at most %d output tiles (this problem has %lld)", UCL_SPLIT_K_MAX_TILES, (long long)total_tiles);
