@@ -380,25 +380,39 @@ __global__ void zero_words_kernel(uint32_t *w) {
 // slice 0, slice 0 first (the same order, starting from +0, as the tile kernel's own loop: the results are
 // bit-identical).  A tile kernel that did this itself would have one workgroup per tile read all slices of its
 // tile; here every 16 bytes of a tile are a thread's work, so that the whole chip streams the partial tiles.
-// `slice_stride` = floats per slice (tiles x tile elements), `n4` = 16-byte words per slice.
-__global__ __launch_bounds__(256) void splitk_reduce_kernel(float *partials, int64_t slice_stride, int slices, int64_t n4) {
-    typedef float f32x4 __attribute__((ext_vector_type(4)));
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= n4) return;
-    const f32x4 *src = (const f32x4 *)partials + i;
-    const int64_t stride4 = slice_stride / 4;
-    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    int s = 0;
-    for (; s + 8 <= slices; s += 8) {
-        f32x4 v[8];
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+// (sixteen, then eight slices' loads in flight per thread: what the kernel moves per microsecond is what it has in
+// flight; the additions stay in slice order.  V = f32x4, or float where 16-byte words would make too few workgroups
+// to occupy the chip: the same additions per element either way.)
+template <int U, class V>
+__device__ inline void sum_slices(const V *src, int64_t stride, int slices, int &s, V &acc) {
+    for (; s + U <= slices; s += U) {
+        V v[U];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load(src + (s + u) * stride4);
+        for (int u = 0; u < U; ++u) v[u] = __builtin_nontemporal_load(src + (s + u) * stride);
 #pragma unroll
-        for (int u = 0; u < 8; ++u) acc += v[u];
+        for (int u = 0; u < U; ++u) acc += v[u];
     }
-    for (; s < slices; ++s) acc += __builtin_nontemporal_load(src + s * stride4);
-    ((f32x4 *)partials)[i] = acc;
 }
+template <class V>
+__device__ inline V sum_slices(const V *src, int64_t stride, int slices) {
+    V acc = V();                     // +0 in every element
+    int s = 0;
+    sum_slices<16>(src, stride, slices, s, acc);
+    sum_slices<8>(src, stride, slices, s, acc);
+    sum_slices<1>(src, stride, slices, s, acc);
+    return acc;
+}
+// `slice_stride` = floats per slice, `n` = elements of type V per slice
+template <class V>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(float *partials, int64_t slice_stride, int slices, int64_t n) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    constexpr int kPer = sizeof(V) / 4;
+    ((V *)partials)[i] = sum_slices((const V *)partials + i, slice_stride / kPer, slices);
+}
+// Words of 16 bytes per slice below which the reduction runs one float per thread (fewer than two workgroups per CU otherwise).
+constexpr int64_t kReduceScalarBelow = 2 * 256 * 256;
 
 // The same reduction for launches whose chain is empty and whose output is fp32: the sums are the result, so they are
 // stored to D directly and the finishing launch of the tile kernel is not needed.  A 16-byte word of a partial tile
@@ -411,22 +425,14 @@ struct ReduceStore {
     int64_t slice_stride, n4, ldd, d_bs;
     int32_t slices, tile_m, tile_n, M, N, tiles_m, tiles_n, tiles_per_batch, raster;
 };
+template <class V>
 __global__ __launch_bounds__(256) void splitk_reduce_store_kernel(const ReduceStore a) {
-    typedef float f32x4 __attribute__((ext_vector_type(4)));
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= a.n4) return;
-    const f32x4 *src = (const f32x4 *)a.partials + i;
-    const int64_t stride4 = a.slice_stride / 4;
-    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    int s = 0;
-    for (; s + 8 <= a.slices; s += 8) {
-        f32x4 v[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load(src + (s + u) * stride4);
-#pragma unroll
-        for (int u = 0; u < 8; ++u) acc += v[u];
-    }
-    for (; s < a.slices; ++s) acc += __builtin_nontemporal_load(src + s * stride4);
+    constexpr int kPer = sizeof(V) / 4;                // 4: a thread per 16-byte word, 1: a thread per element
+    const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (j >= a.n4 * (4 / kPer)) return;
+    const V acc = sum_slices((const V *)a.partials + j, a.slice_stride / kPer, a.slices);
+    const int64_t i = kPer == 4 ? j : j >> 2;          // the 16-byte word
+    const int e0 = kPer == 4 ? 0 : (int)(j & 3);       // the thread's (first) element in it
     const int words_per_tile = a.tile_m * a.tile_n / 4, ni_count = a.tile_n / 32;
     int t = (int)(i / words_per_tile);
     const int w = (int)(i - (int64_t)t * words_per_tile);
@@ -438,12 +444,16 @@ __global__ __launch_bounds__(256) void splitk_reduce_store_kernel(const ReduceSt
     int tm, tn;
     band_raster(t, a.tiles_m, a.tiles_n, a.raster, tm, tn);
     const int m = tm * a.tile_m + m_loc, n = tn * a.tile_n + n_loc;
-    if (m >= a.M || n >= a.N) return;
+    if (m >= a.M || n + e0 >= a.N) return;
     float *dst = a.D + (int64_t)batch * a.d_bs + (int64_t)m * a.ldd + n;
-    if (n + 4 <= a.N) {
-        *(f32x4 *)dst = acc;
+    if constexpr (kPer == 4) {
+        if (n + 4 <= a.N) {
+            *(f32x4 *)dst = acc;
+        } else {
+            for (int e = 0; e < a.N - n; ++e) dst[e] = acc[e];
+        }
     } else {
-        for (int e = 0; e < a.N - n; ++e) dst[e] = acc[e];
+        dst[e0] = acc;
     }
 }
 
@@ -637,10 +647,16 @@ ucl_status run(const Launch &L, KParams &kp, const ucl_tuning *tune, void *strea
                 rs.slice_stride = slice_floats; rs.n4 = n4; rs.ldd = kp.ldd; rs.d_bs = kp.d_bs;
                 rs.slices = sp.slices; rs.tile_m = v->tile_m; rs.tile_n = v->tile_n; rs.M = kp.M; rs.N = kp.N;
                 rs.tiles_m = kp.tiles_m; rs.tiles_n = kp.tiles_n; rs.tiles_per_batch = kp.tiles_per_batch; rs.raster = kp.raster;
-                hipLaunchKernelGGL(splitk_reduce_store_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, (hipStream_t)stream, rs);
+                if (n4 < kReduceScalarBelow)
+                    hipLaunchKernelGGL(splitk_reduce_store_kernel<float>, dim3((unsigned)((slice_floats + 255) / 256)), dim3(256), 0, (hipStream_t)stream, rs);
+                else
+                    hipLaunchKernelGGL(splitk_reduce_store_kernel<f32x4>, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, (hipStream_t)stream, rs);
                 finished = true;
+            } else if (n4 < kReduceScalarBelow) {
+                hipLaunchKernelGGL(splitk_reduce_kernel<float>, dim3((unsigned)((slice_floats + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
+                                   kp.ws_partials, slice_floats, sp.slices, slice_floats);
             } else {
-                hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
+                hipLaunchKernelGGL(splitk_reduce_kernel<f32x4>, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
                                    kp.ws_partials, slice_floats, sp.slices, n4);
             }
             e = hipGetLastError();
