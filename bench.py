@@ -55,7 +55,7 @@ WIDENING_TRAFFIC_BYTES = {
     "conv2d_wgrad_nhwc_32x56x56x64_to_128_3x3_bf16_f32out_splitk_parallel": 106911202,
     "conv2d_wgrad_nhwc_32x56x56x64_to_128_3x3_bf16_f32out_splitk_serial": 66153438,
     "gemm_256x256x16384_bf16_bias_relu_no_split": 50682106,
-    "gemm_256x256x16384_bf16_bias_relu_splitk_parallel": 26219893,
+    "gemm_256x256x16384_bf16_bias_relu_splitk_parallel": 25526644,
     "gemm_256x256x16384_bf16_bias_relu_splitk_serial": 25507331,
     "gemm_8192x8192x64_bf16_bias_relu_tile128_default_scheduler": 144121094,
     "gemm_256x256x16384_bf16_bias_relu_tile64_stream_k_scheduler": 25561483,

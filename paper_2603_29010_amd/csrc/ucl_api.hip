@@ -8,6 +8,7 @@
 
 #include <mutex>
 
+#include "ucl_kernel.h"      // the epilogue's element-wise arithmetic (the split-K reduction kernel finishes simple chains itself)
 #include "ucl_variants.h"
 
 // Split-K workspace of ucl_gemm_static_workspace: counters followed by partial tiles, held by every
@@ -414,16 +415,20 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(float *partials, int
 // Words of 16 bytes per slice below which the reduction runs one float per thread (fewer than two workgroups per CU otherwise).
 constexpr int64_t kReduceScalarBelow = 2 * 256 * 256;
 
-// The same reduction for launches whose chain is empty and whose output is fp32: the sums are the result, so they are
-// stored to D directly and the finishing launch of the tile kernel is not needed.  A 16-byte word of a partial tile
-// is accumulator (mi, ni) of one lane: four consecutive columns of one row (the layout the tile kernel stores:
-// word = (mi * NI + ni) * 256 + thread; thread = wave * 64 + lane, wave = (row half, column half) of the tile;
-// row = mi * 16 + lane % 16, column = ni * 16 + 4 * (lane / 16) inside the wave's quarter).
+// The same reduction for launches whose chain has the form act(alpha * acc + bias[n]) (the empty chain included): the
+// reduction kernel runs the chain on the sums, with the tile kernel's own element-wise functions and in its order of
+// operations (so the bits are the same), and stores D; the finishing launch of the tile kernel is not needed.
+// A 16-byte word of a partial tile is accumulator (mi, ni) of one lane: four consecutive columns of one row (the
+// layout the tile kernel stores: word = (mi * NI + ni) * 256 + thread; thread = wave * 64 + lane, wave = (row half,
+// column half) of the tile; row = mi * 16 + lane % 16, column = ni * 16 + 4 * (lane / 16) inside the wave's quarter).
 struct ReduceStore {
     float *partials;
-    float *D;
+    void *D;
+    const void *bias;
     int64_t slice_stride, n4, ldd, d_bs;
     int32_t slices, tile_m, tile_n, M, N, tiles_m, tiles_n, tiles_per_batch, raster;
+    int32_t dtD, has_bias, bias_dt, act;
+    float alpha, act_p0, act_p1;
 };
 template <class V>
 __global__ __launch_bounds__(256) void splitk_reduce_store_kernel(const ReduceStore a) {
@@ -443,17 +448,65 @@ __global__ __launch_bounds__(256) void splitk_reduce_store_kernel(const ReduceSt
     t -= batch * a.tiles_per_batch;
     int tm, tn;
     band_raster(t, a.tiles_m, a.tiles_n, a.raster, tm, tn);
-    const int m = tm * a.tile_m + m_loc, n = tn * a.tile_n + n_loc;
-    if (m >= a.M || n + e0 >= a.N) return;
-    float *dst = a.D + (int64_t)batch * a.d_bs + (int64_t)m * a.ldd + n;
-    if constexpr (kPer == 4) {
-        if (n + 4 <= a.N) {
-            *(f32x4 *)dst = acc;
-        } else {
-            for (int e = 0; e < a.N - n; ++e) dst[e] = acc[e];
+    const int m = tm * a.tile_m + m_loc, n = tn * a.tile_n + n_loc + e0;
+    if (m >= a.M || n >= a.N) return;
+    const int nvalid = a.N - n < kPer ? a.N - n : kPer;
+    float x[kPer];
+#pragma unroll
+    for (int e = 0; e < kPer; ++e) {
+        float b = 0.f;
+        if (a.has_bias && e < nvalid)
+            b = a.bias_dt == UCL_F32 ? ((const float *)a.bias)[n + e] : bits_to_f32(((const uint16_t *)a.bias)[n + e], a.bias_dt);
+        float s;
+        if constexpr (kPer == 4) s = acc[e]; else s = acc;
+        x[e] = s * a.alpha + b;
+    }
+    switch (a.act) {
+#define UCL_ACT_CASE(OP)                                                                                      \
+    case OP:                                                                                                  \
+        _Pragma("unroll") for (int e = 0; e < kPer; ++e) x[e] = act_f32<OP>(x[e], a.act_p0, a.act_p1);         \
+        break;
+        UCL_ACT_CASE(UCL_EPI_RELU)
+        UCL_ACT_CASE(UCL_EPI_GELU_TANH)
+        UCL_ACT_CASE(UCL_EPI_GELU_ERF)
+        UCL_ACT_CASE(UCL_EPI_SILU)
+        UCL_ACT_CASE(UCL_EPI_SIGMOID)
+        UCL_ACT_CASE(UCL_EPI_TANH)
+        UCL_ACT_CASE(UCL_EPI_MISH)
+        UCL_ACT_CASE(UCL_EPI_HARDSWISH)
+        UCL_ACT_CASE(UCL_EPI_LEAKY_RELU)
+        UCL_ACT_CASE(UCL_EPI_ELU)
+        UCL_ACT_CASE(UCL_EPI_CLAMP)
+#undef UCL_ACT_CASE
+    default: break;
+    }
+    const int64_t at = (int64_t)batch * a.d_bs + (int64_t)m * a.ldd + n;
+    if (a.dtD == UCL_F32) {
+        float *dst = (float *)a.D + at;
+        if constexpr (kPer == 4) {
+            if (nvalid == 4) {
+                *(f32x4 *)dst = f32x4{x[0], x[1], x[2], x[3]};
+                return;
+            }
         }
+#pragma unroll
+        for (int e = 0; e < kPer; ++e)
+            if (e < nvalid) dst[e] = x[e];
     } else {
-        dst[e0] = acc;
+        uint16_t *dst = (uint16_t *)a.D + at;
+        uint32_t bits[kPer];
+#pragma unroll
+        for (int e = 0; e < kPer; ++e) bits[e] = f32_to_bits16(x[e], a.dtD);
+        if constexpr (kPer == 4) {
+            if (nvalid == 4) {
+                typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+                *(u32x2 *)dst = u32x2{bits[0] | (bits[1] << 16), bits[2] | (bits[3] << 16)};
+                return;
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < kPer; ++e)
+            if (e < nvalid) dst[e] = (uint16_t)bits[e];
     }
 }
 
@@ -639,11 +692,13 @@ ucl_status run(const Launch &L, KParams &kp, const ucl_tuning *tune, void *strea
         if (e == hipSuccess && sp.slices > kReduceInTileKernel) {
             // many slices: a launch of its own adds them up with the whole chip, the last launch then finds one slice
             const int64_t slice_floats = total * v->tile_m * v->tile_n, n4 = slice_floats / 4;
-            const bool plain = kp.n_steps == 0 && kp.dtD == UCL_F32 && kp.d_vec && L.mode != 1;
-            if (plain) {
-                // ... or none: an empty chain and an fp32 output, the sums go to D as they are
+            const bool simple = kp.fused.enabled && !kp.fused.has_res && kp.d_vec && L.mode != 1;
+            if (simple) {
+                // ... or none: a chain of the form act(alpha * acc + bias[n]) is run by the reduction kernel on the sums
                 ReduceStore rs;
-                rs.partials = kp.ws_partials; rs.D = (float *)kp.D;
+                rs.partials = kp.ws_partials; rs.D = kp.D; rs.bias = kp.fused.bias;
+                rs.dtD = kp.dtD; rs.has_bias = kp.fused.has_bias; rs.bias_dt = kp.fused.bias_dt & 0xff; rs.act = kp.fused.act;
+                rs.alpha = kp.fused.has_scale ? kp.fused.alpha : 1.f; rs.act_p0 = kp.fused.act_p0; rs.act_p1 = kp.fused.act_p1;
                 rs.slice_stride = slice_floats; rs.n4 = n4; rs.ldd = kp.ldd; rs.d_bs = kp.d_bs;
                 rs.slices = sp.slices; rs.tile_m = v->tile_m; rs.tile_n = v->tile_n; rs.M = kp.M; rs.N = kp.N;
                 rs.tiles_m = kp.tiles_m; rs.tiles_n = kp.tiles_n; rs.tiles_per_batch = kp.tiles_per_batch; rs.raster = kp.raster;

@@ -93,6 +93,32 @@ def test_split_k_parallel_plain_f32_padded_rows():
     assert counters_are_zero()
 
 
+@pytest.mark.parametrize("dt_out,chain", [("bf16", ("bias", "silu")), ("f16", (("scale", 0.5), "bias", "gelu_erf")), ("f32", ("bias", "relu"))])
+def test_split_k_parallel_simple_chain_padded_rows(dt_out, chain):
+    # Chains of the form act(alpha * acc + bias[n]) are finished by the reduction kernel itself (more than two slices):
+    # the same bits as serial mode, where the tile kernel runs the chain; rows of D padded to 136 with N = 134, so the
+    # last vector of a row is cut short and the padding must stay untouched.
+    M, N, K, ldd = 200, 134, 1000, 136
+    spec = synth.gemm_spec(M, N, K, dt_in="f16" if dt_out == "f16" else "bf16", dt_out=dt_out, epilogue=chain)
+    ref, absacc = parity.oracle_result(spec)
+    w = DeviceWorkload(spec)
+    tdt = torch.float32 if dt_out == "f32" else torch.int16
+    for tile in built(0, f16=int(dt_out == "f16")):
+        bits = {}
+        for mode in ("parallel", "serial"):
+            D = torch.full((M + 1, ldd), 12345 if dt_out != "f32" else -777.0, dtype=tdt, device="cuda")
+            ucl.ucl_gemm(M, N, K, w.A.data_ptr(), spec["dt_in"], *spec["a_strides"], w.B.data_ptr(), spec["dt_in"], *spec["b_strides"],
+                         D.data_ptr(), dt_out, ldd, 1, w.epi, split_tune(tile, mode, 6), torch.cuda.current_stream().cuda_stream)
+            torch.cuda.synchronize()
+            raw = D.cpu().numpy()
+            assert (raw[:M, N:] == raw[M, 0]).all() and (raw[M] == raw[M, 0]).all(), f"{mode} {tile}: wrote outside D"
+            bits[mode] = (raw if dt_out == "f32" else raw.view(np.uint16))[:M, :N].copy()
+        assert np.array_equal(bits["parallel"], bits["serial"]), f"{tile}: parallel and serial differ"
+        got = synth.bits_to_f64(np.ascontiguousarray(bits["parallel"]), dt_out)
+        parity.compare(got.reshape(ref.shape), ref, absacc, spec, f"parallel x6 {tile}")
+    assert counters_are_zero()
+
+
 def test_split_k_more_slices_than_k_tiles_and_auto():
     # K = 72: two 64-wide ranges at most; a request for 8 slices is cut down to 2
     spec = synth.gemm_spec(72, 72, 72, dt_out="f32", epilogue=(), integer=True)
