@@ -136,9 +136,10 @@ typedef enum ucl_conv_iterator {
  * (a counter per tile in the workspace) adds the slices up and runs the epilogue.  PARALLEL: the
  * slices are written by one launch and added up and finished by another; with more than two slices
  * a small reduction kernel between them adds the slices up with the whole GPU (three launches in
- * all, on the caller's stream; two where the chain has the form act(alpha * acc + bias[n]) -- the
- * empty chain included -- and the rows of D are 16-byte aligned: the reduction kernel then runs the
- * chain on the sums and stores D itself).  Both give bit-identical results.  With no tile named in the same
+ * all, on the caller's stream; two where the chain has the form act(alpha * acc + bias[n] +
+ * beta * R[m,n]) -- any part may be missing, the empty chain included -- and the rows of D are
+ * 16-byte aligned: the reduction kernel then runs the chain on the sums and stores D itself).
+ * Both give bit-identical results.  With no tile named in the same
  * ucl_tuning, the tile is chosen for the split-K launch (not as for the unsplit problem). */
 typedef enum ucl_split_k_mode { UCL_SPLIT_K_NONE = 0, UCL_SPLIT_K_SERIAL = 1, UCL_SPLIT_K_PARALLEL = 2 } ucl_split_k_mode;
 

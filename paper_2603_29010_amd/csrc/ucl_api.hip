@@ -415,7 +415,8 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(float *partials, int
 // Words of 16 bytes per slice below which the reduction runs one float per thread (fewer than two workgroups per CU otherwise).
 constexpr int64_t kReduceScalarBelow = 2 * 256 * 256;
 
-// The same reduction for launches whose chain has the form act(alpha * acc + bias[n]) (the empty chain included): the
+// The same reduction for launches whose chain has the form act(alpha * acc + bias[n] + beta * R[m, n]) (any part may be
+// missing, the empty chain included): the
 // reduction kernel runs the chain on the sums, with the tile kernel's own element-wise functions and in its order of
 // operations (so the bits are the same), and stores D; the finishing launch of the tile kernel is not needed.
 // A 16-byte word of a partial tile is accumulator (mi, ni) of one lane: four consecutive columns of one row (the
@@ -424,11 +425,11 @@ constexpr int64_t kReduceScalarBelow = 2 * 256 * 256;
 struct ReduceStore {
     float *partials;
     void *D;
-    const void *bias;
-    int64_t slice_stride, n4, ldd, d_bs;
+    const void *bias, *res;
+    int64_t slice_stride, n4, ldd, d_bs, res_ld, res_bs;
     int32_t slices, tile_m, tile_n, M, N, tiles_m, tiles_n, tiles_per_batch, raster;
-    int32_t dtD, has_bias, bias_dt, act;
-    float alpha, act_p0, act_p1;
+    int32_t dtD, has_bias, bias_dt, has_res, res_dt, act;
+    float alpha, beta, act_p0, act_p1;
 };
 template <class V>
 __global__ __launch_bounds__(256) void splitk_reduce_store_kernel(const ReduceStore a) {
@@ -460,6 +461,16 @@ __global__ __launch_bounds__(256) void splitk_reduce_store_kernel(const ReduceSt
         float s;
         if constexpr (kPer == 4) s = acc[e]; else s = acc;
         x[e] = s * a.alpha + b;
+    }
+    if (a.has_res) {
+        const int64_t rat = (int64_t)batch * a.res_bs + (int64_t)m * a.res_ld + n;
+#pragma unroll
+        for (int e = 0; e < kPer; ++e) {
+            float r = 0.f;
+            if (e < nvalid)
+                r = a.res_dt == UCL_F32 ? ((const float *)a.res)[rat + e] : bits_to_f32(((const uint16_t *)a.res)[rat + e], a.res_dt);
+            x[e] += a.beta * r;
+        }
     }
     switch (a.act) {
 #define UCL_ACT_CASE(OP)                                                                                      \
@@ -692,13 +703,15 @@ ucl_status run(const Launch &L, KParams &kp, const ucl_tuning *tune, void *strea
         if (e == hipSuccess && sp.slices > kReduceInTileKernel) {
             // many slices: a launch of its own adds them up with the whole chip, the last launch then finds one slice
             const int64_t slice_floats = total * v->tile_m * v->tile_n, n4 = slice_floats / 4;
-            const bool simple = kp.fused.enabled && !kp.fused.has_res && kp.d_vec && L.mode != 1;
+            const bool simple = kp.fused.enabled && kp.d_vec && L.mode != 1;
             if (simple) {
-                // ... or none: a chain of the form act(alpha * acc + bias[n]) is run by the reduction kernel on the sums
+                // ... or none: a chain of the form act(alpha * acc + bias[n] + beta * R[m, n]) is run by the reduction kernel on the sums
                 ReduceStore rs;
                 rs.partials = kp.ws_partials; rs.D = kp.D; rs.bias = kp.fused.bias;
                 rs.dtD = kp.dtD; rs.has_bias = kp.fused.has_bias; rs.bias_dt = kp.fused.bias_dt & 0xff; rs.act = kp.fused.act;
                 rs.alpha = kp.fused.has_scale ? kp.fused.alpha : 1.f; rs.act_p0 = kp.fused.act_p0; rs.act_p1 = kp.fused.act_p1;
+                rs.has_res = kp.fused.has_res; rs.res = kp.fused.res; rs.res_dt = kp.fused.res_dt & 0xff; rs.beta = kp.fused.beta;
+                rs.res_ld = kp.fused.res_ld; rs.res_bs = kp.fused.res_bs;
                 rs.slice_stride = slice_floats; rs.n4 = n4; rs.ldd = kp.ldd; rs.d_bs = kp.d_bs;
                 rs.slices = sp.slices; rs.tile_m = v->tile_m; rs.tile_n = v->tile_n; rs.M = kp.M; rs.N = kp.N;
                 rs.tiles_m = kp.tiles_m; rs.tiles_n = kp.tiles_n; rs.tiles_per_batch = kp.tiles_per_batch; rs.raster = kp.raster;

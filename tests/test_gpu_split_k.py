@@ -93,9 +93,10 @@ def test_split_k_parallel_plain_f32_padded_rows():
     assert counters_are_zero()
 
 
-@pytest.mark.parametrize("dt_out,chain", [("bf16", ("bias", "silu")), ("f16", (("scale", 0.5), "bias", "gelu_erf")), ("f32", ("bias", "relu"))])
+@pytest.mark.parametrize("dt_out,chain", [("bf16", ("bias", "silu")), ("f16", (("scale", 0.5), "bias", "gelu_erf")), ("f32", ("bias", "relu")),
+                                          ("bf16", ("bias", "aux_load", "relu")), ("f32", ("aux_load",))])
 def test_split_k_parallel_simple_chain_padded_rows(dt_out, chain):
-    # Chains of the form act(alpha * acc + bias[n]) are finished by the reduction kernel itself (more than two slices):
+    # Chains of the form act(alpha * acc + bias[n] + beta * R[m, n]) are finished by the reduction kernel itself (more than two slices):
     # the same bits as serial mode, where the tile kernel runs the chain; rows of D padded to 136 with N = 134, so the
     # last vector of a row is cut short and the padding must stay untouched.
     M, N, K, ldd = 200, 134, 1000, 136
