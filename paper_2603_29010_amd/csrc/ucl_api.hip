@@ -196,7 +196,8 @@ void split_slices(const Launch &L, int64_t want, int64_t total_tiles, int fill, 
 // HBM, ~16 TB/s when the operands stay in the L2s), the MFMA rate, or a workgroup's own chain of copies (stages-1
 // k-tiles in flight, a round trip of ~1.5 us from HBM, ~0.8 us from L2).  The partial tiles then cross memory:
 // in parallel mode through a streaming reduction kernel and two more launches (measured: 6 us plus 1 us per MB
-// of partial tiles), in serial mode through the last workgroup of each tile, which reads all slices alone
+// of partial tiles; chains the reduction kernel finishes itself need one launch less, which is the same for every
+// tile and is left out of the comparison), in serial mode through the last workgroup of each tile, which reads all slices alone
 // (measured 15-28 GB/s per workgroup).
 double estimate_split_seconds(const VariantDesc &v, const Launch &L, const ucl_tuning *tune) {
     const int64_t tiles = count_tiles(L, v.tile_m, v.tile_n);
